@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+A step = build_csr_by_dst + split_hubs + (gcn_norm_scales) + L x (gather_layer + apply_layer) over one
+synthetic graph whose edge list, features and weights are already resident in HBM.  The layer loop is
+issued through the same C-ABI calls that infer_full_graph makes, so that HIP events can bracket the
+gather kernel inside the timed region; `infer_ms` additionally reports infer_full_graph itself.
+
+Prints ONE JSON line (see the design doc for the field definitions)."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="medium_uniform")
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget-s", type=float, default=25.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2307_00228_amd import binding as B
+    from paper_2307_00228_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = W.make(args.workload, args.scale)
+    N, E, L = w.n_nodes, w.n_edges, len(w.layers)
+    esz = 2 if w.dtype == W.BF16 else 4
+    src, dst = torch.from_numpy(w.src).cuda(), torch.from_numpy(w.dst).cuda()
+    x = B.to_device(w.x)
+    layers = B.device_layers(w.layers)
+    use_split = w.threshold < W.NO_SPLIT
+    thr = w.threshold if use_split else (1 << 62)
+    tdt = x.dtype
+
+    # buffers reused by every step (the caching allocator is warm after the first step anyway)
+    states = [torch.empty((N, l.d_out), dtype=tdt, device="cuda") for l in w.layers]
+    aggs = [torch.empty((N, l.d_in), dtype=tdt, device="cuda") for l in w.layers]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stamps = {"gather": [], "apply": [], "csr": [], "split": []}
+
+    def step(record: bool):
+        marks = []
+        e0 = ev(); e0.record()
+        rowptr, col, deg_out = B.build_csr_by_dst(N, src, dst)
+        e1 = ev(); e1.record()
+        split = B.split_hubs(rowptr, thr)
+        e2 = ev(); e2.record()
+        ss = sd = None
+        if any(l.agg == W.AGG_GCN for l in w.layers):
+            ss, sd = B.gcn_norm_scales(rowptr, deg_out)
+        h = x
+        for i, l in enumerate(layers):
+            a = ev(); a.record()
+            B.gather_layer(l.agg, rowptr, col, h, split if use_split else None, ss, sd, out=aggs[i])
+            b = ev(); b.record()
+            B.apply_layer(h, aggs[i], l.w_self, l.w_nbr, l.bias, l.act, out=states[i])
+            c = ev(); c.record()
+            marks.append((a, b, c))
+            h = states[i]
+        if record:
+            stamps["csr"].append((e0, e1)); stamps["split"].append((e1, e2))
+            for a, b, c in marks:
+                stamps["gather"].append((a, b)); stamps["apply"].append((b, c))
+        return rowptr, col, deg_out, split
+
+    for _ in range(args.warmup):
+        graph = step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph = step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    def avg_ms(pairs, sel=None):
+        v = [a.elapsed_time(b) for a, b in pairs]
+        if sel is not None:
+            v = v[sel::L]
+        return float(np.mean(v)) if v else 0.0
+
+    g_ms = [avg_ms(stamps["gather"], i) for i in range(L)]
+    a_ms = [avg_ms(stamps["apply"], i) for i in range(L)]
+    # algorithmic traffic of one gather launch: every in-edge reads its column index and its source row once,
+    # every vertex reads its row pointer and writes its aggregate row once
+    g_bytes = [E * (4 + l.d_in * esz) + N * (8 + l.d_in * esz) for l in w.layers]
+    a_flops = [4.0 * l.d_in * l.d_out * N for l in w.layers]
+    dom = int(np.argmax(g_ms))
+    achieved = g_bytes[dom] / (g_ms[dom] * 1e-3) / 1e9
+
+    # infer_full_graph itself (same kernels, one call)
+    rowptr, col, deg_out, split = graph
+    ws = torch.empty(max(256, B.infer_workspace_bytes(N, E, split if use_split else None, tdt, layers)),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.empty((N, w.layers[-1].d_out), dtype=tdt, device="cuda")
+    for _ in range(2):
+        B.infer_full_graph(rowptr, col, deg_out, split if use_split else None, layers, x, out=out, workspace=ws)
+    i0, i1 = ev(), ev()
+    i0.record()
+    for _ in range(args.steps):
+        B.infer_full_graph(rowptr, col, deg_out, split if use_split else None, layers, x, out=out, workspace=ws)
+    i1.record()
+    torch.cuda.synchronize()
+    infer_ms = i0.elapsed_time(i1) / args.steps
+
+    result = {
+        "metric": "edges/sec per GNN layer (gather) + apply TFLOP/s; % of HBM/MFMA roofline",
+        "value": E * L / (ms_per_step * 1e-3),
+        "unit": "edges/s per layer, whole path incl. CSR build and hub split (E*L / step time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "scale": args.scale, "n_nodes": N, "n_edges": E,
+                   "dims": [w.layers[0].d_in] + [l.d_out for l in w.layers], "aggregator": w.layers[0].agg,
+                   "hub_threshold": w.threshold if use_split else None, "recipe": w.recipe},
+        "roofline": {"bound": "hbm", "kernel": f"gather_layer (layer {dom + 1}, dim {w.layers[dom].d_in})",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": g_bytes[dom], "avg_ms": g_ms[dom]},
+        "breakdown": {
+            "csr_build_ms": avg_ms(stamps["csr"]), "split_hubs_ms": avg_ms(stamps["split"]),
+            "gather_ms": g_ms, "apply_ms": a_ms, "infer_full_graph_ms": infer_ms,
+            "gather_edges_per_s": [E / (t * 1e-3) for t in g_ms],
+            "gather_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(g_bytes, g_ms)],
+            "apply_TFLOPs": [f / (t * 1e-3) / 1e12 for f, t in zip(a_flops, a_ms)],
+            "apply_frac_of_mfma_peak": [f / (t * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype] for f, t in zip(a_flops, a_ms)],
+            "nodes_per_s_per_layer": [N / ((g + a) * 1e-3) for g, a in zip(g_ms, a_ms)],
+            "n_hubs": split.n_hubs, "n_shadows": split.n_shadows,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = oracle.set_threads(0)
+        # bounded sample: the whole path on the first `frac` of the workload's vertices/edges if the full one
+        # would take much longer than the budget (estimated from a small probe)
+        probe = W.make(args.workload, min(args.scale, 0.02 * args.scale if N > 200_000 else args.scale))
+        t = time.perf_counter()
+        r, c, d = oracle.build_csr(probe.n_nodes, probe.src, probe.dst)
+        oracle.split_hubs(r, thr)
+        oracle.infer_full_graph(r, c, d, probe.x, probe.layers, probe.dtype)
+        probe_s = time.perf_counter() - t
+        est_full = probe_s * (E / max(probe.n_edges, 1))
+        frac = 1.0 if est_full <= args.cpu_budget_s else args.cpu_budget_s / est_full
+        sw = w if frac == 1.0 else W.make(args.workload, args.scale * frac)
+        t = time.perf_counter()
+        r, c, d = oracle.build_csr(sw.n_nodes, sw.src, sw.dst)
+        oracle.split_hubs(r, thr)
+        oracle.infer_full_graph(r, c, d, sw.x, sw.layers, sw.dtype)
+        cpu_s = time.perf_counter() - t
+        result["cpu_baseline"] = {"value": sw.n_edges * L / cpu_s, "unit": "edges/s per layer, whole path",
+                                  "cores": cores, "kind": "oracle",
+                                  "sample": f"same workload at scale {args.scale * frac:.4g} "
+                                            f"({sw.n_nodes} nodes, {sw.n_edges} edges, all {L} layers), {cpu_s:.1f} s"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

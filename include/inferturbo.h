@@ -1,0 +1,234 @@
+/*
+ * inferturbo.h -- C ABI of the MI355X (gfx950) hot path of full-graph GNN
+ * inference in the Gather-Apply-Scatter schema (InferTurbo, arXiv 2307.00228).
+ *
+ * One GNN layer is evaluated for EVERY vertex, layer by layer, with no
+ * neighbour sampling (Sec. IV-B "Inference", Sec. IV-C: k supersteps for a
+ * k-layer model).  The stages of the paper's abstraction (Sec. IV-B) map to
+ * the calls below:
+ *   gather_nbrs + aggregate  -> gather_layer   (pull over in-edges, CSR by destination)
+ *   apply_node               -> apply_layer    (dense update of own state + gathered message)
+ *   apply_edge + scatter_nbrs-> the store of the new state that the next layer's gather reads
+ * and the strategies of Sec. IV-D to split_hubs (even split of a hub's edge
+ * set into mirrors, done in preprocessing) and to the partial-gather passes
+ * inside gather_layer (partials per mirror, then an ordered combine).
+ *
+ * Conventions for every call
+ *  - Every pointer is a DEVICE pointer unless marked "host".  All buffers
+ *    (inputs, outputs, workspace) are allocated, owned and freed by the
+ *    caller; the library keeps no allocation and no pointer after return and
+ *    never modifies an input.
+ *  - Workspace protocol: if `workspace` is NULL the call only writes the
+ *    number of bytes it needs for these sizes to *workspace_bytes (host) and
+ *    returns ITB_OK.  Otherwise *workspace_bytes is the size provided;
+ *    too small -> ITB_ERR_WORKSPACE.  Workspace must be 256-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    gather_layer, apply_layer, gcn_norm_scales and infer_full_graph only
+ *    enqueue work and return without synchronising.  build_csr_by_dst and
+ *    split_hubs synchronise the stream before returning (they report range
+ *    errors / counts to the host).
+ *  - Return value: ITB_OK (0) or a negative itb_status.  Argument errors are
+ *    detected on the host before any launch.  Nothing throws, aborts or prints.
+ *  - Dense tensors are row-major.  ITB_BF16 tensors hold IEEE bfloat16
+ *    (round-to-nearest-even on store); all sums accumulate in fp32.
+ *  - Sizes: 0 <= n_nodes < 2^31, 0 <= n_edges < 2^31.
+ *  - Results are bitwise reproducible run to run: no floating-point atomics,
+ *    every summation order is fixed by the inputs and sizes (the paper's
+ *    consistency requirement, Sec. IV-A).
+ */
+#ifndef INFERTURBO_H
+#define INFERTURBO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ITB_OK = 0,
+    ITB_ERR_NULL = -1,        /* a required pointer is NULL */
+    ITB_ERR_SIZE = -2,        /* negative or too large size, threshold <= 0 */
+    ITB_ERR_RANGE = -3,       /* an edge endpoint is outside [0, n_nodes) */
+    ITB_ERR_DTYPE = -4,       /* unknown dtype / aggregator / activation code */
+    ITB_ERR_UNSUPPORTED = -5, /* a width the kernels do not cover (see each call) */
+    ITB_ERR_WORKSPACE = -6,   /* workspace too small or misaligned */
+    ITB_ERR_DEVICE = -7       /* a HIP call failed */
+} itb_status;
+
+enum { ITB_F32 = 0, ITB_BF16 = 1 };
+enum { ITB_AGG_SUM = 0, ITB_AGG_MEAN = 1, ITB_AGG_GCN = 2, ITB_AGG_GAT = 3 };
+enum { ITB_ACT_NONE = 0, ITB_ACT_RELU = 1 };
+
+/* ---------------------------------------------------------------------------
+ * build_csr_by_dst -- group the in-edges of every vertex (Sec. IV-B
+ * gather_nbrs: a vertex receives the messages of its in-edges; Sec. IV-C: the
+ * input is an edge table of (source, destination) pairs).
+ *
+ *   src, dst   [n_edges] int32, edge e goes src[e] -> dst[e]; multi-edges and
+ *              self-loops are ordinary edges.
+ *   rowptr     out [n_nodes+1] int64; rowptr[v+1]-rowptr[v] = in-degree of v.
+ *   col        out [n_edges] int32; col[rowptr[v] + j] = source of the j-th
+ *              in-edge of v in ORIGINAL edge order (stable).
+ *   deg_out    out [n_nodes] int32 out-degree of every vertex; may be NULL.
+ * n_nodes == 0 or n_edges == 0 are valid.  Returns ITB_ERR_RANGE (outputs
+ * unspecified but in bounds) if any endpoint is outside [0, n_nodes).
+ * ------------------------------------------------------------------------- */
+int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges,
+                         const int32_t *src, const int32_t *dst,
+                         int64_t *rowptr, int32_t *col, int32_t *deg_out,
+                         void *workspace, size_t *workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * split_hubs -- mirror ("shadow") split of high-in-degree vertices (Sec. IV-D
+ * "Shadow Nodes": a hub's edges are divided evenly into n groups, one mirror
+ * per group, in preprocessing; activated when the edge count EXCEEDS the
+ * threshold).  A vertex with in-degree d > threshold gets n = ceil(d/threshold)
+ * contiguous segments of its CSR row, segment g covering
+ * [rowptr[v] + floor(g*d/n), rowptr[v] + floor((g+1)*d/n)).
+ *
+ *   n_hubs, n_shadows  host out: number of hubs H and of segments S.
+ *   hub_ids        out [H]   int32, ascending vertex ids.
+ *   hub_shadow_off out [H+1] int64, segments of hub i are [off[i], off[i+1]).
+ *   shadow_begin/shadow_end out [S] int64 edge offsets into col.
+ *   shadow_owner   out [S]   int32 vertex id owning the segment.
+ * Call once with all five arrays NULL to obtain H and S, allocate, call again.
+ * ------------------------------------------------------------------------- */
+int32_t split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t threshold,
+                   int64_t *n_hubs, int64_t *n_shadows,
+                   int32_t *hub_ids, int64_t *hub_shadow_off,
+                   int64_t *shadow_begin, int64_t *shadow_end, int32_t *shadow_owner,
+                   void *workspace, size_t *workspace_bytes, void *stream);
+
+/* The split as consumed by gather_layer / infer_full_graph.  `threshold` must
+ * be the value given to split_hubs: rows with in-degree > threshold are
+ * skipped by the per-row pass and produced by the partial/combine passes. */
+typedef struct {
+    int64_t threshold;
+    int64_t n_hubs, n_shadows;
+    const int32_t *hub_ids;
+    const int64_t *hub_shadow_off;
+    const int64_t *shadow_begin, *shadow_end;
+    const int32_t *shadow_owner;
+} itb_split;
+
+/* ---------------------------------------------------------------------------
+ * gcn_norm_scales -- per-vertex factors of the symmetric degree normalisation:
+ * src_scale[u] = max(deg_out[u],1)^-1/2, dst_scale[v] = max(deg_in[v],1)^-1/2,
+ * so that the coefficient of edge u->v is src_scale[u]*dst_scale[v].
+ * Outputs [n_nodes] fp32.
+ * ------------------------------------------------------------------------- */
+int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *deg_out,
+                        float *src_scale, float *dst_scale, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * gather_layer -- gather_nbrs + aggregate (Sec. IV-B), i.e. the reduce R of
+ * Eq. (1) with the source's hidden state as the message (Sec. II-B).  The
+ * aggregate is commutative and associative, which is what makes the hub
+ * partials exact (Sec. IV-D "Partial-Gather").
+ *
+ *   ITB_AGG_SUM : agg[v] = sum over in-edges of h[col]
+ *   ITB_AGG_MEAN: the sum divided by the in-degree; 0 for an isolated vertex
+ *   ITB_AGG_GCN : dst_scale[v] * sum of src_scale[col] * h[col]  (both required)
+ *   ITB_AGG_GAT : attention-weighted sum, see below.
+ *
+ *   dim        feature width; dim * sizeof(element) must be a multiple of 16.
+ *   h_src      [n_nodes x dim] dtype_in.
+ *   agg_out    [n_nodes x dim] dtype_out (f32->f32, bf16->bf16, bf16->f32).
+ *   split      NULL = every row in one pass; else hub rows go through
+ *              per-segment partial sums (fp32, in workspace) that are combined
+ *              in ascending segment order.
+ *   edge_lo/edge_hi  only rows (and segments) whose first edge offset lies in
+ *              [edge_lo, edge_hi) are produced by this call; pass 0 and
+ *              INT64_MAX for the whole graph.  Rows with no in-edge belong to
+ *              the range that contains their rowptr value.
+ *
+ * ITB_AGG_GAT (Sec. II-B: GAT's reduce is an attention-weighted sum; Sec. IV-B:
+ * it runs after the messages are collected): h_src is the projected state z,
+ * heads divides dim, src_scale = s_src [n_nodes x heads], dst_scale = s_dst
+ * [n_nodes x heads] (fp32).  For vertex v and head k, over its in-edges plus an
+ * implicit self edge: e = LeakyReLU_slope(s_src[u,k] + s_dst[v,k]),
+ * alpha = softmax(e), agg[v,k,:] = sum alpha_u z[u,k,:].
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t agg;        /* ITB_AGG_* */
+    int32_t dtype_in;   /* ITB_F32 | ITB_BF16 */
+    int32_t dtype_out;
+    int32_t dim;
+    int32_t heads;      /* GAT only, else 1 */
+    float leaky_slope;  /* GAT only */
+} itb_gather_desc;
+
+int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
+                     const int64_t *rowptr, const int32_t *col, const itb_split *split,
+                     const void *h_src, const float *src_scale, const float *dst_scale,
+                     void *agg_out, int64_t edge_lo, int64_t edge_hi,
+                     void *workspace, size_t *workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * apply_layer -- apply_node (Sec. IV-B), the update U of Eq. (1): combine the
+ * vertex's former state with the gathered message, then the activation; the
+ * store of h_out is the scatter of the new state for the next layer.
+ *
+ *   h_out[v] = act( h_self[v] . W_self + agg[v] . W_nbr + bias )
+ *
+ *   h_self [n x d_in] or NULL together with w_self (no self term).
+ *   agg    [n x d_in];  w_self, w_nbr [d_in x d_out];  all of `dtype`.
+ *   bias   [d_out] fp32 or NULL.   h_out [n x d_out] of `dtype`.
+ *   dtype ITB_F32: fp32 matrix-core path (d_in % 8 == 0);
+ *   dtype ITB_BF16: bf16 matrix-core path, fp32 accumulate (d_in % 16 == 0).
+ *   1 <= d_out <= 256, d_in <= 512 (else ITB_ERR_UNSUPPORTED).
+ *   att_src/att_dst/s_src/s_dst: optional attention-score epilogue for the GAT
+ *   projection: s_src[v,k] = sum_d att_src[k,d] * y[v,k,d] (fp32, from the fp32
+ *   accumulators before rounding), heads dividing d_out; NULL/0 to skip.
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t dtype;
+    int32_t d_in, d_out;
+    int32_t act;        /* ITB_ACT_* */
+    int32_t heads;      /* score epilogue only, else 0 */
+} itb_apply_desc;
+
+int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes,
+                    const void *h_self, const void *agg,
+                    const void *w_self, const void *w_nbr, const float *bias,
+                    void *h_out,
+                    const float *att_src, const float *att_dst, float *s_src, float *s_dst,
+                    void *stream);
+
+/* ---------------------------------------------------------------------------
+ * infer_full_graph -- the layer loop (Sec. IV-C: after k rounds the result of
+ * a k-layer model is available for every vertex; h^0 = x, Eq. (1)).
+ * Layer l: gather_layer, then apply_layer (GAT: projection, attention gather,
+ * bias, activation).  Intermediate states live in `workspace`.
+ *
+ *   layers     host array of n_layers descriptors; weight pointers are device.
+ *   x          [n_nodes x layers[0].d_in], out [n_nodes x layers[last].d_out],
+ *              both of `dtype` (all layers share it).
+ *   deg_out    required when a layer uses ITB_AGG_GCN, else may be NULL.
+ *   edge_chunk 0 = one gather launch set per layer; else each layer's gather is
+ *              issued per range of `edge_chunk` edge offsets (see gather_layer).
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t agg;        /* ITB_AGG_* */
+    int32_t d_in, d_out;
+    int32_t act;
+    int32_t heads;
+    float leaky_slope;
+    const void *w_self; /* [d_in x d_out], NULL for GAT */
+    const void *w_nbr;  /* [d_in x d_out]; GAT: the projection */
+    const float *bias;  /* [d_out] or NULL */
+    const float *att_src, *att_dst; /* GAT: [heads x d_out/heads] */
+} itb_layer;
+
+int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
+                         const int32_t *deg_out, const itb_split *split,
+                         int32_t dtype, int32_t n_layers, const itb_layer *layers,
+                         const void *x, void *out, int64_t edge_chunk,
+                         void *workspace, size_t *workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFERTURBO_H */

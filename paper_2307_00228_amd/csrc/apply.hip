@@ -1,0 +1,235 @@
+// apply_layer: h_out = act([h_self | agg] . [W_self ; W_nbr] + bias) on the matrix cores.
+//
+// The weights are tiny (<= 256 KB) and the activations are a tall-skinny stream, so:
+//   * each block is persistent: it loads the whole [K_total x BN] weight panel into LDS once, in the exact
+//     fragment order of the MFMA B operand (one conflict-free 16-byte LDS read per lane per k-chunk), and
+//     then walks over 32*waves-row tiles;
+//   * every wavefront owns 32 rows and all BN = 32*NT output columns (NT independent 32x32 accumulators,
+//     so consecutive MFMAs never wait on each other);
+//   * the A operand goes straight from global memory to registers: lane (row i, half kh) loads 16 bytes of
+//     its row per k-chunk.  The k index inside a chunk is permuted identically for A and B (a dot product
+//     does not care), which lets one 16-byte load feed 4 fp32 MFMAs (32x32x2) or 1 bf16 MFMA (32x32x16);
+//   * bias, activation and the store (the scatter of the new state) are fused into the epilogue.
+#include "common.h"
+
+namespace {
+using namespace itb;
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kApplyThreads = 512;
+constexpr int kApplyWaves = kApplyThreads / kWave;
+constexpr int kRowsPerBlockTile = 32 * kApplyWaves;
+constexpr size_t kMaxWeightLds = 128 * 1024;
+
+struct ApplyArgs {
+    int64_t n;
+    const uint4 *h_self;  // nullable
+    const uint4 *agg;
+    const void *w_self;   // nullable
+    const void *w_nbr;
+    const float *bias;    // nullable
+    void *out;
+    int32_t d_in, d_out;
+    int32_t act;
+    int64_t n_row_tiles;
+};
+
+// LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
+// 4 (fp32) or 8 (bf16) consecutive-k weights W[kc*KC + kh*KC/2 + t][col0 + j].
+template <bool BF16, int NT>
+__device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &a, int col0) {
+    constexpr int BN = 32 * NT;
+    constexpr int KC = BF16 ? 16 : 8;
+    constexpr int KH = KC / 2;
+    const int phases = a.h_self ? 2 : 1;
+    const int chunks_per_phase = a.d_in / KC;
+    const int total = phases * chunks_per_phase * 2 * BN;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int j = idx % BN;
+        const int kh = (idx / BN) & 1;
+        const int kcg = idx / (2 * BN);
+        const int phase = kcg / chunks_per_phase;
+        const int kc = kcg % chunks_per_phase;
+        const void *wbase = (phases == 2 && phase == 0) ? a.w_self : a.w_nbr;
+        const int col = col0 + j;
+        const int k0 = kc * KC + kh * KH;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (col < a.d_out) {
+            if constexpr (BF16) {
+                const uint16_t *w = static_cast<const uint16_t *>(wbase);
+                uint32_t e[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) e[t] = w[(int64_t)(k0 + t) * a.d_out + col];
+                v.x = e[0] | (e[1] << 16);
+                v.y = e[2] | (e[3] << 16);
+                v.z = e[4] | (e[5] << 16);
+                v.w = e[6] | (e[7] << 16);
+            } else {
+                const uint32_t *w = static_cast<const uint32_t *>(wbase);
+                v.x = w[(int64_t)(k0 + 0) * a.d_out + col];
+                v.y = w[(int64_t)(k0 + 1) * a.d_out + col];
+                v.z = w[(int64_t)(k0 + 2) * a.d_out + col];
+                v.w = w[(int64_t)(k0 + 3) * a.d_out + col];
+            }
+        }
+        wlds[idx] = v;
+    }
+}
+
+template <bool BF16, int NT>
+__global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
+    extern __shared__ uint4 wlds[];
+    constexpr int BN = 32 * NT;
+    constexpr int KC = BF16 ? 16 : 8;
+    const int col0 = blockIdx.y * BN;
+    load_weight_panel<BF16, NT>(wlds, a, col0);
+    __syncthreads();
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x / kWave;
+    const int i = lane & 31;
+    const int kh = lane >> 5;
+    const int chunks = a.d_in / KC;
+    const int row_vecs = a.d_in * (BF16 ? 2 : 4) / 16;  // == 2 * chunks
+    const int phases = a.h_self ? 2 : 1;
+
+    for (int64_t tile = blockIdx.x; tile < a.n_row_tiles; tile += gridDim.x) {
+        const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
+        if (m0 >= a.n) continue;
+        int64_t row = m0 + i;
+        if (row >= a.n) row = a.n - 1;  // clamped rows are computed but never stored
+        v16f acc[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+
+        for (int phase = 0; phase < phases; ++phase) {
+            const uint4 *arow = ((phases == 2 && phase == 0) ? a.h_self : a.agg) + row * row_vecs + kh;
+            const uint4 *wp = wlds + (int64_t)phase * chunks * 2 * BN + kh * BN + i;
+#pragma unroll 4
+            for (int kc = 0; kc < chunks; ++kc) {
+                const uint4 av = arow[kc * 2];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const uint4 bv = wp[kc * 2 * BN + nt * 32];
+                    if constexpr (BF16) {
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv),
+                                                                          acc[nt], 0, 0, 0);
+                    } else {
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(bv.x), acc[nt], 0, 0, 0);
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(bv.y), acc[nt], 0, 0, 0);
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(bv.z), acc[nt], 0, 0, 0);
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(bv.w), acc[nt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+
+        // Epilogue.  Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of the tile.
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int col = col0 + nt * 32 + i;
+            if (col >= a.d_out) continue;
+            const float b = a.bias ? a.bias[col] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
+                if (orow >= a.n) continue;
+                float y = acc[nt][r] + b;
+                if (a.act == ITB_ACT_RELU) y = y > 0.f ? y : 0.f;
+                if constexpr (BF16) {
+                    static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
+                } else {
+                    static_cast<float *>(a.out)[orow * a.d_out + col] = y;
+                }
+            }
+        }
+    }
+}
+
+template <bool BF16, int NT>
+int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    constexpr int BN = 32 * NT;
+    const int k_total = a.d_in * (a.h_self ? 2 : 1);
+    const size_t lds = (size_t)k_total * BN * (BF16 ? 2 : 4);
+    static bool attr_set = false;
+    if (!attr_set) {
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxWeightLds));
+        attr_set = true;
+    }
+    const int col_tiles = (a.d_out + BN - 1) / BN;
+    int blocks_per_cu = (int)((160 * 1024) / (lds + 1024));
+    if (blocks_per_cu < 1) blocks_per_cu = 1;
+    if (blocks_per_cu > 2) blocks_per_cu = 2;
+    int64_t gx = (int64_t)n_cus * blocks_per_cu / col_tiles;
+    if (gx < 1) gx = 1;
+    if (gx > a.n_row_tiles) gx = a.n_row_tiles;
+    dim3 grid((unsigned)gx, (unsigned)col_tiles);
+    apply_kernel<BF16, NT><<<grid, kApplyThreads, lds, st>>>(a);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
+
+template <bool BF16>
+int32_t dispatch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    const int k_total = a.d_in * (a.h_self ? 2 : 1);
+    const size_t per_tile = (size_t)k_total * 32 * (BF16 ? 2 : 4);
+    int nt = 8;
+    while (nt > 1 && (per_tile * nt > kMaxWeightLds || 32 * (nt / 2) >= a.d_out)) nt /= 2;
+    if (per_tile * nt > kMaxWeightLds) return ITB_ERR_UNSUPPORTED;
+    switch (nt) {
+        case 8: return launch_apply<BF16, 8>(a, n_cus, st);
+        case 4: return launch_apply<BF16, 4>(a, n_cus, st);
+        case 2: return launch_apply<BF16, 2>(a, n_cus, st);
+        default: return launch_apply<BF16, 1>(a, n_cus, st);
+    }
+}
+
+int cached_cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+}  // namespace
+
+extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, const void *h_self, const void *agg,
+                               const void *w_self, const void *w_nbr, const float *bias, void *h_out, const float *att_src,
+                               const float *att_dst, float *s_src, float *s_dst, void *stream) {
+    if (!desc) return ITB_ERR_NULL;
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
+    if (desc->dtype != ITB_F32 && desc->dtype != ITB_BF16) return ITB_ERR_DTYPE;
+    if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
+    if (desc->d_in <= 0 || desc->d_out <= 0) return ITB_ERR_SIZE;
+    const int kc = desc->dtype == ITB_BF16 ? 16 : 8;
+    if (desc->d_in % kc != 0 || desc->d_in > 512 || desc->d_out > 256) return ITB_ERR_UNSUPPORTED;
+    if (desc->heads != 0 || att_src || att_dst || s_src || s_dst) return ITB_ERR_UNSUPPORTED;
+    if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
+    if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;
+    if (n_nodes == 0) return ITB_OK;
+
+    ApplyArgs a{};
+    a.n = n_nodes;
+    a.h_self = static_cast<const uint4 *>(h_self);
+    a.agg = static_cast<const uint4 *>(agg);
+    a.w_self = w_self;
+    a.w_nbr = w_nbr;
+    a.bias = bias;
+    a.out = h_out;
+    a.d_in = desc->d_in;
+    a.d_out = desc->d_out;
+    a.act = desc->act;
+    a.n_row_tiles = (n_nodes + kRowsPerBlockTile - 1) / kRowsPerBlockTile;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return desc->dtype == ITB_BF16 ? dispatch_apply<true>(a, cached_cu_count(), st)
+                                   : dispatch_apply<false>(a, cached_cu_count(), st);
+}

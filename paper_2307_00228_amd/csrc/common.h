@@ -1,0 +1,88 @@
+// Internal helpers shared by the HIP translation units of libinferturbo_hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "inferturbo.h"
+
+#define ITB_HIP(call)                                   \
+    do {                                                \
+        if ((call) != hipSuccess) return ITB_ERR_DEVICE; \
+    } while (0)
+
+#define ITB_LAUNCH_CHECK()                                       \
+    do {                                                         \
+        if (hipGetLastError() != hipSuccess) return ITB_ERR_DEVICE; \
+    } while (0)
+
+namespace itb {
+
+constexpr int kWave = 64;
+
+static inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Carves 256-byte aligned pieces out of the caller's workspace; with base == nullptr it only sizes.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *b) : base(static_cast<char *>(b)) {}
+    template <typename T>
+    T *take(size_t count) {
+        size_t o = off;
+        off += align_up(count * sizeof(T));
+        return base ? reinterpret_cast<T *>(base + o) : nullptr;
+    }
+};
+
+// ---- bf16 storage format -----------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+}
+
+// ---- wave / block scans ------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        T o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan across a block of up to 1024 threads; every thread must call it.
+// `smem` must hold 17 elements of T.  Returns the exclusive prefix; *total gets the block sum.
+template <typename T>
+__device__ __forceinline__ T block_exclusive_scan(T v, T *smem, T *total) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int nwaves = (blockDim.x + kWave - 1) / kWave;
+    T inc = wave_inclusive_scan(v);
+    __syncthreads();  // protects smem reuse between consecutive calls
+    if (lane == kWave - 1) smem[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T run = 0;
+        for (int w = 0; w < nwaves; ++w) {
+            T t = smem[w];
+            smem[w] = run;
+            run += t;
+        }
+        smem[16] = run;
+    }
+    __syncthreads();
+    *total = smem[16];
+    return inc - v + smem[wave];
+}
+
+}  // namespace itb

@@ -1,0 +1,463 @@
+// gather_layer: degree-segmented sum / mean / degree-normalised sum over in-edges (pull over CSR rows).
+//
+// Data movement is the whole cost (one 16-byte vector per lane per edge, one fp32 FMA per element), so the
+// kernels are organised around keeping many independent row loads in flight per wavefront:
+//   * a row of `dim` elements is covered by G = next_pow2(dim*elem/16) lanes, each owning one 16-byte
+//     vector; a 64-lane wavefront therefore carries 64/G edges per load instruction;
+//   * each wavefront owns 64 consecutive destination rows (their row pointers are one coalesced load);
+//     rows with few in-edges are processed 64/G at a time, one lane group per row; longer rows are
+//     processed by the whole wavefront, the lane groups taking interleaved edges and a fixed xor-butterfly
+//     combining the group partials;
+//   * column indices (and per-source scales) are fetched 64 (or G) at a time with one coalesced load and
+//     handed to the lane groups by cross-lane shuffles, so the dependent row loads are issued back to back;
+//   * hub rows (in-degree > threshold) are skipped here; their shadow segments are summed one wavefront per
+//     segment into fp32 partials and a block per hub adds the partials in ascending segment order.
+// No floating-point atomics anywhere: every summation order is a function of the sizes only.
+#include "common.h"
+
+namespace itb {
+int g_small_limit = -1;   // tuning hook: rows with in-degree <= limit use one lane group per row (-1 = auto)
+int g_gather_unroll = 4;  // reserved
+}  // namespace itb
+
+namespace {
+using namespace itb;
+
+enum { kModeSum = 0, kModeMean = 1, kModeScaleDst = 2 };
+
+struct GatherArgs {
+    int64_t n_nodes;
+    const int64_t *rowptr;
+    const int32_t *col;
+    const uint4 *h;          // [n_nodes x row_vecs] 16-byte vectors
+    const float *src_scale;  // nullable
+    const float *dst_scale;  // kModeScaleDst only
+    void *out;               // agg rows, or fp32 partial rows in the segment kernel
+    int64_t threshold;       // rows with in-degree > threshold are hubs (skipped by the row kernel)
+    int64_t edge_lo, edge_hi;
+    int32_t row_vecs;        // 16-byte vectors per input row
+    int32_t mode;
+    int32_t small_limit;
+    // segment kernel only
+    int64_t n_shadows;
+    const int64_t *shadow_begin, *shadow_end;
+    const int32_t *shadow_owner;
+};
+
+template <bool BF16>
+struct Elems {
+    static constexpr int kPerVec = BF16 ? 8 : 4;
+};
+
+template <bool BF16>
+__device__ __forceinline__ void accumulate(float (&acc)[Elems<BF16>::kPerVec], const uint4 &raw, float s) {
+    if constexpr (BF16) {
+        acc[0] = fmaf(s, bf16_lo(raw.x), acc[0]);
+        acc[1] = fmaf(s, bf16_hi(raw.x), acc[1]);
+        acc[2] = fmaf(s, bf16_lo(raw.y), acc[2]);
+        acc[3] = fmaf(s, bf16_hi(raw.y), acc[3]);
+        acc[4] = fmaf(s, bf16_lo(raw.z), acc[4]);
+        acc[5] = fmaf(s, bf16_hi(raw.z), acc[5]);
+        acc[6] = fmaf(s, bf16_lo(raw.w), acc[6]);
+        acc[7] = fmaf(s, bf16_hi(raw.w), acc[7]);
+    } else {
+        acc[0] = fmaf(s, __uint_as_float(raw.x), acc[0]);
+        acc[1] = fmaf(s, __uint_as_float(raw.y), acc[1]);
+        acc[2] = fmaf(s, __uint_as_float(raw.z), acc[2]);
+        acc[3] = fmaf(s, __uint_as_float(raw.w), acc[3]);
+    }
+}
+
+// Store one lane's slice of an output row.  `vec` is the lane's 16-byte vector index in the INPUT row.
+template <bool BF16_IN, bool BF16_OUT>
+__device__ __forceinline__ void store_row_slice(void *out, int64_t row, int32_t row_vecs, int vec,
+                                                const float (&acc)[Elems<BF16_IN>::kPerVec]) {
+    constexpr int VE = Elems<BF16_IN>::kPerVec;
+    const int64_t elem0 = (row * row_vecs + vec) * VE;
+    if constexpr (BF16_OUT) {
+        static_assert(BF16_IN, "bf16 output needs bf16 input");
+        uint4 p;
+        p.x = pack_bf16x2(acc[0], acc[1]);
+        p.y = pack_bf16x2(acc[2], acc[3]);
+        p.z = pack_bf16x2(acc[4], acc[5]);
+        p.w = pack_bf16x2(acc[6], acc[7]);
+        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + elem0) = p;
+    } else {
+        float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(out) + elem0);
+        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        if constexpr (VE == 8) o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+}
+
+template <int VE>
+__device__ __forceinline__ void finish_row(float (&acc)[VE], int mode, int64_t deg, const float *dst_scale, int64_t row) {
+    if (mode == kModeMean) {
+        if (deg > 0) {
+            const float d = (float)deg;
+#pragma unroll
+            for (int i = 0; i < VE; ++i) acc[i] = acc[i] / d;
+        }
+    } else if (mode == kModeScaleDst) {
+        const float s = dst_scale[row];
+#pragma unroll
+        for (int i = 0; i < VE; ++i) acc[i] *= s;
+    }
+}
+
+__device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
+    int lo = __shfl((int)(v & 0xffffffff), src, kWave);
+    int hi = __shfl((int)(v >> 32), src, kWave);
+    return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+// Whole-wavefront sum of h[col[e]] * scale over the edge range [start, start+deg).  Group g takes the edges
+// congruent to g modulo 64/G inside every 64-edge chunk; on return every lane group holds the full sum.
+template <bool BF16, int G>
+__device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerVec], const GatherArgs &a, int64_t start,
+                                                 int64_t deg, int vec, bool lane_on) {
+    constexpr int NG = kWave / G;
+    constexpr int VE = Elems<BF16>::kPerVec;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / G;
+    const bool has_scale = a.src_scale != nullptr;
+#pragma unroll
+    for (int i = 0; i < VE; ++i) acc[i] = 0.f;
+    for (int64_t c = 0; c < deg; c += kWave) {
+        int myc = 0;
+        float mys = 1.f;
+        if (c + lane < deg) {
+            myc = a.col[start + c + lane];
+            if (has_scale) mys = a.src_scale[myc];
+        }
+        const int cnt = (deg - c < kWave) ? (int)(deg - c) : kWave;  // wave-uniform
+        const int steps = (cnt + NG - 1) / NG;
+        for (int t = 0; t < steps; t += U) {
+            uint4 raw[U];
+            float sc[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int ei = (t + q) * NG + g;
+                const int u = __shfl(myc, ei & (kWave - 1), kWave);
+                const float s = __shfl(mys, ei & (kWave - 1), kWave);
+                const bool on = lane_on && ei < cnt;
+                raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
+                sc[q] = on ? s : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < U; ++q) accumulate<BF16>(acc, raw[q], sc[q]);
+        }
+    }
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
+    }
+}
+
+template <bool BF16_IN, bool BF16_OUT, int G>
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
+    constexpr int NG = kWave / G;
+    constexpr int VE = Elems<BF16_IN>::kPerVec;
+    constexpr int U = (G < 4) ? G : 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / G;
+    const int li = lane % G;
+    const int64_t r0 = ((int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave)) * kWave;
+    if (r0 >= a.n_nodes) return;
+    const int vec = blockIdx.y * G + li;
+    const bool lane_on = vec < a.row_vecs;
+    const bool has_scale = a.src_scale != nullptr;
+
+    const int64_t my_row = r0 + lane;
+    int64_t rs = 0, re = 0;
+    if (my_row < a.n_nodes) {
+        rs = a.rowptr[my_row];
+        re = a.rowptr[my_row + 1];
+    }
+    const int64_t deg64 = re - rs;
+    const bool mine = my_row < a.n_nodes && rs >= a.edge_lo && rs < a.edge_hi && deg64 <= a.threshold;
+    const int deg = (int)deg64;
+    const uint64_t small_mask = __ballot(mine && deg <= a.small_limit);
+    uint64_t large_mask = __ballot(mine && deg > a.small_limit);
+
+    // ---- rows with few in-edges: one lane group per row, 64/G rows at a time ----------------------------
+    if (small_mask) {
+        for (int sub = 0; sub < kWave; sub += NG) {
+            const uint64_t sel = (NG == kWave) ? small_mask : ((small_mask >> sub) & ((1ull << NG) - 1ull));
+            if (sel == 0) continue;
+            const int rl = sub + g;
+            const bool act = (small_mask >> rl) & 1ull;
+            int d = __shfl(deg, rl, kWave);
+            if (!act) d = 0;
+            const int64_t st = shfl_i64(rs, rl);
+            float acc[VE];
+#pragma unroll
+            for (int i = 0; i < VE; ++i) acc[i] = 0.f;
+            for (int j = 0; __ballot(j < d) != 0ull; j += G) {
+                int myc = 0;
+                float mys = 1.f;
+                if (j + li < d) {
+                    myc = a.col[st + j + li];
+                    if (has_scale) mys = a.src_scale[myc];
+                }
+                const int cnt = d - j;  // edges left for this group (may be <= 0)
+                for (int t = 0; t < G; t += U) {
+                    if (__ballot(t < cnt) == 0ull) break;
+                    uint4 raw[U];
+                    float sc[U];
+#pragma unroll
+                    for (int q = 0; q < U; ++q) {
+                        const int sl = g * G + t + q;
+                        const int u = __shfl(myc, sl, kWave);
+                        const float s = __shfl(mys, sl, kWave);
+                        const bool on = lane_on && (t + q) < cnt;
+                        raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
+                        sc[q] = on ? s : 0.f;
+                    }
+#pragma unroll
+                    for (int q = 0; q < U; ++q) accumulate<BF16_IN>(acc, raw[q], sc[q]);
+                }
+            }
+            if (act && lane_on) {
+                finish_row<VE>(acc, a.mode, d, a.dst_scale, r0 + rl);
+                store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
+            }
+        }
+    }
+
+    // ---- longer rows: the whole wavefront per row ---------------------------------------------------------
+    while (large_mask) {
+        const int rl = __ffsll((unsigned long long)large_mask) - 1;
+        large_mask &= large_mask - 1;
+        const int d = __shfl(deg, rl, kWave);
+        const int64_t st = shfl_i64(rs, rl);
+        float acc[VE];
+        wave_segment_sum<BF16_IN, G>(acc, a, st, d, vec, lane_on);
+        if (g == 0 && lane_on) {
+            finish_row<VE>(acc, a.mode, d, a.dst_scale, r0 + rl);
+            store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
+        }
+    }
+}
+
+// One wavefront per shadow segment: fp32 partial sums (source scales applied, destination finish deferred).
+template <bool BF16_IN, int G>
+__global__ __launch_bounds__(256) void gather_segments_kernel(GatherArgs a) {
+    constexpr int VE = Elems<BF16_IN>::kPerVec;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / G;
+    const int li = lane % G;
+    const int64_t s = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (s >= a.n_shadows) return;
+    const int64_t owner_start = a.rowptr[a.shadow_owner[s]];
+    if (owner_start < a.edge_lo || owner_start >= a.edge_hi) return;
+    const int vec = blockIdx.y * G + li;
+    const bool lane_on = vec < a.row_vecs;
+    const int64_t b = a.shadow_begin[s];
+    const int64_t e = a.shadow_end[s];
+    float acc[VE];
+    wave_segment_sum<BF16_IN, G>(acc, a, b, e - b, vec, lane_on);
+    if (g == 0 && lane_on) store_row_slice<BF16_IN, false>(a.out, s, a.row_vecs, vec, acc);
+}
+
+// One block per hub: partial rows are added in ascending segment order within each of `slices` interleaved
+// chains, then the chains are added in ascending slice order.
+template <bool BF16_OUT>
+__global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, int32_t dim, int64_t n_hubs,
+                                                            const int32_t *hub_ids, const int64_t *hub_shadow_off,
+                                                            const int64_t *rowptr, const float *dst_scale, int32_t mode,
+                                                            int64_t edge_lo, int64_t edge_hi, void *out) {
+    __shared__ float4 sm[1024];
+    const int64_t hub = blockIdx.x;
+    const int32_t v = hub_ids[hub];
+    const int64_t rs = rowptr[v];
+    if (rs < edge_lo || rs >= edge_hi) return;
+    const int64_t deg = rowptr[v + 1] - rs;
+    const int64_t s0 = hub_shadow_off[hub], s1 = hub_shadow_off[hub + 1];
+    const int lanes_per_row = dim / 4;
+    for (int q0 = 0; q0 < lanes_per_row; q0 += 1024) {  // column tiles of 4096 elements
+        const int cols_here = (lanes_per_row - q0 < 1024) ? (lanes_per_row - q0) : 1024;
+        const int slices = 1024 / cols_here;
+        const int slice = threadIdx.x / cols_here;
+        const int lv = threadIdx.x % cols_here;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (slice < slices) {
+            const float4 *p = reinterpret_cast<const float4 *>(part) + q0 + lv;
+            int64_t s = s0 + slice;
+            for (; s + 3 * (int64_t)slices < s1; s += 4 * (int64_t)slices) {
+                const float4 x0 = p[s * lanes_per_row];
+                const float4 x1 = p[(s + slices) * lanes_per_row];
+                const float4 x2 = p[(s + 2 * (int64_t)slices) * lanes_per_row];
+                const float4 x3 = p[(s + 3 * (int64_t)slices) * lanes_per_row];
+                acc.x += x0.x; acc.y += x0.y; acc.z += x0.z; acc.w += x0.w;
+                acc.x += x1.x; acc.y += x1.y; acc.z += x1.z; acc.w += x1.w;
+                acc.x += x2.x; acc.y += x2.y; acc.z += x2.z; acc.w += x2.w;
+                acc.x += x3.x; acc.y += x3.y; acc.z += x3.z; acc.w += x3.w;
+            }
+            for (; s < s1; s += slices) {
+                const float4 x0 = p[s * lanes_per_row];
+                acc.x += x0.x; acc.y += x0.y; acc.z += x0.z; acc.w += x0.w;
+            }
+        }
+        __syncthreads();
+        sm[threadIdx.x] = acc;
+        __syncthreads();
+        if (slice == 0) {
+            float r[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < slices; ++k) {
+                const float4 x = sm[k * cols_here + lv];
+                r[0] += x.x; r[1] += x.y; r[2] += x.z; r[3] += x.w;
+            }
+            finish_row<4>(r, mode, deg, dst_scale, v);
+            const int64_t elem0 = (int64_t)v * dim + (int64_t)(q0 + lv) * 4;
+            if constexpr (BF16_OUT) {
+                uint2 pk;
+                pk.x = pack_bf16x2(r[0], r[1]);
+                pk.y = pack_bf16x2(r[2], r[3]);
+                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(out) + elem0) = pk;
+            } else {
+                *reinterpret_cast<float4 *>(static_cast<float *>(out) + elem0) = make_float4(r[0], r[1], r[2], r[3]);
+            }
+        }
+    }
+}
+
+template <bool BF16_IN, bool BF16_OUT, int G>
+int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
+    const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
+    dim3 grid((unsigned)((waves + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
+    if (a.n_nodes > 0) {
+        gather_rows_kernel<BF16_IN, BF16_OUT, G><<<grid, 256, 0, st>>>(a);
+        ITB_LAUNCH_CHECK();
+    }
+    return ITB_OK;
+}
+
+template <bool BF16_IN, int G>
+int32_t launch_segments(const GatherArgs &a, hipStream_t st) {
+    dim3 grid((unsigned)((a.n_shadows + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
+    gather_segments_kernel<BF16_IN, G><<<grid, 256, 0, st>>>(a);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
+
+template <bool BF16_IN, bool BF16_OUT>
+int32_t dispatch_rows(int G, const GatherArgs &a, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_rows<BF16_IN, BF16_OUT, 1>(a, st);
+        case 2: return launch_rows<BF16_IN, BF16_OUT, 2>(a, st);
+        case 4: return launch_rows<BF16_IN, BF16_OUT, 4>(a, st);
+        case 8: return launch_rows<BF16_IN, BF16_OUT, 8>(a, st);
+        case 16: return launch_rows<BF16_IN, BF16_OUT, 16>(a, st);
+        case 32: return launch_rows<BF16_IN, BF16_OUT, 32>(a, st);
+        default: return launch_rows<BF16_IN, BF16_OUT, 64>(a, st);
+    }
+}
+
+template <bool BF16_IN>
+int32_t dispatch_segments(int G, const GatherArgs &a, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_segments<BF16_IN, 1>(a, st);
+        case 2: return launch_segments<BF16_IN, 2>(a, st);
+        case 4: return launch_segments<BF16_IN, 4>(a, st);
+        case 8: return launch_segments<BF16_IN, 8>(a, st);
+        case 16: return launch_segments<BF16_IN, 16>(a, st);
+        case 32: return launch_segments<BF16_IN, 32>(a, st);
+        default: return launch_segments<BF16_IN, 64>(a, st);
+    }
+}
+
+}  // namespace
+
+namespace itb {
+int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                        const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, hipStream_t st);
+}
+
+extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                                const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
+                                void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
+                                void *stream) {
+    if (!desc || !workspace_bytes) return ITB_ERR_NULL;
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
+    if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_GAT) return ITB_ERR_DTYPE;
+    if ((desc->dtype_in != ITB_F32 && desc->dtype_in != ITB_BF16) || (desc->dtype_out != ITB_F32 && desc->dtype_out != ITB_BF16))
+        return ITB_ERR_DTYPE;
+    if (desc->dtype_in == ITB_F32 && desc->dtype_out == ITB_BF16) return ITB_ERR_UNSUPPORTED;
+    if (desc->dim <= 0) return ITB_ERR_SIZE;
+    const int elem = desc->dtype_in == ITB_BF16 ? 2 : 4;
+    if ((desc->dim * elem) % 16 != 0) return ITB_ERR_UNSUPPORTED;
+    if (split && (split->threshold <= 0 || split->n_hubs < 0 || split->n_shadows < 0)) return ITB_ERR_SIZE;
+    if (desc->agg == ITB_AGG_GAT)
+        return gat_gather_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
+                               workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+
+    const bool hubs = split && split->n_hubs > 0;
+    Carver cv(workspace);
+    float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
+    if (!workspace) {
+        *workspace_bytes = cv.off;
+        return ITB_OK;
+    }
+    if (*workspace_bytes < cv.off || (cv.off > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u))) return ITB_ERR_WORKSPACE;
+    if (!rowptr || !agg_out || (n_nodes > 0 && !h_src)) return ITB_ERR_NULL;
+    if (desc->agg == ITB_AGG_GCN && (!src_scale || !dst_scale)) return ITB_ERR_NULL;
+    if (hubs && (!split->hub_ids || !split->hub_shadow_off || !split->shadow_begin || !split->shadow_end || !split->shadow_owner))
+        return ITB_ERR_NULL;
+    if (n_nodes == 0) return ITB_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    GatherArgs a{};
+    a.n_nodes = n_nodes;
+    a.rowptr = rowptr;
+    a.col = col;
+    a.h = static_cast<const uint4 *>(h_src);
+    a.src_scale = (desc->agg == ITB_AGG_GCN) ? src_scale : nullptr;
+    a.dst_scale = (desc->agg == ITB_AGG_GCN) ? dst_scale : nullptr;
+    a.out = agg_out;
+    a.threshold = split ? split->threshold : INT64_MAX;
+    a.edge_lo = edge_lo;
+    a.edge_hi = edge_hi;
+    a.row_vecs = desc->dim * elem / 16;
+    a.mode = desc->agg == ITB_AGG_MEAN ? kModeMean : (desc->agg == ITB_AGG_GCN ? kModeScaleDst : kModeSum);
+    int G = 1;
+    while (G < a.row_vecs && G < kWave) G <<= 1;
+    const int ng = kWave / G;
+    a.small_limit = g_small_limit >= 0 ? g_small_limit : 2 * ng;
+
+    const bool bin = desc->dtype_in == ITB_BF16, bout = desc->dtype_out == ITB_BF16;
+    int32_t rc;
+    if (!bin) rc = dispatch_rows<false, false>(G, a, st);
+    else if (bout) rc = dispatch_rows<true, true>(G, a, st);
+    else rc = dispatch_rows<true, false>(G, a, st);
+    if (rc != ITB_OK) return rc;
+
+    if (hubs) {
+        GatherArgs s = a;
+        s.out = part;
+        s.n_shadows = split->n_shadows;
+        s.shadow_begin = split->shadow_begin;
+        s.shadow_end = split->shadow_end;
+        s.shadow_owner = split->shadow_owner;
+        rc = bin ? dispatch_segments<true>(G, s, st) : dispatch_segments<false>(G, s, st);
+        if (rc != ITB_OK) return rc;
+        if (bout)
+            combine_hubs_kernel<true><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
+                                                                                split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
+                                                                                edge_lo, edge_hi, agg_out);
+        else
+            combine_hubs_kernel<false><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
+                                                                                 split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
+                                                                                 edge_lo, edge_hi, agg_out);
+        ITB_LAUNCH_CHECK();
+    }
+    return ITB_OK;
+}
+
+extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
+    if (key == 0) { itb::g_small_limit = value; return ITB_OK; }
+    if (key == 1) { itb::g_gather_unroll = value; return ITB_OK; }
+    return ITB_ERR_UNSUPPORTED;
+}

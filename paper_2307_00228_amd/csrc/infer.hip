@@ -1,0 +1,101 @@
+// infer_full_graph: the layer loop.  Each layer is a gather over every vertex followed by the dense update;
+// states ping-pong between two workspace buffers (the scatter of layer l is the store that layer l+1 reads).
+// Only enqueues work on the caller's stream.
+#include "common.h"
+
+namespace {
+using namespace itb;
+
+__global__ void gcn_scales_kernel(int64_t n, const int64_t *rowptr, const int32_t *deg_out, float *src_scale, float *dst_scale) {
+    for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t din = rowptr[v + 1] - rowptr[v];
+        const int32_t dout = deg_out[v];
+        dst_scale[v] = 1.0f / sqrtf((float)(din > 1 ? din : 1));
+        src_scale[v] = 1.0f / sqrtf((float)(dout > 1 ? dout : 1));
+    }
+}
+
+}  // namespace
+
+extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *deg_out, float *src_scale,
+                                   float *dst_scale, void *stream) {
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
+    if (!rowptr || (n_nodes > 0 && (!deg_out || !src_scale || !dst_scale))) return ITB_ERR_NULL;
+    if (n_nodes == 0) return ITB_OK;
+    int64_t g = (n_nodes + 255) / 256;
+    if (g > 16384) g = 16384;
+    gcn_scales_kernel<<<(unsigned)g, 256, 0, static_cast<hipStream_t>(stream)>>>(n_nodes, rowptr, deg_out, src_scale, dst_scale);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
+
+extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
+                                    const int32_t *deg_out, const itb_split *split, int32_t dtype, int32_t n_layers,
+                                    const itb_layer *layers, const void *x, void *out, int64_t edge_chunk, void *workspace,
+                                    size_t *workspace_bytes, void *stream) {
+    if (!workspace_bytes || !layers) return ITB_ERR_NULL;
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || n_edges < 0 || n_edges >= ((int64_t)1 << 31) || n_layers <= 0 ||
+        edge_chunk < 0)
+        return ITB_ERR_SIZE;
+    if (dtype != ITB_F32 && dtype != ITB_BF16) return ITB_ERR_DTYPE;
+    const size_t elem = dtype == ITB_BF16 ? 2 : 4;
+    int32_t max_d = 0;
+    bool any_gcn = false;
+    size_t gather_ws = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const itb_layer &L = layers[l];
+        if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_GAT) return ITB_ERR_DTYPE;
+        if (L.d_in <= 0 || L.d_out <= 0) return ITB_ERR_SIZE;
+        if (l > 0 && L.d_in != layers[l - 1].d_out) return ITB_ERR_SIZE;
+        if (L.agg == ITB_AGG_GAT) return ITB_ERR_UNSUPPORTED;
+        if (L.d_in > max_d) max_d = L.d_in;
+        if (L.d_out > max_d) max_d = L.d_out;
+        any_gcn = any_gcn || L.agg == ITB_AGG_GCN;
+        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f};
+        size_t need = 0;
+        int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
+                                  &need, nullptr);
+        if (rc != ITB_OK) return rc;
+        if (need > gather_ws) gather_ws = need;
+    }
+    Carver cv(workspace);
+    const size_t state_bytes = (size_t)n_nodes * max_d * elem;
+    char *state0 = cv.take<char>(n_layers > 1 ? state_bytes : 0);
+    char *state1 = cv.take<char>(n_layers > 2 ? state_bytes : 0);
+    char *aggbuf = cv.take<char>(state_bytes);
+    float *src_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
+    float *dst_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
+    char *gws = cv.take<char>(gather_ws);
+    if (!workspace) {
+        *workspace_bytes = cv.off;
+        return ITB_OK;
+    }
+    if (*workspace_bytes < cv.off || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return ITB_ERR_WORKSPACE;
+    if (!rowptr || (n_nodes > 0 && (!x || !out)) || (n_edges > 0 && !col) || (any_gcn && !deg_out)) return ITB_ERR_NULL;
+    if (n_nodes == 0) return ITB_OK;
+
+    if (any_gcn) {
+        int32_t rc = gcn_norm_scales(n_nodes, rowptr, deg_out, src_scale, dst_scale, stream);
+        if (rc != ITB_OK) return rc;
+    }
+    char *state[2] = {state0, state1};
+    const void *cur = x;
+    for (int l = 0; l < n_layers; ++l) {
+        const itb_layer &L = layers[l];
+        void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
+        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f};
+        const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
+        for (int64_t c = 0; c < n_chunks; ++c) {
+            const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
+            const int64_t hi = (c == n_chunks - 1) ? INT64_MAX : (c + 1) * edge_chunk;
+            size_t ws = gather_ws;
+            int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, cur, src_scale, dst_scale, aggbuf, lo, hi, gws, &ws, stream);
+            if (rc != ITB_OK) return rc;
+        }
+        itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
+        int32_t rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr, stream);
+        if (rc != ITB_OK) return rc;
+        cur = dst;
+    }
+    return ITB_OK;
+}

@@ -1,0 +1,93 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+function the header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    lib_path = os.path.join(ROOT, "paper_2307_00228_amd", "libinferturbo_hip.so")
+    if not os.path.exists(lib_path):
+        import __graft_entry__ as g
+        g.build()
+    from paper_2307_00228_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "inferturbo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\bint32_t\s+(\w+)\s*\(", text)
+
+
+def test_header_declares_the_five_entry_points():
+    names = declared_functions()
+    for f in ("build_csr_by_dst", "split_hubs", "gather_layer", "apply_layer", "infer_full_graph"):
+        assert f in names
+
+
+def test_library_exports_every_declared_symbol(B):
+    for f in declared_functions():
+        assert hasattr(B.lib, f), f
+
+
+def test_struct_layouts_match_header(B):
+    assert C.sizeof(B.itb_split) == 8 * 8
+    assert C.sizeof(B.itb_gather_desc) == 6 * 4
+    assert C.sizeof(B.itb_apply_desc) == 5 * 4
+    assert C.sizeof(B.itb_layer) == 6 * 4 + 5 * 8
+
+
+def test_argument_errors_are_reported_on_the_host(B):
+    lib = B.lib
+    need = C.c_size_t(0)
+    # build_csr_by_dst
+    assert lib.build_csr_by_dst(-1, 0, None, None, None, None, None, None, C.byref(need), None) == -2
+    assert lib.build_csr_by_dst(1 << 31, 0, None, None, None, None, None, None, C.byref(need), None) == -2
+    assert lib.build_csr_by_dst(4, 4, None, None, None, None, None, None, None, None) == -1
+    assert lib.build_csr_by_dst(1000, 5000, None, None, None, None, None, None, C.byref(need), None) == 0
+    assert need.value >= 3 * 5000 * 4
+    # split_hubs
+    nh, ns = C.c_int64(0), C.c_int64(0)
+    assert lib.split_hubs(10, None, 0, C.byref(nh), C.byref(ns), None, None, None, None, None, None, C.byref(need), None) == -2
+    assert lib.split_hubs(-1, None, 4, C.byref(nh), C.byref(ns), None, None, None, None, None, None, C.byref(need), None) == -2
+    assert lib.split_hubs(10, None, 4, C.byref(nh), C.byref(ns), None, None, None, None, None, None, C.byref(need), None) == 0
+    # gather_layer
+    d = B.itb_gather_desc(B.AGG_SUM, B.ITB_F32, B.ITB_F32, 64, 1, 0.2)
+    assert lib.gather_layer(None, 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -1
+    assert lib.gather_layer(C.byref(d), -5, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -2
+    bad = B.itb_gather_desc(9, B.ITB_F32, B.ITB_F32, 64, 1, 0.2)
+    assert lib.gather_layer(C.byref(bad), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -4
+    bad = B.itb_gather_desc(B.AGG_SUM, 7, B.ITB_F32, 64, 1, 0.2)
+    assert lib.gather_layer(C.byref(bad), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -4
+    odd = B.itb_gather_desc(B.AGG_SUM, B.ITB_F32, B.ITB_F32, 7, 1, 0.2)        # 28-byte rows
+    assert lib.gather_layer(C.byref(odd), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -5
+    assert lib.gather_layer(C.byref(d), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == 0
+    assert need.value == 0                                                     # no split -> no workspace
+    sp = B.itb_split(16, 2, 9, None, None, None, None, None)
+    assert lib.gather_layer(C.byref(d), 10, None, None, C.byref(sp), None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == 0
+    assert need.value >= 9 * 64 * 4                                            # fp32 partial per segment
+    sp = B.itb_split(0, 2, 9, None, None, None, None, None)
+    assert lib.gather_layer(C.byref(d), 10, None, None, C.byref(sp), None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -2
+    # apply_layer
+    a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
+    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None) == -1
+    a7 = B.itb_apply_desc(B.ITB_F32, 60, 16, B.ACT_RELU, 0)
+    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None) == -5
+    a9 = B.itb_apply_desc(B.ITB_F32, 64, 16, 5, 0)
+    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None) == -4
+    # infer_full_graph
+    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, C.byref(need), None) == -1
+    lay = (B.itb_layer * 2)()
+    lay[0] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_RELU, 1, 0.2, None, None, None, None, None)
+    lay[1] = B.itb_layer(B.AGG_MEAN, 48, 16, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
+    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None) == -2
+    lay[1] = B.itb_layer(B.AGG_MEAN, 32, 16, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
+    assert lib.infer_full_graph(1000, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None) == 0
+    assert need.value >= 2 * 1000 * 64 * 4

@@ -1,0 +1,277 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (needs an MI355X).
+
+Integer results (CSR, hub split) must be bit-exact.  Features: fp32 within max-abs 1e-4
+(for the un-normalised SUM aggregator, whose outputs grow with the in-degree, 1e-4 times
+max(1, largest |oracle value|): fp32 cannot hold 1e-4 absolute on values in the hundreds);
+bf16 storage with fp32 accumulation within |g-o| <= 2e-2 * (|o| + rms(o))."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2307_00228_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+FP32_ATOL = 1e-4
+BF16_RTOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2307_00228_amd import binding
+    return binding
+
+
+def dev_i32(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def check_features(got_st, want64, dtype, what="", magnitude_scaled=False):
+    got = W.as_f32(got_st).astype(np.float64)
+    want64 = np.asarray(want64, dtype=np.float64)
+    assert got.shape == want64.shape, (got.shape, want64.shape)
+    if got.size == 0:
+        return
+    err = np.abs(got - want64)
+    if dtype == W.F32:
+        atol = FP32_ATOL * (max(1.0, np.abs(want64).max()) if magnitude_scaled else 1.0)
+        assert err.max() <= atol, f"{what}: fp32 max abs err {err.max():.3e} (tol {atol:.1e})"
+    else:
+        tol = BF16_RTOL * (np.abs(want64) + np.sqrt(np.mean(want64 ** 2)))
+        bad = err > tol
+        assert not bad.any(), f"{what}: bf16 err {err[bad].max():.3e} at {np.argwhere(bad)[0]} (tol {tol[bad].min():.3e})"
+
+
+# ------------------------------------------------------------------------------------------ CSR build
+CSR_CASES = [
+    ("empty_graph", 0, 0, 0.0), ("nodes_no_edges", 17, 0, 0.0), ("one_node_self_loops", 1, 9, 0.0),
+    ("two_nodes", 2, 5, 0.0), ("tiny", 10, 37, 0.3), ("one_tile_ragged", 1000, 4095, 0.2),
+    ("tile_plus_one", 300, 4097, 0.5), ("several_tiles", 70000, 300001, 0.1), ("all_to_one", 5000, 50000, 1.0),
+    ("wide_ids_3_passes", 1 << 17, 200000, 0.05), ("sparse_rows", 1_000_000, 4000, 0.0),
+]
+
+
+@pytest.mark.parametrize("name,n,e,hub", CSR_CASES, ids=[c[0] for c in CSR_CASES])
+def test_build_csr_bit_exact(B, name, n, e, hub):
+    src, dst, _ = W.random_small_graph(n % 997 + e % 991, n, e, 1, W.F32, hub)
+    if n == 0:
+        src, dst = src[:0], dst[:0]
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    assert np.array_equal(rowptr.cpu().numpy(), r), "rowptr"
+    assert np.array_equal(col.cpu().numpy(), c), "col (stable order)"
+    assert np.array_equal(deg_out.cpu().numpy(), d), "deg_out"
+
+
+def test_build_csr_range_error(B):
+    src = np.array([0, 1, 2, 3], np.int32)
+    for bad_dst in (np.array([1, 4, 0, 0], np.int32), np.array([1, -1, 0, 0], np.int32)):
+        with pytest.raises(B.InferTurboError) as ei:
+            B.build_csr_by_dst(4, dev_i32(src), dev_i32(bad_dst))
+        assert ei.value.code == -3
+    with pytest.raises(B.InferTurboError) as ei:
+        B.build_csr_by_dst(4, dev_i32(np.array([7, 1, 2, 3], np.int32)), dev_i32(src))
+    assert ei.value.code == -3
+
+
+@pytest.mark.parametrize("name,scale", [("tiny_powerlaw", 1.0), ("hub_heavy", 0.01), ("attention", 0.01),
+                                        ("huge_share", 0.0005), ("medium_uniform", 0.05)])
+def test_build_csr_workloads(B, name, scale):
+    w = W.make(name, scale, features=False)
+    rowptr, col, deg_out = B.build_csr_by_dst(w.n_nodes, dev_i32(w.src), dev_i32(w.dst))
+    r, c, d = oracle.build_csr(w.n_nodes, w.src, w.dst)
+    assert np.array_equal(rowptr.cpu().numpy(), r)
+    assert np.array_equal(col.cpu().numpy(), c)
+    assert np.array_equal(deg_out.cpu().numpy(), d)
+
+
+# ------------------------------------------------------------------------------------------ hub split
+def assert_split_equal(sp, want):
+    assert sp.n_hubs == want["n_hubs"] and sp.n_shadows == want["n_shadows"]
+    assert np.array_equal(sp.hub_ids.cpu().numpy(), want["hub_ids"])
+    assert np.array_equal(sp.hub_shadow_off.cpu().numpy(), want["hub_shadow_off"])
+    assert np.array_equal(sp.shadow_begin.cpu().numpy(), want["shadow_begin"])
+    assert np.array_equal(sp.shadow_end.cpu().numpy(), want["shadow_end"])
+    assert np.array_equal(sp.shadow_owner.cpu().numpy(), want["shadow_owner"])
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 7, 64, 999, 1000, 1001, 10 ** 9])
+def test_split_hubs_bit_exact(B, T):
+    import torch
+    n, e = 5000, 60000
+    src, dst, _ = W.random_small_graph(7, n, e, 1, W.F32, 0.3)
+    dst[:1000] = 4999                                   # in-degree of the last vertex >= 1000
+    r, c, _ = oracle.build_csr(n, src, dst)
+    sp = B.split_hubs(torch.from_numpy(r).cuda(), T)
+    assert_split_equal(sp, oracle.split_hubs(r, T))
+
+
+def test_split_hubs_threshold_boundary_and_empty(B):
+    import torch
+    src = np.arange(1, 9, dtype=np.int32)
+    r, _, _ = oracle.build_csr(9, src, np.zeros(8, np.int32))
+    rp = torch.from_numpy(r).cuda()
+    assert B.split_hubs(rp, 8).n_hubs == 0              # in-degree == threshold is not a hub
+    s7 = B.split_hubs(rp, 7)
+    assert s7.n_hubs == 1 and s7.n_shadows == 2
+    assert_split_equal(s7, oracle.split_hubs(r, 7))
+    empty = B.split_hubs(torch.zeros(1, dtype=torch.int64, device="cuda"), 4)
+    assert empty.n_hubs == 0 and empty.n_shadows == 0 and empty.hub_shadow_off.cpu().tolist() == [0]
+
+
+@pytest.mark.parametrize("name,scale", [("hub_heavy", 0.01), ("attention", 0.01), ("huge_share", 0.0005)])
+def test_split_hubs_workloads(B, name, scale):
+    import torch
+    w = W.make(name, scale, features=False)
+    r, _, _ = oracle.build_csr(w.n_nodes, w.src, w.dst)
+    sp = B.split_hubs(torch.from_numpy(r).cuda(), w.threshold)
+    want = oracle.split_hubs(r, w.threshold)
+    assert want["n_hubs"] > 0
+    assert_split_equal(sp, want)
+
+
+# ------------------------------------------------------------------------------------------ gather
+def run_gather(B, kind, n, src, dst, x_st, dtype, T=None, out_f32=False, chunk=None):
+    import torch
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    split = B.split_hubs(rp, T) if T is not None else None
+    h = B.to_device(x_st)
+    ss = sd = None
+    if kind == W.AGG_GCN:
+        ss, sd = B.gcn_norm_scales(rp, torch.from_numpy(d).cuda())
+    out_dtype = torch.float32 if out_f32 else None
+    if chunk is None:
+        out = B.gather_layer(kind, rp, cl, h, split, ss, sd, out_dtype=out_dtype)
+    else:
+        out = torch.full((n, x_st.shape[1]), float("nan"), dtype=out_dtype or h.dtype, device="cuda")
+        e = len(src)
+        lo = 0
+        while True:
+            hi = lo + chunk
+            last = hi >= e
+            B.gather_layer(kind, rp, cl, h, split, ss, sd, out_dtype=out_dtype, edge_lo=lo,
+                           edge_hi=B.INT64_MAX if last else hi, out=out)
+            if last:
+                break
+            lo = hi
+    want = oracle.gather(kind, r, c, x_st, deg_out=d)
+    return B.to_numpy(out), want, (r, c, d)
+
+
+GATHER_DIMS = {W.F32: [4, 16, 64, 100, 128, 260], W.BF16: [8, 64, 128, 256, 520]}
+
+
+@pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN])
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_gather_dims_no_split(B, kind, dtype):
+    for dim in GATHER_DIMS[dtype]:
+        n, e = 3000, 40000
+        src, dst, x = W.random_small_graph(dim, n, e, dim, dtype, 0.15)
+        got, want, _ = run_gather(B, kind, n, src, dst, x, dtype)
+        check_features(got, want, dtype, f"dim={dim}", magnitude_scaled=kind == W.AGG_SUM)
+
+
+@pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN])
+@pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.F32, 128), (W.BF16, 64), (W.BF16, 128), (W.BF16, 256)])
+@pytest.mark.parametrize("T", [1, 5, 64, 1000])
+def test_gather_with_hub_split(B, kind, dtype, dim, T):
+    n, e = 2000, 30000
+    src, dst, x = W.random_small_graph(T + dim, n, e, dim, dtype, 0.35)
+    got, want, _ = run_gather(B, kind, n, src, dst, x, dtype, T=T)
+    check_features(got, want, dtype, f"T={T}", magnitude_scaled=kind == W.AGG_SUM)
+
+
+def test_gather_edge_cases(B):
+    # no edges at all; a single vertex; isolated vertices next to a hub; in-degree == T and T+1
+    for n, e, hub in [(5, 0, 0.0), (1, 0, 0.0), (1, 300, 0.0), (64, 64, 1.0), (65, 4000, 0.9), (129, 1, 0.0)]:
+        src, dst, x = W.random_small_graph(n + e, n, e, 64, W.F32, hub)
+        for T in (None, 16):
+            for kind in (W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN):
+                got, want, _ = run_gather(B, kind, n, src, dst, x, W.F32, T=T)
+                check_features(got, want, W.F32, f"n={n} e={e} T={T} kind={kind}", magnitude_scaled=kind == W.AGG_SUM)
+    src = np.concatenate([np.arange(16), np.arange(17)]).astype(np.int32)
+    dst = np.concatenate([np.zeros(16), np.ones(17)]).astype(np.int32)
+    _, _, x = W.random_small_graph(3, 20, 0, 32, W.BF16)
+    got, want, _ = run_gather(B, W.AGG_MEAN, 20, src, dst, x, W.BF16, T=16)
+    check_features(got, want, W.BF16)
+    assert not W.as_f32(got)[2:].any()                  # isolated vertices aggregate to exactly zero
+
+
+def test_gather_bf16_in_fp32_out(B):
+    n, e, dim = 4000, 50000, 128
+    src, dst, x = W.random_small_graph(11, n, e, dim, W.BF16, 0.3)
+    got, want, _ = run_gather(B, W.AGG_MEAN, n, src, dst, x, W.BF16, T=100, out_f32=True)
+    assert got.dtype == np.float32
+    assert np.abs(got.astype(np.float64) - want).max() <= 1e-4   # fp32 accumulation of exact bf16 inputs
+
+
+def test_gather_chunked_equals_unchunked_and_is_deterministic(B):
+    n, e, dim = 6000, 90000, 64
+    src, dst, x = W.random_small_graph(13, n, e, dim, W.F32, 0.3)
+    full, want, _ = run_gather(B, W.AGG_GCN, n, src, dst, x, W.F32, T=50)
+    again, _, _ = run_gather(B, W.AGG_GCN, n, src, dst, x, W.F32, T=50)
+    assert np.array_equal(full, again)                  # bitwise run-to-run
+    chunked, _, _ = run_gather(B, W.AGG_GCN, n, src, dst, x, W.F32, T=50, chunk=7001)
+    assert np.array_equal(full, chunked)                # every row produced exactly once, same order of sums
+    check_features(full, want, W.F32)
+
+
+# ------------------------------------------------------------------------------------------ apply
+APPLY_CASES = [(W.F32, 64, 64), (W.F32, 64, 16), (W.F32, 128, 128), (W.F32, 128, 64), (W.F32, 8, 1), (W.F32, 256, 256),
+               (W.F32, 40, 100), (W.BF16, 128, 128), (W.BF16, 64, 64), (W.BF16, 64, 32), (W.BF16, 256, 256),
+               (W.BF16, 16, 7), (W.BF16, 48, 200)]
+
+
+@pytest.mark.parametrize("dtype,d_in,d_out", APPLY_CASES)
+@pytest.mark.parametrize("n", [1, 31, 257, 5000])
+def test_apply_layer(B, dtype, d_in, d_out, n):
+    rng = np.random.default_rng(d_in * 1000 + d_out + n)
+    h = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    a = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    lay = W.dense_layers(rng, W.AGG_MEAN, (d_in, d_out, d_out), dtype, bias_random=True)[0]
+    for act, with_self, with_bias in [(W.ACT_RELU, True, True), (W.ACT_NONE, False, False)]:
+        out = B.apply_layer(B.to_device(h) if with_self else None, B.to_device(a),
+                            B.to_device(lay.w_self) if with_self else None, B.to_device(lay.w_nbr),
+                            B.to_device(lay.bias) if with_bias else None, act)
+        want = oracle.apply(h if with_self else None, a, lay.w_self if with_self else None, lay.w_nbr,
+                            lay.bias if with_bias else None, act)
+        check_features(B.to_numpy(out), want, dtype, f"act={act} self={with_self}")
+
+
+# ------------------------------------------------------------------------------------------ whole path
+@pytest.mark.parametrize("name,scale", [("tiny_powerlaw", 1.0), ("medium_uniform", 0.02), ("hub_heavy", 0.005),
+                                        ("hub_heavy_uniform_control", 0.005), ("huge_share", 0.0003)])
+def test_infer_full_graph_matches_oracle(B, name, scale):
+    import torch
+    w = W.make(name, scale, bias_random=True)
+    rowptr, col, deg_out = B.build_csr_by_dst(w.n_nodes, dev_i32(w.src), dev_i32(w.dst))
+    split = B.split_hubs(rowptr, w.threshold) if w.threshold < W.NO_SPLIT else None
+    layers = B.device_layers(w.layers)
+    x = B.to_device(w.x)
+    out = B.infer_full_graph(rowptr, col, deg_out, split, layers, x)
+    r, c, d = oracle.build_csr(w.n_nodes, w.src, w.dst)
+    assert np.array_equal(rowptr.cpu().numpy(), r) and np.array_equal(col.cpu().numpy(), c)
+    if split is not None and name == "hub_heavy":
+        assert split.n_hubs >= 16
+    want = oracle.infer_full_graph(r, c, d, w.x, w.layers, w.dtype)
+    check_features(B.to_numpy(out), W.as_f32(want), w.dtype, name)
+    # bitwise reproducible, also through the chunked launch path
+    out2 = B.infer_full_graph(rowptr, col, deg_out, split, layers, x, edge_chunk=max(1, w.n_edges // 5))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16 if w.dtype == W.BF16 else torch.int32),
+                       out2.view(torch.int16 if w.dtype == W.BF16 else torch.int32))
+
+
+def test_infer_split_equals_unsplit(B):
+    """Shadow split + partial-gather leaves the result unchanged (within fp32 reassociation)."""
+    w = W.make("tiny_powerlaw", 1.0)
+    rowptr, col, deg_out = B.build_csr_by_dst(w.n_nodes, dev_i32(w.src), dev_i32(w.dst))
+    layers, x = B.device_layers(w.layers), B.to_device(w.x)
+    whole = B.infer_full_graph(rowptr, col, deg_out, None, layers, x)
+    for T in (64, 4096):
+        parts = B.infer_full_graph(rowptr, col, deg_out, B.split_hubs(rowptr, T), layers, x)
+        assert (whole - parts).abs().max().item() <= 1e-5
