@@ -228,6 +228,17 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
                          const void *x, void *out, int64_t edge_chunk,
                          void *workspace, size_t *workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------
+ * Measurement aids (not part of the method).
+ * itb_copy_bytes: plain device copy of n_bytes (multiple of 16) with one
+ * 16-byte load and store per lane; the known-size kernel that hardware byte
+ * counters are scaled against.
+ * itb_set_tuning: key 0 = in-degree up to which gather processes one row per
+ * lane group instead of per wavefront (-1 = built-in choice).
+ * ------------------------------------------------------------------------- */
+int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream);
+int32_t itb_set_tuning(int32_t key, int32_t value);
+
 #ifdef __cplusplus
 }
 #endif

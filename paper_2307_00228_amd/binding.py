@@ -70,7 +70,8 @@ def _load():
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
                                      vp, vp, i64, vp, szp, vp]
     lib.itb_set_tuning.argtypes = [i32, i32]
-    for f in ("build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
+    lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
+    for f in ("itb_copy_bytes", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning"):
         getattr(lib, f).restype = i32
     return lib
@@ -105,6 +106,12 @@ def dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.bfloat16:
         return ITB_BF16
     raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def copy_bytes(src: torch.Tensor, dst: torch.Tensor):
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check("itb_copy_bytes", lib.itb_copy_bytes(_ptr(src), _ptr(dst), n, _stream()))
 
 
 def set_tuning(key: int, value: int):

@@ -79,6 +79,27 @@ __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &
 }
 
 template <bool BF16, int NT>
+__device__ __forceinline__ void mfma_chunk(v16f (&acc)[NT], const uint4 &av, const uint4 (&bv)[NT]) {
+    if constexpr (BF16) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv[nt]), acc[nt], 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(bv[nt].x), acc[nt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(bv[nt].y), acc[nt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(bv[nt].z), acc[nt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(bv[nt].w), acc[nt], 0, 0, 0);
+    }
+}
+
+// PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
+// A fragments are double-buffered by group and the request stream runs on across row tiles (the first
+// fragments of the next tile are requested while the current tile finishes and stores).
+template <bool BF16, int NT, int PF>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     extern __shared__ uint4 wlds[];
     constexpr int BN = 32 * NT;
@@ -92,72 +113,133 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     const int i = lane & 31;
     const int kh = lane >> 5;
     const int chunks = a.d_in / KC;
-    const int row_vecs = a.d_in * (BF16 ? 2 : 4) / 16;  // == 2 * chunks
-    const int phases = a.h_self ? 2 : 1;
+    const int chunks_self = a.h_self ? chunks : 0;
+    const int total = chunks_self + chunks;
+    const int64_t row_vecs = 2 * chunks;
+    const uint4 *wbase = wlds + kh * BN + i;
 
-    for (int64_t tile = blockIdx.x; tile < a.n_row_tiles; tile += gridDim.x) {
-        const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
-        if (m0 >= a.n) continue;
-        int64_t row = m0 + i;
-        if (row >= a.n) row = a.n - 1;  // clamped rows are computed but never stored
+    auto tile_rowoff = [&](int64_t tile) -> int64_t {
+        int64_t r = tile * kRowsPerBlockTile + (int64_t)w * 32 + i;
+        r = r < a.n ? r : a.n - 1;  // clamped rows are computed but never stored
+        return r * row_vecs + kh;
+    };
+    // 16-byte fragment c of the concatenated [h_self | agg] row at vector offset `rowoff`
+    auto frag_ptr = [&](int64_t rowoff, int c) -> const uint4 * {
+        const bool in_self = c < chunks_self;
+        const uint4 *base = in_self ? a.h_self : a.agg;
+        const int ci = in_self ? c : c - chunks_self;
+        return base + rowoff + 2 * ci;
+    };
+
+    float bias_v[NT];  // this lane's bias per column tile, fetched once
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int col = col0 + nt * 32 + i;
+        bias_v[nt] = (a.bias && col < a.d_out) ? a.bias[col] : 0.f;
+    }
+
+    int64_t tile = blockIdx.x;
+    if (tile >= a.n_row_tiles) return;
+    int64_t rowoff = tile_rowoff(tile);
+    uint4 cur[PF];
+#pragma unroll
+    for (int p = 0; p < PF; ++p) cur[p] = *frag_ptr(rowoff, p);
+    uint4 bcur[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) bcur[nt] = wbase[nt * 32];
+
+    for (; tile < a.n_row_tiles; tile += gridDim.x) {
+        const int64_t next_tile = tile + gridDim.x;
+        const int64_t rowoff_next = next_tile < a.n_row_tiles ? tile_rowoff(next_tile) : rowoff;
         v16f acc[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
 
-        for (int phase = 0; phase < phases; ++phase) {
-            const uint4 *arow = ((phases == 2 && phase == 0) ? a.h_self : a.agg) + row * row_vecs + kh;
-            const uint4 *wp = wlds + (int64_t)phase * chunks * 2 * BN + kh * BN + i;
-#pragma unroll 4
-            for (int kc = 0; kc < chunks; ++kc) {
-                const uint4 av = arow[kc * 2];
+        for (int c0 = 0; c0 < total; c0 += PF) {
+            // Double-buffered A: the PF fragments of the NEXT k-group (running on into the next row tile) are
+            // requested first and are only touched a whole group of MFMAs later.
+            uint4 nxt[PF];
+            {
+                const int s0 = c0 + PF;
+                const bool wrap = s0 >= total;  // PF divides total: a group never straddles two tiles
+                const int64_t ro = wrap ? rowoff_next : rowoff;
+                const int sb = wrap ? s0 - total : s0;
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const uint4 bv = wp[kc * 2 * BN + nt * 32];
+                for (int p = 0; p < PF; ++p) nxt[p] = *frag_ptr(ro, sb + p);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                const int c = c0 + p;
+                const int cn = (c + 1 == total) ? 0 : c + 1;
+                uint4 bnext[NT];  // B fragments of the next chunk, read from LDS under the current MFMAs
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) bnext[nt] = wbase[(int64_t)cn * 2 * BN + nt * 32];
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_chunk<BF16, NT>(acc, cur[p], bcur);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) bcur[nt] = bnext[nt];
+            }
+#pragma unroll
+            for (int p = 0; p < PF; ++p) cur[p] = nxt[p];
+        }
+
+        // Epilogue.  Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of the tile.
+        const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
+        const bool full = (m0 + 32 <= a.n) && (col0 + BN <= a.d_out);
+        if (full) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int col = col0 + nt * 32 + i;
+                const float b = bias_v[nt];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
+                    float y = acc[nt][r] + b;
+                    if (a.act == ITB_ACT_RELU) y = fmaxf(y, 0.f);
                     if constexpr (BF16) {
-                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bv),
-                                                                          acc[nt], 0, 0, 0);
+                        static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
                     } else {
-                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(bv.x), acc[nt], 0, 0, 0);
-                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(bv.y), acc[nt], 0, 0, 0);
-                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(bv.z), acc[nt], 0, 0, 0);
-                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(bv.w), acc[nt], 0, 0, 0);
+                        static_cast<float *>(a.out)[orow * a.d_out + col] = y;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int col = col0 + nt * 32 + i;
+                const bool col_ok = col < a.d_out;
+                const float b = bias_v[nt];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
+                    float y = acc[nt][r] + b;
+                    if (a.act == ITB_ACT_RELU) y = fmaxf(y, 0.f);
+                    if (col_ok && orow < a.n) {
+                        if constexpr (BF16) {
+                            static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
+                        } else {
+                            static_cast<float *>(a.out)[orow * a.d_out + col] = y;
+                        }
                     }
                 }
             }
         }
-
-        // Epilogue.  Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of the tile.
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int col = col0 + nt * 32 + i;
-            if (col >= a.d_out) continue;
-            const float b = a.bias ? a.bias[col] : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
-                if (orow >= a.n) continue;
-                float y = acc[nt][r] + b;
-                if (a.act == ITB_ACT_RELU) y = y > 0.f ? y : 0.f;
-                if constexpr (BF16) {
-                    static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
-                } else {
-                    static_cast<float *>(a.out)[orow * a.d_out + col] = y;
-                }
-            }
-        }
+        rowoff = rowoff_next;
     }
 }
 
-template <bool BF16, int NT>
-int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
+template <bool BF16, int NT, int PF>
+int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
     const size_t lds = (size_t)k_total * BN * (BF16 ? 2 : 4);
     static bool attr_set = false;
     if (!attr_set) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxWeightLds));
         attr_set = true;
     }
@@ -169,9 +251,18 @@ int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_kernel<BF16, NT><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_kernel<BF16, NT, PF><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
+}
+
+template <bool BF16, int NT>
+int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    const int total = (a.d_in / (BF16 ? 16 : 8)) * (a.h_self ? 2 : 1);
+    if (total % 8 == 0 && NT < 8) return launch_apply_pf<BF16, NT, 8>(a, n_cus, st);
+    if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4>(a, n_cus, st);
+    if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2>(a, n_cus, st);
+    return launch_apply_pf<BF16, NT, 1>(a, n_cus, st);
 }
 
 template <bool BF16>

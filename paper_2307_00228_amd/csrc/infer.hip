@@ -15,7 +15,21 @@ __global__ void gcn_scales_kernel(int64_t n, const int64_t *rowptr, const int32_
     }
 }
 
+// Plain 16-byte-per-lane copy: the known-size reference against which hardware byte counters are scaled.
+__global__ void copy_kernel(const uint4 *src, uint4 *dst, int64_t n_vec) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 }  // namespace
+
+extern "C" int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream) {
+    if (n_bytes < 0 || (n_bytes & 15)) return ITB_ERR_SIZE;
+    if (n_bytes > 0 && (!src || !dst)) return ITB_ERR_NULL;
+    if (n_bytes == 0) return ITB_OK;
+    copy_kernel<<<8192, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n_bytes / 16);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
 
 extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *deg_out, float *src_scale,
                                    float *dst_scale, void *stream) {
