@@ -149,7 +149,10 @@ int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *d
  * heads divides dim, src_scale = s_src [n_nodes x heads], dst_scale = s_dst
  * [n_nodes x heads] (fp32).  For vertex v and head k, over its in-edges plus an
  * implicit self edge: e = LeakyReLU_slope(s_src[u,k] + s_dst[v,k]),
- * alpha = softmax(e), agg[v,k,:] = sum alpha_u z[u,k,:].
+ * alpha = softmax(e), agg[v,k,:] = sum alpha_u z[u,k,:]; then bias and the
+ * activation of the layer (the update that follows GAT's reduce) are applied
+ * before the row is stored.  dim/heads must be a multiple of the 16-byte
+ * vector (4 fp32 / 8 bf16 elements); dtype_out == dtype_in.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t agg;        /* ITB_AGG_* */
@@ -158,6 +161,8 @@ typedef struct {
     int32_t dim;
     int32_t heads;      /* GAT only, else 1 */
     float leaky_slope;  /* GAT only */
+    int32_t act;        /* GAT only: activation applied after the bias; else ITB_ACT_NONE */
+    const float *bias;  /* GAT only: [dim] fp32 added to the reduced row, or NULL; else NULL */
 } itb_gather_desc;
 
 int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,

@@ -40,7 +40,7 @@ class itb_split(C.Structure):
 
 class itb_gather_desc(C.Structure):
     _fields_ = [("agg", C.c_int32), ("dtype_in", C.c_int32), ("dtype_out", C.c_int32), ("dim", C.c_int32),
-                ("heads", C.c_int32), ("leaky_slope", C.c_float)]
+                ("heads", C.c_int32), ("leaky_slope", C.c_float), ("act", C.c_int32), ("bias", C.c_void_p)]
 
 
 class itb_apply_desc(C.Structure):
@@ -187,12 +187,14 @@ def gcn_norm_scales(rowptr: torch.Tensor, deg_out: torch.Tensor):
 
 def gather_layer(agg: int, rowptr, col, h, split: Optional[Split] = None, src_scale=None, dst_scale=None,
                  out_dtype=None, heads: int = 1, leaky_slope: float = 0.2, edge_lo: int = 0, edge_hi: int = INT64_MAX,
-                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 act: int = ACT_NONE, bias: Optional[torch.Tensor] = None):
     n, dim = h.shape
     out_dtype = out_dtype or h.dtype
     if out is None:
         out = torch.empty((n, dim), dtype=out_dtype, device="cuda")
-    desc = itb_gather_desc(agg, dtype_code(h), dtype_code(out), dim, heads, leaky_slope)
+    desc = itb_gather_desc(agg, dtype_code(h), dtype_code(out), dim, heads, leaky_slope, act,
+                           bias.data_ptr() if bias is not None else None)
     sp = split.c_struct() if split is not None else None
     spp = C.byref(sp) if sp is not None else None
     need = C.c_size_t(0)

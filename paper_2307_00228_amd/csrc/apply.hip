@@ -34,6 +34,12 @@ struct ApplyArgs {
     int32_t d_in, d_out;
     int32_t act;
     int64_t n_row_tiles;
+    // attention-score epilogue (GAT projection): s[v,k] = sum_d att[k,d] * y[v,k,d] from the fp32 accumulators
+    int32_t heads;         // 0 = none
+    const float *att_src;  // [heads x d_out/heads]
+    const float *att_dst;
+    float *s_src;          // [n x heads]
+    float *s_dst;
 };
 
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
@@ -94,6 +100,22 @@ __device__ __forceinline__ void mfma_chunk(v16f (&acc)[NT], const uint4 &av, con
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(bv[nt].w), acc[nt], 0, 0, 0);
     }
+}
+
+// Sum v[0..15] over the 32 lanes that share a k-half: a halving butterfly (8+4+2+1 exchanges) followed by one
+// pair exchange; afterwards lanes i and i^1 both hold the total of accumulator register r = i >> 1.
+__device__ __forceinline__ float reduce_rows_over_columns(float (&v)[16], int i) {
+#pragma unroll
+    for (int half = 8, m = 16; half >= 1; half >>= 1, m >>= 1) {
+        const bool upper = (i & m) != 0;
+#pragma unroll
+        for (int j = 0; j < half; ++j) {
+            const float send = upper ? v[j] : v[j + half];
+            const float keep = upper ? v[j + half] : v[j];
+            v[j] = keep + __shfl_xor(send, m, kWave);
+        }
+    }
+    return v[0] + __shfl_xor(v[0], 1, kWave);
 }
 
 // PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
@@ -228,6 +250,37 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                 }
             }
         }
+        if (a.heads > 0) {
+            // every head's columns lie inside this block's column panel (checked on the host)
+            const int dh = a.d_out / a.heads;
+            const int tiles_per_head = dh / 32;
+            const int head0 = col0 / dh;
+            for (int hd = 0; hd < BN / dh && head0 + hd < a.heads; ++hd) {
+                float ps[16], pd[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ps[r] = pd[r] = 0.f;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    if (nt / tiles_per_head != hd) continue;
+                    const int d = (nt % tiles_per_head) * 32 + i;
+                    const float as = a.att_src[(head0 + hd) * dh + d];
+                    const float ad = a.att_dst[(head0 + hd) * dh + d];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        ps[r] = fmaf(as, acc[nt][r], ps[r]);
+                        pd[r] = fmaf(ad, acc[nt][r], pd[r]);
+                    }
+                }
+                const float ts = reduce_rows_over_columns(ps, i);
+                const float td = reduce_rows_over_columns(pd, i);
+                const int r = i >> 1;
+                const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
+                if ((i & 1) == 0 && orow < a.n) {
+                    a.s_src[orow * a.heads + head0 + hd] = ts;
+                    a.s_dst[orow * a.heads + head0 + hd] = td;
+                }
+            }
+        }
         rowoff = rowoff_next;
     }
 }
@@ -272,6 +325,7 @@ int32_t dispatch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     int nt = 8;
     while (nt > 1 && (per_tile * nt > kMaxWeightLds || 32 * (nt / 2) >= a.d_out)) nt /= 2;
     if (per_tile * nt > kMaxWeightLds) return ITB_ERR_UNSUPPORTED;
+    if (a.heads > 0 && (32 * nt) % (a.d_out / a.heads) != 0) return ITB_ERR_UNSUPPORTED;  // a head must not straddle panels
     switch (nt) {
         case 8: return launch_apply<BF16, 8>(a, n_cus, st);
         case 4: return launch_apply<BF16, 4>(a, n_cus, st);
@@ -303,7 +357,12 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if (desc->d_in <= 0 || desc->d_out <= 0) return ITB_ERR_SIZE;
     const int kc = desc->dtype == ITB_BF16 ? 16 : 8;
     if (desc->d_in % kc != 0 || desc->d_in > 512 || desc->d_out > 256) return ITB_ERR_UNSUPPORTED;
-    if (desc->heads != 0 || att_src || att_dst || s_src || s_dst) return ITB_ERR_UNSUPPORTED;
+    if (desc->heads < 0) return ITB_ERR_SIZE;
+    if (desc->heads == 0 && (att_src || att_dst || s_src || s_dst)) return ITB_ERR_SIZE;
+    if (desc->heads > 0) {
+        if (!att_src || !att_dst || !s_src || !s_dst) return ITB_ERR_NULL;
+        if (desc->d_out % desc->heads != 0 || (desc->d_out / desc->heads) % 32 != 0) return ITB_ERR_UNSUPPORTED;
+    }
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
     if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;
@@ -320,6 +379,11 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     a.d_out = desc->d_out;
     a.act = desc->act;
     a.n_row_tiles = (n_nodes + kRowsPerBlockTile - 1) / kRowsPerBlockTile;
+    a.heads = desc->heads;
+    a.att_src = att_src;
+    a.att_dst = att_dst;
+    a.s_src = s_src;
+    a.s_dst = s_dst;
     hipStream_t st = static_cast<hipStream_t>(stream);
     return desc->dtype == ITB_BF16 ? dispatch_apply<true>(a, cached_cu_count(), st)
                                    : dispatch_apply<false>(a, cached_cu_count(), st);

@@ -394,6 +394,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         return gat_gather_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
                                workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 
+    if (desc->bias || desc->act != ITB_ACT_NONE) return ITB_ERR_UNSUPPORTED;  // epilogue exists for the GAT reduce only
     const bool hubs = split && split->n_hubs > 0;
     Carver cv(workspace);
     float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);

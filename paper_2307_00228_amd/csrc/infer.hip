@@ -55,17 +55,19 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     const size_t elem = dtype == ITB_BF16 ? 2 : 4;
     int32_t max_d = 0;
     bool any_gcn = false;
+    int32_t max_heads = 0;
     size_t gather_ws = 0;
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_GAT) return ITB_ERR_DTYPE;
         if (L.d_in <= 0 || L.d_out <= 0) return ITB_ERR_SIZE;
         if (l > 0 && L.d_in != layers[l - 1].d_out) return ITB_ERR_SIZE;
-        if (L.agg == ITB_AGG_GAT) return ITB_ERR_UNSUPPORTED;
         if (L.d_in > max_d) max_d = L.d_in;
         if (L.d_out > max_d) max_d = L.d_out;
         any_gcn = any_gcn || L.agg == ITB_AGG_GCN;
-        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f};
+        const bool gat = L.agg == ITB_AGG_GAT;
+        if (gat && L.heads > max_heads) max_heads = L.heads;
+        itb_gather_desc gd{L.agg, dtype, dtype, gat ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr};
         size_t need = 0;
         int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
                                   &need, nullptr);
@@ -79,6 +81,8 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     char *aggbuf = cv.take<char>(state_bytes);
     float *src_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *dst_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
+    float *att_s_src = cv.take<float>((size_t)n_nodes * max_heads);
+    float *att_s_dst = cv.take<float>((size_t)n_nodes * max_heads);
     char *gws = cv.take<char>(gather_ws);
     if (!workspace) {
         *workspace_bytes = cv.off;
@@ -97,18 +101,37 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
-        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f};
+        const bool gat = L.agg == ITB_AGG_GAT;
+        const void *gather_src = cur;
+        const float *gs = src_scale, *gd_scale = dst_scale;
+        void *gather_out = aggbuf;
+        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr};
+        if (gat) {
+            // project first (z and the per-head scores), then the attention reduce writes the new state directly
+            if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
+            itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, L.heads};
+            int32_t rc = apply_layer(&pd, n_nodes, nullptr, cur, nullptr, L.w_nbr, nullptr, aggbuf, L.att_src, L.att_dst,
+                                     att_s_src, att_s_dst, stream);
+            if (rc != ITB_OK) return rc;
+            gather_src = aggbuf;
+            gs = att_s_src;
+            gd_scale = att_s_dst;
+            gather_out = dst;
+            gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias};
+        }
         const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
         for (int64_t c = 0; c < n_chunks; ++c) {
             const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
             const int64_t hi = (c == n_chunks - 1) ? INT64_MAX : (c + 1) * edge_chunk;
             size_t ws = gather_ws;
-            int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, cur, src_scale, dst_scale, aggbuf, lo, hi, gws, &ws, stream);
+            int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws, stream);
             if (rc != ITB_OK) return rc;
         }
-        itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-        int32_t rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr, stream);
-        if (rc != ITB_OK) return rc;
+        if (!gat) {
+            itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
+            int32_t rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr, stream);
+            if (rc != ITB_OK) return rc;
+        }
         cur = dst;
     }
     return ITB_OK;

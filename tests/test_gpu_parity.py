@@ -242,9 +242,68 @@ def test_apply_layer(B, dtype, d_in, d_out, n):
         check_features(B.to_numpy(out), want, dtype, f"act={act} self={with_self}")
 
 
+# ------------------------------------------------------------------------------------------ GAT
+@pytest.mark.parametrize("dtype,heads,dh", [(W.F32, 4, 16), (W.F32, 1, 64), (W.BF16, 4, 64), (W.BF16, 2, 8), (W.BF16, 8, 32)])
+@pytest.mark.parametrize("T", [None, 7, 300])
+def test_gat_gather(B, dtype, heads, dh, T):
+    import torch
+    n, e, dim = 2500, 36000, heads * dh
+    src, dst, z = W.random_small_graph(heads * 100 + dh, n, e, dim, dtype, 0.3)
+    dst[dst == 5] = 6                                   # vertex 5 is isolated: attends to itself only
+    rng = np.random.default_rng(dim)
+    s_src = (rng.standard_normal((n, heads)) * 2).astype(np.float32)
+    s_dst = (rng.standard_normal((n, heads)) * 2).astype(np.float32)
+    bias = rng.uniform(-0.5, 0.5, dim).astype(np.float32)
+    r, c, _ = oracle.build_csr(n, src, dst)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    split = B.split_hubs(rp, T) if T is not None else None
+    for act, b in ((W.ACT_NONE, None), (W.ACT_RELU, bias)):
+        out = B.gather_layer(W.AGG_GAT, rp, cl, B.to_device(z), split, torch.from_numpy(s_src).cuda(),
+                             torch.from_numpy(s_dst).cuda(), heads=heads, leaky_slope=0.2, act=act,
+                             bias=None if b is None else torch.from_numpy(b).cuda())
+        want = oracle.gat_gather(r, c, z, s_src, s_dst, heads, 0.2)
+        if b is not None:
+            want = np.maximum(want + b, 0.0)
+        check_features(B.to_numpy(out), want, dtype, f"act={act}")
+        if b is None:
+            np.testing.assert_allclose(W.as_f32(B.to_numpy(out))[5], W.as_f32(z)[5], rtol=1e-6)
+
+
+@pytest.mark.parametrize("dtype,d_in,heads,dh", [(W.F32, 64, 4, 32), (W.BF16, 256, 4, 64), (W.BF16, 64, 1, 64), (W.BF16, 32, 3, 64)])
+@pytest.mark.parametrize("n", [1, 33, 3000])
+def test_apply_projection_with_scores(B, dtype, d_in, heads, dh, n):
+    rng = np.random.default_rng(d_in + heads + n)
+    h = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    lay = W.gat_layers(rng, (d_in, heads * dh), heads, dtype)[0]
+    out, s_src, s_dst = B.apply_layer(None, B.to_device(h), None, B.to_device(lay.w_nbr), None, W.ACT_NONE, heads=heads,
+                                      att_src=B.to_device(lay.att_src), att_dst=B.to_device(lay.att_dst))
+    z64 = oracle.apply(None, h, None, lay.w_nbr, None, oracle.ACT_NONE)
+    check_features(B.to_numpy(out), z64, dtype)
+    for got, att in ((s_src, lay.att_src), (s_dst, lay.att_dst)):
+        want = oracle.gat_scores(z64, att)
+        assert np.abs(got.cpu().numpy() - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_gat_layers_small_graph(B, dtype):
+    import torch
+    n, e = 3000, 30000
+    src, dst, x = W.random_small_graph(77, n, e, 64, dtype, 0.3)
+    rng = np.random.default_rng(78)
+    layers = W.gat_layers(rng, (64, 128, 64), 2, dtype, bias_random=True)
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    want = oracle.infer_full_graph(r, c, d, x, layers, dtype)
+    for T in (None, 50):
+        split = B.split_hubs(rowptr, T) if T else None
+        out = B.infer_full_graph(rowptr, col, deg_out, split, B.device_layers(layers), B.to_device(x))
+        check_features(B.to_numpy(out), W.as_f32(want), dtype, f"T={T}")
+
+
 # ------------------------------------------------------------------------------------------ whole path
 @pytest.mark.parametrize("name,scale", [("tiny_powerlaw", 1.0), ("medium_uniform", 0.02), ("hub_heavy", 0.005),
-                                        ("hub_heavy_uniform_control", 0.005), ("huge_share", 0.0003)])
+                                        ("hub_heavy_uniform_control", 0.005), ("huge_share", 0.0003),
+                                        ("attention", 0.005)])
 def test_infer_full_graph_matches_oracle(B, name, scale):
     import torch
     w = W.make(name, scale, bias_random=True)
