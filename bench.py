@@ -68,9 +68,14 @@ def main():
     thr = w.threshold if use_split else (1 << 62)
     tdt = x.dtype
 
+    for kv in os.environ.get("ITB_TUNING", "").split(","):       # e.g. ITB_TUNING=2:0 (measurement aid)
+        if kv:
+            B.set_tuning(int(kv.split(":")[0]), int(kv.split(":")[1]))
+
     # buffers reused by every step (the caching allocator is warm after the first step anyway)
+    is_gat = [l.agg == W.AGG_GAT for l in w.layers]
     states = [torch.empty((N, l.d_out), dtype=tdt, device="cuda") for l in w.layers]
-    aggs = [torch.empty((N, l.d_in), dtype=tdt, device="cuda") for l in w.layers]
+    aggs = [torch.empty((N, l.d_out if g else l.d_in), dtype=tdt, device="cuda") for l, g in zip(w.layers, is_gat)]
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stamps = {"gather": [], "apply": [], "csr": [], "split": []}
 
@@ -86,17 +91,28 @@ def main():
             ss, sd = B.gcn_norm_scales(rowptr, deg_out)
         h = x
         for i, l in enumerate(layers):
-            a = ev(); a.record()
-            B.gather_layer(l.agg, rowptr, col, h, split if use_split else None, ss, sd, out=aggs[i])
-            b = ev(); b.record()
-            B.apply_layer(h, aggs[i], l.w_self, l.w_nbr, l.bias, l.act, out=states[i])
-            c = ev(); c.record()
-            marks.append((a, b, c))
+            if is_gat[i]:
+                # GAT order: projection (with the score epilogue) first, then the attention reduce + bias + activation
+                b0 = ev(); b0.record()
+                _, s_src, s_dst = B.apply_layer(None, h, None, l.w_nbr, None, W.ACT_NONE, out=aggs[i], heads=l.heads,
+                                                att_src=l.att_src, att_dst=l.att_dst)
+                a = ev(); a.record()
+                B.gather_layer(l.agg, rowptr, col, aggs[i], split if use_split else None, s_src, s_dst, heads=l.heads,
+                               leaky_slope=l.leaky_slope, act=l.act, bias=l.bias, out=states[i])
+                b = ev(); b.record()
+                marks.append((a, b, b0, a))
+            else:
+                a = ev(); a.record()
+                B.gather_layer(l.agg, rowptr, col, h, split if use_split else None, ss, sd, out=aggs[i])
+                b = ev(); b.record()
+                B.apply_layer(h, aggs[i], l.w_self, l.w_nbr, l.bias, l.act, out=states[i])
+                c = ev(); c.record()
+                marks.append((a, b, b, c))
             h = states[i]
         if record:
             stamps["csr"].append((e0, e1)); stamps["split"].append((e1, e2))
-            for a, b, c in marks:
-                stamps["gather"].append((a, b)); stamps["apply"].append((b, c))
+            for g0, g1, a0, a1 in marks:
+                stamps["gather"].append((g0, g1)); stamps["apply"].append((a0, a1))
         return rowptr, col, deg_out, split
 
     for _ in range(args.warmup):
@@ -119,8 +135,11 @@ def main():
     a_ms = [avg_ms(stamps["apply"], i) for i in range(L)]
     # algorithmic traffic of one gather launch: every in-edge reads its column index and its source row once,
     # every vertex reads its row pointer and writes its aggregate row once
-    g_bytes = [E * (4 + l.d_in * esz) + N * (8 + l.d_in * esz) for l in w.layers]
-    a_flops = [4.0 * l.d_in * l.d_out * N for l in w.layers]
+    # (GAT: the row is the projected state of width d_out; plus the 4-byte source score of each head per edge, and per
+    # vertex its own row and scores for the implicit self edge)
+    g_bytes = [E * (4 + 4 * l.heads + l.d_out * esz) + N * (8 + 2 * l.d_out * esz + 8 * l.heads) if g
+               else E * (4 + l.d_in * esz) + N * (8 + l.d_in * esz) for l, g in zip(w.layers, is_gat)]
+    a_flops = [(2.0 if g else 4.0) * l.d_in * l.d_out * N for l, g in zip(w.layers, is_gat)]
     dom = int(np.argmax(g_ms))
     achieved = g_bytes[dom] / (g_ms[dom] * 1e-3) / 1e9
 
@@ -158,7 +177,7 @@ def main():
         "config": {"workload": args.workload, "scale": args.scale, "n_nodes": N, "n_edges": E,
                    "dims": [w.layers[0].d_in] + [l.d_out for l in w.layers], "aggregator": w.layers[0].agg,
                    "hub_threshold": w.threshold if use_split else None, "recipe": w.recipe},
-        "roofline": {"bound": "hbm", "kernel": f"gather_layer (layer {dom + 1}, dim {w.layers[dom].d_in})",
+        "roofline": {"bound": "hbm", "kernel": f"gather_layer (layer {dom + 1}, dim {w.layers[dom].d_out if is_gat[dom] else w.layers[dom].d_in})",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes": g_bytes[dom], "avg_ms": g_ms[dom]},
         "breakdown": {

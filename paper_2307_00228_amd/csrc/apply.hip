@@ -52,6 +52,7 @@ __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &
     const int phases = a.h_self ? 2 : 1;
     const int chunks_per_phase = a.d_in / KC;
     const int total = phases * chunks_per_phase * 2 * BN;
+#pragma unroll 4
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
         const int j = idx % BN;
         const int kh = (idx / BN) & 1;
@@ -121,8 +122,9 @@ __device__ __forceinline__ float reduce_rows_over_columns(float (&v)[16], int i)
 // PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
 // A fragments are double-buffered by group and the request stream runs on across row tiles (the first
 // fragments of the next tile are requested while the current tile finishes and stores).
-template <bool BF16, int NT, int PF>
+template <bool BF16, int NT, int PF, int TPH>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
+    constexpr bool kDoubleBufferB = NT < 8;  // with 8 accumulator tiles there is no room for a second B set
     extern __shared__ uint4 wlds[];
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
@@ -195,15 +197,22 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
 #pragma unroll
             for (int p = 0; p < PF; ++p) {
                 const int c = c0 + p;
-                const int cn = (c + 1 == total) ? 0 : c + 1;
-                uint4 bnext[NT];  // B fragments of the next chunk, read from LDS under the current MFMAs
+                if constexpr (kDoubleBufferB) {
+                    const int cn = (c + 1 == total) ? 0 : c + 1;
+                    uint4 bnext[NT];  // B fragments of the next chunk, read from LDS under the current MFMAs
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) bnext[nt] = wbase[(int64_t)cn * 2 * BN + nt * 32];
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_chunk<BF16, NT>(acc, cur[p], bcur);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int nt = 0; nt < NT; ++nt) bnext[nt] = wbase[(int64_t)cn * 2 * BN + nt * 32];
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_chunk<BF16, NT>(acc, cur[p], bcur);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) bcur[nt] = bnext[nt];
+                    for (int nt = 0; nt < NT; ++nt) bcur[nt] = bnext[nt];
+                } else {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) bcur[nt] = wbase[(int64_t)c * 2 * BN + nt * 32];
+                    mfma_chunk<BF16, NT>(acc, cur[p], bcur);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
 #pragma unroll
             for (int p = 0; p < PF; ++p) cur[p] = nxt[p];
@@ -250,34 +259,33 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                 }
             }
         }
-        if (a.heads > 0) {
-            // every head's columns lie inside this block's column panel (checked on the host)
-            const int dh = a.d_out / a.heads;
-            const int tiles_per_head = dh / 32;
+        if constexpr (TPH > 0) {
+            // Attention scores from the fp32 accumulators; every head's TPH column tiles lie inside this block's
+            // panel (checked on the host).  Source and destination vectors are reduced one after the other to
+            // keep the live register set small.
+            const int dh = TPH * 32;
             const int head0 = col0 / dh;
-            for (int hd = 0; hd < BN / dh && head0 + hd < a.heads; ++hd) {
-                float ps[16], pd[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) ps[r] = pd[r] = 0.f;
+            for (int hd = 0; hd < NT / TPH; ++hd) {
+                if (head0 + hd < a.heads) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    if (nt / tiles_per_head != hd) continue;
-                    const int d = (nt % tiles_per_head) * 32 + i;
-                    const float as = a.att_src[(head0 + hd) * dh + d];
-                    const float ad = a.att_dst[(head0 + hd) * dh + d];
+                    for (int which = 0; which < 2; ++which) {
+                        const float *att = which ? a.att_dst : a.att_src;
+                        float *dst = which ? a.s_dst : a.s_src;
+                        float ps[16];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        ps[r] = fmaf(as, acc[nt][r], ps[r]);
-                        pd[r] = fmaf(ad, acc[nt][r], pd[r]);
+                        for (int r = 0; r < 16; ++r) ps[r] = 0.f;
+#pragma unroll
+                        for (int t = 0; t < TPH; ++t) {
+                            const float av = att[(head0 + hd) * dh + t * 32 + i];
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) ps[r] = fmaf(av, acc[hd * TPH + t][r], ps[r]);
+                        }
+                        const float tot = reduce_rows_over_columns(ps, i);
+                        const int r = i >> 1;
+                        const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
+                        if ((i & 1) == 0 && orow < a.n) dst[orow * a.heads + head0 + hd] = tot;
                     }
-                }
-                const float ts = reduce_rows_over_columns(ps, i);
-                const float td = reduce_rows_over_columns(pd, i);
-                const int r = i >> 1;
-                const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
-                if ((i & 1) == 0 && orow < a.n) {
-                    a.s_src[orow * a.heads + head0 + hd] = ts;
-                    a.s_dst[orow * a.heads + head0 + hd] = td;
                 }
             }
         }
@@ -285,14 +293,14 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     }
 }
 
-template <bool BF16, int NT, int PF>
+template <bool BF16, int NT, int PF, int TPH>
 int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
     const size_t lds = (size_t)k_total * BN * (BF16 ? 2 : 4);
     static bool attr_set = false;
     if (!attr_set) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, TPH>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxWeightLds));
         attr_set = true;
     }
@@ -304,7 +312,7 @@ int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_kernel<BF16, NT, PF><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_kernel<BF16, NT, PF, TPH><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -312,10 +320,19 @@ int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
 template <bool BF16, int NT>
 int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     const int total = (a.d_in / (BF16 ? 16 : 8)) * (a.h_self ? 2 : 1);
-    if (total % 8 == 0 && NT < 8) return launch_apply_pf<BF16, NT, 8>(a, n_cus, st);
-    if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4>(a, n_cus, st);
-    if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2>(a, n_cus, st);
-    return launch_apply_pf<BF16, NT, 1>(a, n_cus, st);
+    if (a.heads > 0) {
+        // score epilogue: tiles per head must divide the panel; groups of 2 k-chunks keep the register set small
+        const int tph = (a.d_out / a.heads) / 32;
+        if (total % 2 != 0) return ITB_ERR_UNSUPPORTED;
+        if constexpr (NT >= 1) if (tph == 1) return launch_apply_pf<BF16, NT, 2, 1>(a, n_cus, st);
+        if constexpr (NT >= 2) if (tph == 2) return launch_apply_pf<BF16, NT, 2, 2>(a, n_cus, st);
+        if constexpr (NT >= 4) if (tph == 4) return launch_apply_pf<BF16, NT, 2, 4>(a, n_cus, st);
+        return ITB_ERR_UNSUPPORTED;
+    }
+    if (total % 8 == 0 && NT < 8) return launch_apply_pf<BF16, NT, 8, 0>(a, n_cus, st);
+    if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, 0>(a, n_cus, st);
+    if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, 0>(a, n_cus, st);
+    return launch_apply_pf<BF16, NT, 1, 0>(a, n_cus, st);
 }
 
 template <bool BF16>
@@ -361,7 +378,9 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if (desc->heads == 0 && (att_src || att_dst || s_src || s_dst)) return ITB_ERR_SIZE;
     if (desc->heads > 0) {
         if (!att_src || !att_dst || !s_src || !s_dst) return ITB_ERR_NULL;
-        if (desc->d_out % desc->heads != 0 || (desc->d_out / desc->heads) % 32 != 0) return ITB_ERR_UNSUPPORTED;
+        if (desc->d_out % desc->heads != 0) return ITB_ERR_SIZE;
+        const int dh = desc->d_out / desc->heads;
+        if (dh != 32 && dh != 64 && dh != 128) return ITB_ERR_UNSUPPORTED;
     }
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
     if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;

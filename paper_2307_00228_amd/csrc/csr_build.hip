@@ -7,6 +7,10 @@
 // ordering, so the result is the unique stable grouping.
 #include "common.h"
 
+namespace itb {
+int g_csr_xcd_remap = 1;  // tuning hook (key 2): 0 = tiles in launch order
+}
+
 namespace {
 using namespace itb;
 
@@ -19,6 +23,17 @@ constexpr int kMaxRadix = 256;
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 8;
 constexpr int kScanTile = kScanThreads * kScanItems;
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Giving XCD x a
+// CONTIGUOUS range of tiles makes neighbouring tiles -- which append to neighbouring positions of every digit
+// bucket -- meet in one L2, where their partial-line stores merge before they are written back.
+__device__ __forceinline__ int64_t xcd_contiguous_tile(int64_t block, int64_t nblocks, int remap) {
+    if (!remap) return block;
+    constexpr int64_t kXcds = 8;
+    const int64_t per = nblocks / kXcds, rem = nblocks % kXcds;
+    const int64_t x = block % kXcds, j = block / kXcds;
+    return x * per + (x < rem ? x : rem) + j;
+}
 
 __global__ void fill_i64_kernel(int64_t *p, int64_t n, int64_t v) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
@@ -44,20 +59,21 @@ __global__ void check_edges_kernel(int64_t n_edges, uint32_t n_nodes, const int3
 
 // hist[digit * nblocks + block] = number of keys of this block's tile with that digit.
 __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *keys, int64_t n, int shift, int bits,
-                                                              uint32_t *hist, int64_t nblocks) {
+                                                              uint32_t *hist, int64_t nblocks, int remap) {
     __shared__ uint32_t h[kMaxRadix];
+    const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
     const int radix = 1 << bits;
     const uint32_t mask = radix - 1;
     for (int d = threadIdx.x; d < radix; d += kThreads) h[d] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kTile;
+    const int64_t base = tile * kTile;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         int64_t idx = base + i * kThreads + threadIdx.x;
         if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & mask], 1u);
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += kThreads) hist[(int64_t)d * nblocks + blockIdx.x] = h[d];
+    for (int d = threadIdx.x; d < radix; d += kThreads) hist[(int64_t)d * nblocks + tile] = h[d];
 }
 
 // Stable scatter of one digit.  Tile order is (wave, slot, lane) = ascending input index, and the rank of a
@@ -66,7 +82,7 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *ke
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t *keys_in, const int32_t *vals_in,
                                                                  uint32_t *keys_out, int32_t *vals_out, int64_t n,
                                                                  int shift, int bits, const uint32_t *hist_scanned,
-                                                                 int64_t nblocks) {
+                                                                 int64_t nblocks, int remap) {
     __shared__ uint32_t cnt[kWaves][kMaxRadix];
     __shared__ uint32_t base[kMaxRadix];
     const int radix = 1 << bits;
@@ -74,10 +90,11 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
     for (int d = threadIdx.x; d < kWaves * kMaxRadix; d += kThreads) (&cnt[0][0])[d] = 0;
-    for (int d = threadIdx.x; d < radix; d += kThreads) base[d] = hist_scanned[(int64_t)d * nblocks + blockIdx.x];
+    const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
+    for (int d = threadIdx.x; d < radix; d += kThreads) base[d] = hist_scanned[(int64_t)d * nblocks + tile];
     __syncthreads();
 
-    const int64_t wave_base = (int64_t)blockIdx.x * kTile + (int64_t)w * (kWave * kItems);
+    const int64_t wave_base = tile * kTile + (int64_t)w * (kWave * kItems);
     const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
     uint32_t key[kItems];
     uint32_t rank[kItems];
@@ -266,11 +283,12 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
         uint32_t *kout = kbuf[p & 1];
         int32_t *vout = ((passes - 1 - p) % 2 == 0) ? col : vtmp;
         const int64_t hist_n = ((int64_t)1 << bits) * nblocks;
-        radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, hist, nblocks);
+        radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, hist, nblocks, itb::g_csr_xcd_remap);
         ITB_LAUNCH_CHECK();
         int32_t rc = exclusive_scan_u32(hist, hist_n, scan_ws, st);
         if (rc != ITB_OK) return rc;
-        radix_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist, nblocks);
+        radix_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist, nblocks,
+                                                                     itb::g_csr_xcd_remap);
         ITB_LAUNCH_CHECK();
         kin = kout;
         vin = vout;

@@ -16,6 +16,7 @@
 #include "common.h"
 
 namespace itb {
+extern int g_csr_xcd_remap;
 int g_small_limit = -1;   // tuning hook: rows with in-degree <= limit use one lane group per row (-1 = auto)
 int g_gather_unroll = 4;  // reserved
 }  // namespace itb
@@ -460,5 +461,6 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
 extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 0) { itb::g_small_limit = value; return ITB_OK; }
     if (key == 1) { itb::g_gather_unroll = value; return ITB_OK; }
+    if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }
