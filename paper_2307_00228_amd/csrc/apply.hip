@@ -124,7 +124,7 @@ __device__ __forceinline__ float reduce_rows_over_columns(float (&v)[16], int i)
 // fragments of the next tile are requested while the current tile finishes and stores).
 template <bool BF16, int NT, int PF, int TPH>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
-    constexpr bool kDoubleBufferB = NT < 8;  // with 8 accumulator tiles there is no room for a second B set
+    constexpr bool kDoubleBufferB = true;
     extern __shared__ uint4 wlds[];
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
@@ -220,21 +220,52 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
 
         // Epilogue.  Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of the tile.
         const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
-        const bool full = (m0 + 32 <= a.n) && (col0 + BN <= a.d_out);
+        const bool full = (m0 + 32 <= a.n) && (col0 + BN <= a.d_out) && (a.d_out % 4 == 0);
         if (full) {
+            // 4x4 transposes inside lane quads (two butterfly steps, lanes ^1 then ^2) turn "4 rows of one column"
+            // into "4 consecutive columns of one row", so a lane stores 16 bytes (fp32) / 8 bytes (bf16) at once:
+            // lane i ends up with row 8*b + 4*kh + (i&3) and columns 4*(i>>2) .. +3 of the tile.
+            const bool odd = (i & 1) != 0, hi = (i & 2) != 0;
+            const int64_t row_q = m0 + 4 * kh + (i & 3);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int col = col0 + nt * 32 + i;
                 const float b = bias_v[nt];
+                const float b1 = __shfl_xor(b, 1, kWave);   // bias of the neighbouring column
+                const float blo = odd ? b1 : b, bhi = odd ? b : b1;   // biases of columns (pair start, pair start + 1)
+                const int colq = col0 + nt * 32 + 4 * (i >> 2);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
-                    float y = acc[nt][r] + b;
-                    if (a.act == ITB_ACT_RELU) y = fmaxf(y, 0.f);
+                for (int bq = 0; bq < 4; ++bq) {
+                    float p0[2], p1[2];  // after step 1: pair jj holds two adjacent columns of one row
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        const float va = acc[nt][4 * bq + 2 * jj], vb = acc[nt][4 * bq + 2 * jj + 1];
+                        const float got = __shfl_xor(odd ? va : vb, 1, kWave);
+                        p0[jj] = odd ? got : va;   // even lane: row 2jj, cols (c, c+1); odd lane: row 2jj+1, cols (c-1, c)
+                        p1[jj] = odd ? vb : got;
+                        p0[jj] += blo;
+                        p1[jj] += bhi;
+                        if (a.act == ITB_ACT_RELU) {
+                            p0[jj] = fmaxf(p0[jj], 0.f);
+                            p1[jj] = fmaxf(p1[jj], 0.f);
+                        }
+                    }
+                    const int64_t off = (row_q + 8 * bq) * a.d_out + colq;
                     if constexpr (BF16) {
-                        static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
+                        const uint32_t k0 = pack_bf16x2(p0[0], p1[0]), k1 = pack_bf16x2(p0[1], p1[1]);
+                        const uint32_t got = (uint32_t)__shfl_xor((int)(hi ? k0 : k1), 2, kWave);
+                        uint2 o;
+                        o.x = hi ? got : k0;   // lanes with bit1 clear keep pair 0 (their row), receive columns +2,+3
+                        o.y = hi ? k1 : got;
+                        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + off) = o;
                     } else {
-                        static_cast<float *>(a.out)[orow * a.d_out + col] = y;
+                        const float g0 = __shfl_xor(hi ? p0[0] : p0[1], 2, kWave);
+                        const float g1 = __shfl_xor(hi ? p1[0] : p1[1], 2, kWave);
+                        float4 o;
+                        o.x = hi ? g0 : p0[0];
+                        o.y = hi ? g1 : p1[0];
+                        o.z = hi ? p0[1] : g0;
+                        o.w = hi ? p1[1] : g1;
+                        *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + off) = o;
                     }
                 }
             }
@@ -323,13 +354,19 @@ int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (a.heads > 0) {
         // score epilogue: tiles per head must divide the panel; groups of 2 k-chunks keep the register set small
         const int tph = (a.d_out / a.heads) / 32;
-        if (total % 2 != 0) return ITB_ERR_UNSUPPORTED;
-        if constexpr (NT >= 1) if (tph == 1) return launch_apply_pf<BF16, NT, 2, 1>(a, n_cus, st);
-        if constexpr (NT >= 2) if (tph == 2) return launch_apply_pf<BF16, NT, 2, 2>(a, n_cus, st);
-        if constexpr (NT >= 4) if (tph == 4) return launch_apply_pf<BF16, NT, 2, 4>(a, n_cus, st);
+#define ITB_SCORE_CASE(TPH_)                                                                         \
+    if (tph == TPH_) {                                                                               \
+        if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, TPH_>(a, n_cus, st);                 \
+        if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, TPH_>(a, n_cus, st);                 \
+        return launch_apply_pf<BF16, NT, 1, TPH_>(a, n_cus, st);                                     \
+    }
+        if constexpr (NT >= 1) ITB_SCORE_CASE(1)
+        if constexpr (NT >= 2) ITB_SCORE_CASE(2)
+        if constexpr (NT >= 4) ITB_SCORE_CASE(4)
+#undef ITB_SCORE_CASE
         return ITB_ERR_UNSUPPORTED;
     }
-    if (total % 8 == 0 && NT < 8) return launch_apply_pf<BF16, NT, 8, 0>(a, n_cus, st);
+    if (total % 8 == 0) return launch_apply_pf<BF16, NT, 8, 0>(a, n_cus, st);
     if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, 0>(a, n_cus, st);
     if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, 0>(a, n_cus, st);
     return launch_apply_pf<BF16, NT, 1, 0>(a, n_cus, st);
@@ -339,12 +376,11 @@ template <bool BF16>
 int32_t dispatch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
     const size_t per_tile = (size_t)k_total * 32 * (BF16 ? 2 : 4);
-    int nt = 8;
+    int nt = 4;  // 8 accumulator tiles per wave would not leave registers for the prefetch buffers
     while (nt > 1 && (per_tile * nt > kMaxWeightLds || 32 * (nt / 2) >= a.d_out)) nt /= 2;
     if (per_tile * nt > kMaxWeightLds) return ITB_ERR_UNSUPPORTED;
     if (a.heads > 0 && (32 * nt) % (a.d_out / a.heads) != 0) return ITB_ERR_UNSUPPORTED;  // a head must not straddle panels
     switch (nt) {
-        case 8: return launch_apply<BF16, 8>(a, n_cus, st);
         case 4: return launch_apply<BF16, 4>(a, n_cus, st);
         case 2: return launch_apply<BF16, 2>(a, n_cus, st);
         default: return launch_apply<BF16, 1>(a, n_cus, st);

@@ -78,33 +78,46 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *ke
 
 // Stable scatter of one digit.  Tile order is (wave, slot, lane) = ascending input index, and the rank of a
 // key among equal digits is: keys of earlier blocks (scanned histogram) + earlier waves of the tile + earlier
-// slots of the wave + lower lanes of the slot.
+// slots of the wave + lower lanes of the slot.  The tile is first put in digit order in LDS and then written
+// out by consecutive threads, so that each digit's run leaves the block as contiguous, coalesced stores
+// (scattering straight from registers costs one memory transaction per 4-byte element).
+template <bool HAS_VALS>
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t *keys_in, const int32_t *vals_in,
                                                                  uint32_t *keys_out, int32_t *vals_out, int64_t n,
                                                                  int shift, int bits, const uint32_t *hist_scanned,
                                                                  int64_t nblocks, int remap) {
-    __shared__ uint32_t cnt[kWaves][kMaxRadix];
-    __shared__ uint32_t base[kMaxRadix];
+    __shared__ uint32_t cnt[kWaves][kMaxRadix];   // per wave and digit: count, then start inside the sorted tile
+    __shared__ uint32_t gbase[kMaxRadix];         // global position of the tile's first key of the digit
+    __shared__ uint32_t lstart[kMaxRadix];        // position of the digit's first key inside the sorted tile
+    __shared__ uint32_t skey[kTile];
+    __shared__ int32_t sval[HAS_VALS ? kTile : 1];
+    __shared__ uint32_t scan_sm[17];
     const int radix = 1 << bits;
     const uint32_t mask = radix - 1;
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
     for (int d = threadIdx.x; d < kWaves * kMaxRadix; d += kThreads) (&cnt[0][0])[d] = 0;
     const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
-    for (int d = threadIdx.x; d < radix; d += kThreads) base[d] = hist_scanned[(int64_t)d * nblocks + tile];
+    for (int d = threadIdx.x; d < radix; d += kThreads) gbase[d] = hist_scanned[(int64_t)d * nblocks + tile];
     __syncthreads();
 
-    const int64_t wave_base = tile * kTile + (int64_t)w * (kWave * kItems);
+    const int64_t tile_base = tile * kTile;
+    const int64_t wave_base = tile_base + (int64_t)w * (kWave * kItems);
     const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
     uint32_t key[kItems];
+    int32_t val[kItems];
     uint32_t rank[kItems];
 #pragma unroll
     for (int s = 0; s < kItems; ++s) {
         const int64_t idx = wave_base + s * kWave + lane;
+        key[s] = (idx < n) ? keys_in[idx] : 0u;
+        if constexpr (HAS_VALS) val[s] = (idx < n) ? vals_in[idx] : 0;
+    }
+#pragma unroll
+    for (int s = 0; s < kItems; ++s) {
+        const int64_t idx = wave_base + s * kWave + lane;
         const bool valid = idx < n;
-        const uint32_t k = valid ? keys_in[idx] : 0u;
-        key[s] = k;
-        const uint32_t d = (k >> shift) & mask;
+        const uint32_t d = (key[s] >> shift) & mask;
         uint64_t peers = __ballot(valid);
         for (int b = 0; b < bits; ++b) {
             const bool bit = (d >> b) & 1u;
@@ -118,24 +131,37 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t 
         __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += kThreads) {
-        uint32_t run = base[d];
+    // per digit: exclusive prefix over the waves, tile total; then exclusive prefix over the digits
+    uint32_t total_d = 0;
+    if (threadIdx.x < radix) {
+        const int d = threadIdx.x;
         for (int ww = 0; ww < kWaves; ++ww) {
-            uint32_t t = cnt[ww][d];
-            cnt[ww][d] = run;
-            run += t;
+            const uint32_t t = cnt[ww][d];
+            cnt[ww][d] = total_d;
+            total_d += t;
         }
     }
+    uint32_t tile_total;
+    const uint32_t ls = block_exclusive_scan<uint32_t>(total_d, scan_sm, &tile_total);
+    if (threadIdx.x < radix) lstart[threadIdx.x] = ls;
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < kItems; ++s) {
         const int64_t idx = wave_base + s * kWave + lane;
         if (idx < n) {
             const uint32_t d = (key[s] >> shift) & mask;
-            const uint32_t pos = cnt[w][d] + rank[s];
-            keys_out[pos] = key[s];
-            vals_out[pos] = vals_in[idx];
+            const uint32_t lp = lstart[d] + cnt[w][d] + rank[s];
+            skey[lp] = key[s];
+            if constexpr (HAS_VALS) sval[lp] = val[s];
         }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < tile_total; i += kThreads) {
+        const uint32_t k = skey[i];
+        const uint32_t d = (k >> shift) & mask;
+        const uint32_t pos = gbase[d] + (i - lstart[d]);
+        keys_out[pos] = k;
+        if constexpr (HAS_VALS) vals_out[pos] = sval[i];
     }
 }
 
@@ -287,8 +313,8 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
         ITB_LAUNCH_CHECK();
         int32_t rc = exclusive_scan_u32(hist, hist_n, scan_ws, st);
         if (rc != ITB_OK) return rc;
-        radix_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist, nblocks,
-                                                                     itb::g_csr_xcd_remap);
+        radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist, nblocks,
+                                                                           itb::g_csr_xcd_remap);
         ITB_LAUNCH_CHECK();
         kin = kout;
         vin = vout;

@@ -30,6 +30,7 @@ struct GatArgs {
     float slope;
     int32_t small_limit;
     // hub passes
+    int32_t sub_parts;     // pieces per shadow segment (one wavefront and one partial state each)
     int64_t n_shadows;
     const int64_t *shadow_begin, *shadow_end;
     const int32_t *shadow_owner;
@@ -73,6 +74,32 @@ __device__ __forceinline__ void absorb(SoftState<Elems<BF16>::kPerVec> &st, floa
 #pragma unroll
     for (int i = 0; i < VE; ++i) st.acc[i] = fmaf(st.acc[i], sc, p * f[i]);
     st.m = mn;
+}
+
+// A batch of U edges.  The running maximum settles after a few edges of a row (it changes about ln(degree)
+// times), so the common case -- no lane of the wavefront sees a larger score -- skips the rescaling of the
+// accumulators: one exponential and one fused multiply-add per element.
+template <bool BF16, int U>
+__device__ __forceinline__ void absorb_batch(SoftState<Elems<BF16>::kPerVec> &st, const float (&e)[U], const uint4 (&raw)[U],
+                                             const bool (&on)[U]) {
+    constexpr int VE = Elems<BF16>::kPerVec;
+    bool grows = false;
+#pragma unroll
+    for (int q = 0; q < U; ++q) grows = grows || (on[q] && e[q] > st.m);
+    if (__ballot(grows) == 0ull) {
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const float p = on[q] ? __expf(e[q] - st.m) : 0.f;
+            float f[VE];
+            unpack<BF16>(f, raw[q]);
+            st.l += p;
+#pragma unroll
+            for (int i = 0; i < VE; ++i) st.acc[i] = fmaf(p, f[i], st.acc[i]);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < U; ++q) absorb<BF16>(st, e[q], raw[q], on[q]);
+    }
 }
 
 // merge the state held by the lane `off` lanes away (same head: off is a multiple of the lane-group size)
@@ -123,7 +150,8 @@ __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPer
                 e[q] = on[q] ? a.s_src[(int64_t)u * a.heads + hk] : 0.f;
             }
 #pragma unroll
-            for (int q = 0; q < U; ++q) absorb<BF16>(st, leaky(e[q] + sd, a.slope), raw[q], on[q]);
+            for (int q = 0; q < U; ++q) e[q] = leaky(e[q] + sd, a.slope);
+            absorb_batch<BF16, U>(st, e, raw, on);
         }
     }
 #pragma unroll
@@ -212,7 +240,8 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
                         e[q] = on[q] ? a.s_src[(int64_t)u * a.heads + hk] : 0.f;
                     }
 #pragma unroll
-                    for (int q = 0; q < U; ++q) absorb<BF16>(st, leaky(e[q] + sd, a.slope), raw[q], on[q]);
+                    for (int q = 0; q < U; ++q) e[q] = leaky(e[q] + sd, a.slope);
+                    absorb_batch<BF16, U>(st, e, raw, on);
                 }
             }
             if (on_v) finish_store<BF16, VE>(a, v, vec, st.acc, st.l);
@@ -250,7 +279,9 @@ __global__ __launch_bounds__(256) void gat_segments_kernel(GatArgs a) {
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
     const int li = lane % G;
-    const int64_t s = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t p = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t s = p / a.sub_parts;
+    const int64_t f = p % a.sub_parts;
     if (s >= a.n_shadows) return;
     const int64_t v = a.shadow_owner[s];
     const int64_t owner_start = a.rowptr[v];
@@ -264,15 +295,18 @@ __global__ __launch_bounds__(256) void gat_segments_kernel(GatArgs a) {
     st.l = 0.f;
 #pragma unroll
     for (int i = 0; i < VE; ++i) st.acc[i] = 0.f;
-    const int64_t b = a.shadow_begin[s];
-    wave_segment_softmax<BF16, G>(st, a, b, a.shadow_end[s] - b, sd, vec, hk, lane_on);
+    const int64_t sb = a.shadow_begin[s];
+    const int64_t len = a.shadow_end[s] - sb;
+    const int64_t b = sb + f * len / a.sub_parts;
+    const int64_t e = sb + (f + 1) * len / a.sub_parts;
+    wave_segment_softmax<BF16, G>(st, a, b, e - b, sd, vec, hk, lane_on);
     if (g == 0 && lane_on) {
-        float4 *o = reinterpret_cast<float4 *>(a.part_acc + (s * a.row_vecs + vec) * VE);
+        float4 *o = reinterpret_cast<float4 *>(a.part_acc + (p * a.row_vecs + vec) * VE);
         o[0] = make_float4(st.acc[0], st.acc[1], st.acc[2], st.acc[3]);
         if constexpr (VE == 8) o[1] = make_float4(st.acc[4], st.acc[5], st.acc[6], st.acc[7]);
         if ((vec * VE) % a.dh == 0) {   // one lane per head records the scalar state
-            a.part_m[s * a.heads + hk] = st.m;
-            a.part_l[s * a.heads + hk] = st.l;
+            a.part_m[p * a.heads + hk] = st.m;
+            a.part_l[p * a.heads + hk] = st.l;
         }
     }
 }
@@ -290,7 +324,7 @@ __global__ __launch_bounds__(1024) void gat_combine_kernel(GatArgs a, int64_t n_
     const int64_t v = hub_ids[blockIdx.x];
     const int64_t rs = a.rowptr[v];
     if (rs < a.edge_lo || rs >= a.edge_hi) return;
-    const int64_t s0 = hub_shadow_off[blockIdx.x], s1 = hub_shadow_off[blockIdx.x + 1];
+    const int64_t s0 = hub_shadow_off[blockIdx.x] * a.sub_parts, s1 = hub_shadow_off[blockIdx.x + 1] * a.sub_parts;
     const int dim = a.row_vecs * VE;
     const int lanes_per_row = dim / 4;
 
@@ -374,7 +408,7 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
     gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
     if (hubs) {
-        gat_segments_kernel<BF16, G><<<dim3((unsigned)((a.n_shadows + 3) / 4), gy), 256, 0, st>>>(a);
+        gat_segments_kernel<BF16, G><<<dim3((unsigned)((a.n_shadows * a.sub_parts + 3) / 4), gy), 256, 0, st>>>(a);
         ITB_LAUNCH_CHECK();
         gat_combine_kernel<BF16><<<(unsigned)n_hubs, 1024, 0, st>>>(a, n_hubs, hub_ids, hub_shadow_off);
         ITB_LAUNCH_CHECK();
@@ -400,6 +434,7 @@ int32_t dispatch(int G, const GatArgs &a, bool hubs, int64_t n_hubs, const int32
 
 namespace itb {
 extern int g_small_limit;
+int segment_sub_parts(int64_t threshold);
 
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
@@ -412,10 +447,11 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     const int ve = bf16 ? 8 : 4;
     if (dh % ve != 0) return ITB_ERR_UNSUPPORTED;  // a lane's 16-byte vector must lie inside one head
     const bool hubs = split && split->n_hubs > 0;
+    const int sub_parts = hubs ? segment_sub_parts(split->threshold) : 1;
     Carver cv(workspace);
-    float *part_acc = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
-    float *part_m = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->heads : 0);
-    float *part_l = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->heads : 0);
+    float *part_acc = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->dim : 0);
+    float *part_m = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->heads : 0);
+    float *part_l = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->heads : 0);
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -448,6 +484,7 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     a.small_limit = g_small_limit >= 0 ? g_small_limit : 2 * (kWave / G);
     if (hubs) {
         a.n_shadows = split->n_shadows;
+        a.sub_parts = sub_parts;
         a.shadow_begin = split->shadow_begin;
         a.shadow_end = split->shadow_end;
         a.shadow_owner = split->shadow_owner;

@@ -17,6 +17,12 @@
 
 namespace itb {
 extern int g_csr_xcd_remap;
+int g_segment_piece = 2048;  // tuning hook (key 3): target edges per wavefront in the hub passes
+// pieces per shadow segment: a function of the threshold only, so partial layouts are reproducible
+int segment_sub_parts(int64_t threshold) {
+    int64_t f = (threshold + g_segment_piece - 1) / g_segment_piece;
+    return (int)(f < 1 ? 1 : (f > 64 ? 64 : f));
+}
 int g_small_limit = -1;   // tuning hook: rows with in-degree <= limit use one lane group per row (-1 = auto)
 int g_gather_unroll = 4;  // reserved
 }  // namespace itb
@@ -40,6 +46,7 @@ struct GatherArgs {
     int32_t mode;
     int32_t small_limit;
     // segment kernel only
+    int32_t sub_parts;       // every shadow segment is cut evenly into this many pieces, one wavefront and one partial each
     int64_t n_shadows;
     const int64_t *shadow_begin, *shadow_end;
     const int32_t *shadow_owner;
@@ -242,24 +249,30 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     }
 }
 
-// One wavefront per shadow segment: fp32 partial sums (source scales applied, destination finish deferred).
+// One wavefront per piece of a shadow segment: fp32 partial sums (source scales applied, destination finish
+// deferred).  Segments of up to `threshold` edges are cut into sub_parts even pieces so that a few thousand
+// segments still put enough independent row loads in flight to cover the memory latency.
 template <bool BF16_IN, int G>
 __global__ __launch_bounds__(256) void gather_segments_kernel(GatherArgs a) {
     constexpr int VE = Elems<BF16_IN>::kPerVec;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
     const int li = lane % G;
-    const int64_t s = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t p = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t s = p / a.sub_parts;
+    const int64_t f = p % a.sub_parts;
     if (s >= a.n_shadows) return;
     const int64_t owner_start = a.rowptr[a.shadow_owner[s]];
     if (owner_start < a.edge_lo || owner_start >= a.edge_hi) return;
     const int vec = blockIdx.y * G + li;
     const bool lane_on = vec < a.row_vecs;
-    const int64_t b = a.shadow_begin[s];
-    const int64_t e = a.shadow_end[s];
+    const int64_t sb = a.shadow_begin[s];
+    const int64_t len = a.shadow_end[s] - sb;
+    const int64_t b = sb + f * len / a.sub_parts;
+    const int64_t e = sb + (f + 1) * len / a.sub_parts;
     float acc[VE];
     wave_segment_sum<BF16_IN, G>(acc, a, b, e - b, vec, lane_on);
-    if (g == 0 && lane_on) store_row_slice<BF16_IN, false>(a.out, s, a.row_vecs, vec, acc);
+    if (g == 0 && lane_on) store_row_slice<BF16_IN, false>(a.out, p, a.row_vecs, vec, acc);
 }
 
 // One block per hub: partial rows are added in ascending segment order within each of `slices` interleaved
@@ -268,14 +281,14 @@ template <bool BF16_OUT>
 __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, int32_t dim, int64_t n_hubs,
                                                             const int32_t *hub_ids, const int64_t *hub_shadow_off,
                                                             const int64_t *rowptr, const float *dst_scale, int32_t mode,
-                                                            int64_t edge_lo, int64_t edge_hi, void *out) {
+                                                            int64_t edge_lo, int64_t edge_hi, int32_t sub_parts, void *out) {
     __shared__ float4 sm[1024];
     const int64_t hub = blockIdx.x;
     const int32_t v = hub_ids[hub];
     const int64_t rs = rowptr[v];
     if (rs < edge_lo || rs >= edge_hi) return;
     const int64_t deg = rowptr[v + 1] - rs;
-    const int64_t s0 = hub_shadow_off[hub], s1 = hub_shadow_off[hub + 1];
+    const int64_t s0 = hub_shadow_off[hub] * sub_parts, s1 = hub_shadow_off[hub + 1] * sub_parts;  // partial rows
     const int lanes_per_row = dim / 4;
     for (int q0 = 0; q0 < lanes_per_row; q0 += 1024) {  // column tiles of 4096 elements
         const int cols_here = (lanes_per_row - q0 < 1024) ? (lanes_per_row - q0) : 1024;
@@ -337,7 +350,7 @@ int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
 
 template <bool BF16_IN, int G>
 int32_t launch_segments(const GatherArgs &a, hipStream_t st) {
-    dim3 grid((unsigned)((a.n_shadows + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
+    dim3 grid((unsigned)((a.n_shadows * a.sub_parts + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
     gather_segments_kernel<BF16_IN, G><<<grid, 256, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
@@ -397,8 +410,9 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
 
     if (desc->bias || desc->act != ITB_ACT_NONE) return ITB_ERR_UNSUPPORTED;  // epilogue exists for the GAT reduce only
     const bool hubs = split && split->n_hubs > 0;
+    const int sub_parts = hubs ? itb::segment_sub_parts(split->threshold) : 1;
     Carver cv(workspace);
-    float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
+    float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->dim : 0);
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -439,6 +453,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     if (hubs) {
         GatherArgs s = a;
         s.out = part;
+        s.sub_parts = sub_parts;
         s.n_shadows = split->n_shadows;
         s.shadow_begin = split->shadow_begin;
         s.shadow_end = split->shadow_end;
@@ -448,11 +463,11 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         if (bout)
             combine_hubs_kernel<true><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
                                                                                 split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
-                                                                                edge_lo, edge_hi, agg_out);
+                                                                                edge_lo, edge_hi, sub_parts, agg_out);
         else
             combine_hubs_kernel<false><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
                                                                                  split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
-                                                                                 edge_lo, edge_hi, agg_out);
+                                                                                 edge_lo, edge_hi, sub_parts, agg_out);
         ITB_LAUNCH_CHECK();
     }
     return ITB_OK;
@@ -462,5 +477,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 0) { itb::g_small_limit = value; return ITB_OK; }
     if (key == 1) { itb::g_gather_unroll = value; return ITB_OK; }
     if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
+    if (key == 3 && value > 0) { itb::g_segment_piece = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }
