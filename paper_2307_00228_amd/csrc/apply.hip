@@ -21,7 +21,8 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 constexpr int kApplyThreads = 512;
 constexpr int kApplyWaves = kApplyThreads / kWave;
 constexpr int kRowsPerBlockTile = 32 * kApplyWaves;
-constexpr size_t kMaxWeightLds = 128 * 1024;
+constexpr size_t kMaxWeightLds = 128 * 1024;  // weight panel of the plain update
+constexpr size_t kMaxLds = 160 * 1024;        // whole LDS of a CU (weight panel + score panel)
 
 struct ApplyArgs {
     int64_t n;
@@ -103,33 +104,73 @@ __device__ __forceinline__ void mfma_chunk(v16f (&acc)[NT], const uint4 &av, con
     }
 }
 
-// Sum v[0..15] over the 32 lanes that share a k-half: a halving butterfly (8+4+2+1 exchanges) followed by one
-// pair exchange; afterwards lanes i and i^1 both hold the total of accumulator register r = i >> 1.
-__device__ __forceinline__ float reduce_rows_over_columns(float (&v)[16], int i) {
+// Attention-score panel for the GAT projection.  s[v,j] = sum_d att[j][d] * (h[v] . W[:, head(j)*dh + d]) is
+// linear in h[v], so it equals h[v] . U[:, j] with U[k][j] = sum_d W[k][head*dh + d] * att[j][d]: 2*heads extra
+// output columns.  Every block folds U once (fp32) and keeps it in LDS in B-fragment order as a fifth 32-column
+// tile; the scores then come out of the matrix cores with the projection, with no cross-lane reduction.
+// Column j < heads is the source score of head j, heads <= j < 2*heads the destination score of head j - heads.
+// bf16: U is split into hi + lo bf16 parts (two B fragments per chunk, same accumulator), which keeps it
+// accurate to ~2^-17 relative.
+template <bool BF16>
+__device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a) {
+    constexpr int KC = BF16 ? 16 : 8;
+    constexpr int KH = KC / 2;
+    constexpr int PARTS = BF16 ? 2 : 1;
+    const int chunks = a.d_in / KC;
+    const int dh = a.d_out / a.heads;
+    const int total = chunks * 2 * 32;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int j = idx & 31;
+        const int kh = (idx >> 5) & 1;
+        const int kc = idx >> 6;
+        const int k0 = kc * KC + kh * KH;
+        float u[KH];
 #pragma unroll
-    for (int half = 8, m = 16; half >= 1; half >>= 1, m >>= 1) {
-        const bool upper = (i & m) != 0;
+        for (int t = 0; t < KH; ++t) u[t] = 0.f;
+        if (j < 2 * a.heads) {
+            const int hd = j < a.heads ? j : j - a.heads;
+            const float *att = (j < a.heads ? a.att_src : a.att_dst) + hd * dh;
+            for (int d = 0; d < dh; ++d) {
+                const float av = att[d];
 #pragma unroll
-        for (int j = 0; j < half; ++j) {
-            const float send = upper ? v[j] : v[j + half];
-            const float keep = upper ? v[j + half] : v[j];
-            v[j] = keep + __shfl_xor(send, m, kWave);
+                for (int t = 0; t < KH; ++t) {
+                    const int64_t wi = (int64_t)(k0 + t) * a.d_out + hd * dh + d;
+                    float wv;
+                    if constexpr (BF16) wv = __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.w_nbr)[wi] << 16);
+                    else wv = static_cast<const float *>(a.w_nbr)[wi];
+                    u[t] = fmaf(wv, av, u[t]);
+                }
+            }
+        }
+        if constexpr (BF16) {
+            uint32_t hi[8], lo[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                hi[t] = f32_to_bf16(u[t]);
+                lo[t] = f32_to_bf16(u[t] - __uint_as_float(hi[t] << 16));
+            }
+            slds[idx] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+            slds[total + idx] = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+        } else {
+            slds[idx] = make_uint4(__float_as_uint(u[0]), __float_as_uint(u[1]), __float_as_uint(u[2]), __float_as_uint(u[3]));
         }
     }
-    return v[0] + __shfl_xor(v[0], 1, kWave);
+    (void)PARTS;
 }
 
 // PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
 // A fragments are double-buffered by group and the request stream runs on across row tiles (the first
 // fragments of the next tile are requested while the current tile finishes and stores).
-template <bool BF16, int NT, int PF, int TPH>
+template <bool BF16, int NT, int PF, bool SCORES>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
-    constexpr bool kDoubleBufferB = true;
+    constexpr int SPARTS = BF16 ? 2 : 1;  // B fragments of the score tile per chunk (bf16: hi and lo part)
     extern __shared__ uint4 wlds[];
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
     const int col0 = blockIdx.y * BN;
     load_weight_panel<BF16, NT>(wlds, a, col0);
+    uint4 *slds = wlds + (int64_t)(a.d_in / KC) * (a.h_self ? 2 : 1) * 2 * BN;  // score panel behind the weight panel
+    if constexpr (SCORES) load_score_panel<BF16>(slds, a);
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -141,6 +182,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     const int total = chunks_self + chunks;
     const int64_t row_vecs = 2 * chunks;
     const uint4 *wbase = wlds + kh * BN + i;
+    const uint4 *sbase = slds + kh * 32 + i;   // score panel: [part][chunk][kh][32]
 
     auto tile_rowoff = [&](int64_t tile) -> int64_t {
         int64_t r = tile * kRowsPerBlockTile + (int64_t)w * 32 + i;
@@ -171,6 +213,11 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     uint4 bcur[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) bcur[nt] = wbase[nt * 32];
+    uint4 scur[SCORES ? SPARTS : 1];
+    if constexpr (SCORES) {
+#pragma unroll
+        for (int q = 0; q < SPARTS; ++q) scur[q] = sbase[(int64_t)q * total * 64];
+    }
 
     for (; tile < a.n_row_tiles; tile += gridDim.x) {
         const int64_t next_tile = tile + gridDim.x;
@@ -180,6 +227,9 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+        v16f sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 
         for (int c0 = 0; c0 < total; c0 += PF) {
             // Double-buffered A: the PF fragments of the NEXT k-group (running on into the next row tile) are
@@ -197,21 +247,32 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
 #pragma unroll
             for (int p = 0; p < PF; ++p) {
                 const int c = c0 + p;
-                if constexpr (kDoubleBufferB) {
-                    const int cn = (c + 1 == total) ? 0 : c + 1;
-                    uint4 bnext[NT];  // B fragments of the next chunk, read from LDS under the current MFMAs
+                const int cn = (c + 1 == total) ? 0 : c + 1;
+                uint4 bnext[NT];  // B fragments of the next chunk, read from LDS under the current MFMAs
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) bnext[nt] = wbase[(int64_t)cn * 2 * BN + nt * 32];
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfma_chunk<BF16, NT>(acc, cur[p], bcur);
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int nt = 0; nt < NT; ++nt) bnext[nt] = wbase[(int64_t)cn * 2 * BN + nt * 32];
+                uint4 snext[SCORES ? SPARTS : 1];
+                if constexpr (SCORES) {
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) bcur[nt] = bnext[nt];
-                } else {
+                    for (int q = 0; q < SPARTS; ++q) snext[q] = sbase[(int64_t)q * total * 64 + (int64_t)cn * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_chunk<BF16, NT>(acc, cur[p], bcur);
+                if constexpr (SCORES) {
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) bcur[nt] = wbase[(int64_t)c * 2 * BN + nt * 32];
-                    mfma_chunk<BF16, NT>(acc, cur[p], bcur);
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int q = 0; q < SPARTS; ++q) {
+                        v16f one[1] = {sacc};
+                        const uint4 bq[1] = {scur[q]};
+                        mfma_chunk<BF16, 1>(one, cur[p], bq);
+                        sacc = one[0];
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) bcur[nt] = bnext[nt];
+                if constexpr (SCORES) {
+#pragma unroll
+                    for (int q = 0; q < SPARTS; ++q) scur[q] = snext[q];
                 }
             }
 #pragma unroll
@@ -290,33 +351,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                 }
             }
         }
-        if constexpr (TPH > 0) {
-            // Attention scores from the fp32 accumulators; every head's TPH column tiles lie inside this block's
-            // panel (checked on the host).  Source and destination vectors are reduced one after the other to
-            // keep the live register set small.
-            const int dh = TPH * 32;
-            const int head0 = col0 / dh;
+        if constexpr (SCORES) {
+            // column i of the score tile: source score of head i, or destination score of head i - heads
+            if (blockIdx.y == 0 && i < 2 * a.heads) {
+                float *dst = i < a.heads ? a.s_src : a.s_dst;
+                const int hd = i < a.heads ? i : i - a.heads;
 #pragma unroll
-            for (int hd = 0; hd < NT / TPH; ++hd) {
-                if (head0 + hd < a.heads) {
-#pragma unroll
-                    for (int which = 0; which < 2; ++which) {
-                        const float *att = which ? a.att_dst : a.att_src;
-                        float *dst = which ? a.s_dst : a.s_src;
-                        float ps[16];
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) ps[r] = 0.f;
-#pragma unroll
-                        for (int t = 0; t < TPH; ++t) {
-                            const float av = att[(head0 + hd) * dh + t * 32 + i];
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) ps[r] = fmaf(av, acc[hd * TPH + t][r], ps[r]);
-                        }
-                        const float tot = reduce_rows_over_columns(ps, i);
-                        const int r = i >> 1;
-                        const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
-                        if ((i & 1) == 0 && orow < a.n) dst[orow * a.heads + head0 + hd] = tot;
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
+                    if (orow < a.n) dst[orow * a.heads + hd] = sacc[r];
                 }
             }
         }
@@ -324,15 +367,16 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     }
 }
 
-template <bool BF16, int NT, int PF, int TPH>
+template <bool BF16, int NT, int PF, bool SCORES>
 int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
-    const size_t lds = (size_t)k_total * BN * (BF16 ? 2 : 4);
+    const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4);
+    if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     static bool attr_set = false;
     if (!attr_set) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, TPH>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxWeightLds));
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, SCORES>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set = true;
     }
     const int col_tiles = (a.d_out + BN - 1) / BN;
@@ -343,7 +387,7 @@ int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_kernel<BF16, NT, PF, TPH><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_kernel<BF16, NT, PF, SCORES><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -352,24 +396,14 @@ template <bool BF16, int NT>
 int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     const int total = (a.d_in / (BF16 ? 16 : 8)) * (a.h_self ? 2 : 1);
     if (a.heads > 0) {
-        // score epilogue: tiles per head must divide the panel; groups of 2 k-chunks keep the register set small
-        const int tph = (a.d_out / a.heads) / 32;
-#define ITB_SCORE_CASE(TPH_)                                                                         \
-    if (tph == TPH_) {                                                                               \
-        if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, TPH_>(a, n_cus, st);                 \
-        if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, TPH_>(a, n_cus, st);                 \
-        return launch_apply_pf<BF16, NT, 1, TPH_>(a, n_cus, st);                                     \
+        if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, true>(a, n_cus, st);
+        if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, true>(a, n_cus, st);
+        return launch_apply_pf<BF16, NT, 1, true>(a, n_cus, st);
     }
-        if constexpr (NT >= 1) ITB_SCORE_CASE(1)
-        if constexpr (NT >= 2) ITB_SCORE_CASE(2)
-        if constexpr (NT >= 4) ITB_SCORE_CASE(4)
-#undef ITB_SCORE_CASE
-        return ITB_ERR_UNSUPPORTED;
-    }
-    if (total % 8 == 0) return launch_apply_pf<BF16, NT, 8, 0>(a, n_cus, st);
-    if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, 0>(a, n_cus, st);
-    if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, 0>(a, n_cus, st);
-    return launch_apply_pf<BF16, NT, 1, 0>(a, n_cus, st);
+    if (total % 8 == 0) return launch_apply_pf<BF16, NT, 8, false>(a, n_cus, st);
+    if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, false>(a, n_cus, st);
+    if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, false>(a, n_cus, st);
+    return launch_apply_pf<BF16, NT, 1, false>(a, n_cus, st);
 }
 
 template <bool BF16>
@@ -379,7 +413,11 @@ int32_t dispatch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
     int nt = 4;  // 8 accumulator tiles per wave would not leave registers for the prefetch buffers
     while (nt > 1 && (per_tile * nt > kMaxWeightLds || 32 * (nt / 2) >= a.d_out)) nt /= 2;
     if (per_tile * nt > kMaxWeightLds) return ITB_ERR_UNSUPPORTED;
-    if (a.heads > 0 && (32 * nt) % (a.d_out / a.heads) != 0) return ITB_ERR_UNSUPPORTED;  // a head must not straddle panels
+    if (a.heads > 0) {  // leave room for the score panel
+        const size_t score = (size_t)k_total * 32 * (BF16 ? 4 : 4);
+        while (nt > 1 && per_tile * nt + score > kMaxLds) nt /= 2;
+        if (per_tile * nt + score > kMaxLds) return ITB_ERR_UNSUPPORTED;
+    }
     switch (nt) {
         case 4: return launch_apply<BF16, 4>(a, n_cus, st);
         case 2: return launch_apply<BF16, 2>(a, n_cus, st);
@@ -415,8 +453,7 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if (desc->heads > 0) {
         if (!att_src || !att_dst || !s_src || !s_dst) return ITB_ERR_NULL;
         if (desc->d_out % desc->heads != 0) return ITB_ERR_SIZE;
-        const int dh = desc->d_out / desc->heads;
-        if (dh != 32 && dh != 64 && dh != 128) return ITB_ERR_UNSUPPORTED;
+        if (desc->heads > 16 || h_self) return ITB_ERR_UNSUPPORTED;  // 2*heads score columns share one 32-column tile
     }
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
     if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;

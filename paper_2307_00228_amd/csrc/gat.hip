@@ -29,8 +29,10 @@ struct GatArgs {
     int32_t row_vecs, heads, dh, act;
     float slope;
     int32_t small_limit;
+    int32_t long_limit;    // rows with more in-edges go to the work list and get a whole block
+    int32_t *long_list;
+    uint32_t *long_count;
     // hub passes
-    int32_t sub_parts;     // pieces per shadow segment (one wavefront and one partial state each)
     int64_t n_shadows;
     const int64_t *shadow_begin, *shadow_end;
     const int32_t *shadow_owner;
@@ -127,12 +129,13 @@ __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
 // edges congruent to g modulo 64/G in every 64-edge chunk; on return all lane groups hold the merged state.
 template <bool BF16, int G>
 __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPerVec> &st, const GatArgs &a, int64_t start,
-                                                     int64_t deg, float sd, int vec, int hk, bool lane_on) {
+                                                     int64_t deg, float sd, int vec, int hk, bool lane_on,
+                                                     int first_chunk = 0, int chunk_stride = 1) {
     constexpr int NG = kWave / G;
     constexpr int U = 4;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
-    for (int64_t c = 0; c < deg; c += kWave) {
+    for (int64_t c = (int64_t)first_chunk * kWave; c < deg; c += (int64_t)chunk_stride * kWave) {
         int myc = 0;
         if (c + lane < deg) myc = a.col[start + c + lane];
         const int cnt = (deg - c < kWave) ? (int)(deg - c) : kWave;
@@ -202,7 +205,17 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
     const bool mine = my_row < a.n_nodes && rs >= a.edge_lo && rs < a.edge_hi && deg64 <= a.threshold;
     const int deg = (int)deg64;
     const uint64_t small_mask = __ballot(mine && deg <= a.small_limit);
-    uint64_t large_mask = __ballot(mine && deg > a.small_limit);
+    uint64_t large_mask = __ballot(mine && deg > a.small_limit && deg <= a.long_limit);
+    const uint64_t long_mask = __ballot(mine && deg > a.long_limit);
+    if (long_mask) {  // hand the long rows to the block-per-row kernel (the list order enters no result)
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(a.long_count, (uint32_t)__popcll(long_mask));
+        base = __shfl(base, 0, kWave);
+        if ((long_mask >> lane) & 1ull) {
+            const uint64_t below = (lane == 0) ? 0ull : (long_mask & (~0ull >> (kWave - lane)));
+            a.long_list[base + (uint32_t)__popcll(below)] = (int32_t)my_row;
+        }
+    }
 
     if (small_mask) {
         for (int sub = 0; sub < kWave; sub += NG) {
@@ -272,17 +285,57 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
     }
 }
 
-// One wavefront per shadow segment: the partial softmax state (without the self edge).
+constexpr int kRangeWaves = 8;  // wavefronts that share one edge range (a shadow segment or a long row)
+
+// Block-cooperative pass over one edge range: wave w takes the 64-edge chunks congruent to w modulo kRangeWaves,
+// the wave states are merged in wave order.  `st` is the caller's starting state for wave 0's lane group 0
+// (the self edge, or empty); every other lane group starts empty.  On return lane group 0 of wave 0 holds
+// the merged state.
 template <bool BF16, int G>
-__global__ __launch_bounds__(256) void gat_segments_kernel(GatArgs a) {
+__device__ __forceinline__ void block_range_softmax(SoftState<Elems<BF16>::kPerVec> &st, const GatArgs &a, int64_t start,
+                                                    int64_t deg, float sd, int vec, int hk, bool lane_on, float *sm) {
     constexpr int VE = Elems<BF16>::kPerVec;
+    constexpr int SV = VE + 2;  // floats per lane state
     const int lane = threadIdx.x & (kWave - 1);
-    const int g = lane / G;
+    const int w = threadIdx.x / kWave;
+    if (!(w == 0 && lane < G)) {
+        st.m = kNegInf;
+        st.l = 0.f;
+#pragma unroll
+        for (int i = 0; i < VE; ++i) st.acc[i] = 0.f;
+    }
+    wave_segment_softmax<BF16, G>(st, a, start, deg, sd, vec, hk, lane_on, w, kRangeWaves);
+    __syncthreads();  // the buffer may still be read from the previous range
+    if (lane < G) {
+        float *o = sm + (w * G + lane) * SV;
+        o[0] = st.m;
+        o[1] = st.l;
+#pragma unroll
+        for (int i = 0; i < VE; ++i) o[2 + i] = st.acc[i];
+    }
+    __syncthreads();
+    if (w == 0 && lane < G) {
+        for (int ww = 1; ww < kRangeWaves; ++ww) {
+            const float *o = sm + (ww * G + lane) * SV;
+            const float m2 = o[0], l2 = o[1];
+            const float M = fmaxf(st.m, m2);
+            const float s1 = __expf(st.m - M), s2 = __expf(m2 - M);
+            st.l = st.l * s1 + l2 * s2;
+#pragma unroll
+            for (int i = 0; i < VE; ++i) st.acc[i] = st.acc[i] * s1 + o[2 + i] * s2;
+            st.m = M;
+        }
+    }
+}
+
+// One block per shadow segment: the partial softmax state (without the self edge).
+template <bool BF16, int G>
+__global__ __launch_bounds__(kRangeWaves * kWave) void gat_segments_kernel(GatArgs a) {
+    constexpr int VE = Elems<BF16>::kPerVec;
+    __shared__ float sm[kRangeWaves * G * (VE + 2)];
+    const int lane = threadIdx.x & (kWave - 1);
     const int li = lane % G;
-    const int64_t p = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    const int64_t s = p / a.sub_parts;
-    const int64_t f = p % a.sub_parts;
-    if (s >= a.n_shadows) return;
+    const int64_t s = blockIdx.x;
     const int64_t v = a.shadow_owner[s];
     const int64_t owner_start = a.rowptr[v];
     if (owner_start < a.edge_lo || owner_start >= a.edge_hi) return;
@@ -295,21 +348,48 @@ __global__ __launch_bounds__(256) void gat_segments_kernel(GatArgs a) {
     st.l = 0.f;
 #pragma unroll
     for (int i = 0; i < VE; ++i) st.acc[i] = 0.f;
-    const int64_t sb = a.shadow_begin[s];
-    const int64_t len = a.shadow_end[s] - sb;
-    const int64_t b = sb + f * len / a.sub_parts;
-    const int64_t e = sb + (f + 1) * len / a.sub_parts;
-    wave_segment_softmax<BF16, G>(st, a, b, e - b, sd, vec, hk, lane_on);
-    if (g == 0 && lane_on) {
-        float4 *o = reinterpret_cast<float4 *>(a.part_acc + (p * a.row_vecs + vec) * VE);
+    const int64_t b = a.shadow_begin[s];
+    block_range_softmax<BF16, G>(st, a, b, a.shadow_end[s] - b, sd, vec, hk, lane_on, sm);
+    if (threadIdx.x < G && lane_on) {
+        float4 *o = reinterpret_cast<float4 *>(a.part_acc + (s * a.row_vecs + vec) * VE);
         o[0] = make_float4(st.acc[0], st.acc[1], st.acc[2], st.acc[3]);
         if constexpr (VE == 8) o[1] = make_float4(st.acc[4], st.acc[5], st.acc[6], st.acc[7]);
         if ((vec * VE) % a.dh == 0) {   // one lane per head records the scalar state
-            a.part_m[p * a.heads + hk] = st.m;
-            a.part_l[p * a.heads + hk] = st.l;
+            a.part_m[s * a.heads + hk] = st.m;
+            a.part_l[s * a.heads + hk] = st.l;
         }
     }
 }
+
+// Long rows from the work list, one block per row at a time.
+template <bool BF16, int G>
+__global__ __launch_bounds__(kRangeWaves * kWave) void gat_long_rows_kernel(GatArgs a) {
+    constexpr int VE = Elems<BF16>::kPerVec;
+    __shared__ float sm[kRangeWaves * G * (VE + 2)];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int li = lane % G;
+    const int vec = blockIdx.y * G + li;
+    const bool lane_on = vec < a.row_vecs;
+    const int hk = lane_on ? (vec * VE) / a.dh : 0;
+    const uint32_t count = *a.long_count;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const int64_t v = a.long_list[i];
+        const int64_t b = a.rowptr[v];
+        const int64_t d = a.rowptr[v + 1] - b;
+        const float sd = lane_on ? a.s_dst[v * a.heads + hk] : 0.f;
+        SoftState<VE> st;
+        {   // the implicit self edge starts the state of wave 0's lane group 0
+            const uint4 raw = lane_on ? a.z[v * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
+            st.m = lane_on ? leaky(a.s_src[v * a.heads + hk] + sd, a.slope) : 0.f;
+            st.l = 1.f;
+            unpack<BF16>(st.acc, raw);
+        }
+        block_range_softmax<BF16, G>(st, a, b, d, sd, vec, hk, lane_on, sm);
+        if (threadIdx.x < G && lane_on) finish_store<BF16, VE>(a, v, vec, st.acc, st.l);
+    }
+}
+
+__global__ void zero_u32_kernel(uint32_t *p) { *p = 0u; }
 
 // One block per hub.  Per head: M = max over the segment maxima and the self score (exact, order-free), then
 // the rescaled partials are added in ascending segment order within interleaved chains and the chains in
@@ -324,7 +404,7 @@ __global__ __launch_bounds__(1024) void gat_combine_kernel(GatArgs a, int64_t n_
     const int64_t v = hub_ids[blockIdx.x];
     const int64_t rs = a.rowptr[v];
     if (rs < a.edge_lo || rs >= a.edge_hi) return;
-    const int64_t s0 = hub_shadow_off[blockIdx.x] * a.sub_parts, s1 = hub_shadow_off[blockIdx.x + 1] * a.sub_parts;
+    const int64_t s0 = hub_shadow_off[blockIdx.x], s1 = hub_shadow_off[blockIdx.x + 1];
     const int dim = a.row_vecs * VE;
     const int lanes_per_row = dim / 4;
 
@@ -350,7 +430,26 @@ __global__ __launch_bounds__(1024) void gat_combine_kernel(GatArgs a, int64_t n_
         float l = 0.f;
         if (slice < slices) {
             const float4 *p = reinterpret_cast<const float4 *>(a.part_acc) + q0 + lv;
-            for (int64_t s = s0 + slice; s < s1; s += slices) {
+            int64_t s = s0 + slice;
+            for (; s + 3 * (int64_t)slices < s1; s += 4 * (int64_t)slices) {   // four partials in flight, added in order
+                float w[4], pl[4];
+                float4 x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t su = s + u * (int64_t)slices;
+                    w[u] = a.part_m[su * a.heads + hk];
+                    pl[u] = a.part_l[su * a.heads + hk];
+                    x[u] = p[su * lanes_per_row];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float wu = __expf(w[u] - M);
+                    acc.x = fmaf(x[u].x, wu, acc.x); acc.y = fmaf(x[u].y, wu, acc.y);
+                    acc.z = fmaf(x[u].z, wu, acc.z); acc.w = fmaf(x[u].w, wu, acc.w);
+                    l = fmaf(pl[u], wu, l);
+                }
+            }
+            for (; s < s1; s += slices) {
                 const float w = __expf(a.part_m[s * a.heads + hk] - M);
                 const float4 x = p[s * lanes_per_row];
                 acc.x = fmaf(x.x, w, acc.x); acc.y = fmaf(x.y, w, acc.y); acc.z = fmaf(x.z, w, acc.z); acc.w = fmaf(x.w, w, acc.w);
@@ -405,10 +504,15 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
                    hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
     const unsigned gy = (unsigned)((a.row_vecs + G - 1) / G);
+    zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
+    ITB_LAUNCH_CHECK();
     gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
+    int64_t lg = waves > 2048 ? 2048 : waves;  // fixed grid over the device-side work list
+    gat_long_rows_kernel<BF16, G><<<dim3((unsigned)lg, gy), kRangeWaves * kWave, 0, st>>>(a);
+    ITB_LAUNCH_CHECK();
     if (hubs) {
-        gat_segments_kernel<BF16, G><<<dim3((unsigned)((a.n_shadows * a.sub_parts + 3) / 4), gy), 256, 0, st>>>(a);
+        gat_segments_kernel<BF16, G><<<dim3((unsigned)a.n_shadows, gy), kRangeWaves * kWave, 0, st>>>(a);
         ITB_LAUNCH_CHECK();
         gat_combine_kernel<BF16><<<(unsigned)n_hubs, 1024, 0, st>>>(a, n_hubs, hub_ids, hub_shadow_off);
         ITB_LAUNCH_CHECK();
@@ -434,7 +538,7 @@ int32_t dispatch(int G, const GatArgs &a, bool hubs, int64_t n_hubs, const int32
 
 namespace itb {
 extern int g_small_limit;
-int segment_sub_parts(int64_t threshold);
+extern int g_long_row;
 
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
@@ -447,11 +551,12 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     const int ve = bf16 ? 8 : 4;
     if (dh % ve != 0) return ITB_ERR_UNSUPPORTED;  // a lane's 16-byte vector must lie inside one head
     const bool hubs = split && split->n_hubs > 0;
-    const int sub_parts = hubs ? segment_sub_parts(split->threshold) : 1;
     Carver cv(workspace);
-    float *part_acc = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->dim : 0);
-    float *part_m = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->heads : 0);
-    float *part_l = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->heads : 0);
+    uint32_t *long_count = cv.take<uint32_t>(64);
+    int32_t *long_list = cv.take<int32_t>((size_t)n_nodes);
+    float *part_acc = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
+    float *part_m = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->heads : 0);
+    float *part_l = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->heads : 0);
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -482,9 +587,11 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     int G = 1;
     while (G < a.row_vecs && G < kWave) G <<= 1;
     a.small_limit = g_small_limit >= 0 ? g_small_limit : 2 * (kWave / G);
+    a.long_limit = g_long_row > a.small_limit ? g_long_row : a.small_limit;
+    a.long_list = long_list;
+    a.long_count = long_count;
     if (hubs) {
         a.n_shadows = split->n_shadows;
-        a.sub_parts = sub_parts;
         a.shadow_begin = split->shadow_begin;
         a.shadow_end = split->shadow_end;
         a.shadow_owner = split->shadow_owner;

@@ -10,21 +10,20 @@
 //     combining the group partials;
 //   * column indices (and per-source scales) are fetched 64 (or G) at a time with one coalesced load and
 //     handed to the lane groups by cross-lane shuffles, so the dependent row loads are issued back to back;
-//   * hub rows (in-degree > threshold) are skipped here; their shadow segments are summed one wavefront per
-//     segment into fp32 partials and a block per hub adds the partials in ascending segment order.
+//   * rows longer than kLongRow edges would leave one wavefront working alone for a long time, so the row
+//     kernel only appends their ids to a work list (integer atomics; the list order does not enter any
+//     result) and a second kernel gives each such row a whole 8-wave block;
+//   * hub rows (in-degree > threshold) are skipped here; each shadow segment is summed by one 8-wave block
+//     into one fp32 partial (wave w takes the 64-edge chunks congruent to w, the wave results are added in
+//     wave order through LDS) and a block per hub adds the partials in ascending segment order.
 // No floating-point atomics anywhere: every summation order is a function of the sizes only.
 #include "common.h"
 
 namespace itb {
 extern int g_csr_xcd_remap;
-int g_segment_piece = 2048;  // tuning hook (key 3): target edges per wavefront in the hub passes
-// pieces per shadow segment: a function of the threshold only, so partial layouts are reproducible
-int segment_sub_parts(int64_t threshold) {
-    int64_t f = (threshold + g_segment_piece - 1) / g_segment_piece;
-    return (int)(f < 1 ? 1 : (f > 64 ? 64 : f));
-}
-int g_small_limit = -1;   // tuning hook: rows with in-degree <= limit use one lane group per row (-1 = auto)
+int g_small_limit = -1;   // tuning hook (key 0): rows with in-degree <= limit use one lane group per row (-1 = auto)
 int g_gather_unroll = 4;  // reserved
+int g_long_row = 512;     // tuning hook (key 3): rows with more in-edges get a whole block
 }  // namespace itb
 
 namespace {
@@ -45,8 +44,10 @@ struct GatherArgs {
     int32_t row_vecs;        // 16-byte vectors per input row
     int32_t mode;
     int32_t small_limit;
+    int32_t long_limit;      // rows with more in-edges than this go to the work list
+    int32_t *long_list;      // [n_nodes] work list of long rows
+    uint32_t *long_count;    // its length
     // segment kernel only
-    int32_t sub_parts;       // every shadow segment is cut evenly into this many pieces, one wavefront and one partial each
     int64_t n_shadows;
     const int64_t *shadow_begin, *shadow_end;
     const int32_t *shadow_owner;
@@ -118,11 +119,13 @@ __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
     return ((int64_t)hi << 32) | (uint32_t)lo;
 }
 
-// Whole-wavefront sum of h[col[e]] * scale over the edge range [start, start+deg).  Group g takes the edges
-// congruent to g modulo 64/G inside every 64-edge chunk; on return every lane group holds the full sum.
+// Whole-wavefront sum of h[col[e]] * scale over the 64-edge chunks first_chunk, first_chunk + chunk_stride, ...
+// of the edge range [start, start+deg).  Group g takes the edges congruent to g modulo 64/G inside every
+// chunk; on return every lane group holds the sum over all the wavefront's chunks.
 template <bool BF16, int G>
 __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerVec], const GatherArgs &a, int64_t start,
-                                                 int64_t deg, int vec, bool lane_on) {
+                                                 int64_t deg, int vec, bool lane_on, int first_chunk = 0,
+                                                 int chunk_stride = 1) {
     constexpr int NG = kWave / G;
     constexpr int VE = Elems<BF16>::kPerVec;
     constexpr int U = 4;
@@ -131,7 +134,7 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
     const bool has_scale = a.src_scale != nullptr;
 #pragma unroll
     for (int i = 0; i < VE; ++i) acc[i] = 0.f;
-    for (int64_t c = 0; c < deg; c += kWave) {
+    for (int64_t c = (int64_t)first_chunk * kWave; c < deg; c += (int64_t)chunk_stride * kWave) {
         int myc = 0;
         float mys = 1.f;
         if (c + lane < deg) {
@@ -187,7 +190,17 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     const bool mine = my_row < a.n_nodes && rs >= a.edge_lo && rs < a.edge_hi && deg64 <= a.threshold;
     const int deg = (int)deg64;
     const uint64_t small_mask = __ballot(mine && deg <= a.small_limit);
-    uint64_t large_mask = __ballot(mine && deg > a.small_limit);
+    uint64_t large_mask = __ballot(mine && deg > a.small_limit && deg <= a.long_limit);
+    const uint64_t long_mask = __ballot(mine && deg > a.long_limit);
+    if (long_mask) {  // hand the long rows to the block-per-row kernel
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(a.long_count, (uint32_t)__popcll(long_mask));
+        base = __shfl(base, 0, kWave);
+        if ((long_mask >> lane) & 1ull) {
+            const uint64_t below = (lane == 0) ? 0ull : (long_mask & (~0ull >> (kWave - lane)));
+            a.long_list[base + (uint32_t)__popcll(below)] = (int32_t)my_row;
+        }
+    }
 
     // ---- rows with few in-edges: one lane group per row, 64/G rows at a time ----------------------------
     if (small_mask) {
@@ -249,31 +262,75 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     }
 }
 
-// One wavefront per piece of a shadow segment: fp32 partial sums (source scales applied, destination finish
-// deferred).  Segments of up to `threshold` edges are cut into sub_parts even pieces so that a few thousand
-// segments still put enough independent row loads in flight to cover the memory latency.
-template <bool BF16_IN, int G>
-__global__ __launch_bounds__(256) void gather_segments_kernel(GatherArgs a) {
-    constexpr int VE = Elems<BF16_IN>::kPerVec;
+constexpr int kRangeWaves = 8;  // wavefronts that share one edge range (a shadow segment or a long row)
+
+// Block-cooperative sum over one edge range: wave w takes the 64-edge chunks congruent to w modulo kRangeWaves,
+// the wave results are added in wave order.  On return lane group 0 of wave 0 holds the sum.
+template <bool BF16, int G>
+__device__ __forceinline__ void block_range_sum(float (&acc)[Elems<BF16>::kPerVec], const GatherArgs &a, int64_t start,
+                                                int64_t deg, int vec, bool lane_on, float *sm) {
+    constexpr int VE = Elems<BF16>::kPerVec;
     const int lane = threadIdx.x & (kWave - 1);
-    const int g = lane / G;
+    const int w = threadIdx.x / kWave;
+    wave_segment_sum<BF16, G>(acc, a, start, deg, vec, lane_on, w, kRangeWaves);
+    __syncthreads();  // the buffer may still be read from the previous range
+    if (lane < G) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) sm[(w * G + lane) * VE + i] = acc[i];
+    }
+    __syncthreads();
+    if (w == 0 && lane < G) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) acc[i] = 0.f;
+        for (int ww = 0; ww < kRangeWaves; ++ww) {
+#pragma unroll
+            for (int i = 0; i < VE; ++i) acc[i] += sm[(ww * G + lane) * VE + i];
+        }
+    }
+}
+
+// One block per shadow segment: one fp32 partial row (source scales applied, destination finish deferred).
+template <bool BF16_IN, int G>
+__global__ __launch_bounds__(kRangeWaves * kWave) void gather_segments_kernel(GatherArgs a) {
+    constexpr int VE = Elems<BF16_IN>::kPerVec;
+    __shared__ float sm[kRangeWaves * G * VE];
+    const int lane = threadIdx.x & (kWave - 1);
     const int li = lane % G;
-    const int64_t p = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    const int64_t s = p / a.sub_parts;
-    const int64_t f = p % a.sub_parts;
-    if (s >= a.n_shadows) return;
+    const int64_t s = blockIdx.x;
     const int64_t owner_start = a.rowptr[a.shadow_owner[s]];
     if (owner_start < a.edge_lo || owner_start >= a.edge_hi) return;
     const int vec = blockIdx.y * G + li;
     const bool lane_on = vec < a.row_vecs;
-    const int64_t sb = a.shadow_begin[s];
-    const int64_t len = a.shadow_end[s] - sb;
-    const int64_t b = sb + f * len / a.sub_parts;
-    const int64_t e = sb + (f + 1) * len / a.sub_parts;
+    const int64_t b = a.shadow_begin[s];
     float acc[VE];
-    wave_segment_sum<BF16_IN, G>(acc, a, b, e - b, vec, lane_on);
-    if (g == 0 && lane_on) store_row_slice<BF16_IN, false>(a.out, p, a.row_vecs, vec, acc);
+    block_range_sum<BF16_IN, G>(acc, a, b, a.shadow_end[s] - b, vec, lane_on, sm);
+    if (threadIdx.x < G && lane_on) store_row_slice<BF16_IN, false>(a.out, s, a.row_vecs, vec, acc);
 }
+
+// Long rows from the work list, one block per row at a time.
+template <bool BF16_IN, bool BF16_OUT, int G>
+__global__ __launch_bounds__(kRangeWaves * kWave) void gather_long_rows_kernel(GatherArgs a) {
+    constexpr int VE = Elems<BF16_IN>::kPerVec;
+    __shared__ float sm[kRangeWaves * G * VE];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int li = lane % G;
+    const int vec = blockIdx.y * G + li;
+    const bool lane_on = vec < a.row_vecs;
+    const uint32_t count = *a.long_count;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const int64_t row = a.long_list[i];
+        const int64_t b = a.rowptr[row];
+        const int64_t d = a.rowptr[row + 1] - b;
+        float acc[VE];
+        block_range_sum<BF16_IN, G>(acc, a, b, d, vec, lane_on, sm);
+        if (threadIdx.x < G && lane_on) {
+            finish_row<VE>(acc, a.mode, d, a.dst_scale, row);
+            store_row_slice<BF16_IN, BF16_OUT>(a.out, row, a.row_vecs, vec, acc);
+        }
+    }
+}
+
+__global__ void zero_u32_kernel(uint32_t *p) { *p = 0u; }
 
 // One block per hub: partial rows are added in ascending segment order within each of `slices` interleaved
 // chains, then the chains are added in ascending slice order.
@@ -281,14 +338,14 @@ template <bool BF16_OUT>
 __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, int32_t dim, int64_t n_hubs,
                                                             const int32_t *hub_ids, const int64_t *hub_shadow_off,
                                                             const int64_t *rowptr, const float *dst_scale, int32_t mode,
-                                                            int64_t edge_lo, int64_t edge_hi, int32_t sub_parts, void *out) {
+                                                            int64_t edge_lo, int64_t edge_hi, void *out) {
     __shared__ float4 sm[1024];
     const int64_t hub = blockIdx.x;
     const int32_t v = hub_ids[hub];
     const int64_t rs = rowptr[v];
     if (rs < edge_lo || rs >= edge_hi) return;
     const int64_t deg = rowptr[v + 1] - rs;
-    const int64_t s0 = hub_shadow_off[hub] * sub_parts, s1 = hub_shadow_off[hub + 1] * sub_parts;  // partial rows
+    const int64_t s0 = hub_shadow_off[hub], s1 = hub_shadow_off[hub + 1];
     const int lanes_per_row = dim / 4;
     for (int q0 = 0; q0 < lanes_per_row; q0 += 1024) {  // column tiles of 4096 elements
         const int cols_here = (lanes_per_row - q0 < 1024) ? (lanes_per_row - q0) : 1024;
@@ -342,7 +399,14 @@ int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
     dim3 grid((unsigned)((waves + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
     if (a.n_nodes > 0) {
+        zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
+        ITB_LAUNCH_CHECK();
         gather_rows_kernel<BF16_IN, BF16_OUT, G><<<grid, 256, 0, st>>>(a);
+        ITB_LAUNCH_CHECK();
+        // the list length is only known on the device: a fixed grid walks it (blocks beyond the length exit)
+        int64_t lg = (a.n_nodes + 63) / 64;
+        if (lg > 2048) lg = 2048;
+        gather_long_rows_kernel<BF16_IN, BF16_OUT, G><<<dim3((unsigned)lg, grid.y), kRangeWaves * kWave, 0, st>>>(a);
         ITB_LAUNCH_CHECK();
     }
     return ITB_OK;
@@ -350,8 +414,8 @@ int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
 
 template <bool BF16_IN, int G>
 int32_t launch_segments(const GatherArgs &a, hipStream_t st) {
-    dim3 grid((unsigned)((a.n_shadows * a.sub_parts + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
-    gather_segments_kernel<BF16_IN, G><<<grid, 256, 0, st>>>(a);
+    dim3 grid((unsigned)a.n_shadows, (unsigned)((a.row_vecs + G - 1) / G));
+    gather_segments_kernel<BF16_IN, G><<<grid, kRangeWaves * kWave, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -410,9 +474,10 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
 
     if (desc->bias || desc->act != ITB_ACT_NONE) return ITB_ERR_UNSUPPORTED;  // epilogue exists for the GAT reduce only
     const bool hubs = split && split->n_hubs > 0;
-    const int sub_parts = hubs ? itb::segment_sub_parts(split->threshold) : 1;
     Carver cv(workspace);
-    float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * sub_parts * desc->dim : 0);
+    uint32_t *long_count = cv.take<uint32_t>(64);
+    int32_t *long_list = cv.take<int32_t>((size_t)n_nodes);
+    float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -442,6 +507,9 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     while (G < a.row_vecs && G < kWave) G <<= 1;
     const int ng = kWave / G;
     a.small_limit = g_small_limit >= 0 ? g_small_limit : 2 * ng;
+    a.long_limit = g_long_row > a.small_limit ? g_long_row : a.small_limit;
+    a.long_list = long_list;
+    a.long_count = long_count;
 
     const bool bin = desc->dtype_in == ITB_BF16, bout = desc->dtype_out == ITB_BF16;
     int32_t rc;
@@ -453,7 +521,6 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     if (hubs) {
         GatherArgs s = a;
         s.out = part;
-        s.sub_parts = sub_parts;
         s.n_shadows = split->n_shadows;
         s.shadow_begin = split->shadow_begin;
         s.shadow_end = split->shadow_end;
@@ -463,11 +530,11 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         if (bout)
             combine_hubs_kernel<true><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
                                                                                 split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
-                                                                                edge_lo, edge_hi, sub_parts, agg_out);
+                                                                                edge_lo, edge_hi, agg_out);
         else
             combine_hubs_kernel<false><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
                                                                                  split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
-                                                                                 edge_lo, edge_hi, sub_parts, agg_out);
+                                                                                 edge_lo, edge_hi, agg_out);
         ITB_LAUNCH_CHECK();
     }
     return ITB_OK;
@@ -477,6 +544,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 0) { itb::g_small_limit = value; return ITB_OK; }
     if (key == 1) { itb::g_gather_unroll = value; return ITB_OK; }
     if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
-    if (key == 3 && value > 0) { itb::g_segment_piece = value; return ITB_OK; }
+    if (key == 3 && value > 0) { itb::g_long_row = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }

@@ -1,8 +1,10 @@
 // split_hubs: even split of every high-in-degree row into contiguous segments ("shadow" mirrors).
 //
-// Three small kernels over the row pointers: per-block (hub, segment) counts, a single-block exclusive scan
-// of those counts, and an emit pass that recomputes the in-block prefix and writes the arrays in ascending
-// vertex order.  Integer only; the output is unique.
+// Small kernels over the row pointers: per-block (hub, segment) counts, a single-block exclusive scan of those
+// counts, an emit pass that recomputes the in-block prefix and writes the hub arrays in ascending vertex
+// order, and one thread per segment that finds its hub by binary search and writes its bounds (a hub with
+// millions of in-edges has thousands of segments, so they must not be written by one thread).
+// Integer only; the output is unique.
 #include "common.h"
 
 namespace {
@@ -68,8 +70,7 @@ __global__ __launch_bounds__(1024) void hub_scan_kernel(int64_t *blk_hubs, int64
 
 __global__ __launch_bounds__(kThreads) void hub_emit_kernel(const int64_t *rowptr, int64_t n_nodes, int64_t threshold,
                                                             const int64_t *blk_hubs, const int64_t *blk_segs,
-                                                            const int64_t *totals, int32_t *hub_ids, int64_t *hub_shadow_off,
-                                                            int64_t *shadow_begin, int64_t *shadow_end, int32_t *shadow_owner) {
+                                                            const int64_t *totals, int32_t *hub_ids, int64_t *hub_shadow_off) {
     __shared__ int64_t sm[17];
     const int64_t row0 = (int64_t)blockIdx.x * kRowsPerBlock + (int64_t)threadIdx.x * kRowsPerThread;
     int64_t h, s, th, ts;
@@ -81,20 +82,35 @@ __global__ __launch_bounds__(kThreads) void hub_emit_kernel(const int64_t *rowpt
     for (int i = 0; i < kRowsPerThread; ++i) {
         const int64_t v = row0 + i;
         if (v >= n_nodes) break;
-        const int64_t b = rowptr[v];
-        const int64_t d = rowptr[v + 1] - b;
+        const int64_t d = rowptr[v + 1] - rowptr[v];
         if (d > threshold) {
-            const int64_t n = (d + threshold - 1) / threshold;
             hub_ids[hi] = (int32_t)v;
             hub_shadow_off[hi] = si;
-            for (int64_t g = 0; g < n; ++g) {
-                shadow_begin[si + g] = b + (g * d) / n;   // g*d < 2^62: d < 2^31 and n <= d
-                shadow_end[si + g] = b + ((g + 1) * d) / n;
-                shadow_owner[si + g] = (int32_t)v;
-            }
             hi += 1;
-            si += n;
+            si += (d + threshold - 1) / threshold;
         }
+    }
+}
+
+// Segment s belongs to the hub h with hub_shadow_off[h] <= s < hub_shadow_off[h+1]; it is group g = s - off[h]
+// of n = off[h+1] - off[h] and covers [floor(g*d/n), floor((g+1)*d/n)) of the hub's row.
+__global__ void segment_emit_kernel(const int64_t *rowptr, int64_t n_hubs, int64_t n_shadows, const int32_t *hub_ids,
+                                    const int64_t *hub_shadow_off, int64_t *shadow_begin, int64_t *shadow_end,
+                                    int32_t *shadow_owner) {
+    for (int64_t s = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; s < n_shadows; s += (int64_t)gridDim.x * blockDim.x) {
+        int64_t lo = 0, hi = n_hubs - 1;  // last h with off[h] <= s
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if (hub_shadow_off[mid] <= s) lo = mid; else hi = mid - 1;
+        }
+        const int64_t v = hub_ids[lo];
+        const int64_t b = rowptr[v];
+        const int64_t d = rowptr[v + 1] - b;
+        const int64_t n = hub_shadow_off[lo + 1] - hub_shadow_off[lo];
+        const int64_t g = s - hub_shadow_off[lo];
+        shadow_begin[s] = b + (g * d) / n;   // g*d < 2^62: d < 2^31 and n <= d
+        shadow_end[s] = b + ((g + 1) * d) / n;
+        shadow_owner[s] = (int32_t)v;
     }
 }
 
@@ -136,8 +152,15 @@ extern "C" int32_t split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t th
     if (host_totals[0] > 0 && (!hub_ids || !shadow_begin || !shadow_end || !shadow_owner)) return ITB_ERR_NULL;
     if (nblocks > 0) {
         hub_emit_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(rowptr, n_nodes, threshold, blk_hubs, blk_segs, totals,
-                                                              hub_ids, hub_shadow_off, shadow_begin, shadow_end, shadow_owner);
+                                                              hub_ids, hub_shadow_off);
         ITB_LAUNCH_CHECK();
+        if (host_totals[1] > 0) {
+            int64_t g = (host_totals[1] + 255) / 256;
+            if (g > 65536) g = 65536;
+            segment_emit_kernel<<<(unsigned)g, 256, 0, st>>>(rowptr, host_totals[0], host_totals[1], hub_ids, hub_shadow_off,
+                                                            shadow_begin, shadow_end, shadow_owner);
+            ITB_LAUNCH_CHECK();
+        }
     } else {
         ITB_HIP(hipMemsetAsync(hub_shadow_off, 0, sizeof(int64_t), st));
     }
