@@ -140,20 +140,40 @@ def destinations_from_degrees(rng, deg_by_slot: np.ndarray, n_nodes: int) -> np.
     return np.repeat(ids, deg_by_slot)
 
 
-def shuffle_edges(rng, src: np.ndarray, dst: np.ndarray):
-    p = rng.permutation(len(src))
-    return np.ascontiguousarray(src[p]), np.ascontiguousarray(dst[p])
+def shuffle_edges(rng, src: np.ndarray, dst: np.ndarray, log=None):
+    """Deliver the edge list unsorted.  Up to 2^27 edges: one uniform permutation.  Beyond that (where a single
+    permutation would take minutes and tens of GB): a stride-64 interleave followed by an independent uniform
+    permutation inside each of the 64 parts -- every part draws from the whole destination range."""
+    e = len(src)
+    if e <= (1 << 27):
+        p = rng.permutation(e)
+        return np.ascontiguousarray(src[p]), np.ascontiguousarray(dst[p])
+    parts = 64
+    out_s, out_d = np.empty_like(src), np.empty_like(dst)
+    pos = 0
+    for k in range(parts):
+        s_k, d_k = src[k::parts], dst[k::parts]
+        p = rng.permutation(len(s_k))
+        out_s[pos:pos + len(s_k)] = s_k[p]
+        out_d[pos:pos + len(d_k)] = d_k[p]
+        pos += len(s_k)
+        if log and k % 8 == 7:
+            log(f"  shuffle: part {k + 1}/{parts}")
+    return out_s, out_d
 
 
 # ----------------------------------------------------------------------------
 # features and weights
 # ----------------------------------------------------------------------------
-def normal_features(rng, n: int, d: int, dtype: str) -> np.ndarray:
-    out = np.empty((n, d), dtype=np.float32)
+def normal_features(rng, n: int, d: int, dtype: str, log=None) -> np.ndarray:
+    """N(0,1) features in the storage dtype, drawn and rounded chunk by chunk (bounded temporary memory)."""
+    out = np.empty((n, d), dtype=np.uint16 if dtype == BF16 else np.float32)
     step = max(1, (1 << 24) // max(d, 1))
-    for i in range(0, n, step):
-        out[i:i + step] = rng.standard_normal((min(step, n - i), d), dtype=np.float32)
-    return store(out, dtype)
+    for k, i in enumerate(range(0, n, step)):
+        out[i:i + step] = store(rng.standard_normal((min(step, n - i), d), dtype=np.float32), dtype)
+        if log and k % 64 == 63:
+            log(f"  features: {min(i + step, n)}/{n} rows")
+    return out
 
 
 def glorot(rng, fan_in: int, fan_out: int, shape, dtype: str) -> np.ndarray:
@@ -202,10 +222,12 @@ NAMES = ("tiny_powerlaw", "medium_uniform", "hub_heavy", "hub_heavy_uniform_cont
 
 
 def make(name: str, scale: float = 1.0, seed: int = 0, bias_random: bool = False,
-         features: bool = True) -> Workload:
+         features: bool = True, log=None) -> Workload:
     """Build a named workload.  ``scale`` shrinks node and edge counts together
-    (hub sizes and thresholds shrink with it) for parity tests; 1.0 is the full size."""
+    (hub sizes and thresholds shrink with it) for parity tests; 1.0 is the full size.
+    ``log`` (e.g. ``print``) receives a line per generation stage of the large workloads."""
     topo, feat, wts = _rng(seed, 1), _rng(seed, 2), _rng(seed, 3)
+    say = log or (lambda msg: None)
 
     def sz(v, lo=1):
         return max(lo, int(round(v * scale)))
@@ -250,11 +272,18 @@ def make(name: str, scale: float = 1.0, seed: int = 0, bias_random: bool = False
     elif name == "huge_share":
         n, e = sz(100_000_000, 64), sz(2_000_000_000, 1024)
         d_max = max(2, sz(10_000_000))
+        say(f"huge_share: degree sequence for {n} vertices")
         deg = power_law_degree_sequence(topo, n, e - d_max, 2.0, d_max)
         deg[0] += d_max
+        say(f"huge_share: expanding {e} destinations")
         dst = destinations_from_degrees(topo, deg, n)
-        src = topo.integers(0, n, size=e, dtype=np.int32)
-        src, dst = shuffle_edges(topo, src, dst)
+        del deg
+        say("huge_share: drawing sources")
+        src = np.empty(e, dtype=np.int32)
+        for i in range(0, e, 1 << 27):
+            src[i:i + (1 << 27)] = topo.integers(0, n, size=min(1 << 27, e - i), dtype=np.int32)
+        say("huge_share: shuffling the edge list")
+        src, dst = shuffle_edges(topo, src, dst, log)
         dtype, dims, agg = BF16, (64, 64, 32), AGG_MEAN
         thr = max(4, sz(16384)) if scale < 1.0 else 16384
         recipe = "power-law(2.0) in-degree with one ~1e7 hub, SAGE-mean 64-64-32 bf16, T=16384"
@@ -263,7 +292,8 @@ def make(name: str, scale: float = 1.0, seed: int = 0, bias_random: bool = False
 
     src = np.ascontiguousarray(src, dtype=np.int32)
     dst = np.ascontiguousarray(dst, dtype=np.int32)
-    x = normal_features(feat, n, dims[0], dtype) if features else np.zeros((0, dims[0]), np.float32)
+    say(f"{name}: features {n} x {dims[0]} {dtype}")
+    x = normal_features(feat, n, dims[0], dtype, log) if features else np.zeros((0, dims[0]), np.float32)
     if agg == AGG_GAT:
         layers = gat_layers(wts, dims, 4, dtype, bias_random)
     else:
