@@ -76,6 +76,7 @@ def main():
     is_gat = [l.agg == W.AGG_GAT for l in w.layers]
     states = [torch.empty((N, l.d_out), dtype=tdt, device="cuda") for l in w.layers]
     aggs = [torch.empty((N, l.d_out if g else l.d_in), dtype=tdt, device="cuda") for l, g in zip(w.layers, is_gat)]
+    msgs = [torch.empty((N, l.d_in), dtype=tdt, device="cuda") if l.agg == W.AGG_GCN else None for l in w.layers]
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stamps = {"gather": [], "apply": [], "csr": [], "split": []}
 
@@ -90,6 +91,7 @@ def main():
         if any(l.agg == W.AGG_GCN for l in w.layers):
             ss, sd = B.gcn_norm_scales(rowptr, deg_out)
         h = x
+        msg = None      # source-scaled copy of h (the message a GCN edge carries), written once per vertex
         for i, l in enumerate(layers):
             if is_gat[i]:
                 # GAT order: projection (with the score epilogue) first, then the attention reduce + bias + activation
@@ -102,12 +104,18 @@ def main():
                 b = ev(); b.record()
                 marks.append((a, b, b0, a))
             else:
+                gcn = l.agg == W.AGG_GCN
+                if gcn and msg is None:
+                    msg = B.scale_rows(h, ss, out=msgs[i])
                 a = ev(); a.record()
-                B.gather_layer(l.agg, rowptr, col, h, split if use_split else None, ss, sd, out=aggs[i])
+                B.gather_layer(l.agg, rowptr, col, msg if gcn else h, split if use_split else None, None, sd, out=aggs[i])
                 b = ev(); b.record()
-                B.apply_layer(h, aggs[i], l.w_self, l.w_nbr, l.bias, l.act, out=states[i])
+                next_gcn = i + 1 < L and layers[i + 1].agg == W.AGG_GCN
+                B.apply_layer(h, aggs[i], l.w_self, l.w_nbr, l.bias, l.act, out=states[i],
+                              msg_scale=ss if next_gcn else None, msg_out=msgs[i + 1] if next_gcn else None)
                 c = ev(); c.record()
                 marks.append((a, b, b, c))
+                msg = msgs[i + 1] if next_gcn else None
             h = states[i]
         if record:
             stamps["csr"].append((e0, e1)); stamps["split"].append((e1, e2))

@@ -130,7 +130,9 @@ int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *d
  *
  *   ITB_AGG_SUM : agg[v] = sum over in-edges of h[col]
  *   ITB_AGG_MEAN: the sum divided by the in-degree; 0 for an isolated vertex
- *   ITB_AGG_GCN : dst_scale[v] * sum of src_scale[col] * h[col]  (both required)
+ *   ITB_AGG_GCN : dst_scale[v] * sum of src_scale[col] * h[col]; dst_scale is
+ *                 required; src_scale == NULL means the rows of h_src already
+ *                 carry their source coefficient (see scale_rows / msg_out)
  *   ITB_AGG_GAT : attention-weighted sum, see below.
  *
  *   dim        feature width; dim * sizeof(element) must be a multiple of 16.
@@ -186,7 +188,12 @@ int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
  *   1 <= d_out <= 256, d_in <= 512 (else ITB_ERR_UNSUPPORTED).
  *   att_src/att_dst/s_src/s_dst: optional attention-score epilogue for the GAT
  *   projection: s_src[v,k] = sum_d att_src[k,d] * y[v,k,d] (fp32, from the fp32
- *   accumulators before rounding), heads dividing d_out; NULL/0 to skip.
+ *   accumulators before rounding), heads dividing d_out, heads <= 16, no self
+ *   term; NULL/0 to skip.
+ *   msg_scale/msg_out: optional second output, the message the vertex sends in
+ *   the next round (apply_edge of the scatter stage, Sec. IV-B):
+ *   msg_out[v] = h_out[v] * msg_scale[v] ([n] fp32, [n x d_out] of `dtype`);
+ *   both NULL to skip.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t dtype;
@@ -200,7 +207,18 @@ int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes,
                     const void *w_self, const void *w_nbr, const float *bias,
                     void *h_out,
                     const float *att_src, const float *att_dst, float *s_src, float *s_dst,
+                    const float *msg_scale, void *msg_out,
                     void *stream);
+
+/* ---------------------------------------------------------------------------
+ * scale_rows -- apply_edge for the first round (Sec. IV-B: a vertex generates
+ * its messages from its state; Sec. IV-C: the first round turns the raw
+ * features into what is sent): out[v][:] = x[v][:] * row_scale[v].
+ * x, out [n_nodes x dim] of `dtype`; dim * sizeof(element) multiple of 16.
+ * Later rounds get the same from apply_layer's msg_out.
+ * ------------------------------------------------------------------------- */
+int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, const float *row_scale,
+                   void *out, void *stream);
 
 /* ---------------------------------------------------------------------------
  * infer_full_graph -- the layer loop (Sec. IV-C: after k rounds the result of

@@ -66,12 +66,13 @@ def _load():
     lib.gcn_norm_scales.argtypes = [i64, vp, vp, vp, vp, vp]
     lib.gather_layer.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                  i64, i64, vp, szp, vp]
-    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
                                      vp, vp, i64, vp, szp, vp]
     lib.itb_set_tuning.argtypes = [i32, i32]
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
-    for f in ("itb_copy_bytes", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
+    for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning"):
         getattr(lib, f).restype = i32
     return lib
@@ -207,8 +208,16 @@ def gather_layer(agg: int, rowptr, col, h, split: Optional[Split] = None, src_sc
     return out
 
 
+def scale_rows(x: torch.Tensor, row_scale: torch.Tensor, out: Optional[torch.Tensor] = None):
+    n, dim = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    _check("scale_rows", lib.scale_rows(dtype_code(x), n, dim, _ptr(x), _ptr(row_scale), _ptr(out), _stream()))
+    return out
+
+
 def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.Tensor] = None,
-                heads: int = 0, att_src=None, att_dst=None):
+                heads: int = 0, att_src=None, att_dst=None, msg_scale=None, msg_out=None):
     n, d_in = agg.shape
     d_out = w_nbr.shape[1]
     if out is None:
@@ -219,7 +228,8 @@ def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.
         s_src = torch.empty((n, heads), dtype=torch.float32, device="cuda")
         s_dst = torch.empty((n, heads), dtype=torch.float32, device="cuda")
     _check("apply_layer", lib.apply_layer(C.byref(desc), n, _ptr(h_self), _ptr(agg), _ptr(w_self), _ptr(w_nbr), _ptr(bias),
-                                          _ptr(out), _ptr(att_src), _ptr(att_dst), _ptr(s_src), _ptr(s_dst), _stream()))
+                                          _ptr(out), _ptr(att_src), _ptr(att_dst), _ptr(s_src), _ptr(s_dst),
+                                          _ptr(msg_scale), _ptr(msg_out), _stream()))
     return (out, s_src, s_dst) if heads else out
 
 

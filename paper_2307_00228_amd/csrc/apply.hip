@@ -41,6 +41,9 @@ struct ApplyArgs {
     const float *att_dst;
     float *s_src;          // [n x heads]
     float *s_dst;
+    // message output (the scatter-side apply_edge): msg_out[v] = h_out[v] * msg_scale[v], both nullable together
+    const float *msg_scale;
+    void *msg_out;
 };
 
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
@@ -161,7 +164,7 @@ __device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a
 // PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
 // A fragments are double-buffered by group and the request stream runs on across row tiles (the first
 // fragments of the next tile are requested while the current tile finishes and stores).
-template <bool BF16, int NT, int PF, bool SCORES>
+template <bool BF16, int NT, int PF, bool SCORES, bool MSG>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     constexpr int SPARTS = BF16 ? 2 : 1;  // B fragments of the score tile per chunk (bf16: hi and lo part)
     extern __shared__ uint4 wlds[];
@@ -311,6 +314,12 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                         }
                     }
                     const int64_t off = (row_q + 8 * bq) * a.d_out + colq;
+                    // after step 1 pair jj of a lane belongs to row 8*bq + 4*kh + 2*jj + (i&1) of the tile
+                    float ms0 = 0.f, ms1 = 0.f;
+                    if constexpr (MSG) {
+                        ms0 = a.msg_scale[m0 + 8 * bq + 4 * kh + (i & 1)];
+                        ms1 = a.msg_scale[m0 + 8 * bq + 4 * kh + 2 + (i & 1)];
+                    }
                     if constexpr (BF16) {
                         const uint32_t k0 = pack_bf16x2(p0[0], p1[0]), k1 = pack_bf16x2(p0[1], p1[1]);
                         const uint32_t got = (uint32_t)__shfl_xor((int)(hi ? k0 : k1), 2, kWave);
@@ -318,6 +327,14 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                         o.x = hi ? got : k0;   // lanes with bit1 clear keep pair 0 (their row), receive columns +2,+3
                         o.y = hi ? k1 : got;
                         *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + off) = o;
+                        if constexpr (MSG) {
+                            const uint32_t q0 = pack_bf16x2(p0[0] * ms0, p1[0] * ms0), q1 = pack_bf16x2(p0[1] * ms1, p1[1] * ms1);
+                            const uint32_t gq = (uint32_t)__shfl_xor((int)(hi ? q0 : q1), 2, kWave);
+                            uint2 m;
+                            m.x = hi ? gq : q0;
+                            m.y = hi ? q1 : gq;
+                            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.msg_out) + off) = m;
+                        }
                     } else {
                         const float g0 = __shfl_xor(hi ? p0[0] : p0[1], 2, kWave);
                         const float g1 = __shfl_xor(hi ? p1[0] : p1[1], 2, kWave);
@@ -327,6 +344,11 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                         o.z = hi ? p0[1] : g0;
                         o.w = hi ? p1[1] : g1;
                         *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + off) = o;
+                        if constexpr (MSG) {
+                            const float ms = hi ? ms1 : ms0;  // this lane's final row is 8*bq + 4*kh + (i&3)
+                            *reinterpret_cast<float4 *>(static_cast<float *>(a.msg_out) + off) =
+                                make_float4(o.x * ms, o.y * ms, o.z * ms, o.w * ms);
+                        }
                     }
                 }
             }
@@ -344,8 +366,11 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                     if (col_ok && orow < a.n) {
                         if constexpr (BF16) {
                             static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
+                            if constexpr (MSG)
+                                static_cast<uint16_t *>(a.msg_out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y * a.msg_scale[orow]);
                         } else {
                             static_cast<float *>(a.out)[orow * a.d_out + col] = y;
+                            if constexpr (MSG) static_cast<float *>(a.msg_out)[orow * a.d_out + col] = y * a.msg_scale[orow];
                         }
                     }
                 }
@@ -367,15 +392,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     }
 }
 
-template <bool BF16, int NT, int PF, bool SCORES>
-int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
+template <bool BF16, int NT, int PF, bool SCORES, bool MSG>
+int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
     const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4);
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     static bool attr_set = false;
     if (!attr_set) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, SCORES>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, SCORES, MSG>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set = true;
     }
@@ -387,9 +412,17 @@ int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_kernel<BF16, NT, PF, SCORES><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_kernel<BF16, NT, PF, SCORES, MSG><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
+}
+
+template <bool BF16, int NT, int PF, bool SCORES>
+int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    if constexpr (!SCORES) {
+        if (a.msg_out) return launch_apply_cfg<BF16, NT, PF, false, true>(a, n_cus, st);
+    }
+    return launch_apply_cfg<BF16, NT, PF, SCORES, false>(a, n_cus, st);
 }
 
 template <bool BF16, int NT>
@@ -440,7 +473,8 @@ int cached_cu_count() {
 
 extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, const void *h_self, const void *agg,
                                const void *w_self, const void *w_nbr, const float *bias, void *h_out, const float *att_src,
-                               const float *att_dst, float *s_src, float *s_dst, void *stream) {
+                               const float *att_dst, float *s_src, float *s_dst, const float *msg_scale, void *msg_out,
+                               void *stream) {
     if (!desc) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->dtype != ITB_F32 && desc->dtype != ITB_BF16) return ITB_ERR_DTYPE;
@@ -456,6 +490,8 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
         if (desc->heads > 16 || h_self) return ITB_ERR_UNSUPPORTED;  // 2*heads score columns share one 32-column tile
     }
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
+    if ((msg_scale == nullptr) != (msg_out == nullptr)) return ITB_ERR_NULL;
+    if (msg_out && desc->heads > 0) return ITB_ERR_UNSUPPORTED;
     if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;
 
@@ -476,6 +512,8 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     a.att_dst = att_dst;
     a.s_src = s_src;
     a.s_dst = s_dst;
+    a.msg_scale = msg_scale;
+    a.msg_out = msg_out;
     hipStream_t st = static_cast<hipStream_t>(stream);
     return desc->dtype == ITB_BF16 ? dispatch_apply<true>(a, cached_cu_count(), st)
                                    : dispatch_apply<false>(a, cached_cu_count(), st);

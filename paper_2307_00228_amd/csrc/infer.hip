@@ -20,7 +20,50 @@ __global__ void copy_kernel(const uint4 *src, uint4 *dst, int64_t n_vec) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x) dst[i] = src[i];
 }
 
+// out[v][:] = x[v][:] * scale[v]; one 16-byte vector per thread.
+template <bool BF16>
+__global__ void scale_rows_kernel(const uint4 *x, const float *scale, uint4 *out, int64_t n_vec, int32_t row_vecs) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x) {
+        const float s = scale[i / row_vecs];
+        const uint4 v = x[i];
+        uint4 o;
+        if constexpr (BF16) {
+            o.x = pack_bf16x2(bf16_lo(v.x) * s, bf16_hi(v.x) * s);
+            o.y = pack_bf16x2(bf16_lo(v.y) * s, bf16_hi(v.y) * s);
+            o.z = pack_bf16x2(bf16_lo(v.z) * s, bf16_hi(v.z) * s);
+            o.w = pack_bf16x2(bf16_lo(v.w) * s, bf16_hi(v.w) * s);
+        } else {
+            o.x = __float_as_uint(__uint_as_float(v.x) * s);
+            o.y = __float_as_uint(__uint_as_float(v.y) * s);
+            o.z = __float_as_uint(__uint_as_float(v.z) * s);
+            o.w = __float_as_uint(__uint_as_float(v.w) * s);
+        }
+        out[i] = o;
+    }
+}
+
 }  // namespace
+
+extern "C" int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, const float *row_scale, void *out,
+                              void *stream) {
+    if (dtype != ITB_F32 && dtype != ITB_BF16) return ITB_ERR_DTYPE;
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || dim <= 0) return ITB_ERR_SIZE;
+    const int elem = dtype == ITB_BF16 ? 2 : 4;
+    if ((dim * elem) % 16 != 0) return ITB_ERR_UNSUPPORTED;
+    if (n_nodes > 0 && (!x || !row_scale || !out)) return ITB_ERR_NULL;
+    if (n_nodes == 0) return ITB_OK;
+    const int32_t row_vecs = dim * elem / 16;
+    const int64_t n_vec = n_nodes * row_vecs;
+    int64_t g = (n_vec + 255) / 256;
+    if (g > 32768) g = 32768;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == ITB_BF16)
+        scale_rows_kernel<true><<<(unsigned)g, 256, 0, st>>>(static_cast<const uint4 *>(x), row_scale, static_cast<uint4 *>(out), n_vec, row_vecs);
+    else
+        scale_rows_kernel<false><<<(unsigned)g, 256, 0, st>>>(static_cast<const uint4 *>(x), row_scale, static_cast<uint4 *>(out), n_vec, row_vecs);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
 
 extern "C" int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream) {
     if (n_bytes < 0 || (n_bytes & 15)) return ITB_ERR_SIZE;
@@ -79,6 +122,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     char *state0 = cv.take<char>(n_layers > 1 ? state_bytes : 0);
     char *state1 = cv.take<char>(n_layers > 2 ? state_bytes : 0);
     char *aggbuf = cv.take<char>(state_bytes);
+    char *msgbuf = cv.take<char>(any_gcn ? state_bytes : 0);  // source-scaled copy of the state a GCN gather reads
     float *src_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *dst_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *att_s_src = cv.take<float>((size_t)n_nodes * max_heads);
@@ -98,20 +142,32 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     }
     char *state[2] = {state0, state1};
     const void *cur = x;
+    bool msg_ready = false;
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
         const bool gat = L.agg == ITB_AGG_GAT;
+        const bool gcn = L.agg == ITB_AGG_GCN;
         const void *gather_src = cur;
-        const float *gs = src_scale, *gd_scale = dst_scale;
+        const float *gs = nullptr, *gd_scale = gcn ? dst_scale : nullptr;
         void *gather_out = aggbuf;
         itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr};
+        if (gcn) {
+            // The message of a GCN edge is the source state times the source's coefficient (apply_edge on the
+            // scatter side): it is produced once per vertex -- by the previous layer's epilogue, or here for the
+            // input features -- instead of being looked up once per edge.
+            if (!msg_ready) {
+                int32_t rc = scale_rows(dtype, n_nodes, L.d_in, cur, src_scale, msgbuf, stream);
+                if (rc != ITB_OK) return rc;
+            }
+            gather_src = msgbuf;
+        }
         if (gat) {
             // project first (z and the per-head scores), then the attention reduce writes the new state directly
             if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, L.heads};
             int32_t rc = apply_layer(&pd, n_nodes, nullptr, cur, nullptr, L.w_nbr, nullptr, aggbuf, L.att_src, L.att_dst,
-                                     att_s_src, att_s_dst, stream);
+                                     att_s_src, att_s_dst, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             gather_src = aggbuf;
             gs = att_s_src;
@@ -127,10 +183,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws, stream);
             if (rc != ITB_OK) return rc;
         }
+        msg_ready = false;
         if (!gat) {
+            // if the next layer is a GCN layer, its messages are written by this update's epilogue
+            const bool next_gcn = (l + 1 < n_layers) && layers[l + 1].agg == ITB_AGG_GCN;
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-            int32_t rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr, stream);
+            int32_t rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
+                                     next_gcn ? src_scale : nullptr, next_gcn ? static_cast<void *>(msgbuf) : nullptr, stream);
             if (rc != ITB_OK) return rc;
+            msg_ready = next_gcn;
         }
         cur = dst;
     }

@@ -73,9 +73,16 @@ def test_full_size_dense_workloads(B, name):
         ss, sd = B.gcn_norm_scales(rowptr, deg_out)
     verts = sample_vertices(np.random.default_rng(5), n, r, osplit)
     h_dev, h_host = x, w.x
+    msg = None          # GCN: the source-scaled message copy of the state, as infer_full_graph keeps it
     for i, (lay, dl) in enumerate(zip(w.layers, layers)):
-        agg = B.gather_layer(dl.agg, rowptr, col, h_dev, split, ss, sd)
-        out = B.apply_layer(h_dev, agg, dl.w_self, dl.w_nbr, dl.bias, dl.act)
+        gcn = dl.agg == W.AGG_GCN
+        if gcn and msg is None:
+            msg = B.scale_rows(h_dev, ss)
+        agg = B.gather_layer(dl.agg, rowptr, col, msg if gcn else h_dev, split, None, sd)
+        next_gcn = i + 1 < len(layers) and layers[i + 1].agg == W.AGG_GCN
+        nmsg = torch.empty((n, dl.d_out), dtype=x.dtype, device="cuda") if next_gcn else None
+        out = B.apply_layer(h_dev, agg, dl.w_self, dl.w_nbr, dl.bias, dl.act, msg_scale=ss if next_gcn else None, msg_out=nmsg)
+        msg = nmsg
         a64 = oracle.gather(lay.agg, r, c, h_host, deg_out=d, verts=verts)
         ok, worst = tolerance_ok(B.to_numpy(agg[torch.from_numpy(verts).cuda()]), a64, w.dtype)
         assert ok, f"layer {i + 1} gather: {worst}"

@@ -242,6 +242,40 @@ def test_apply_layer(B, dtype, d_in, d_out, n):
         check_features(B.to_numpy(out), want, dtype, f"act={act} self={with_self}")
 
 
+@pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 64, 64), (W.F32, 128, 40), (W.BF16, 64, 128), (W.BF16, 32, 16)])
+@pytest.mark.parametrize("n", [5, 300, 4001])
+def test_apply_message_output_and_scale_rows(B, dtype, d_in, d_out, n):
+    """The scatter-side message h' * c(v): second output of the update, and scale_rows for the input features."""
+    import torch
+    rng = np.random.default_rng(n + d_in)
+    h = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    a = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    scale = rng.uniform(0.05, 1.0, n).astype(np.float32)
+    lay = W.dense_layers(rng, W.AGG_GCN, (d_in, d_out, d_out), dtype, bias_random=True)[0]
+    msg = torch.empty((n, d_out), dtype=B.to_device(h).dtype, device="cuda")
+    out = B.apply_layer(B.to_device(h), B.to_device(a), B.to_device(lay.w_self), B.to_device(lay.w_nbr), B.to_device(lay.bias),
+                        W.ACT_RELU, msg_scale=torch.from_numpy(scale).cuda(), msg_out=msg)
+    y64 = oracle.apply(h, a, lay.w_self, lay.w_nbr, lay.bias, oracle.ACT_RELU)
+    check_features(B.to_numpy(out), y64, dtype)
+    check_features(B.to_numpy(msg), y64 * scale[:, None].astype(np.float64), dtype)
+    xs = B.scale_rows(B.to_device(h), torch.from_numpy(scale).cuda())
+    check_features(B.to_numpy(xs), W.as_f32(h).astype(np.float64) * scale[:, None].astype(np.float64), dtype)
+
+
+def test_gcn_gather_of_prescaled_rows(B):
+    import torch
+    n, e, dim = 5000, 80000, 128
+    src, dst, x = W.random_small_graph(321, n, e, dim, W.F32, 0.25)
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    ss, sd = B.gcn_norm_scales(rp, torch.from_numpy(d).cuda())
+    want = oracle.gather(oracle.GCN, r, c, x, deg_out=d)
+    for T in (None, 100):
+        split = B.split_hubs(rp, T) if T else None
+        out = B.gather_layer(W.AGG_GCN, rp, cl, B.scale_rows(B.to_device(x), ss), split, None, sd)
+        check_features(B.to_numpy(out), want, W.F32, f"T={T}")
+
+
 # ------------------------------------------------------------------------------------------ GAT
 @pytest.mark.parametrize("dtype,heads,dh", [(W.F32, 4, 16), (W.F32, 1, 64), (W.BF16, 4, 64), (W.BF16, 2, 8), (W.BF16, 8, 32)])
 @pytest.mark.parametrize("T", [None, 7, 300])
