@@ -42,17 +42,13 @@ __global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
-// Range check of both endpoints; out-degree histogram (integer atomics: order-independent result).
+// Range check of both endpoints.
 __global__ void check_edges_kernel(int64_t n_edges, uint32_t n_nodes, const int32_t *src, const int32_t *dst,
-                                   int32_t *deg_out, uint32_t *bad_flag) {
+                                   uint32_t *bad_flag) {
     bool bad = false;
     for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n_edges; e += (int64_t)gridDim.x * blockDim.x) {
         uint32_t s = (uint32_t)src[e], d = (uint32_t)dst[e];
-        if (s >= n_nodes || d >= n_nodes) {
-            bad = true;
-        } else if (deg_out) {
-            atomicAdd(&deg_out[s], 1);
-        }
+        bad = bad || s >= n_nodes || d >= n_nodes;
     }
     if (bad) atomicOr(bad_flag, 1u);
 }
@@ -225,17 +221,23 @@ int32_t exclusive_scan_u32(uint32_t *data, int64_t n, uint32_t *ws, hipStream_t 
 
 // rowptr[v] = index of the first sorted key >= v.  The thread at the start of each run of equal keys fills
 // the row pointers of its own key and of the empty rows just before it; the last thread fills the tail.
-__global__ void rowptr_from_sorted_kernel(const uint32_t *keys, int64_t n_edges, int64_t n_nodes, int64_t *rowptr) {
+template <typename OutT>
+__global__ void rowptr_from_sorted_kernel(const uint32_t *keys, int64_t n_edges, int64_t n_nodes, OutT *rowptr) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_edges; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t k = keys[i];
         const int64_t kp = (i == 0) ? -1 : (int64_t)keys[i - 1];
         if (k != kp) {
             const int64_t hi = k < n_nodes ? k : n_nodes;
-            for (int64_t v = kp + 1; v <= hi; ++v) rowptr[v] = i;
+            for (int64_t v = kp + 1; v <= hi; ++v) rowptr[v] = (OutT)i;
         }
         if (i == n_edges - 1)
-            for (int64_t v = k + 1; v <= n_nodes; ++v) rowptr[v] = n_edges;
+            for (int64_t v = k + 1; v <= n_nodes; ++v) rowptr[v] = (OutT)n_edges;
     }
+}
+
+__global__ void adjacent_difference_kernel(const uint32_t *bounds, int64_t n, int32_t *out) {
+    for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x)
+        out[v] = (int32_t)(bounds[v + 1] - bounds[v]);
 }
 
 int ceil_log2(int64_t n) {
@@ -268,6 +270,7 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     int32_t *vtmp = cv.take<int32_t>((size_t)n_edges);
     uint32_t *hist = cv.take<uint32_t>((size_t)hist_elems);
     uint32_t *scan_ws = cv.take<uint32_t>(scan_workspace_elems(hist_elems) + 64);
+    uint32_t *bounds = cv.take<uint32_t>((size_t)n_nodes + 1);
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -289,11 +292,7 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
 
     fill_u32_kernel<<<1, 64, 0, st>>>(flag, 64, 0u);
     ITB_LAUNCH_CHECK();
-    if (deg_out) {
-        fill_u32_kernel<<<grid_for(n_nodes, 256), 256, 0, st>>>(reinterpret_cast<uint32_t *>(deg_out), n_nodes, 0u);
-        ITB_LAUNCH_CHECK();
-    }
-    check_edges_kernel<<<grid_for(n_edges, 256, 8192), 256, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, deg_out, flag);
+    check_edges_kernel<<<grid_for(n_edges, 256, 8192), 256, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, flag);
     ITB_LAUNCH_CHECK();
 
     int bits_total = ceil_log2(n_nodes);
@@ -301,26 +300,43 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     const int passes = (bits_total + 7) / 8;
     const int base_bits = bits_total / passes, extra = bits_total % passes;
     uint32_t *kbuf[2] = {kbuf0, kbuf1};
-    int shift = 0;
-    const uint32_t *kin = reinterpret_cast<const uint32_t *>(dst);
-    const int32_t *vin = src;
-    for (int p = 0; p < passes; ++p) {
-        const int bits = base_bits + (p < extra ? 1 : 0);
-        uint32_t *kout = kbuf[p & 1];
-        int32_t *vout = ((passes - 1 - p) % 2 == 0) ? col : vtmp;
-        const int64_t hist_n = ((int64_t)1 << bits) * nblocks;
-        radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, hist, nblocks, itb::g_csr_xcd_remap);
-        ITB_LAUNCH_CHECK();
-        int32_t rc = exclusive_scan_u32(hist, hist_n, scan_ws, st);
-        if (rc != ITB_OK) return rc;
-        radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist, nblocks,
-                                                                           itb::g_csr_xcd_remap);
-        ITB_LAUNCH_CHECK();
-        kin = kout;
-        vin = vout;
-        shift += bits;
+
+    // One radix sort, run once or twice: keys only over the sources (their run lengths are the out-degrees;
+    // a histogram by atomics would cost one memory-side atomic per edge), then (dst, src) pairs for the CSR.
+    const uint32_t *kin = nullptr;
+    for (int which = deg_out ? 0 : 1; which < 2; ++which) {
+        const bool pairs = which == 1;
+        kin = reinterpret_cast<const uint32_t *>(pairs ? dst : src);
+        const int32_t *vin = src;
+        int shift = 0;
+        for (int p = 0; p < passes; ++p) {
+            const int bits = base_bits + (p < extra ? 1 : 0);
+            uint32_t *kout = kbuf[p & 1];
+            int32_t *vout = ((passes - 1 - p) % 2 == 0) ? col : vtmp;
+            const int64_t hist_n = ((int64_t)1 << bits) * nblocks;
+            radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, hist, nblocks, itb::g_csr_xcd_remap);
+            ITB_LAUNCH_CHECK();
+            int32_t rc = exclusive_scan_u32(hist, hist_n, scan_ws, st);
+            if (rc != ITB_OK) return rc;
+            if (pairs)
+                radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist,
+                                                                                   nblocks, itb::g_csr_xcd_remap);
+            else
+                radix_scatter_kernel<false><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, nullptr, kout, nullptr, n_edges, shift, bits,
+                                                                                    hist, nblocks, itb::g_csr_xcd_remap);
+            ITB_LAUNCH_CHECK();
+            kin = kout;
+            vin = vout;
+            shift += bits;
+        }
+        if (!pairs) {
+            rowptr_from_sorted_kernel<uint32_t><<<grid_for(n_edges, 256), 256, 0, st>>>(kin, n_edges, n_nodes, bounds);
+            ITB_LAUNCH_CHECK();
+            adjacent_difference_kernel<<<grid_for(n_nodes, 256), 256, 0, st>>>(bounds, n_nodes, deg_out);
+            ITB_LAUNCH_CHECK();
+        }
     }
-    rowptr_from_sorted_kernel<<<grid_for(n_edges, 256), 256, 0, st>>>(kin, n_edges, n_nodes, rowptr);
+    rowptr_from_sorted_kernel<int64_t><<<grid_for(n_edges, 256), 256, 0, st>>>(kin, n_edges, n_nodes, rowptr);
     ITB_LAUNCH_CHECK();
 
     uint32_t host_flag = 0;
