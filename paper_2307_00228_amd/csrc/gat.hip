@@ -12,6 +12,11 @@
 // Bias and activation of the layer are applied when the row is finished.
 #include "common.h"
 
+namespace itb {
+extern int g_rows_waves_per_simd;
+size_t lds_for_occupancy(int waves, int lanes_per_row);
+}  // namespace itb
+
 namespace {
 using namespace itb;
 
@@ -185,7 +190,6 @@ template <bool BF16, int G>
 __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
     constexpr int NG = kWave / G;
     constexpr int VE = Elems<BF16>::kPerVec;
-    constexpr int U = (G < 4) ? G : 4;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
     const int li = lane % G;
@@ -204,7 +208,35 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
     const int64_t deg64 = re - rs;
     const bool mine = my_row < a.n_nodes && rs >= a.edge_lo && rs < a.edge_hi && deg64 <= a.threshold;
     const int deg = (int)deg64;
-    const uint64_t small_mask = __ballot(mine && deg <= a.small_limit);
+    // A vertex without in-edges attends to itself only: alpha = 1, the row is finish(z[v]).  Power-law
+    // in-degrees leave most vertices in this state, so they get a streaming pass of their own: no scores, no
+    // exponentials, four independent row copies in flight per lane group.
+    const uint64_t iso_mask = __ballot(mine && deg == 0);
+    if (iso_mask) {
+        constexpr int Q = 4;
+        constexpr int STEP = (NG * Q > kWave) ? kWave : NG * Q;
+        for (int sub = 0; sub < kWave; sub += STEP) {
+            const uint64_t sel = (STEP == kWave) ? iso_mask : ((iso_mask >> sub) & ((1ull << STEP) - 1ull));
+            if (sel == 0) continue;
+            uint4 raw[Q];
+            bool on[Q];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int rl = sub + q * NG + g;
+                on[q] = lane_on && rl < kWave && ((iso_mask >> (rl & (kWave - 1))) & 1ull);
+                raw[q] = on[q] ? a.z[(r0 + rl) * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                if (on[q]) {
+                    float f[VE];
+                    unpack<BF16>(f, raw[q]);
+                    finish_store<BF16, VE>(a, r0 + sub + q * NG + g, vec, f, 1.f);
+                }
+            }
+        }
+    }
+    const uint64_t small_mask = __ballot(mine && deg > 0 && deg <= a.small_limit);
     uint64_t large_mask = __ballot(mine && deg > a.small_limit && deg <= a.long_limit);
     const uint64_t long_mask = __ballot(mine && deg > a.long_limit);
     if (long_mask) {  // hand the long rows to the block-per-row kernel (the list order enters no result)
@@ -217,47 +249,67 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
         }
     }
 
+    // Rows with few in-edges (most rows of a power-law graph, isolated ones included): one lane group per row and
+    // R rows per lane group in flight, so that R independent row loads are outstanding per lane.
     if (small_mask) {
-        for (int sub = 0; sub < kWave; sub += NG) {
-            const uint64_t sel = (NG == kWave) ? small_mask : ((small_mask >> sub) & ((1ull << NG) - 1ull));
+        constexpr int R = 2;
+        constexpr int STEP = (NG * R > kWave) ? kWave : NG * R;
+        for (int sub = 0; sub < kWave; sub += STEP) {
+            const uint64_t sel = (STEP == kWave) ? small_mask : ((small_mask >> sub) & ((1ull << STEP) - 1ull));
             if (sel == 0) continue;
-            const int rl = sub + g;
-            const bool act = (small_mask >> rl) & 1ull;
-            int d = __shfl(deg, rl, kWave);
-            if (!act) d = 0;
-            const int64_t st0 = shfl_i64(rs, rl);
-            const int64_t v = (r0 + rl < a.n_nodes) ? r0 + rl : a.n_nodes - 1;
-            const bool on_v = act && lane_on;
-            const float sd = on_v ? a.s_dst[v * a.heads + hk] : 0.f;
-            SoftState<VE> st;
-            {   // the implicit self edge starts the state
-                const uint4 raw = on_v ? a.z[v * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
-                st.m = on_v ? leaky(a.s_src[v * a.heads + hk] + sd, a.slope) : 0.f;
-                st.l = 1.f;
-                unpack<BF16>(st.acc, raw);
-            }
-            for (int j = 0; __ballot(j < d) != 0ull; j += G) {
-                int myc = 0;
-                if (j + li < d) myc = a.col[st0 + j + li];
-                const int cnt = d - j;
-                for (int t = 0; t < G; t += U) {
-                    if (__ballot(t < cnt) == 0ull) break;
-                    uint4 raw[U];
-                    float e[U];
-                    bool on[U];
+            int d[R];
+            int64_t st0[R], v[R];
+            bool on_v[R];
+            float sd[R];
+            SoftState<VE> st[R];
 #pragma unroll
-                    for (int q = 0; q < U; ++q) {
-                        const int u = __shfl(myc, g * G + t + q, kWave);
-                        on[q] = lane_on && (t + q) < cnt;
-                        raw[q] = on[q] ? a.z[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
-                        e[q] = on[q] ? a.s_src[(int64_t)u * a.heads + hk] : 0.f;
+            for (int r = 0; r < R; ++r) {
+                const int rl = sub + r * NG + g;
+                const bool act = rl < kWave && ((small_mask >> (rl & (kWave - 1))) & 1ull);
+                d[r] = __shfl(deg, rl & (kWave - 1), kWave);
+                if (!act) d[r] = 0;
+                st0[r] = shfl_i64(rs, rl & (kWave - 1));
+                v[r] = (act && r0 + rl < a.n_nodes) ? r0 + rl : a.n_nodes - 1;
+                on_v[r] = act && lane_on;
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {   // the implicit self edge starts each state
+                sd[r] = on_v[r] ? a.s_dst[v[r] * a.heads + hk] : 0.f;
+                const uint4 raw = on_v[r] ? a.z[v[r] * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
+                st[r].m = on_v[r] ? leaky(a.s_src[v[r] * a.heads + hk] + sd[r], a.slope) : 0.f;
+                st[r].l = 1.f;
+                unpack<BF16>(st[r].acc, raw);
+            }
+            for (int j = 0;; j += G) {
+                bool more = false;
+#pragma unroll
+                for (int r = 0; r < R; ++r) more = more || j < d[r];
+                if (__ballot(more) == 0ull) break;
+                int myc[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) myc[r] = (j + li < d[r]) ? a.col[st0[r] + j + li] : 0;
+                for (int t = 0; t < G; ++t) {
+                    bool any = false;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) any = any || (j + t) < d[r];
+                    if (__ballot(any) == 0ull) break;
+                    uint4 raw[R];
+                    float e[R];
+                    bool on[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const int u = __shfl(myc[r], g * G + t, kWave);
+                        on[r] = lane_on && (j + t) < d[r];
+                        raw[r] = on[r] ? a.z[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
+                        e[r] = on[r] ? a.s_src[(int64_t)u * a.heads + hk] : 0.f;
                     }
 #pragma unroll
-                    for (int q = 0; q < U; ++q) e[q] = leaky(e[q] + sd, a.slope);
-                    absorb_batch<BF16, U>(st, e, raw, on);
+                    for (int r = 0; r < R; ++r) absorb<BF16>(st[r], leaky(e[r] + sd[r], a.slope), raw[r], on[r]);
                 }
             }
-            if (on_v) finish_store<BF16, VE>(a, v, vec, st.acc, st.l);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (on_v[r]) finish_store<BF16, VE>(a, v[r], vec, st[r].acc, st[r].l);
         }
     }
 
@@ -506,7 +558,7 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
     const unsigned gy = (unsigned)((a.row_vecs + G - 1) / G);
     zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
     ITB_LAUNCH_CHECK();
-    gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, 0, st>>>(a);
+    gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, itb::lds_for_occupancy(itb::g_rows_waves_per_simd == -1 ? 0 : itb::g_rows_waves_per_simd, G), st>>>(a);
     ITB_LAUNCH_CHECK();
     int64_t lg = waves > 2048 ? 2048 : waves;  // fixed grid over the device-side work list
     gat_long_rows_kernel<BF16, G><<<dim3((unsigned)lg, gy), kRangeWaves * kWave, 0, st>>>(a);

@@ -24,6 +24,18 @@ extern int g_csr_xcd_remap;
 int g_small_limit = -1;   // tuning hook (key 0): rows with in-degree <= limit use one lane group per row (-1 = auto)
 int g_gather_unroll = 4;  // reserved
 int g_long_row = 512;     // tuning hook (key 3): rows with more in-edges get a whole block
+int g_rows_waves_per_simd = -1;  // tuning hook (key 4): cap on resident wavefronts per SIMD of the row kernels
+                                 // (0 = no cap, -1 = built-in choice)
+// Dynamic LDS that limits a 256-thread (4-wave) block to `waves` wavefronts per SIMD: a CU has 4 SIMDs and
+// 160 KB of LDS, so `waves` blocks fit when each asks for 160 KB / waves.
+size_t lds_for_occupancy(int waves, int lanes_per_row) {
+    // Measured on MI355X: with rows of 512 bytes and more (32+ lanes per row) the random row gather runs ~10 %
+    // faster with 4 resident wavefronts per SIMD than with 8 (fewer requests queued per memory channel); with
+    // shorter rows the extra wavefronts pay off.
+    if (waves < 0) waves = lanes_per_row >= 32 ? 4 : 0;
+    if (waves <= 0 || waves >= 8) return 0;
+    return (size_t)(160 * 1024 / waves) - 512;
+}
 }  // namespace itb
 
 namespace {
@@ -401,7 +413,7 @@ int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
     if (a.n_nodes > 0) {
         zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
         ITB_LAUNCH_CHECK();
-        gather_rows_kernel<BF16_IN, BF16_OUT, G><<<grid, 256, 0, st>>>(a);
+        gather_rows_kernel<BF16_IN, BF16_OUT, G><<<grid, 256, lds_for_occupancy(g_rows_waves_per_simd, G), st>>>(a);
         ITB_LAUNCH_CHECK();
         // the list length is only known on the device: a fixed grid walks it (blocks beyond the length exit)
         int64_t lg = (a.n_nodes + 63) / 64;
@@ -545,5 +557,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 1) { itb::g_gather_unroll = value; return ITB_OK; }
     if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
     if (key == 3 && value > 0) { itb::g_long_row = value; return ITB_OK; }
+    if (key == 4) { itb::g_rows_waves_per_simd = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }
