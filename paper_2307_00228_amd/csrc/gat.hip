@@ -166,14 +166,24 @@ __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPer
     for (int off = G; off < kWave; off <<= 1) merge_xor(st, off);
 }
 
+// out = act(acc / l + bias): one reciprocal per lane and row, bias fetched as 16-byte vectors.
 template <bool BF16, int VE>
 __device__ __forceinline__ void finish_store(const GatArgs &a, int64_t row, int vec, const float (&acc)[VE], float l) {
     float y[VE];
+    const float inv = 1.0f / l;
 #pragma unroll
-    for (int i = 0; i < VE; ++i) {
-        y[i] = acc[i] / l;
-        if (a.bias) y[i] += a.bias[vec * VE + i];
-        if (a.act == ITB_ACT_RELU) y[i] = fmaxf(y[i], 0.f);
+    for (int i = 0; i < VE; ++i) y[i] = acc[i] * inv;
+    if (a.bias) {
+        const float4 *b4 = reinterpret_cast<const float4 *>(a.bias + vec * VE);
+#pragma unroll
+        for (int k = 0; k < VE / 4; ++k) {
+            const float4 b = b4[k];
+            y[4 * k + 0] += b.x; y[4 * k + 1] += b.y; y[4 * k + 2] += b.z; y[4 * k + 3] += b.w;
+        }
+    }
+    if (a.act == ITB_ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) y[i] = fmaxf(y[i], 0.f);
     }
     const int64_t elem0 = (row * a.row_vecs + vec) * VE;
     if constexpr (BF16) {
@@ -598,6 +608,7 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     const bool bf16 = desc->dtype_in == ITB_BF16;
     if (desc->dtype_out != desc->dtype_in) return ITB_ERR_UNSUPPORTED;
     if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
+    if (reinterpret_cast<uintptr_t>(desc->bias) & 15u) return ITB_ERR_UNSUPPORTED;  // bias is read as 16-byte vectors
     if (desc->heads <= 0 || desc->heads > 64 || desc->dim % desc->heads != 0) return ITB_ERR_SIZE;
     const int dh = desc->dim / desc->heads;
     const int ve = bf16 ? 8 : 4;

@@ -114,9 +114,9 @@ template <int VE>
 __device__ __forceinline__ void finish_row(float (&acc)[VE], int mode, int64_t deg, const float *dst_scale, int64_t row) {
     if (mode == kModeMean) {
         if (deg > 0) {
-            const float d = (float)deg;
+            const float inv = 1.0f / (float)deg;  // one division per lane and row; the elements are scaled by it
 #pragma unroll
-            for (int i = 0; i < VE; ++i) acc[i] = acc[i] / d;
+            for (int i = 0; i < VE; ++i) acc[i] *= inv;
         }
     } else if (mode == kModeScaleDst) {
         const float s = dst_scale[row];
