@@ -72,55 +72,30 @@ def main():
         if kv:
             B.set_tuning(int(kv.split(":")[0]), int(kv.split(":")[1]))
 
-    # buffers reused by every step (the caching allocator is warm after the first step anyway)
+    from paper_2307_00228_amd import compose
     is_gat = [l.agg == W.AGG_GAT for l in w.layers]
-    states = [torch.empty((N, l.d_out), dtype=tdt, device="cuda") for l in w.layers]
-    aggs = [torch.empty((N, l.d_out if g else l.d_in), dtype=tdt, device="cuda") for l, g in zip(w.layers, is_gat)]
-    msgs = [torch.empty((N, l.d_in), dtype=tdt, device="cuda") if l.agg == W.AGG_GCN else None for l in w.layers]
+    projected = [compose.project_before_gather(l, tdt) for l in layers]
+    buffers = {}                       # intermediates reused by every step
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stamps = {"gather": [], "apply": [], "csr": [], "split": []}
 
     def step(record: bool):
-        marks = []
         e0 = ev(); e0.record()
         rowptr, col, deg_out = B.build_csr_by_dst(N, src, dst)
         e1 = ev(); e1.record()
         split = B.split_hubs(rowptr, thr)
         e2 = ev(); e2.record()
-        ss = sd = None
-        if any(l.agg == W.AGG_GCN for l in w.layers):
-            ss, sd = B.gcn_norm_scales(rowptr, deg_out)
-        h = x
-        msg = None      # source-scaled copy of h (the message a GCN edge carries), written once per vertex
-        for i, l in enumerate(layers):
-            if is_gat[i]:
-                # GAT order: projection (with the score epilogue) first, then the attention reduce + bias + activation
-                b0 = ev(); b0.record()
-                _, s_src, s_dst = B.apply_layer(None, h, None, l.w_nbr, None, W.ACT_NONE, out=aggs[i], heads=l.heads,
-                                                att_src=l.att_src, att_dst=l.att_dst)
-                a = ev(); a.record()
-                B.gather_layer(l.agg, rowptr, col, aggs[i], split if use_split else None, s_src, s_dst, heads=l.heads,
-                               leaky_slope=l.leaky_slope, act=l.act, bias=l.bias, out=states[i])
-                b = ev(); b.record()
-                marks.append((a, b, b0, a))
-            else:
-                gcn = l.agg == W.AGG_GCN
-                if gcn and msg is None:
-                    msg = B.scale_rows(h, ss, out=msgs[i])
-                a = ev(); a.record()
-                B.gather_layer(l.agg, rowptr, col, msg if gcn else h, split if use_split else None, None, sd, out=aggs[i])
-                b = ev(); b.record()
-                next_gcn = i + 1 < L and layers[i + 1].agg == W.AGG_GCN
-                B.apply_layer(h, aggs[i], l.w_self, l.w_nbr, l.bias, l.act, out=states[i],
-                              msg_scale=ss if next_gcn else None, msg_out=msgs[i + 1] if next_gcn else None)
-                c = ev(); c.record()
-                marks.append((a, b, b, c))
-                msg = msgs[i + 1] if next_gcn else None
-            h = states[i]
+        marks = {}
+
+        def mark(tag, i):
+            e = ev(); e.record(); marks[(tag, i)] = e
+
+        compose.run_layers(rowptr, col, deg_out, split if use_split else None, layers, x, mark, buffers)
         if record:
             stamps["csr"].append((e0, e1)); stamps["split"].append((e1, e2))
-            for g0, g1, a0, a1 in marks:
-                stamps["gather"].append((g0, g1)); stamps["apply"].append((a0, a1))
+            for i in range(L):
+                stamps["gather"].append((marks[("gather_begin", i)], marks[("gather_end", i)]))
+                stamps["apply"].append((marks[("apply_begin", i)], marks[("apply_end", i)]))
         return rowptr, col, deg_out, split
 
     for _ in range(args.warmup):
@@ -145,9 +120,14 @@ def main():
     # every vertex reads its row pointer and writes its aggregate row once
     # (GAT: the row is the projected state of width d_out; plus the 4-byte source score of each head per edge, and per
     # vertex its own row and scores for the implicit self edge)
+    # (a narrowing layer gathers rows already multiplied by W_nbr: width d_out)
+    def gather_width(l, g, pf):
+        return l.d_out if (g or pf) else l.d_in
     g_bytes = [E * (4 + 4 * l.heads + l.d_out * esz) + N * (8 + 2 * l.d_out * esz + 8 * l.heads) if g
-               else E * (4 + l.d_in * esz) + N * (8 + l.d_in * esz) for l, g in zip(w.layers, is_gat)]
-    a_flops = [(2.0 if g else 4.0) * l.d_in * l.d_out * N for l, g in zip(w.layers, is_gat)]
+               else E * (4 + gather_width(l, g, pf) * esz) + N * (8 + gather_width(l, g, pf) * esz)
+               for l, g, pf in zip(w.layers, is_gat, projected)]
+    # flops of the final update launch of the layer (GAT: the projection; projected layers: the self product)
+    a_flops = [(2.0 if (g or pf) else 4.0) * l.d_in * l.d_out * N for l, g, pf in zip(w.layers, is_gat, projected)]
     dom = int(np.argmax(g_ms))
     achieved = g_bytes[dom] / (g_ms[dom] * 1e-3) / 1e9
 
@@ -185,7 +165,7 @@ def main():
         "config": {"workload": args.workload, "scale": args.scale, "n_nodes": N, "n_edges": E,
                    "dims": [w.layers[0].d_in] + [l.d_out for l in w.layers], "aggregator": w.layers[0].agg,
                    "hub_threshold": w.threshold if use_split else None, "recipe": w.recipe},
-        "roofline": {"bound": "hbm", "kernel": f"gather_layer (layer {dom + 1}, dim {w.layers[dom].d_out if is_gat[dom] else w.layers[dom].d_in})",
+        "roofline": {"bound": "hbm", "kernel": f"gather_layer (layer {dom + 1}, dim {gather_width(w.layers[dom], is_gat[dom], projected[dom])})",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes": g_bytes[dom], "avg_ms": g_ms[dom]},
         "breakdown": {
@@ -195,6 +175,7 @@ def main():
             "gather_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(g_bytes, g_ms)],
             "apply_TFLOPs": [f / (t * 1e-3) / 1e12 for f, t in zip(a_flops, a_ms)],
             "apply_frac_of_mfma_peak": [f / (t * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype] for f, t in zip(a_flops, a_ms)],
+            "projected_before_gather": projected,
             "nodes_per_s_per_layer": [N / ((g + a) * 1e-3) for g, a in zip(g_ms, a_ms)],
             "n_hubs": split.n_hubs, "n_shadows": split.n_shadows,
         },

@@ -194,6 +194,11 @@ int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
  *   the next round (apply_edge of the scatter stage, Sec. IV-B):
  *   msg_out[v] = h_out[v] * msg_scale[v] ([n] fp32, [n x d_out] of `dtype`);
  *   both NULL to skip.
+ *   addend: optional [n x d_out] tensor of `dtype` added before the
+ *   activation: h_out = act(... + addend + bias).  It carries the gathered
+ *   projection when W_nbr was applied before the gather (sum, mean and the
+ *   degree-normalised sum are linear, so a narrowing layer can gather d_out
+ *   instead of d_in elements per edge); NULL to skip.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t dtype;
@@ -208,6 +213,7 @@ int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes,
                     void *h_out,
                     const float *att_src, const float *att_dst, float *s_src, float *s_dst,
                     const float *msg_scale, void *msg_out,
+                    const void *addend,
                     void *stream);
 
 /* ---------------------------------------------------------------------------
@@ -232,6 +238,9 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  *   deg_out    required when a layer uses ITB_AGG_GCN, else may be NULL.
  *   edge_chunk 0 = one gather launch set per layer; else each layer's gather is
  *              issued per range of `edge_chunk` edge offsets (see gather_layer).
+ * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
+ * gather(h . W_nbr) (see apply_layer's addend); a GCN layer reads per-vertex
+ * message rows h * deg_out^-1/2 written by the previous update (or scale_rows).
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t agg;        /* ITB_AGG_* */

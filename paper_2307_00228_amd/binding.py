@@ -66,7 +66,7 @@ def _load():
     lib.gcn_norm_scales.argtypes = [i64, vp, vp, vp, vp, vp]
     lib.gather_layer.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                  i64, i64, vp, szp, vp]
-    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
                                      vp, vp, i64, vp, szp, vp]
@@ -217,7 +217,7 @@ def scale_rows(x: torch.Tensor, row_scale: torch.Tensor, out: Optional[torch.Ten
 
 
 def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.Tensor] = None,
-                heads: int = 0, att_src=None, att_dst=None, msg_scale=None, msg_out=None):
+                heads: int = 0, att_src=None, att_dst=None, msg_scale=None, msg_out=None, addend=None):
     n, d_in = agg.shape
     d_out = w_nbr.shape[1]
     if out is None:
@@ -229,7 +229,7 @@ def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.
         s_dst = torch.empty((n, heads), dtype=torch.float32, device="cuda")
     _check("apply_layer", lib.apply_layer(C.byref(desc), n, _ptr(h_self), _ptr(agg), _ptr(w_self), _ptr(w_nbr), _ptr(bias),
                                           _ptr(out), _ptr(att_src), _ptr(att_dst), _ptr(s_src), _ptr(s_dst),
-                                          _ptr(msg_scale), _ptr(msg_out), _stream()))
+                                          _ptr(msg_scale), _ptr(msg_out), _ptr(addend), _stream()))
     return (out, s_src, s_dst) if heads else out
 
 

@@ -1,0 +1,89 @@
+"""The layer loop of ``infer_full_graph`` issued call by call through the C ABI.
+
+Same kernels, same order, same strategy choices as the single call (the results are bitwise identical, which
+the tests assert); it exists so that the benchmark can bracket each gather with events and the stage-wise
+parity tests can look at every intermediate tensor.  It allocates torch tensors for the intermediates and does
+nothing else: every step of the path runs inside the library.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Callable, List, Optional
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class LayerTrace:
+    gather_src: torch.Tensor        # rows the gather read (state, message rows, or projected rows)
+    agg: torch.Tensor               # gather output (GAT: the new state)
+    out: torch.Tensor               # new state
+    projected: bool                 # W_nbr applied before the gather
+    scores: Optional[tuple] = None  # GAT: (s_src, s_dst)
+
+
+def project_before_gather(layer: B.DeviceLayer, dtype: torch.dtype) -> bool:
+    elem = 2 if dtype == torch.bfloat16 else 4
+    return (layer.agg != B.AGG_GAT and layer.w_self is not None and layer.d_out < layer.d_in
+            and (layer.d_out * elem) % 16 == 0)
+
+
+def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torch.Tensor,
+               mark: Optional[Callable[[str, int], None]] = None, buffers: Optional[dict] = None) -> List[LayerTrace]:
+    """``mark(tag, layer)`` is called right before/after the gather and the update of every layer
+    (tags: gather_begin, gather_end, apply_begin, apply_end).  ``buffers`` caches the intermediates across calls."""
+    mark = mark or (lambda tag, i: None)
+    buffers = buffers if buffers is not None else {}
+    n = x.shape[0]
+
+    def buf(key, cols, dtype=x.dtype):
+        t = buffers.get(key)
+        if t is None or t.shape != (n, cols) or t.dtype != dtype:
+            t = torch.empty((n, cols), dtype=dtype, device="cuda")
+            buffers[key] = t
+        return t
+
+    ss = sd = None
+    if any(l.agg == B.AGG_GCN for l in layers):
+        ss, sd = B.gcn_norm_scales(rowptr, deg_out)
+    traces = []
+    h, msg = x, None
+    for i, l in enumerate(layers):
+        gcn, gat = l.agg == B.AGG_GCN, l.agg == B.AGG_GAT
+        next_gcn = i + 1 < len(layers) and layers[i + 1].agg == B.AGG_GCN
+        out = buf(("out", i), l.d_out)
+        if gat:
+            mark("apply_begin", i)
+            z, s_src, s_dst = B.apply_layer(None, h, None, l.w_nbr, None, B.ACT_NONE, out=buf(("z", i), l.d_out), heads=l.heads,
+                                            att_src=l.att_src, att_dst=l.att_dst)
+            mark("apply_end", i)
+            mark("gather_begin", i)
+            B.gather_layer(l.agg, rowptr, col, z, split, s_src, s_dst, heads=l.heads, leaky_slope=l.leaky_slope, act=l.act,
+                           bias=l.bias, out=out)
+            mark("gather_end", i)
+            traces.append(LayerTrace(z, out, out, False, (s_src, s_dst)))
+            h, msg = out, None
+            continue
+        src_rows = h
+        if gcn:
+            if msg is None:
+                msg = B.scale_rows(h, ss, out=buf(("msg", i), l.d_in))
+            src_rows = msg
+        pf = project_before_gather(l, x.dtype)
+        if pf:
+            src_rows = B.apply_layer(None, src_rows, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out))
+        mark("gather_begin", i)
+        agg = B.gather_layer(l.agg, rowptr, col, src_rows, split, None, sd if gcn else None, out=buf(("agg", i), src_rows.shape[1]))
+        mark("gather_end", i)
+        nmsg = buf(("msg", i + 1), l.d_out) if next_gcn else None
+        mark("apply_begin", i)
+        if pf:
+            B.apply_layer(None, h, None, l.w_self, l.bias, l.act, out=out, msg_scale=ss if next_gcn else None, msg_out=nmsg, addend=agg)
+        else:
+            B.apply_layer(h, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out, msg_scale=ss if next_gcn else None, msg_out=nmsg)
+        mark("apply_end", i)
+        traces.append(LayerTrace(src_rows, agg, out, pf))
+        h, msg = out, nmsg
+    return traces

@@ -44,6 +44,9 @@ struct ApplyArgs {
     // message output (the scatter-side apply_edge): msg_out[v] = h_out[v] * msg_scale[v], both nullable together
     const float *msg_scale;
     void *msg_out;
+    // optional addend [n x d_out] of the storage dtype, added before the activation (the gathered projection when
+    // the neighbour product was taken before the gather)
+    const void *addend;
 };
 
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
@@ -164,7 +167,7 @@ __device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a
 // PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
 // A fragments are double-buffered by group and the request stream runs on across row tiles (the first
 // fragments of the next tile are requested while the current tile finishes and stores).
-template <bool BF16, int NT, int PF, bool SCORES, bool MSG>
+template <bool BF16, int NT, int PF, bool SCORES, bool MSG, bool ADD>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     constexpr int SPARTS = BF16 ? 2 : 1;  // B fragments of the score tile per chunk (bf16: hi and lo part)
     extern __shared__ uint4 wlds[];
@@ -308,12 +311,45 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                         p1[jj] = odd ? vb : got;
                         p0[jj] += blo;
                         p1[jj] += bhi;
-                        if (a.act == ITB_ACT_RELU) {
+                        if (!ADD && a.act == ITB_ACT_RELU) {
                             p0[jj] = fmaxf(p0[jj], 0.f);
                             p1[jj] = fmaxf(p1[jj], 0.f);
                         }
                     }
                     const int64_t off = (row_q + 8 * bq) * a.d_out + colq;
+                    if constexpr (ADD) {
+                        // finish the transpose in fp32, add the addend's four columns of this lane's row, then the
+                        // activation, rounding and stores
+                        const float g0 = __shfl_xor(hi ? p0[0] : p0[1], 2, kWave);
+                        const float g1 = __shfl_xor(hi ? p1[0] : p1[1], 2, kWave);
+                        float o[4] = {hi ? g0 : p0[0], hi ? g1 : p1[0], hi ? p0[1] : g0, hi ? p1[1] : g1};
+                        if constexpr (BF16) {
+                            const uint2 ad = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.addend) + off);
+                            o[0] += bf16_lo(ad.x); o[1] += bf16_hi(ad.x); o[2] += bf16_lo(ad.y); o[3] += bf16_hi(ad.y);
+                        } else {
+                            const float4 ad = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.addend) + off);
+                            o[0] += ad.x; o[1] += ad.y; o[2] += ad.z; o[3] += ad.w;
+                        }
+                        if (a.act == ITB_ACT_RELU) {
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) o[t] = fmaxf(o[t], 0.f);
+                        }
+                        float ms = 0.f;
+                        if constexpr (MSG) ms = a.msg_scale[row_q + 8 * bq];
+                        if constexpr (BF16) {
+                            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + off) =
+                                make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+                            if constexpr (MSG)
+                                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.msg_out) + off) =
+                                    make_uint2(pack_bf16x2(o[0] * ms, o[1] * ms), pack_bf16x2(o[2] * ms, o[3] * ms));
+                        } else {
+                            *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + off) = make_float4(o[0], o[1], o[2], o[3]);
+                            if constexpr (MSG)
+                                *reinterpret_cast<float4 *>(static_cast<float *>(a.msg_out) + off) =
+                                    make_float4(o[0] * ms, o[1] * ms, o[2] * ms, o[3] * ms);
+                        }
+                        continue;
+                    }
                     // after step 1 pair jj of a lane belongs to row 8*bq + 4*kh + 2*jj + (i&1) of the tile
                     float ms0 = 0.f, ms1 = 0.f;
                     if constexpr (MSG) {
@@ -362,6 +398,12 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                 for (int r = 0; r < 16; ++r) {
                     const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
                     float y = acc[nt][r] + b;
+                    if constexpr (ADD) {
+                        if (col_ok && orow < a.n) {
+                            if constexpr (BF16) y += __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.addend)[orow * a.d_out + col] << 16);
+                            else y += static_cast<const float *>(a.addend)[orow * a.d_out + col];
+                        }
+                    }
                     if (a.act == ITB_ACT_RELU) y = fmaxf(y, 0.f);
                     if (col_ok && orow < a.n) {
                         if constexpr (BF16) {
@@ -392,7 +434,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     }
 }
 
-template <bool BF16, int NT, int PF, bool SCORES, bool MSG>
+template <bool BF16, int NT, int PF, bool SCORES, bool MSG, bool ADD>
 int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
@@ -400,7 +442,7 @@ int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     static bool attr_set = false;
     if (!attr_set) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, SCORES, MSG>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, SCORES, MSG, ADD>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set = true;
     }
@@ -412,7 +454,7 @@ int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_kernel<BF16, NT, PF, SCORES, MSG><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_kernel<BF16, NT, PF, SCORES, MSG, ADD><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -420,9 +462,11 @@ int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
 template <bool BF16, int NT, int PF, bool SCORES>
 int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if constexpr (!SCORES) {
-        if (a.msg_out) return launch_apply_cfg<BF16, NT, PF, false, true>(a, n_cus, st);
+        if (a.msg_out && a.addend) return launch_apply_cfg<BF16, NT, PF, false, true, true>(a, n_cus, st);
+        if (a.msg_out) return launch_apply_cfg<BF16, NT, PF, false, true, false>(a, n_cus, st);
+        if (a.addend) return launch_apply_cfg<BF16, NT, PF, false, false, true>(a, n_cus, st);
     }
-    return launch_apply_cfg<BF16, NT, PF, SCORES, false>(a, n_cus, st);
+    return launch_apply_cfg<BF16, NT, PF, SCORES, false, false>(a, n_cus, st);
 }
 
 template <bool BF16, int NT>
@@ -474,7 +518,7 @@ int cached_cu_count() {
 extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, const void *h_self, const void *agg,
                                const void *w_self, const void *w_nbr, const float *bias, void *h_out, const float *att_src,
                                const float *att_dst, float *s_src, float *s_dst, const float *msg_scale, void *msg_out,
-                               void *stream) {
+                               const void *addend, void *stream) {
     if (!desc) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->dtype != ITB_F32 && desc->dtype != ITB_BF16) return ITB_ERR_DTYPE;
@@ -491,7 +535,7 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     }
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
     if ((msg_scale == nullptr) != (msg_out == nullptr)) return ITB_ERR_NULL;
-    if (msg_out && desc->heads > 0) return ITB_ERR_UNSUPPORTED;
+    if ((msg_out || addend) && desc->heads > 0) return ITB_ERR_UNSUPPORTED;
     if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;
 
@@ -514,6 +558,7 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     a.s_dst = s_dst;
     a.msg_scale = msg_scale;
     a.msg_out = msg_out;
+    a.addend = addend;
     hipStream_t st = static_cast<hipStream_t>(stream);
     return desc->dtype == ITB_BF16 ? dispatch_apply<true>(a, cached_cu_count(), st)
                                    : dispatch_apply<false>(a, cached_cu_count(), st);

@@ -86,6 +86,14 @@ extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const
     return ITB_OK;
 }
 
+// Sum, mean and the degree-normalised sum are linear in the source rows, so W_nbr can be applied before the gather
+// (the computation flow may be reorganised around the aggregate, Sec. IV-B "Inference"): when a layer narrows
+// (d_out < d_in) the edges then carry d_out instead of d_in elements.
+static bool project_before_gather(const itb_layer &L, int32_t dtype) {
+    const int elem = dtype == ITB_BF16 ? 2 : 4;
+    return L.agg != ITB_AGG_GAT && L.w_self != nullptr && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
+}
+
 extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
                                     const int32_t *deg_out, const itb_split *split, int32_t dtype, int32_t n_layers,
                                     const itb_layer *layers, const void *x, void *out, int64_t edge_chunk, void *workspace,
@@ -97,7 +105,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     if (dtype != ITB_F32 && dtype != ITB_BF16) return ITB_ERR_DTYPE;
     const size_t elem = dtype == ITB_BF16 ? 2 : 4;
     int32_t max_d = 0;
-    bool any_gcn = false;
+    bool any_gcn = false, any_project = false;
     int32_t max_heads = 0;
     size_t gather_ws = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -110,7 +118,9 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         any_gcn = any_gcn || L.agg == ITB_AGG_GCN;
         const bool gat = L.agg == ITB_AGG_GAT;
         if (gat && L.heads > max_heads) max_heads = L.heads;
-        itb_gather_desc gd{L.agg, dtype, dtype, gat ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr};
+        const bool pf = project_before_gather(L, dtype);
+        any_project = any_project || pf;
+        itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr};
         size_t need = 0;
         int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
                                   &need, nullptr);
@@ -123,6 +133,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     char *state1 = cv.take<char>(n_layers > 2 ? state_bytes : 0);
     char *aggbuf = cv.take<char>(state_bytes);
     char *msgbuf = cv.take<char>(any_gcn ? state_bytes : 0);  // source-scaled copy of the state a GCN gather reads
+    char *projbuf = cv.take<char>(any_project ? state_bytes : 0);  // W_nbr-projected rows of a narrowing layer
     float *src_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *dst_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *att_s_src = cv.take<float>((size_t)n_nodes * max_heads);
@@ -167,13 +178,22 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, L.heads};
             int32_t rc = apply_layer(&pd, n_nodes, nullptr, cur, nullptr, L.w_nbr, nullptr, aggbuf, L.att_src, L.att_dst,
-                                     att_s_src, att_s_dst, nullptr, nullptr, stream);
+                                     att_s_src, att_s_dst, nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             gather_src = aggbuf;
             gs = att_s_src;
             gd_scale = att_s_dst;
             gather_out = dst;
             gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias};
+        }
+        const bool pf = project_before_gather(L, dtype);
+        if (pf) {
+            itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
+            int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, L.w_nbr, nullptr, projbuf, nullptr, nullptr, nullptr,
+                                     nullptr, nullptr, nullptr, nullptr, stream);
+            if (rc != ITB_OK) return rc;
+            gather_src = projbuf;
+            gd.dim = L.d_out;
         }
         const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
         for (int64_t c = 0; c < n_chunks; ++c) {
@@ -187,9 +207,18 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (!gat) {
             // if the next layer is a GCN layer, its messages are written by this update's epilogue
             const bool next_gcn = (l + 1 < n_layers) && layers[l + 1].agg == ITB_AGG_GCN;
-            itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-            int32_t rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
-                                     next_gcn ? src_scale : nullptr, next_gcn ? static_cast<void *>(msgbuf) : nullptr, stream);
+            const float *ms = next_gcn ? src_scale : nullptr;
+            void *mo = next_gcn ? static_cast<void *>(msgbuf) : nullptr;
+            int32_t rc;
+            if (pf) {  // the gathered projection enters the update as an addend to the self product
+                itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
+                rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_self, L.bias, dst, nullptr, nullptr, nullptr, nullptr, ms, mo,
+                                 aggbuf, stream);
+            } else {
+                itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
+                rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr, ms, mo,
+                                 nullptr, stream);
+            }
             if (rc != ITB_OK) return rc;
             msg_ready = next_gcn;
         }

@@ -77,12 +77,12 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert lib.gather_layer(C.byref(d), 10, None, None, C.byref(sp), None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -2
     # apply_layer
     a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
-    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
-    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
     a7 = B.itb_apply_desc(B.ITB_F32, 60, 16, B.ACT_RELU, 0)
-    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
+    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
     a9 = B.itb_apply_desc(B.ITB_F32, 64, 16, 5, 0)
-    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
+    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
     # infer_full_graph
     assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, C.byref(need), None) == -1
     lay = (B.itb_layer * 2)()

@@ -66,32 +66,36 @@ def test_full_size_dense_workloads(B, name):
         if name == "hub_heavy":
             assert osplit["n_hubs"] >= 16 and np.diff(r).max() >= 4_000_000
 
+    from paper_2307_00228_amd import compose
     layers = B.device_layers(w.layers)
     x = B.to_device(w.x)
-    ss = sd = None
-    if w.layers[0].agg == W.AGG_GCN:
-        ss, sd = B.gcn_norm_scales(rowptr, deg_out)
     verts = sample_vertices(np.random.default_rng(5), n, r, osplit)
-    h_dev, h_host = x, w.x
-    msg = None          # GCN: the source-scaled message copy of the state, as infer_full_graph keeps it
-    for i, (lay, dl) in enumerate(zip(w.layers, layers)):
-        gcn = dl.agg == W.AGG_GCN
-        if gcn and msg is None:
-            msg = B.scale_rows(h_dev, ss)
-        agg = B.gather_layer(dl.agg, rowptr, col, msg if gcn else h_dev, split, None, sd)
-        next_gcn = i + 1 < len(layers) and layers[i + 1].agg == W.AGG_GCN
-        nmsg = torch.empty((n, dl.d_out), dtype=x.dtype, device="cuda") if next_gcn else None
-        out = B.apply_layer(h_dev, agg, dl.w_self, dl.w_nbr, dl.bias, dl.act, msg_scale=ss if next_gcn else None, msg_out=nmsg)
-        msg = nmsg
-        a64 = oracle.gather(lay.agg, r, c, h_host, deg_out=d, verts=verts)
-        ok, worst = tolerance_ok(B.to_numpy(agg[torch.from_numpy(verts).cuda()]), a64, w.dtype)
-        assert ok, f"layer {i + 1} gather: {worst}"
-        # the update is checked on the aggregate the GPU stored
-        agg_v = B.to_numpy(agg[torch.from_numpy(verts).cuda()])
-        y64 = oracle.apply(np.asarray(h_host)[verts], agg_v, lay.w_self, lay.w_nbr, lay.bias, lay.act)
-        ok, worst = tolerance_ok(B.to_numpy(out[torch.from_numpy(verts).cuda()]), y64, w.dtype)
-        assert ok, f"layer {i + 1} apply: {worst}"
-        h_dev, h_host = out, B.to_numpy(out)
+    vt = torch.from_numpy(verts).cuda()
+    traces = compose.run_layers(rowptr, col, deg_out, split, layers, x)
+    h_host = w.x
+    for i, (lay, tr) in enumerate(zip(w.layers, traces)):
+        # the whole layer from the state the GPU stored for the previous one
+        a_st, y64 = oracle.dense_layer(r, c, d, h_host, lay, w.dtype, verts=verts)
+        ok, worst = tolerance_ok(B.to_numpy(tr.out[vt]), y64, w.dtype)
+        assert ok, f"layer {i + 1}: {worst}"
+        if not tr.projected:
+            # stage-wise: the aggregate, then the update on the aggregate the GPU stored
+            a64 = oracle.gather(lay.agg, r, c, h_host, deg_out=d, verts=verts)
+            ok, worst = tolerance_ok(B.to_numpy(tr.agg[vt]), a64, w.dtype)
+            assert ok, f"layer {i + 1} gather: {worst}"
+            y64 = oracle.apply(np.asarray(h_host)[verts], B.to_numpy(tr.agg[vt]), lay.w_self, lay.w_nbr, lay.bias, lay.act)
+            ok, worst = tolerance_ok(B.to_numpy(tr.out[vt]), y64, w.dtype)
+            assert ok, f"layer {i + 1} apply: {worst}"
+        else:
+            # W_nbr was applied before the gather: the gather itself is a plain aggregate of the projected rows
+            kind = lay.agg
+            p64 = oracle.gather(kind, r, c, B.to_numpy(tr.gather_src), deg_out=None if kind != W.AGG_GCN else d, verts=verts) \
+                if kind != W.AGG_GCN else None
+            if p64 is not None:
+                ok, worst = tolerance_ok(B.to_numpy(tr.agg[vt]), p64, w.dtype)
+                assert ok, f"layer {i + 1} gather of projected rows: {worst}"
+        h_host = B.to_numpy(tr.out)
+    h_dev = traces[-1].out
 
     # the single-call path launches the same kernels: bitwise identical, also when issued in edge-range chunks
     view = torch.int16 if w.dtype == W.BF16 else torch.int32

@@ -262,6 +262,28 @@ def test_apply_message_output_and_scale_rows(B, dtype, d_in, d_out, n):
     check_features(B.to_numpy(xs), W.as_f32(h).astype(np.float64) * scale[:, None].astype(np.float64), dtype)
 
 
+@pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 64, 16), (W.F32, 128, 64), (W.BF16, 64, 32), (W.BF16, 128, 40)])
+@pytest.mark.parametrize("n", [7, 1000, 4100])
+def test_apply_with_addend(B, dtype, d_in, d_out, n):
+    """h_out = act(h . W + addend + bias), optionally with the message output."""
+    import torch
+    rng = np.random.default_rng(n + d_out)
+    h = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    add = W.store(rng.standard_normal((n, d_out)).astype(np.float32), dtype)
+    scale = rng.uniform(0.1, 1.0, n).astype(np.float32)
+    lay = W.dense_layers(rng, W.AGG_MEAN, (d_in, d_out, d_out), dtype, bias_random=True)[0]
+    y64 = oracle.apply(None, h, None, lay.w_self, lay.bias, oracle.ACT_NONE) + W.as_f32(add).astype(np.float64)
+    want = np.maximum(y64, 0.0)
+    out = B.apply_layer(None, B.to_device(h), None, B.to_device(lay.w_self), B.to_device(lay.bias), W.ACT_RELU,
+                        addend=B.to_device(add))
+    check_features(B.to_numpy(out), want, dtype)
+    msg = torch.empty_like(out)
+    out2 = B.apply_layer(None, B.to_device(h), None, B.to_device(lay.w_self), B.to_device(lay.bias), W.ACT_RELU,
+                         addend=B.to_device(add), msg_scale=torch.from_numpy(scale).cuda(), msg_out=msg)
+    assert torch.equal(out2.view(torch.int16 if dtype == W.BF16 else torch.int32), out.view(torch.int16 if dtype == W.BF16 else torch.int32))
+    check_features(B.to_numpy(msg), want * scale[:, None].astype(np.float64), dtype)
+
+
 def test_gcn_gather_of_prescaled_rows(B):
     import torch
     n, e, dim = 5000, 80000, 128
