@@ -58,7 +58,13 @@ typedef enum {
 } itb_status;
 
 enum { ITB_F32 = 0, ITB_BF16 = 1 };
-enum { ITB_AGG_SUM = 0, ITB_AGG_MEAN = 1, ITB_AGG_GCN = 2, ITB_AGG_GAT = 3 };
+enum {
+    ITB_AGG_SUM = 0, ITB_AGG_MEAN = 1, ITB_AGG_GCN = 2, ITB_AGG_GAT = 3,
+    ITB_AGG_MAX = 4, ITB_AGG_MIN = 5, /* element-wise extrema (Sec. IV-B lists max and min among the reduces that
+                                         satisfy the commutative and associative laws) */
+    ITB_AGG_NONE = 6                  /* infer_full_graph only: a layer without a gather (feature encoder before
+                                         the first round, prediction head after the last, Sec. IV-C) */
+};
 enum { ITB_ACT_NONE = 0, ITB_ACT_RELU = 1 };
 
 /* ---------------------------------------------------------------------------
@@ -133,6 +139,10 @@ int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *d
  *   ITB_AGG_GCN : dst_scale[v] * sum of src_scale[col] * h[col]; dst_scale is
  *                 required; src_scale == NULL means the rows of h_src already
  *                 carry their source coefficient (see scale_rows / msg_out)
+ *   ITB_AGG_MAX / ITB_AGG_MIN: element-wise maximum / minimum of h[col] over
+ *                 the in-edges, exactly (no rounding: the result is one of
+ *                 the stored values); 0 for an isolated vertex; hub partials
+ *                 are merged by the same operator
  *   ITB_AGG_GAT : attention-weighted sum, see below.
  *
  *   dim        feature width; dim * sizeof(element) must be a multiple of 16.
@@ -241,6 +251,8 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
  * gather(h . W_nbr) (see apply_layer's addend); a GCN layer reads per-vertex
  * message rows h * deg_out^-1/2 written by the previous update (or scale_rows).
+ * An ITB_AGG_NONE layer is h' = act(h . w_nbr + bias) per vertex, no edges
+ * touched (w_self must be NULL).
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t agg;        /* ITB_AGG_* */

@@ -23,7 +23,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libgas_oracle.so")
 _lib = None
 
-SUM, MEAN, GCN, GAT = 0, 1, 2, 3
+SUM, MEAN, GCN, GAT, MAX, MIN, NONE = 0, 1, 2, 3, 4, 5, 6
 ACT_NONE, ACT_RELU = 0, 1
 
 
@@ -199,7 +199,12 @@ def round_store(x64, dtype):
 
 # ------------------------------------------------------------------ whole layers
 def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None):
-    """One SAGE/GCN-style layer: gather, store agg, apply.  Returns (agg_stored, y64)."""
+    """One SAGE/GCN-style layer: gather (sum, mean, degree-normalised sum, max or min), store agg, apply.
+    Returns (agg_stored, y64).  A layer without a gather (NONE: encoder before the first round, prediction
+    head after the last, Sec. IV-C) is the update of the vertex's own state alone: (None, y64)."""
+    if layer.agg == NONE:
+        hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
+        return None, apply(None, hs, None, layer.w_nbr, layer.bias, layer.act)
     a64 = gather(layer.agg, rowptr, col, h, deg_out=deg_out, verts=verts)
     a_st = round_store(a64, dtype)
     hs = h if verts is None else np.asarray(h)[np.asarray(verts)]

@@ -26,7 +26,7 @@
 #include <omp.h>
 #endif
 
-enum { ORC_SUM = 0, ORC_MEAN = 1, ORC_GCN = 2 };
+enum { ORC_SUM = 0, ORC_MEAN = 1, ORC_GCN = 2, ORC_MAX = 4, ORC_MIN = 5 };
 enum { ORC_ACT_NONE = 0, ORC_ACT_RELU = 1 };
 
 int oracle_set_threads(int n)
@@ -113,6 +113,9 @@ int oracle_split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t threshold,
  *   sum : agg[v] = sum_{u in in(v)} h[u]
  *   mean: sum / in-degree (0 for an isolated vertex)
  *   gcn : sum_{u} h[u] / sqrt(max(deg_out(u),1) * max(deg_in(v),1))
+ *   max / min: element-wise maximum / minimum over the in-neighbours' states
+ *         (Sec. IV-B lists max and min pooling among the commutative and
+ *         associative aggregates); 0 for an isolated vertex
  * h holds fp32 values (bf16 inputs are widened exactly by the caller).
  * verts == NULL: all vertices, out is [n_nodes x dim]; else out is
  * [n_verts x dim] for the listed vertices.
@@ -132,7 +135,12 @@ int oracle_gather(int agg, int64_t n_nodes, const int64_t *rowptr, const int32_t
         for (int64_t j = b; j < e; ++j) {
             int64_t u = col[j];
             const float *hu = h + u * dim;
-            if (agg == ORC_GCN) {
+            if (agg == ORC_MAX || agg == ORC_MIN) {
+                for (int64_t k = 0; k < dim; ++k) {
+                    double x = (double)hu[k];
+                    if (j == b || (agg == ORC_MAX ? x > acc[k] : x < acc[k])) acc[k] = x;
+                }
+            } else if (agg == ORC_GCN) {
                 double du = deg_out[u] > 1 ? (double)deg_out[u] : 1.0;
                 double dv = d > 1 ? (double)d : 1.0;
                 double c = 1.0 / sqrt(du * dv);
@@ -176,7 +184,14 @@ int oracle_gather_split(int agg, int64_t n_nodes, const int64_t *rowptr, const i
             int64_t u = col[j];
             double c = 1.0;
             if (agg == ORC_GCN) c = 1.0 / sqrt((deg_out[u] > 1 ? (double)deg_out[u] : 1.0) * (d > 1 ? (double)d : 1.0));
-            for (int64_t k = 0; k < dim; ++k) acc[k] += c * (double)h[u * dim + k];
+            if (agg == ORC_MAX || agg == ORC_MIN) {
+                for (int64_t k = 0; k < dim; ++k) {
+                    double x = (double)h[u * dim + k];
+                    if (j == rowptr[v] || (agg == ORC_MAX ? x > acc[k] : x < acc[k])) acc[k] = x;
+                }
+            } else {
+                for (int64_t k = 0; k < dim; ++k) acc[k] += c * (double)h[u * dim + k];
+            }
         }
         if (agg == ORC_MEAN && d > 0) for (int64_t k = 0; k < dim; ++k) acc[k] /= (double)d;
         if (edge_count) edge_count[v] = d;
@@ -193,10 +208,22 @@ int oracle_gather_split(int agg, int64_t n_nodes, const int64_t *rowptr, const i
                 int64_t u = col[j];
                 double c = 1.0;
                 if (agg == ORC_GCN) c = 1.0 / sqrt((deg_out[u] > 1 ? (double)deg_out[u] : 1.0) * (d > 1 ? (double)d : 1.0));
-                for (int64_t k = 0; k < dim; ++k) part[k] += c * (double)h[u * dim + k];
+                if (agg == ORC_MAX || agg == ORC_MIN) {
+                    for (int64_t k = 0; k < dim; ++k) {
+                        double x = (double)h[u * dim + k];
+                        if (j == shadow_begin[s] || (agg == ORC_MAX ? x > part[k] : x < part[k])) part[k] = x;
+                    }
+                } else {
+                    for (int64_t k = 0; k < dim; ++k) part[k] += c * (double)h[u * dim + k];
+                }
+            }
+            if (agg == ORC_MAX || agg == ORC_MIN) {   /* the partials of the mirrors are reduced by the same operator */
+                for (int64_t k = 0; k < dim; ++k)
+                    if (count == 0 || (agg == ORC_MAX ? part[k] > acc[k] : part[k] < acc[k])) acc[k] = part[k];
+            } else {
+                for (int64_t k = 0; k < dim; ++k) acc[k] += part[k];
             }
             count += shadow_end[s] - shadow_begin[s];
-            for (int64_t k = 0; k < dim; ++k) acc[k] += part[k];
         }
         if (agg == ORC_MEAN && count > 0) for (int64_t k = 0; k < dim; ++k) acc[k] /= (double)count;
         if (edge_count) edge_count[v] = count;

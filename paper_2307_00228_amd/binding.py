@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libinferturbo_hip.so")
 
 ITB_F32, ITB_BF16 = 0, 1
-AGG_SUM, AGG_MEAN, AGG_GCN, AGG_GAT = 0, 1, 2, 3
+AGG_SUM, AGG_MEAN, AGG_GCN, AGG_GAT, AGG_MAX, AGG_MIN, AGG_NONE = 0, 1, 2, 3, 4, 5, 6
 ACT_NONE, ACT_RELU = 0, 1
 INT64_MAX = (1 << 63) - 1
 

@@ -26,8 +26,8 @@ class LayerTrace:
 
 def project_before_gather(layer: B.DeviceLayer, dtype: torch.dtype) -> bool:
     elem = 2 if dtype == torch.bfloat16 else 4
-    return (layer.agg != B.AGG_GAT and layer.w_self is not None and layer.d_out < layer.d_in
-            and (layer.d_out * elem) % 16 == 0)
+    linear = layer.agg in (B.AGG_SUM, B.AGG_MEAN, B.AGG_GCN)
+    return linear and layer.w_self is not None and layer.d_out < layer.d_in and (layer.d_out * elem) % 16 == 0
 
 
 def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torch.Tensor,
@@ -54,6 +54,16 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         gcn, gat = l.agg == B.AGG_GCN, l.agg == B.AGG_GAT
         next_gcn = i + 1 < len(layers) and layers[i + 1].agg == B.AGG_GCN
         out = buf(("out", i), l.d_out)
+        if l.agg == B.AGG_NONE:       # encoder / prediction head: the update alone
+            nmsg = buf(("msg", i + 1), l.d_out) if next_gcn else None
+            mark("gather_begin", i)
+            mark("gather_end", i)
+            mark("apply_begin", i)
+            B.apply_layer(None, h, None, l.w_nbr, l.bias, l.act, out=out, msg_scale=ss if next_gcn else None, msg_out=nmsg)
+            mark("apply_end", i)
+            traces.append(LayerTrace(h, h, out, False))
+            h, msg = out, nmsg
+            continue
         if gat:
             mark("apply_begin", i)
             z, s_src, s_dst = B.apply_layer(None, h, None, l.w_nbr, None, B.ACT_NONE, out=buf(("z", i), l.d_out), heads=l.heads,

@@ -1,4 +1,4 @@
-// gather_layer: degree-segmented sum / mean / degree-normalised sum over in-edges (pull over CSR rows).
+// gather_layer: degree-segmented sum / mean / degree-normalised sum / max / min over in-edges (pull over CSR rows).
 //
 // Data movement is the whole cost (one 16-byte vector per lane per edge, one fp32 FMA per element), so the
 // kernels are organised around keeping many independent row loads in flight per wavefront:
@@ -41,7 +41,11 @@ size_t lds_for_occupancy(int waves, int lanes_per_row) {
 namespace {
 using namespace itb;
 
-enum { kModeSum = 0, kModeMean = 1, kModeScaleDst = 2 };
+enum { kModeSum = 0, kModeMean = 1, kModeScaleDst = 2, kModeMax = 3, kModeMin = 4 };
+
+// The extremum aggregators (EXT kernels) run as a maximum of sign * x with sign = +1 (max) or -1 (min); the
+// multiplication by +-1 is exact, so the result is bit-for-bit the extremum of the stored values.
+__device__ __forceinline__ float ext_sign(int mode) { return mode == kModeMin ? -1.f : 1.f; }
 
 struct GatherArgs {
     int64_t n_nodes;
@@ -70,9 +74,25 @@ struct Elems {
     static constexpr int kPerVec = BF16 ? 8 : 4;
 };
 
-template <bool BF16>
+template <bool BF16, bool EXT = false>
 __device__ __forceinline__ void accumulate(float (&acc)[Elems<BF16>::kPerVec], const uint4 &raw, float s) {
-    if constexpr (BF16) {
+    if constexpr (EXT) {
+        if constexpr (BF16) {
+            acc[0] = fmaxf(acc[0], s * bf16_lo(raw.x));
+            acc[1] = fmaxf(acc[1], s * bf16_hi(raw.x));
+            acc[2] = fmaxf(acc[2], s * bf16_lo(raw.y));
+            acc[3] = fmaxf(acc[3], s * bf16_hi(raw.y));
+            acc[4] = fmaxf(acc[4], s * bf16_lo(raw.z));
+            acc[5] = fmaxf(acc[5], s * bf16_hi(raw.z));
+            acc[6] = fmaxf(acc[6], s * bf16_lo(raw.w));
+            acc[7] = fmaxf(acc[7], s * bf16_hi(raw.w));
+        } else {
+            acc[0] = fmaxf(acc[0], s * __uint_as_float(raw.x));
+            acc[1] = fmaxf(acc[1], s * __uint_as_float(raw.y));
+            acc[2] = fmaxf(acc[2], s * __uint_as_float(raw.z));
+            acc[3] = fmaxf(acc[3], s * __uint_as_float(raw.w));
+        }
+    } else if constexpr (BF16) {
         acc[0] = fmaf(s, bf16_lo(raw.x), acc[0]);
         acc[1] = fmaf(s, bf16_hi(raw.x), acc[1]);
         acc[2] = fmaf(s, bf16_lo(raw.y), acc[2]);
@@ -87,6 +107,17 @@ __device__ __forceinline__ void accumulate(float (&acc)[Elems<BF16>::kPerVec], c
         acc[2] = fmaf(s, __uint_as_float(raw.z), acc[2]);
         acc[3] = fmaf(s, __uint_as_float(raw.w), acc[3]);
     }
+}
+
+// What a masked-off lane feeds to accumulate(): (raw, scale) that leave the accumulator unchanged.  Sums: 0 * 0.
+// Extrema: sign * (-sign * inf) = -inf, the identity of the running maximum.
+// (One 32-bit word of the vector; the callers build the vector as a temporary so that the select stays a select
+// of values and never becomes a select of addresses.)
+template <bool BF16, bool EXT>
+__device__ __forceinline__ uint32_t idle_word(float sign) {
+    if constexpr (!EXT) return 0u;
+    const uint32_t inf = BF16 ? 0x7f807f80u : 0x7f800000u, ninf = BF16 ? 0xff80ff80u : 0xff800000u;
+    return sign > 0.f ? ninf : inf;
 }
 
 // Store one lane's slice of an output row.  `vec` is the lane's 16-byte vector index in the INPUT row.
@@ -110,9 +141,14 @@ __device__ __forceinline__ void store_row_slice(void *out, int64_t row, int32_t 
     }
 }
 
-template <int VE>
+template <int VE, bool EXT = false>
 __device__ __forceinline__ void finish_row(float (&acc)[VE], int mode, int64_t deg, const float *dst_scale, int64_t row) {
-    if (mode == kModeMean) {
+    if constexpr (EXT) {
+        // back from sign * x to x; a vertex without in-edges aggregates to 0
+        const float s = deg > 0 ? ext_sign(mode) : 0.f;
+#pragma unroll
+        for (int i = 0; i < VE; ++i) acc[i] = deg > 0 ? acc[i] * s : 0.f;
+    } else if (mode == kModeMean) {
         if (deg > 0) {
             const float inv = 1.0f / (float)deg;  // one division per lane and row; the elements are scaled by it
 #pragma unroll
@@ -134,7 +170,7 @@ __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
 // Whole-wavefront sum of h[col[e]] * scale over the 64-edge chunks first_chunk, first_chunk + chunk_stride, ...
 // of the edge range [start, start+deg).  Group g takes the edges congruent to g modulo 64/G inside every
 // chunk; on return every lane group holds the sum over all the wavefront's chunks.
-template <bool BF16, int G>
+template <bool BF16, int G, bool EXT = false>
 __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerVec], const GatherArgs &a, int64_t start,
                                                  int64_t deg, int vec, bool lane_on, int first_chunk = 0,
                                                  int chunk_stride = 1) {
@@ -143,12 +179,15 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
     constexpr int U = 4;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
-    const bool has_scale = a.src_scale != nullptr;
+    const bool has_scale = !EXT && a.src_scale != nullptr;
+    const float unit = EXT ? ext_sign(a.mode) : 1.f;  // scale of an edge without a source coefficient
+    const float idle_s = EXT ? unit : 0.f;
+    const uint32_t idle = idle_word<BF16, EXT>(unit);
 #pragma unroll
-    for (int i = 0; i < VE; ++i) acc[i] = 0.f;
+    for (int i = 0; i < VE; ++i) acc[i] = EXT ? -INFINITY : 0.f;
     for (int64_t c = (int64_t)first_chunk * kWave; c < deg; c += (int64_t)chunk_stride * kWave) {
         int myc = 0;
-        float mys = 1.f;
+        float mys = unit;
         if (c + lane < deg) {
             myc = a.col[start + c + lane];
             if (has_scale) mys = a.src_scale[myc];
@@ -164,21 +203,24 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
                 const int u = __shfl(myc, ei & (kWave - 1), kWave);
                 const float s = __shfl(mys, ei & (kWave - 1), kWave);
                 const bool on = lane_on && ei < cnt;
-                raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
-                sc[q] = on ? s : 0.f;
+                raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(idle, idle, idle, idle);
+                sc[q] = on ? s : idle_s;
             }
 #pragma unroll
-            for (int q = 0; q < U; ++q) accumulate<BF16>(acc, raw[q], sc[q]);
+            for (int q = 0; q < U; ++q) accumulate<BF16, EXT>(acc, raw[q], sc[q]);
         }
     }
 #pragma unroll
     for (int off = G; off < kWave; off <<= 1) {
 #pragma unroll
-        for (int i = 0; i < VE; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
+        for (int i = 0; i < VE; ++i) {
+            const float o = __shfl_xor(acc[i], off, kWave);
+            acc[i] = EXT ? fmaxf(acc[i], o) : acc[i] + o;
+        }
     }
 }
 
-template <bool BF16_IN, bool BF16_OUT, int G>
+template <bool BF16_IN, bool BF16_OUT, int G, bool EXT>
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     constexpr int NG = kWave / G;
     constexpr int VE = Elems<BF16_IN>::kPerVec;
@@ -190,7 +232,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     if (r0 >= a.n_nodes) return;
     const int vec = blockIdx.y * G + li;
     const bool lane_on = vec < a.row_vecs;
-    const bool has_scale = a.src_scale != nullptr;
+    const bool has_scale = !EXT && a.src_scale != nullptr;
+    const float unit = EXT ? ext_sign(a.mode) : 1.f;
+    const float idle_s = EXT ? unit : 0.f;
+    const uint32_t idle = idle_word<BF16_IN, EXT>(unit);
 
     const int64_t my_row = r0 + lane;
     int64_t rs = 0, re = 0;
@@ -226,10 +271,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
             const int64_t st = shfl_i64(rs, rl);
             float acc[VE];
 #pragma unroll
-            for (int i = 0; i < VE; ++i) acc[i] = 0.f;
+            for (int i = 0; i < VE; ++i) acc[i] = EXT ? -INFINITY : 0.f;
             for (int j = 0; __ballot(j < d) != 0ull; j += G) {
                 int myc = 0;
-                float mys = 1.f;
+                float mys = unit;
                 if (j + li < d) {
                     myc = a.col[st + j + li];
                     if (has_scale) mys = a.src_scale[myc];
@@ -245,15 +290,15 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
                         const int u = __shfl(myc, sl, kWave);
                         const float s = __shfl(mys, sl, kWave);
                         const bool on = lane_on && (t + q) < cnt;
-                        raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
-                        sc[q] = on ? s : 0.f;
+                        raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(idle, idle, idle, idle);
+                        sc[q] = on ? s : idle_s;
                     }
 #pragma unroll
-                    for (int q = 0; q < U; ++q) accumulate<BF16_IN>(acc, raw[q], sc[q]);
+                    for (int q = 0; q < U; ++q) accumulate<BF16_IN, EXT>(acc, raw[q], sc[q]);
                 }
             }
             if (act && lane_on) {
-                finish_row<VE>(acc, a.mode, d, a.dst_scale, r0 + rl);
+                finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
                 store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
             }
         }
@@ -266,9 +311,9 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
         const int d = __shfl(deg, rl, kWave);
         const int64_t st = shfl_i64(rs, rl);
         float acc[VE];
-        wave_segment_sum<BF16_IN, G>(acc, a, st, d, vec, lane_on);
+        wave_segment_sum<BF16_IN, G, EXT>(acc, a, st, d, vec, lane_on);
         if (g == 0 && lane_on) {
-            finish_row<VE>(acc, a.mode, d, a.dst_scale, r0 + rl);
+            finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
             store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
         }
     }
@@ -278,13 +323,13 @@ constexpr int kRangeWaves = 8;  // wavefronts that share one edge range (a shado
 
 // Block-cooperative sum over one edge range: wave w takes the 64-edge chunks congruent to w modulo kRangeWaves,
 // the wave results are added in wave order.  On return lane group 0 of wave 0 holds the sum.
-template <bool BF16, int G>
+template <bool BF16, int G, bool EXT>
 __device__ __forceinline__ void block_range_sum(float (&acc)[Elems<BF16>::kPerVec], const GatherArgs &a, int64_t start,
                                                 int64_t deg, int vec, bool lane_on, float *sm) {
     constexpr int VE = Elems<BF16>::kPerVec;
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x / kWave;
-    wave_segment_sum<BF16, G>(acc, a, start, deg, vec, lane_on, w, kRangeWaves);
+    wave_segment_sum<BF16, G, EXT>(acc, a, start, deg, vec, lane_on, w, kRangeWaves);
     __syncthreads();  // the buffer may still be read from the previous range
     if (lane < G) {
 #pragma unroll
@@ -293,16 +338,20 @@ __device__ __forceinline__ void block_range_sum(float (&acc)[Elems<BF16>::kPerVe
     __syncthreads();
     if (w == 0 && lane < G) {
 #pragma unroll
-        for (int i = 0; i < VE; ++i) acc[i] = 0.f;
+        for (int i = 0; i < VE; ++i) acc[i] = EXT ? -INFINITY : 0.f;
         for (int ww = 0; ww < kRangeWaves; ++ww) {
 #pragma unroll
-            for (int i = 0; i < VE; ++i) acc[i] += sm[(ww * G + lane) * VE + i];
+            for (int i = 0; i < VE; ++i) {
+                const float o = sm[(ww * G + lane) * VE + i];
+                acc[i] = EXT ? fmaxf(acc[i], o) : acc[i] + o;
+            }
         }
     }
 }
 
-// One block per shadow segment: one fp32 partial row (source scales applied, destination finish deferred).
-template <bool BF16_IN, int G>
+// One block per shadow segment: one fp32 partial row (source scales applied, destination finish deferred; for the
+// extrema the partial is the maximum of sign * x).
+template <bool BF16_IN, int G, bool EXT>
 __global__ __launch_bounds__(kRangeWaves * kWave) void gather_segments_kernel(GatherArgs a) {
     constexpr int VE = Elems<BF16_IN>::kPerVec;
     __shared__ float sm[kRangeWaves * G * VE];
@@ -315,12 +364,12 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gather_segments_kernel(Ga
     const bool lane_on = vec < a.row_vecs;
     const int64_t b = a.shadow_begin[s];
     float acc[VE];
-    block_range_sum<BF16_IN, G>(acc, a, b, a.shadow_end[s] - b, vec, lane_on, sm);
+    block_range_sum<BF16_IN, G, EXT>(acc, a, b, a.shadow_end[s] - b, vec, lane_on, sm);
     if (threadIdx.x < G && lane_on) store_row_slice<BF16_IN, false>(a.out, s, a.row_vecs, vec, acc);
 }
 
 // Long rows from the work list, one block per row at a time.
-template <bool BF16_IN, bool BF16_OUT, int G>
+template <bool BF16_IN, bool BF16_OUT, int G, bool EXT>
 __global__ __launch_bounds__(kRangeWaves * kWave) void gather_long_rows_kernel(GatherArgs a) {
     constexpr int VE = Elems<BF16_IN>::kPerVec;
     __shared__ float sm[kRangeWaves * G * VE];
@@ -334,9 +383,9 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gather_long_rows_kernel(G
         const int64_t b = a.rowptr[row];
         const int64_t d = a.rowptr[row + 1] - b;
         float acc[VE];
-        block_range_sum<BF16_IN, G>(acc, a, b, d, vec, lane_on, sm);
+        block_range_sum<BF16_IN, G, EXT>(acc, a, b, d, vec, lane_on, sm);
         if (threadIdx.x < G && lane_on) {
-            finish_row<VE>(acc, a.mode, d, a.dst_scale, row);
+            finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, row);
             store_row_slice<BF16_IN, BF16_OUT>(a.out, row, a.row_vecs, vec, acc);
         }
     }
@@ -345,8 +394,8 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gather_long_rows_kernel(G
 __global__ void zero_u32_kernel(uint32_t *p) { *p = 0u; }
 
 // One block per hub: partial rows are added in ascending segment order within each of `slices` interleaved
-// chains, then the chains are added in ascending slice order.
-template <bool BF16_OUT>
+// chains, then the chains are added in ascending slice order (extrema: merged by maximum in the same order).
+template <bool BF16_OUT, bool EXT>
 __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, int32_t dim, int64_t n_hubs,
                                                             const int32_t *hub_ids, const int64_t *hub_shadow_off,
                                                             const int64_t *rowptr, const float *dst_scale, int32_t mode,
@@ -364,7 +413,9 @@ __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, i
         const int slices = 1024 / cols_here;
         const int slice = threadIdx.x / cols_here;
         const int lv = threadIdx.x % cols_here;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float zero = EXT ? -INFINITY : 0.f;
+        auto join = [](float x, float y) { return EXT ? fmaxf(x, y) : x + y; };
+        float4 acc = make_float4(zero, zero, zero, zero);
         if (slice < slices) {
             const float4 *p = reinterpret_cast<const float4 *>(part) + q0 + lv;
             int64_t s = s0 + slice;
@@ -373,26 +424,26 @@ __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, i
                 const float4 x1 = p[(s + slices) * lanes_per_row];
                 const float4 x2 = p[(s + 2 * (int64_t)slices) * lanes_per_row];
                 const float4 x3 = p[(s + 3 * (int64_t)slices) * lanes_per_row];
-                acc.x += x0.x; acc.y += x0.y; acc.z += x0.z; acc.w += x0.w;
-                acc.x += x1.x; acc.y += x1.y; acc.z += x1.z; acc.w += x1.w;
-                acc.x += x2.x; acc.y += x2.y; acc.z += x2.z; acc.w += x2.w;
-                acc.x += x3.x; acc.y += x3.y; acc.z += x3.z; acc.w += x3.w;
+                acc.x = join(acc.x, x0.x); acc.y = join(acc.y, x0.y); acc.z = join(acc.z, x0.z); acc.w = join(acc.w, x0.w);
+                acc.x = join(acc.x, x1.x); acc.y = join(acc.y, x1.y); acc.z = join(acc.z, x1.z); acc.w = join(acc.w, x1.w);
+                acc.x = join(acc.x, x2.x); acc.y = join(acc.y, x2.y); acc.z = join(acc.z, x2.z); acc.w = join(acc.w, x2.w);
+                acc.x = join(acc.x, x3.x); acc.y = join(acc.y, x3.y); acc.z = join(acc.z, x3.z); acc.w = join(acc.w, x3.w);
             }
             for (; s < s1; s += slices) {
                 const float4 x0 = p[s * lanes_per_row];
-                acc.x += x0.x; acc.y += x0.y; acc.z += x0.z; acc.w += x0.w;
+                acc.x = join(acc.x, x0.x); acc.y = join(acc.y, x0.y); acc.z = join(acc.z, x0.z); acc.w = join(acc.w, x0.w);
             }
         }
         __syncthreads();
         sm[threadIdx.x] = acc;
         __syncthreads();
         if (slice == 0) {
-            float r[4] = {0.f, 0.f, 0.f, 0.f};
+            float r[4] = {zero, zero, zero, zero};
             for (int k = 0; k < slices; ++k) {
                 const float4 x = sm[k * cols_here + lv];
-                r[0] += x.x; r[1] += x.y; r[2] += x.z; r[3] += x.w;
+                r[0] = join(r[0], x.x); r[1] = join(r[1], x.y); r[2] = join(r[2], x.z); r[3] = join(r[3], x.w);
             }
-            finish_row<4>(r, mode, deg, dst_scale, v);
+            finish_row<4, EXT>(r, mode, deg, dst_scale, v);
             const int64_t elem0 = (int64_t)v * dim + (int64_t)(q0 + lv) * 4;
             if constexpr (BF16_OUT) {
                 uint2 pk;
@@ -406,55 +457,55 @@ __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, i
     }
 }
 
-template <bool BF16_IN, bool BF16_OUT, int G>
+template <bool BF16_IN, bool BF16_OUT, int G, bool EXT>
 int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
     dim3 grid((unsigned)((waves + 3) / 4), (unsigned)((a.row_vecs + G - 1) / G));
     if (a.n_nodes > 0) {
         zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
         ITB_LAUNCH_CHECK();
-        gather_rows_kernel<BF16_IN, BF16_OUT, G><<<grid, 256, lds_for_occupancy(g_rows_waves_per_simd, G), st>>>(a);
+        gather_rows_kernel<BF16_IN, BF16_OUT, G, EXT><<<grid, 256, lds_for_occupancy(g_rows_waves_per_simd, G), st>>>(a);
         ITB_LAUNCH_CHECK();
         // the list length is only known on the device: a fixed grid walks it (blocks beyond the length exit)
         int64_t lg = (a.n_nodes + 63) / 64;
         if (lg > 2048) lg = 2048;
-        gather_long_rows_kernel<BF16_IN, BF16_OUT, G><<<dim3((unsigned)lg, grid.y), kRangeWaves * kWave, 0, st>>>(a);
+        gather_long_rows_kernel<BF16_IN, BF16_OUT, G, EXT><<<dim3((unsigned)lg, grid.y), kRangeWaves * kWave, 0, st>>>(a);
         ITB_LAUNCH_CHECK();
     }
     return ITB_OK;
 }
 
-template <bool BF16_IN, int G>
+template <bool BF16_IN, int G, bool EXT>
 int32_t launch_segments(const GatherArgs &a, hipStream_t st) {
     dim3 grid((unsigned)a.n_shadows, (unsigned)((a.row_vecs + G - 1) / G));
-    gather_segments_kernel<BF16_IN, G><<<grid, kRangeWaves * kWave, 0, st>>>(a);
+    gather_segments_kernel<BF16_IN, G, EXT><<<grid, kRangeWaves * kWave, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
 
-template <bool BF16_IN, bool BF16_OUT>
+template <bool BF16_IN, bool BF16_OUT, bool EXT>
 int32_t dispatch_rows(int G, const GatherArgs &a, hipStream_t st) {
     switch (G) {
-        case 1: return launch_rows<BF16_IN, BF16_OUT, 1>(a, st);
-        case 2: return launch_rows<BF16_IN, BF16_OUT, 2>(a, st);
-        case 4: return launch_rows<BF16_IN, BF16_OUT, 4>(a, st);
-        case 8: return launch_rows<BF16_IN, BF16_OUT, 8>(a, st);
-        case 16: return launch_rows<BF16_IN, BF16_OUT, 16>(a, st);
-        case 32: return launch_rows<BF16_IN, BF16_OUT, 32>(a, st);
-        default: return launch_rows<BF16_IN, BF16_OUT, 64>(a, st);
+        case 1: return launch_rows<BF16_IN, BF16_OUT, 1, EXT>(a, st);
+        case 2: return launch_rows<BF16_IN, BF16_OUT, 2, EXT>(a, st);
+        case 4: return launch_rows<BF16_IN, BF16_OUT, 4, EXT>(a, st);
+        case 8: return launch_rows<BF16_IN, BF16_OUT, 8, EXT>(a, st);
+        case 16: return launch_rows<BF16_IN, BF16_OUT, 16, EXT>(a, st);
+        case 32: return launch_rows<BF16_IN, BF16_OUT, 32, EXT>(a, st);
+        default: return launch_rows<BF16_IN, BF16_OUT, 64, EXT>(a, st);
     }
 }
 
-template <bool BF16_IN>
+template <bool BF16_IN, bool EXT>
 int32_t dispatch_segments(int G, const GatherArgs &a, hipStream_t st) {
     switch (G) {
-        case 1: return launch_segments<BF16_IN, 1>(a, st);
-        case 2: return launch_segments<BF16_IN, 2>(a, st);
-        case 4: return launch_segments<BF16_IN, 4>(a, st);
-        case 8: return launch_segments<BF16_IN, 8>(a, st);
-        case 16: return launch_segments<BF16_IN, 16>(a, st);
-        case 32: return launch_segments<BF16_IN, 32>(a, st);
-        default: return launch_segments<BF16_IN, 64>(a, st);
+        case 1: return launch_segments<BF16_IN, 1, EXT>(a, st);
+        case 2: return launch_segments<BF16_IN, 2, EXT>(a, st);
+        case 4: return launch_segments<BF16_IN, 4, EXT>(a, st);
+        case 8: return launch_segments<BF16_IN, 8, EXT>(a, st);
+        case 16: return launch_segments<BF16_IN, 16, EXT>(a, st);
+        case 32: return launch_segments<BF16_IN, 32, EXT>(a, st);
+        default: return launch_segments<BF16_IN, 64, EXT>(a, st);
     }
 }
 
@@ -472,7 +523,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
                                 void *stream) {
     if (!desc || !workspace_bytes) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
-    if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_GAT) return ITB_ERR_DTYPE;
+    if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_MIN) return ITB_ERR_DTYPE;
     if ((desc->dtype_in != ITB_F32 && desc->dtype_in != ITB_BF16) || (desc->dtype_out != ITB_F32 && desc->dtype_out != ITB_BF16))
         return ITB_ERR_DTYPE;
     if (desc->dtype_in == ITB_F32 && desc->dtype_out == ITB_BF16) return ITB_ERR_UNSUPPORTED;
@@ -514,7 +565,12 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     a.edge_lo = edge_lo;
     a.edge_hi = edge_hi;
     a.row_vecs = desc->dim * elem / 16;
-    a.mode = desc->agg == ITB_AGG_MEAN ? kModeMean : (desc->agg == ITB_AGG_GCN ? kModeScaleDst : kModeSum);
+    const bool ext = desc->agg == ITB_AGG_MAX || desc->agg == ITB_AGG_MIN;
+    a.mode = desc->agg == ITB_AGG_MEAN ? kModeMean
+             : desc->agg == ITB_AGG_GCN ? kModeScaleDst
+             : desc->agg == ITB_AGG_MAX ? kModeMax
+             : desc->agg == ITB_AGG_MIN ? kModeMin
+                                        : kModeSum;
     int G = 1;
     while (G < a.row_vecs && G < kWave) G <<= 1;
     const int ng = kWave / G;
@@ -525,9 +581,15 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
 
     const bool bin = desc->dtype_in == ITB_BF16, bout = desc->dtype_out == ITB_BF16;
     int32_t rc;
-    if (!bin) rc = dispatch_rows<false, false>(G, a, st);
-    else if (bout) rc = dispatch_rows<true, true>(G, a, st);
-    else rc = dispatch_rows<true, false>(G, a, st);
+    if (ext) {
+        if (!bin) rc = dispatch_rows<false, false, true>(G, a, st);
+        else if (bout) rc = dispatch_rows<true, true, true>(G, a, st);
+        else rc = dispatch_rows<true, false, true>(G, a, st);
+    } else {
+        if (!bin) rc = dispatch_rows<false, false, false>(G, a, st);
+        else if (bout) rc = dispatch_rows<true, true, false>(G, a, st);
+        else rc = dispatch_rows<true, false, false>(G, a, st);
+    }
     if (rc != ITB_OK) return rc;
 
     if (hubs) {
@@ -537,16 +599,13 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         s.shadow_begin = split->shadow_begin;
         s.shadow_end = split->shadow_end;
         s.shadow_owner = split->shadow_owner;
-        rc = bin ? dispatch_segments<true>(G, s, st) : dispatch_segments<false>(G, s, st);
+        if (ext) rc = bin ? dispatch_segments<true, true>(G, s, st) : dispatch_segments<false, true>(G, s, st);
+        else rc = bin ? dispatch_segments<true, false>(G, s, st) : dispatch_segments<false, false>(G, s, st);
         if (rc != ITB_OK) return rc;
-        if (bout)
-            combine_hubs_kernel<true><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
-                                                                                split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
-                                                                                edge_lo, edge_hi, agg_out);
-        else
-            combine_hubs_kernel<false><<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids,
-                                                                                 split->hub_shadow_off, rowptr, a.dst_scale, a.mode,
-                                                                                 edge_lo, edge_hi, agg_out);
+        auto combine = bout ? (ext ? combine_hubs_kernel<true, true> : combine_hubs_kernel<true, false>)
+                            : (ext ? combine_hubs_kernel<false, true> : combine_hubs_kernel<false, false>);
+        combine<<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids, split->hub_shadow_off,
+                                                          rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out);
         ITB_LAUNCH_CHECK();
     }
     return ITB_OK;

@@ -91,7 +91,8 @@ extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const
 // (d_out < d_in) the edges then carry d_out instead of d_in elements.
 static bool project_before_gather(const itb_layer &L, int32_t dtype) {
     const int elem = dtype == ITB_BF16 ? 2 : 4;
-    return L.agg != ITB_AGG_GAT && L.w_self != nullptr && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
+    const bool linear = L.agg == ITB_AGG_SUM || L.agg == ITB_AGG_MEAN || L.agg == ITB_AGG_GCN;
+    return linear && L.w_self != nullptr && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
 }
 
 extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
@@ -110,11 +111,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     size_t gather_ws = 0;
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
-        if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_GAT) return ITB_ERR_DTYPE;
+        if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_NONE) return ITB_ERR_DTYPE;
         if (L.d_in <= 0 || L.d_out <= 0) return ITB_ERR_SIZE;
         if (l > 0 && L.d_in != layers[l - 1].d_out) return ITB_ERR_SIZE;
         if (L.d_in > max_d) max_d = L.d_in;
         if (L.d_out > max_d) max_d = L.d_out;
+        if (L.agg == ITB_AGG_NONE) {  // per-vertex layer: no gather, no gather workspace
+            if (L.w_self) return ITB_ERR_UNSUPPORTED;
+            continue;
+        }
         any_gcn = any_gcn || L.agg == ITB_AGG_GCN;
         const bool gat = L.agg == ITB_AGG_GAT;
         if (gat && L.heads > max_heads) max_heads = L.heads;
@@ -157,6 +162,18 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
+        if (L.agg == ITB_AGG_NONE) {
+            // encoder / prediction head (Sec. IV-C): the update alone, on the vertex's own state
+            const bool next_gcn = (l + 1 < n_layers) && layers[l + 1].agg == ITB_AGG_GCN;
+            itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
+            int32_t rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
+                                     next_gcn ? src_scale : nullptr, next_gcn ? static_cast<void *>(msgbuf) : nullptr, nullptr,
+                                     stream);
+            if (rc != ITB_OK) return rc;
+            msg_ready = next_gcn;
+            cur = dst;
+            continue;
+        }
         const bool gat = L.agg == ITB_AGG_GAT;
         const bool gcn = L.agg == ITB_AGG_GCN;
         const void *gather_src = cur;

@@ -26,7 +26,7 @@ import numpy as np
 F32 = "f32"
 BF16 = "bf16"
 
-AGG_SUM, AGG_MEAN, AGG_GCN, AGG_GAT = 0, 1, 2, 3
+AGG_SUM, AGG_MEAN, AGG_GCN, AGG_GAT, AGG_MAX, AGG_MIN, AGG_NONE = 0, 1, 2, 3, 4, 5, 6
 ACT_NONE, ACT_RELU = 0, 1
 
 
@@ -181,15 +181,20 @@ def glorot(rng, fan_in: int, fan_out: int, shape, dtype: str) -> np.ndarray:
     return store(rng.uniform(-a, a, size=shape).astype(np.float32), dtype)
 
 
-def dense_layers(rng, agg: int, dims, dtype: str, bias_random: bool = False) -> List[Layer]:
+def dense_layers(rng, agg, dims, dtype: str, bias_random: bool = False) -> List[Layer]:
+    """``agg`` is one aggregator for every layer or a sequence with one entry per layer; an AGG_NONE entry is a
+    per-vertex layer (encoder / prediction head) that has no self matrix."""
     layers = []
+    kinds = [agg] * (len(dims) - 1) if isinstance(agg, int) else list(agg)
+    assert len(kinds) == len(dims) - 1
     for i in range(len(dims) - 1):
         di, do = dims[i], dims[i + 1]
         b = (rng.uniform(-0.1, 0.1, size=do).astype(np.float32) if bias_random
              else np.zeros(do, dtype=np.float32))
-        layers.append(Layer(agg=agg, d_in=di, d_out=do,
+        w_self = glorot(rng, di, do, (di, do), dtype)
+        layers.append(Layer(agg=kinds[i], d_in=di, d_out=do,
                             act=ACT_RELU if i < len(dims) - 2 else ACT_NONE,
-                            w_self=glorot(rng, di, do, (di, do), dtype),
+                            w_self=None if kinds[i] == AGG_NONE else w_self,
                             w_nbr=glorot(rng, di, do, (di, do), dtype),
                             bias=b))
     return layers

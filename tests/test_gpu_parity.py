@@ -220,6 +220,90 @@ def test_gather_chunked_equals_unchunked_and_is_deterministic(B):
     check_features(full, want, W.F32)
 
 
+# ------------------------------------------------------------------------------------------ max / min
+def assert_same_values(got_st, want64, what=""):
+    """Extrema select one of the stored inputs: the result must equal the oracle's value exactly (as numbers:
+    -0.0 == 0.0)."""
+    got = W.as_f32(got_st).astype(np.float64)
+    assert got.shape == want64.shape
+    bad = got != want64
+    assert not bad.any(), f"{what}: {int(bad.sum())} mismatches, first at {np.argwhere(bad)[0]}"
+
+
+@pytest.mark.parametrize("kind", [W.AGG_MAX, W.AGG_MIN])
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_extremum_gather_dims_no_split(B, kind, dtype):
+    for dim in GATHER_DIMS[dtype]:
+        n, e = 3000, 40000
+        src, dst, x = W.random_small_graph(dim + 1, n, e, dim, dtype, 0.15)
+        got, want, _ = run_gather(B, kind, n, src, dst, x, dtype)
+        assert_same_values(got, want, f"dim={dim}")
+
+
+@pytest.mark.parametrize("kind", [W.AGG_MAX, W.AGG_MIN])
+@pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.F32, 128), (W.BF16, 64), (W.BF16, 128), (W.BF16, 256)])
+@pytest.mark.parametrize("T", [1, 5, 64, 1000])
+def test_extremum_gather_with_hub_split(B, kind, dtype, dim, T):
+    n, e = 2000, 30000
+    src, dst, x = W.random_small_graph(T + dim + 2, n, e, dim, dtype, 0.35)
+    got, want, (r, _, _) = run_gather(B, kind, n, src, dst, x, dtype, T=T)
+    assert_same_values(got, want, f"T={T}")
+    assert (np.diff(r) > max(T, 512)).any()              # a hub went through partials (and beyond the long-row limit)
+
+
+def test_extremum_gather_edge_cases(B):
+    for n, e, hub in [(5, 0, 0.0), (1, 0, 0.0), (1, 300, 0.0), (64, 64, 1.0), (65, 4000, 0.9), (129, 1, 0.0)]:
+        src, dst, x = W.random_small_graph(n + e + 1, n, e, 64, W.F32, hub)
+        x = (x - np.float32(5.0)).astype(np.float32)        # all-negative rows: a zero-initialised maximum would show
+        for T in (None, 16):
+            for kind in (W.AGG_MAX, W.AGG_MIN):
+                got, want, (r, _, _) = run_gather(B, kind, n, src, dst, x, W.F32, T=T)
+                assert_same_values(got, want, f"n={n} e={e} T={T} kind={kind}")
+                assert not got[np.diff(r) == 0].any()       # no in-edge: exactly zero
+    # bf16 in, fp32 out and chunked launches: still the same numbers
+    n, e, dim = 4000, 50000, 128
+    src, dst, x = W.random_small_graph(12, n, e, dim, W.BF16, 0.3)
+    got, want, _ = run_gather(B, W.AGG_MAX, n, src, dst, x, W.BF16, T=100, out_f32=True)
+    assert got.dtype == np.float32
+    assert_same_values(got, want)
+    got, want, _ = run_gather(B, W.AGG_MIN, n, src, dst, x, W.BF16, T=100, chunk=7001)
+    assert_same_values(got, want)
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_infer_with_encoder_extremum_layers_and_head(B, dtype):
+    """Encoder (no gather) -> max -> min -> GCN -> mean -> prediction head (no gather), one infer_full_graph call."""
+    n, e = 5000, 80000
+    src, dst, x = W.random_small_graph(31, n, e, 48, dtype, 0.3)
+    kinds = [W.AGG_NONE, W.AGG_MAX, W.AGG_MIN, W.AGG_GCN, W.AGG_MEAN, W.AGG_NONE]
+    layers = W.dense_layers(np.random.default_rng(32), kinds, (48, 64, 64, 32, 64, 32, 8), dtype, bias_random=True)
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    want = oracle.infer_full_graph(r, c, d, x, layers, dtype)
+    from paper_2307_00228_amd import compose
+    import torch
+    for T in (None, 40):
+        split = B.split_hubs(rowptr, T) if T else None
+        dl, xd = B.device_layers(layers), B.to_device(x)
+        out = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd)
+        if dtype == W.F32:
+            check_features(B.to_numpy(out), W.as_f32(want), dtype, f"T={T}")
+        view = torch.int16 if dtype == W.BF16 else torch.int32
+        again = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd, edge_chunk=9000)
+        assert torch.equal(out.view(view), again.view(view))
+        steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd)
+        assert torch.equal(out.view(view), steps[-1].out.view(view))
+        # every layer on its own, from the state the GPU stored for the previous one (six bf16 roundings in a row,
+        # two of them through an extremum that picks the worst case, do not average out end to end)
+        h = x
+        for i, (lay, tr) in enumerate(zip(layers, steps)):
+            y64 = oracle.dense_layer(r, c, d, h, lay, dtype)[1]
+            check_features(B.to_numpy(tr.out), y64, dtype, f"T={T} layer {i}")
+            if lay.agg in (W.AGG_MAX, W.AGG_MIN):
+                assert_same_values(B.to_numpy(tr.agg), oracle.gather(lay.agg, r, c, h), f"T={T} layer {i} aggregate")
+            h = B.to_numpy(tr.out)
+
+
 # ------------------------------------------------------------------------------------------ apply
 APPLY_CASES = [(W.F32, 64, 64), (W.F32, 64, 16), (W.F32, 128, 128), (W.F32, 128, 64), (W.F32, 8, 1), (W.F32, 256, 256),
                (W.F32, 40, 100), (W.BF16, 128, 128), (W.BF16, 64, 64), (W.BF16, 64, 32), (W.BF16, 256, 256),

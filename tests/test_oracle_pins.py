@@ -255,6 +255,93 @@ def test_partial_gather_equals_unsplit(kind, T):
     assert np.array_equal(cnt, np.diff(rowptr))                  # message counts are exact
 
 
+# ---------------------------------------------------------------- max / min aggregators (Sec. IV-B)
+def brute_extremum(kind, n, src, dst, h):
+    """Straight from the edge list: the element-wise extremum over the rows of the in-neighbours."""
+    h = np.asarray(h, dtype=np.float64)
+    out = np.zeros((n, h.shape[1]))
+    for v in range(n):
+        nb = src[dst == v]
+        if len(nb):
+            out[v] = h[nb].max(axis=0) if kind == oracle.MAX else h[nb].min(axis=0)
+    return out
+
+
+@pytest.mark.parametrize("seed,n,e", [(0, 1, 0), (1, 1, 5), (2, 7, 0), (3, 12, 40), (4, 33, 300), (5, 64, 1000)])
+@pytest.mark.parametrize("kind", [oracle.MAX, oracle.MIN])
+def test_extremum_matches_brute_force(seed, n, e, kind):
+    src, dst, x = small_graph(seed, n, e, 5, hub=0.3)
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    got = oracle.gather(kind, rowptr, col, x)
+    assert np.array_equal(got, brute_extremum(kind, n, src, dst, x))     # exact: the result is one of the inputs
+    assert not got[np.diff(rowptr) == 0].any()                           # isolated vertex -> 0
+
+
+def test_extremum_invariants():
+    n, e, d = 70, 900, 5
+    src, dst, x = small_graph(83, n, e, d, hub=0.2)
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    mx, mn = oracle.gather(oracle.MAX, rowptr, col, x), oracle.gather(oracle.MIN, rowptr, col, x)
+    mean = oracle.gather(oracle.MEAN, rowptr, col, x)
+    has = np.diff(rowptr) > 0
+    assert (mx[has] >= mean[has] - 1e-12).all() and (mean[has] >= mn[has] - 1e-12).all()
+    assert (mx[has] > mn[has]).any()
+    assert np.array_equal(oracle.gather(oracle.MIN, rowptr, col, -x), -mx)   # min(x) = -max(-x)
+    # a monotone map commutes with the extremum; doubling every edge changes nothing (idempotent)
+    y = (np.float32(3.0) * x + np.float32(1.0)).astype(np.float32)
+    assert np.array_equal(oracle.gather(oracle.MAX, rowptr, col, y),
+                          np.where(has[:, None], (np.float32(3.0) * mx.astype(np.float32) + np.float32(1.0)).astype(np.float64), 0.0))
+    r2, c2, _ = oracle.build_csr(n, np.concatenate([src, src]), np.concatenate([dst, dst]))
+    assert np.array_equal(oracle.gather(oracle.MAX, r2, c2, x), mx)
+    # a single in-edge returns the source row; the order of the edges does not matter
+    one = np.nonzero(np.diff(rowptr) == 1)[0]
+    if len(one):
+        assert np.array_equal(mx[one], x[col[rowptr[one]]].astype(np.float64))
+        assert np.array_equal(mn[one], mx[one])
+    p = np.random.default_rng(84).permutation(e)
+    r3, c3, _ = oracle.build_csr(n, src[p], dst[p])
+    assert np.array_equal(oracle.gather(oracle.MIN, r3, c3, x), mn)
+    verts = np.array([0, 5, 69, 17, 5], dtype=np.int64)
+    assert np.array_equal(oracle.gather(oracle.MAX, rowptr, col, x, verts=verts), mx[verts])
+
+
+@pytest.mark.parametrize("kind", [oracle.MAX, oracle.MIN])
+@pytest.mark.parametrize("T", [1, 2, 3, 5, 64, 10_000])
+def test_partial_extremum_equals_unsplit(kind, T):
+    n, e, d = 80, 2500, 6
+    src, dst, x = small_graph(71, n, e, d, hub=0.4)
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    whole = oracle.gather(kind, rowptr, col, x)
+    parts, cnt = oracle.gather_split(kind, rowptr, col, x, oracle.split_hubs(rowptr, T))
+    assert np.array_equal(parts, whole)
+    assert np.array_equal(cnt, np.diff(rowptr))
+    assert np.array_equal(whole, brute_extremum(kind, n, src, dst, x))
+
+
+def test_layer_without_gather_and_extremum_layers_against_numpy():
+    """Encoder -> max-pool layer -> min-pool layer -> prediction head, recomputed with numpy from the stored states."""
+    n, e = 60, 700
+    src, dst, x = small_graph(150, n, e, 12)
+    rng = np.random.default_rng(151)
+    layers = W.dense_layers(rng, [W.AGG_NONE, W.AGG_MAX, W.AGG_MIN, W.AGG_NONE], (12, 8, 8, 8, 3), W.F32, bias_random=True)
+    assert layers[0].w_self is None and layers[3].w_self is None and layers[1].w_self is not None
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    outs = oracle.infer_full_graph(rowptr, col, deg_out, x, layers, W.F32, return_all=True)
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    h = f64(x)
+    for i, lay in enumerate(layers):
+        if lay.agg == W.AGG_NONE:
+            y = h @ f64(lay.w_nbr) + lay.bias
+        else:
+            agg = brute_extremum(oracle.MAX if lay.agg == W.AGG_MAX else oracle.MIN, n, src, dst, h)
+            y = h @ f64(lay.w_self) + agg @ f64(lay.w_nbr) + lay.bias
+        if i < len(layers) - 1:
+            y = np.maximum(y, 0.0)
+        np.testing.assert_allclose(f64(outs[i]), y, rtol=1e-6, atol=1e-6)
+        h = f64(outs[i])                                         # next layer reads the stored (rounded) state
+    assert outs[-1].shape == (n, 3)
+
+
 # ---------------------------------------------------------------- algebraic invariants
 def test_linearity_and_edge_permutation_and_relabelling():
     n, e, d = 70, 900, 5
