@@ -42,15 +42,48 @@ __global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
-// Range check of both endpoints.
-__global__ void check_edges_kernel(int64_t n_edges, uint32_t n_nodes, const int32_t *src, const int32_t *dst,
-                                   uint32_t *bad_flag) {
+// First read of the raw edge table: range check of both endpoints and, in the same pass, the first-digit tile
+// histograms of both sorts (the destinations' for the CSR, the sources' for the out-degrees when WITH_SRC).
+// Layout of each histogram as in radix_hist_kernel.
+template <bool WITH_SRC>
+__global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, uint32_t n_nodes, const int32_t *src,
+                                                              const int32_t *dst, int bits, uint32_t *hist_dst,
+                                                              uint32_t *hist_src, int64_t nblocks, int remap,
+                                                              uint32_t *bad_flag) {
+    __shared__ uint32_t hd[kMaxRadix];
+    __shared__ uint32_t hs[WITH_SRC ? kMaxRadix : 1];
+    const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
+    const int radix = 1 << bits;
+    const uint32_t mask = radix - 1;
+    for (int d = threadIdx.x; d < radix; d += kThreads) {
+        hd[d] = 0;
+        if constexpr (WITH_SRC) hs[d] = 0;
+    }
+    __syncthreads();
+    const int64_t base = tile * kTile;
     bool bad = false;
-    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n_edges; e += (int64_t)gridDim.x * blockDim.x) {
-        uint32_t s = (uint32_t)src[e], d = (uint32_t)dst[e];
-        bad = bad || s >= n_nodes || d >= n_nodes;
+    uint32_t kd[kItems], ks[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t idx = base + i * kThreads + threadIdx.x;
+        kd[i] = idx < n_edges ? (uint32_t)dst[idx] : 0u;
+        ks[i] = idx < n_edges ? (uint32_t)src[idx] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t idx = base + i * kThreads + threadIdx.x;
+        if (idx < n_edges) {
+            bad = bad || kd[i] >= n_nodes || ks[i] >= n_nodes;
+            atomicAdd(&hd[kd[i] & mask], 1u);
+            if constexpr (WITH_SRC) atomicAdd(&hs[ks[i] & mask], 1u);
+        }
     }
     if (bad) atomicOr(bad_flag, 1u);
+    __syncthreads();
+    for (int d = threadIdx.x; d < radix; d += kThreads) {
+        hist_dst[(int64_t)d * nblocks + tile] = hd[d];
+        if constexpr (WITH_SRC) hist_src[(int64_t)d * nblocks + tile] = hs[d];
+    }
 }
 
 // hist[digit * nblocks + block] = number of keys of this block's tile with that digit.
@@ -221,17 +254,35 @@ int32_t exclusive_scan_u32(uint32_t *data, int64_t n, uint32_t *ws, hipStream_t 
 
 // rowptr[v] = index of the first sorted key >= v.  The thread at the start of each run of equal keys fills
 // the row pointers of its own key and of the empty rows just before it; the last thread fills the tail.
+// A thread looks at four consecutive keys (one 16-byte load; `keys` is 16-byte aligned) and the key before them.
 template <typename OutT>
 __global__ void rowptr_from_sorted_kernel(const uint32_t *keys, int64_t n_edges, int64_t n_nodes, OutT *rowptr) {
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_edges; i += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t k = keys[i];
-        const int64_t kp = (i == 0) ? -1 : (int64_t)keys[i - 1];
-        if (k != kp) {
-            const int64_t hi = k < n_nodes ? k : n_nodes;
-            for (int64_t v = kp + 1; v <= hi; ++v) rowptr[v] = (OutT)i;
+    const int64_t n_quads = (n_edges + 3) / 4;
+    for (int64_t q = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; q < n_quads; q += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i0 = 4 * q;
+        uint32_t kk[4];
+        if (i0 + 3 < n_edges) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(keys + i0);
+            kk[0] = v.x; kk[1] = v.y; kk[2] = v.z; kk[3] = v.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kk[j] = (i0 + j < n_edges) ? keys[i0 + j] : 0u;
         }
-        if (i == n_edges - 1)
-            for (int64_t v = k + 1; v <= n_nodes; ++v) rowptr[v] = (OutT)n_edges;
+        int64_t kp = (i0 == 0) ? -1 : (int64_t)keys[i0 - 1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t i = i0 + j;
+            if (i < n_edges) {
+                const int64_t k = kk[j];
+                if (k != kp) {
+                    const int64_t hi = k < n_nodes ? k : n_nodes;
+                    for (int64_t v = kp + 1; v <= hi; ++v) rowptr[v] = (OutT)i;
+                }
+                if (i == n_edges - 1)
+                    for (int64_t v = k + 1; v <= n_nodes; ++v) rowptr[v] = (OutT)n_edges;
+                kp = k;
+            }
+        }
     }
 }
 
@@ -269,6 +320,8 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     uint32_t *kbuf1 = cv.take<uint32_t>((size_t)n_edges);
     int32_t *vtmp = cv.take<int32_t>((size_t)n_edges);
     uint32_t *hist = cv.take<uint32_t>((size_t)hist_elems);
+    uint32_t *hist_src = cv.take<uint32_t>((size_t)hist_elems);  // histograms of the source sort (reserved whether or not
+                                                                  // deg_out is asked for: the size query passes no pointers)
     uint32_t *scan_ws = cv.take<uint32_t>(scan_workspace_elems(hist_elems) + 64);
     uint32_t *bounds = cv.take<uint32_t>((size_t)n_nodes + 1);
     if (!workspace) {
@@ -290,16 +343,24 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
         return (n_edges > 0) ? ITB_ERR_RANGE : ITB_OK;
     }
 
-    fill_u32_kernel<<<1, 64, 0, st>>>(flag, 64, 0u);
-    ITB_LAUNCH_CHECK();
-    check_edges_kernel<<<grid_for(n_edges, 256, 8192), 256, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, flag);
-    ITB_LAUNCH_CHECK();
-
     int bits_total = ceil_log2(n_nodes);
     if (bits_total < 1) bits_total = 1;
     const int passes = (bits_total + 7) / 8;
     const int base_bits = bits_total / passes, extra = bits_total % passes;
     uint32_t *kbuf[2] = {kbuf0, kbuf1};
+
+    fill_u32_kernel<<<1, 64, 0, st>>>(flag, 64, 0u);
+    ITB_LAUNCH_CHECK();
+    {
+        const int bits0 = base_bits + (0 < extra ? 1 : 0);
+        if (deg_out)
+            first_pass_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, hist_src,
+                                                                            nblocks, itb::g_csr_xcd_remap, flag);
+        else
+            first_pass_kernel<false><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, nullptr,
+                                                                             nblocks, itb::g_csr_xcd_remap, flag);
+        ITB_LAUNCH_CHECK();
+    }
 
     // One radix sort, run once or twice: keys only over the sources (their run lengths are the out-degrees;
     // a histogram by atomics would cost one memory-side atomic per edge), then (dst, src) pairs for the CSR.
@@ -314,16 +375,20 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
             uint32_t *kout = kbuf[p & 1];
             int32_t *vout = ((passes - 1 - p) % 2 == 0) ? col : vtmp;
             const int64_t hist_n = ((int64_t)1 << bits) * nblocks;
-            radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, hist, nblocks, itb::g_csr_xcd_remap);
-            ITB_LAUNCH_CHECK();
-            int32_t rc = exclusive_scan_u32(hist, hist_n, scan_ws, st);
+            // the first digit of both sorts was counted while the raw table was range-checked
+            uint32_t *h = pairs ? hist : hist_src;  // separate buffers: the pairs' first histogram must survive the source sort
+            if (p > 0) {
+                radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, h, nblocks, itb::g_csr_xcd_remap);
+                ITB_LAUNCH_CHECK();
+            }
+            int32_t rc = exclusive_scan_u32(h, hist_n, scan_ws, st);
             if (rc != ITB_OK) return rc;
             if (pairs)
-                radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, hist,
+                radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, h,
                                                                                    nblocks, itb::g_csr_xcd_remap);
             else
                 radix_scatter_kernel<false><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, nullptr, kout, nullptr, n_edges, shift, bits,
-                                                                                    hist, nblocks, itb::g_csr_xcd_remap);
+                                                                                    h, nblocks, itb::g_csr_xcd_remap);
             ITB_LAUNCH_CHECK();
             kin = kout;
             vin = vout;
