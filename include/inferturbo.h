@@ -277,8 +277,12 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
  * itb_copy_bytes: plain device copy of n_bytes (multiple of 16) with one
  * 16-byte load and store per lane; the known-size kernel that hardware byte
  * counters are scaled against.
- * itb_set_tuning: key 0 = in-degree up to which gather processes one row per
- * lane group instead of per wavefront (-1 = built-in choice).
+ * itb_set_tuning: process-wide switches for A/B measurements.  key 0 = in-degree
+ * up to which gather processes one row per lane group instead of per wavefront
+ * (-1 = built-in choice); 2 = XCD-contiguous tile order in the radix passes
+ * (1 = on); 3 = in-degree above which a non-hub row gets a whole block (512);
+ * 4 = resident wavefronts per SIMD of the row gather (-1 = built-in choice);
+ * 5 = out-degrees from a keys-only sort instead of partition + bucket counts.
  * ------------------------------------------------------------------------- */
 int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream);
 int32_t itb_set_tuning(int32_t key, int32_t value);

@@ -9,6 +9,7 @@
 
 namespace itb {
 int g_csr_xcd_remap = 1;  // tuning hook (key 2): 0 = tiles in launch order
+int g_csr_deg_by_sort = 0;  // tuning hook (key 5): 1 = out-degrees always from a keys-only run of the stable sort
 }
 
 namespace {
@@ -19,6 +20,11 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kItems = 16;
 constexpr int kTile = kThreads * kItems;  // keys per block
 constexpr int kMaxRadix = 256;
+constexpr int kMaxPartRadix = 512;  // buckets of the out-degree partition (top bits of the source id)
+constexpr int kMaxLowBits = 13;     // vertex ids per bucket: 2^13 counters of 4 bytes in LDS
+constexpr int kDegThreads = 1024;
+constexpr int kDegSlice = 1 << 18;  // keys one block counts per visit
+constexpr int kDegSlicesY = 16;
 
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 8;
@@ -35,6 +41,13 @@ __device__ __forceinline__ int64_t xcd_contiguous_tile(int64_t block, int64_t nb
     return x * per + (x < rem ? x : rem) + j;
 }
 
+// Digit of the out-degree partition: the bits above `shift`, clamped so that an out-of-range id (reported as an
+// error by the range check) still lands in a valid bucket.
+__device__ __forceinline__ uint32_t partition_digit(uint32_t key, int shift, int radix) {
+    const uint32_t d = key >> shift;
+    return d < (uint32_t)radix ? d : (uint32_t)radix - 1u;
+}
+
 __global__ void fill_i64_kernel(int64_t *p, int64_t n, int64_t v) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -45,20 +58,22 @@ __global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v) {
 // First read of the raw edge table: range check of both endpoints and, in the same pass, the first-digit tile
 // histograms of both sorts (the destinations' for the CSR, the sources' for the out-degrees when WITH_SRC).
 // Layout of each histogram as in radix_hist_kernel.
-template <bool WITH_SRC>
+// SRC_MODE 0: destinations only; 1: source digit = key & (src_radix - 1) (first pass of the keys-only sort);
+// 2: source digit = partition_digit(key, src_shift, src_radix).
+template <int SRC_MODE>
 __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, uint32_t n_nodes, const int32_t *src,
                                                               const int32_t *dst, int bits, uint32_t *hist_dst,
-                                                              uint32_t *hist_src, int64_t nblocks, int remap,
-                                                              uint32_t *bad_flag) {
+                                                              int src_shift, int src_radix, uint32_t *hist_src,
+                                                              int64_t nblocks, int remap, uint32_t *bad_flag) {
     __shared__ uint32_t hd[kMaxRadix];
-    __shared__ uint32_t hs[WITH_SRC ? kMaxRadix : 1];
+    constexpr bool WITH_SRC = SRC_MODE != 0;
+    __shared__ uint32_t hs[WITH_SRC ? kMaxPartRadix : 1];
     const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
     const int radix = 1 << bits;
     const uint32_t mask = radix - 1;
-    for (int d = threadIdx.x; d < radix; d += kThreads) {
-        hd[d] = 0;
-        if constexpr (WITH_SRC) hs[d] = 0;
-    }
+    for (int d = threadIdx.x; d < radix; d += kThreads) hd[d] = 0;
+    if constexpr (WITH_SRC)
+        for (int d = threadIdx.x; d < src_radix; d += kThreads) hs[d] = 0;
     __syncthreads();
     const int64_t base = tile * kTile;
     bool bad = false;
@@ -75,14 +90,121 @@ __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, u
         if (idx < n_edges) {
             bad = bad || kd[i] >= n_nodes || ks[i] >= n_nodes;
             atomicAdd(&hd[kd[i] & mask], 1u);
-            if constexpr (WITH_SRC) atomicAdd(&hs[ks[i] & mask], 1u);
+            if constexpr (SRC_MODE == 1) atomicAdd(&hs[ks[i] & (uint32_t)(src_radix - 1)], 1u);
+            if constexpr (SRC_MODE == 2) atomicAdd(&hs[partition_digit(ks[i], src_shift, src_radix)], 1u);
         }
     }
     if (bad) atomicOr(bad_flag, 1u);
     __syncthreads();
+    for (int d = threadIdx.x; d < radix; d += kThreads) hist_dst[(int64_t)d * nblocks + tile] = hd[d];
+    if constexpr (WITH_SRC)
+        for (int d = threadIdx.x; d < src_radix; d += kThreads) hist_src[(int64_t)d * nblocks + tile] = hs[d];
+}
+
+// ---- out-degrees: one partition pass + one histogram per bucket -----------------------------------------
+// deg_out is the histogram of the source column.  Only counts are wanted, so nothing has to be stable: the
+// sources are partitioned once by their top bits (order inside a bucket arbitrary, only the low bits are kept,
+// as 16-bit values), and each bucket -- a contiguous range of at most 2^13 vertex ids -- is counted in LDS and
+// stored.  All counters are integers, so the result does not depend on any ordering.
+//
+// Unstable partition of one tile: local slot by LDS atomics, tile put in digit order in LDS, runs written out
+// by consecutive threads.  Same tile numbering and histogram layout as the stable scatter.
+__global__ __launch_bounds__(kThreads) void partition_scatter_kernel(const uint32_t *keys_in, uint16_t *low_out, int64_t n,
+                                                                     int shift, int radix, const uint32_t *hist_scanned,
+                                                                     int64_t nblocks, int remap) {
+    __shared__ uint32_t cnt[kMaxPartRadix];
+    __shared__ uint32_t lstart[kMaxPartRadix];
+    __shared__ uint32_t gbase[kMaxPartRadix];
+    __shared__ uint32_t skey[kTile];  // (digit << 16) | low bits
+    __shared__ uint32_t scan_sm[17];
+    const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
     for (int d = threadIdx.x; d < radix; d += kThreads) {
-        hist_dst[(int64_t)d * nblocks + tile] = hd[d];
-        if constexpr (WITH_SRC) hist_src[(int64_t)d * nblocks + tile] = hs[d];
+        cnt[d] = 0;
+        gbase[d] = hist_scanned[(int64_t)d * nblocks + tile];
+    }
+    __syncthreads();
+    const int64_t base = tile * kTile;
+    const uint32_t low_mask = (1u << shift) - 1u;
+    uint32_t key[kItems], slot[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t idx = base + i * kThreads + threadIdx.x;
+        key[i] = idx < n ? keys_in[idx] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t idx = base + i * kThreads + threadIdx.x;
+        slot[i] = 0;
+        if (idx < n) slot[i] = atomicAdd(&cnt[partition_digit(key[i], shift, radix)], 1u);
+    }
+    __syncthreads();
+    // exclusive prefix over the digits, two digits per thread (radix <= 2 * kThreads)
+    const int d0 = 2 * threadIdx.x, d1 = d0 + 1;
+    const uint32_t c0 = d0 < radix ? cnt[d0] : 0u, c1 = d1 < radix ? cnt[d1] : 0u;
+    uint32_t tile_total;
+    const uint32_t ex = block_exclusive_scan<uint32_t>(c0 + c1, scan_sm, &tile_total);
+    if (d0 < radix) lstart[d0] = ex;
+    if (d1 < radix) lstart[d1] = ex + c0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t idx = base + i * kThreads + threadIdx.x;
+        if (idx < n) {
+            const uint32_t d = partition_digit(key[i], shift, radix);
+            skey[lstart[d] + slot[i]] = (d << 16) | (key[i] & low_mask);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < tile_total; i += kThreads) {
+        const uint32_t k = skey[i];
+        const uint32_t d = k >> 16;
+        low_out[gbase[d] + (i - lstart[d])] = (uint16_t)(k & 0xffffu);
+    }
+}
+
+// Block (b, y): bucket b = vertex ids [b << low, (b+1) << low), its keys are low_keys[start_b, start_{b+1}).
+// The bucket is cut into slices of kDegSlice keys; block y counts slices y, y + gridDim.y, ...  A bucket with one
+// slice (the normal case) is stored directly; a larger one adds its non-zero counters with integer atomics to
+// deg_out, which the caller has zeroed.
+__global__ __launch_bounds__(kDegThreads) void bucket_degree_kernel(const uint16_t *low_keys, int64_t n_edges,
+                                                                    const uint32_t *hist_scanned, int64_t nblocks, int radix,
+                                                                    int low, int64_t n_nodes, int32_t *deg_out) {
+    __shared__ uint32_t h[1 << kMaxLowBits];
+    const int b = blockIdx.x;
+    const int64_t start = hist_scanned[(int64_t)b * nblocks];
+    const int64_t end = (b + 1 < radix) ? (int64_t)hist_scanned[(int64_t)(b + 1) * nblocks] : n_edges;
+    const int64_t len = end - start;
+    const int64_t n_slices = (len + kDegSlice - 1) / kDegSlice;
+    if ((int64_t)blockIdx.y >= (n_slices > 1 ? n_slices : 1)) return;
+    const int bins = 1 << low;
+    for (int i = threadIdx.x; i < bins; i += kDegThreads) h[i] = 0;
+    __syncthreads();
+    for (int64_t sl = blockIdx.y; sl < n_slices; sl += gridDim.y) {
+        const int64_t s0 = start + sl * kDegSlice;
+        const int64_t s1 = (s0 + kDegSlice < end) ? s0 + kDegSlice : end;
+        // head and tail by single elements, the 16-byte aligned body eight keys at a time
+        int64_t a0 = (s0 + 7) & ~(int64_t)7, a1 = s1 & ~(int64_t)7;
+        if (a0 > a1) { a0 = s1; a1 = s1; }
+        for (int64_t i = s0 + threadIdx.x; i < a0; i += kDegThreads) atomicAdd(&h[low_keys[i]], 1u);
+        for (int64_t i = a1 + threadIdx.x; i < s1; i += kDegThreads) atomicAdd(&h[low_keys[i]], 1u);
+        const uint4 *body = reinterpret_cast<const uint4 *>(low_keys + a0);
+        const int64_t n_vec = (a1 - a0) / 8;
+        for (int64_t i = threadIdx.x; i < n_vec; i += kDegThreads) {
+            const uint4 v = body[i];
+            atomicAdd(&h[v.x & 0xffffu], 1u); atomicAdd(&h[v.x >> 16], 1u);
+            atomicAdd(&h[v.y & 0xffffu], 1u); atomicAdd(&h[v.y >> 16], 1u);
+            atomicAdd(&h[v.z & 0xffffu], 1u); atomicAdd(&h[v.z >> 16], 1u);
+            atomicAdd(&h[v.w & 0xffffu], 1u); atomicAdd(&h[v.w >> 16], 1u);
+        }
+    }
+    __syncthreads();
+    const int64_t v0 = (int64_t)b << low;
+    for (int i = threadIdx.x; i < bins; i += kDegThreads) {
+        const int64_t v = v0 + i;
+        if (v < n_nodes) {
+            if (n_slices <= 1) deg_out[v] = (int32_t)h[i];
+            else if (h[i]) atomicAdd(&deg_out[v], (int32_t)h[i]);
+        }
     }
 }
 
@@ -314,15 +436,16 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
 
     const int64_t nblocks = (n_edges + kTile - 1) / kTile;
     const int64_t hist_elems = (int64_t)kMaxRadix * (nblocks > 0 ? nblocks : 1);
+    const int64_t part_hist_elems = (int64_t)kMaxPartRadix * (nblocks > 0 ? nblocks : 1);
     Carver cv(workspace);
     uint32_t *flag = cv.take<uint32_t>(64);
     uint32_t *kbuf0 = cv.take<uint32_t>((size_t)n_edges);
     uint32_t *kbuf1 = cv.take<uint32_t>((size_t)n_edges);
     int32_t *vtmp = cv.take<int32_t>((size_t)n_edges);
     uint32_t *hist = cv.take<uint32_t>((size_t)hist_elems);
-    uint32_t *hist_src = cv.take<uint32_t>((size_t)hist_elems);  // histograms of the source sort (reserved whether or not
+    uint32_t *hist_src = cv.take<uint32_t>((size_t)part_hist_elems);  // histograms of the source sort (reserved whether or not
                                                                   // deg_out is asked for: the size query passes no pointers)
-    uint32_t *scan_ws = cv.take<uint32_t>(scan_workspace_elems(hist_elems) + 64);
+    uint32_t *scan_ws = cv.take<uint32_t>(scan_workspace_elems(part_hist_elems) + 64);
     uint32_t *bounds = cv.take<uint32_t>((size_t)n_nodes + 1);
     if (!workspace) {
         *workspace_bytes = cv.off;
@@ -349,23 +472,49 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     const int base_bits = bits_total / passes, extra = bits_total % passes;
     uint32_t *kbuf[2] = {kbuf0, kbuf1};
 
+    // Out-degrees by partition + bucket histogram when a bucket's id range fits the LDS counters (N <= 2^22);
+    // otherwise by a keys-only run of the stable sort (run lengths of the sorted sources).
+    int part_high = bits_total - 6;
+    if (part_high < 1) part_high = 1;
+    if (part_high > 9) part_high = 9;
+    if (part_high > bits_total) part_high = bits_total;
+    const int part_low = bits_total - part_high;
+    const bool deg_by_partition = deg_out && part_low <= kMaxLowBits && itb::g_csr_deg_by_sort == 0;
+
     fill_u32_kernel<<<1, 64, 0, st>>>(flag, 64, 0u);
     ITB_LAUNCH_CHECK();
     {
         const int bits0 = base_bits + (0 < extra ? 1 : 0);
-        if (deg_out)
-            first_pass_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, hist_src,
-                                                                            nblocks, itb::g_csr_xcd_remap, flag);
+        if (deg_by_partition)
+            first_pass_kernel<2><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, part_low,
+                                                                         1 << part_high, hist_src, nblocks, itb::g_csr_xcd_remap, flag);
+        else if (deg_out)
+            first_pass_kernel<1><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, 0, 1 << bits0,
+                                                                         hist_src, nblocks, itb::g_csr_xcd_remap, flag);
         else
-            first_pass_kernel<false><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, nullptr,
-                                                                             nblocks, itb::g_csr_xcd_remap, flag);
+            first_pass_kernel<0><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, 0, 1,
+                                                                             nullptr, nblocks, itb::g_csr_xcd_remap, flag);
+        ITB_LAUNCH_CHECK();
+    }
+    if (deg_by_partition) {
+        const int radix = 1 << part_high;
+        int32_t rc = exclusive_scan_u32(hist_src, (int64_t)radix * nblocks, scan_ws, st);
+        if (rc != ITB_OK) return rc;
+        uint16_t *low_keys = reinterpret_cast<uint16_t *>(kbuf0);
+        partition_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(reinterpret_cast<const uint32_t *>(src), low_keys, n_edges,
+                                                                         part_low, radix, hist_src, nblocks, itb::g_csr_xcd_remap);
+        ITB_LAUNCH_CHECK();
+        fill_u32_kernel<<<grid_for(n_nodes, 256), 256, 0, st>>>(reinterpret_cast<uint32_t *>(deg_out), n_nodes, 0u);
+        ITB_LAUNCH_CHECK();
+        bucket_degree_kernel<<<dim3((unsigned)radix, kDegSlicesY), kDegThreads, 0, st>>>(low_keys, n_edges, hist_src, nblocks, radix,
+                                                                                         part_low, n_nodes, deg_out);
         ITB_LAUNCH_CHECK();
     }
 
     // One radix sort, run once or twice: keys only over the sources (their run lengths are the out-degrees;
     // a histogram by atomics would cost one memory-side atomic per edge), then (dst, src) pairs for the CSR.
     const uint32_t *kin = nullptr;
-    for (int which = deg_out ? 0 : 1; which < 2; ++which) {
+    for (int which = (deg_out && !deg_by_partition) ? 0 : 1; which < 2; ++which) {
         const bool pairs = which == 1;
         kin = reinterpret_cast<const uint32_t *>(pairs ? dst : src);
         const int32_t *vin = src;

@@ -21,6 +21,7 @@
 
 namespace itb {
 extern int g_csr_xcd_remap;
+extern int g_csr_deg_by_sort;
 int g_small_limit = -1;   // tuning hook (key 0): rows with in-degree <= limit use one lane group per row (-1 = auto)
 int g_gather_unroll = 4;  // reserved
 int g_long_row = 512;     // tuning hook (key 3): rows with more in-edges get a whole block
@@ -617,5 +618,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
     if (key == 3 && value > 0) { itb::g_long_row = value; return ITB_OK; }
     if (key == 4) { itb::g_rows_waves_per_simd = value; return ITB_OK; }
+    if (key == 5) { itb::g_csr_deg_by_sort = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }

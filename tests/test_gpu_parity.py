@@ -66,6 +66,27 @@ def test_build_csr_bit_exact(B, name, n, e, hub):
     assert np.array_equal(deg_out.cpu().numpy(), d), "deg_out"
 
 
+@pytest.mark.parametrize("n,e,hub", [(5000, 700000, 0.6), (1, 9, 0.0), (17, 100, 0.5), (1 << 17, 200000, 0.1),
+                                     (5_000_000, 100000, 0.2), (3000, 0, 0.0)])
+def test_out_degrees_both_strategies(B, n, e, hub):
+    """deg_out comes from a partition + per-bucket count (ids up to 2^22; a source with more than 2^18 out-edges
+    spans several slices of its bucket) or from the keys-only sort (wider ids, or forced): both exact."""
+    import torch
+    dst, src, _ = W.random_small_graph(n + e + 5, n, e, 4, W.F32, hub)      # swapped: the hub is a SOURCE here
+    want = np.bincount(src, minlength=n).astype(np.int32)
+    assert np.array_equal(oracle.build_csr(n, src, dst)[2], want)
+    for forced_sort in (0, 1):
+        B.set_tuning(5, forced_sort)
+        try:
+            rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+            torch.cuda.synchronize()
+        finally:
+            B.set_tuning(5, 0)
+        assert np.array_equal(deg_out.cpu().numpy(), want), f"forced_sort={forced_sort}"
+        r, c, _ = oracle.build_csr(n, src, dst)
+        assert np.array_equal(rowptr.cpu().numpy(), r) and np.array_equal(col.cpu().numpy(), c)
+
+
 def test_build_csr_range_error(B):
     src = np.array([0, 1, 2, 3], np.int32)
     for bad_dst in (np.array([1, 4, 0, 0], np.int32), np.array([1, -1, 0, 0], np.int32)):
