@@ -17,6 +17,16 @@
 
 namespace itb {
 
+// A helper stream per device on which gather_layer runs the hub passes (segment partials + combine) next to the
+// row passes of the caller's stream: fork = event recorded on the caller's stream that the helper waits for,
+// join = event recorded on the helper that the caller's stream waits for.  Default priority, non-blocking.
+struct SideStream {
+    hipStream_t stream;
+    hipEvent_t fork, join;
+};
+SideStream *side_stream();  // nullptr if it cannot be created (callers then stay on the one stream)
+extern int g_overlap_hubs;  // tuning hook (key 6): 0 = everything on the caller's stream
+
 constexpr int kWave = 64;
 
 static inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }

@@ -566,6 +566,20 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
                    hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
     const unsigned gy = (unsigned)((a.row_vecs + G - 1) / G);
+    // hub passes first, on the helper stream when there is one (see gather_layer)
+    itb::SideStream *side = (hubs && itb::g_overlap_hubs) ? itb::side_stream() : nullptr;
+    if (hubs) {
+        hipStream_t hst = side ? side->stream : st;
+        if (side) {
+            ITB_HIP(hipEventRecord(side->fork, st));
+            ITB_HIP(hipStreamWaitEvent(hst, side->fork, 0));
+        }
+        gat_segments_kernel<BF16, G><<<dim3((unsigned)a.n_shadows, gy), kRangeWaves * kWave, 0, hst>>>(a);
+        ITB_LAUNCH_CHECK();
+        gat_combine_kernel<BF16><<<(unsigned)n_hubs, 1024, 0, hst>>>(a, n_hubs, hub_ids, hub_shadow_off);
+        ITB_LAUNCH_CHECK();
+        if (side) ITB_HIP(hipEventRecord(side->join, hst));
+    }
     zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
     ITB_LAUNCH_CHECK();
     gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, itb::lds_for_occupancy(itb::g_rows_waves_per_simd == -1 ? 0 : itb::g_rows_waves_per_simd, G), st>>>(a);
@@ -573,12 +587,7 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
     int64_t lg = waves > 2048 ? 2048 : waves;  // fixed grid over the device-side work list
     gat_long_rows_kernel<BF16, G><<<dim3((unsigned)lg, gy), kRangeWaves * kWave, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
-    if (hubs) {
-        gat_segments_kernel<BF16, G><<<dim3((unsigned)a.n_shadows, gy), kRangeWaves * kWave, 0, st>>>(a);
-        ITB_LAUNCH_CHECK();
-        gat_combine_kernel<BF16><<<(unsigned)n_hubs, 1024, 0, st>>>(a, n_hubs, hub_ids, hub_shadow_off);
-        ITB_LAUNCH_CHECK();
-    }
+    if (side) ITB_HIP(hipStreamWaitEvent(st, side->join, 0));
     return ITB_OK;
 }
 

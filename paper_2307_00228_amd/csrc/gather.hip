@@ -19,7 +19,29 @@
 // No floating-point atomics anywhere: every summation order is a function of the sizes only.
 #include "common.h"
 
+#include <mutex>
+
 namespace itb {
+int g_overlap_hubs = 1;
+SideStream *side_stream() {
+    constexpr int kMaxDevices = 64;
+    static SideStream table[kMaxDevices];
+    static bool made[kMaxDevices];
+    static std::mutex mu;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!made[dev]) {
+        SideStream s{};
+        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess)
+            return nullptr;
+        table[dev] = s;
+        made[dev] = true;
+    }
+    return &table[dev];
+}
 extern int g_csr_xcd_remap;
 extern int g_csr_deg_by_sort;
 int g_small_limit = -1;   // tuning hook (key 0): rows with in-degree <= limit use one lane group per row (-1 = auto)
@@ -582,6 +604,31 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
 
     const bool bin = desc->dtype_in == ITB_BF16, bout = desc->dtype_out == ITB_BF16;
     int32_t rc;
+    // The hub passes touch other rows and other workspace than the row passes: they go first and, when the helper
+    // stream exists, run beside the row passes, whose many small blocks fill the gaps the large segment blocks leave.
+    SideStream *side = (hubs && g_overlap_hubs) ? side_stream() : nullptr;
+    if (hubs) {
+        hipStream_t hst = side ? side->stream : st;
+        if (side) {
+            ITB_HIP(hipEventRecord(side->fork, st));
+            ITB_HIP(hipStreamWaitEvent(hst, side->fork, 0));
+        }
+        GatherArgs s = a;
+        s.out = part;
+        s.n_shadows = split->n_shadows;
+        s.shadow_begin = split->shadow_begin;
+        s.shadow_end = split->shadow_end;
+        s.shadow_owner = split->shadow_owner;
+        if (ext) rc = bin ? dispatch_segments<true, true>(G, s, hst) : dispatch_segments<false, true>(G, s, hst);
+        else rc = bin ? dispatch_segments<true, false>(G, s, hst) : dispatch_segments<false, false>(G, s, hst);
+        if (rc != ITB_OK) return rc;
+        auto combine = bout ? (ext ? combine_hubs_kernel<true, true> : combine_hubs_kernel<true, false>)
+                            : (ext ? combine_hubs_kernel<false, true> : combine_hubs_kernel<false, false>);
+        combine<<<(unsigned)split->n_hubs, 1024, 0, hst>>>(part, desc->dim, split->n_hubs, split->hub_ids, split->hub_shadow_off,
+                                                           rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out);
+        ITB_LAUNCH_CHECK();
+        if (side) ITB_HIP(hipEventRecord(side->join, hst));
+    }
     if (ext) {
         if (!bin) rc = dispatch_rows<false, false, true>(G, a, st);
         else if (bout) rc = dispatch_rows<true, true, true>(G, a, st);
@@ -592,23 +639,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         else rc = dispatch_rows<true, false, false>(G, a, st);
     }
     if (rc != ITB_OK) return rc;
-
-    if (hubs) {
-        GatherArgs s = a;
-        s.out = part;
-        s.n_shadows = split->n_shadows;
-        s.shadow_begin = split->shadow_begin;
-        s.shadow_end = split->shadow_end;
-        s.shadow_owner = split->shadow_owner;
-        if (ext) rc = bin ? dispatch_segments<true, true>(G, s, st) : dispatch_segments<false, true>(G, s, st);
-        else rc = bin ? dispatch_segments<true, false>(G, s, st) : dispatch_segments<false, false>(G, s, st);
-        if (rc != ITB_OK) return rc;
-        auto combine = bout ? (ext ? combine_hubs_kernel<true, true> : combine_hubs_kernel<true, false>)
-                            : (ext ? combine_hubs_kernel<false, true> : combine_hubs_kernel<false, false>);
-        combine<<<(unsigned)split->n_hubs, 1024, 0, st>>>(part, desc->dim, split->n_hubs, split->hub_ids, split->hub_shadow_off,
-                                                          rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out);
-        ITB_LAUNCH_CHECK();
-    }
+    if (side) ITB_HIP(hipStreamWaitEvent(st, side->join, 0));
     return ITB_OK;
 }
 
@@ -619,5 +650,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 3 && value > 0) { itb::g_long_row = value; return ITB_OK; }
     if (key == 4) { itb::g_rows_waves_per_simd = value; return ITB_OK; }
     if (key == 5) { itb::g_csr_deg_by_sort = value; return ITB_OK; }
+    if (key == 6) { itb::g_overlap_hubs = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }
