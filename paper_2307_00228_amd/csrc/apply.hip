@@ -1,4 +1,4 @@
-// apply_layer: h_out = act([h_self | agg] . [W_self ; W_nbr] + bias) on the matrix cores.
+// apply_layer: h_out = act([h_self | agg] . [W_self ; W_nbr] + bias (+ addend)) on the matrix cores.
 //
 // The weights are tiny (<= 256 KB) and the activations are a tall-skinny stream, so:
 //   * each block is persistent: it loads the whole [K_total x BN] weight panel into LDS once, in the exact
@@ -6,10 +6,12 @@
 //     then walks over 32*waves-row tiles;
 //   * every wavefront owns 32 rows and all BN = 32*NT output columns (NT independent 32x32 accumulators,
 //     so consecutive MFMAs never wait on each other);
-//   * the A operand goes straight from global memory to registers: lane (row i, half kh) loads 16 bytes of
-//     its row per k-chunk.  The k index inside a chunk is permuted identically for A and B (a dot product
-//     does not care), which lets one 16-byte load feed 4 fp32 MFMAs (32x32x2) or 1 bf16 MFMA (32x32x16);
-//   * bias, activation and the store (the scatter of the new state) are fused into the epilogue.
+//   * rows travel global -> registers -> a per-wavefront LDS staging area -> A fragments, and the finished tile
+//     goes back through the same area, so that every global access is a full 64-byte piece of one row;
+//   * the k index inside a chunk is permuted identically for A and B (a dot product does not care), which lets
+//     one 16-byte fragment feed 4 fp32 MFMAs (32x32x2) or 1 bf16 MFMA (32x32x16);
+//   * bias, addend, activation, rounding, the store (the scatter of the new state) and the optional message rows
+//     are fused into the epilogue.
 #include "common.h"
 
 namespace {
@@ -21,7 +23,6 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 constexpr int kApplyThreads = 512;
 constexpr int kApplyWaves = kApplyThreads / kWave;
 constexpr int kRowsPerBlockTile = 32 * kApplyWaves;
-constexpr size_t kMaxWeightLds = 128 * 1024;  // weight panel of the plain update
 constexpr size_t kMaxLds = 160 * 1024;        // whole LDS of a CU (weight panel + score panel)
 
 struct ApplyArgs {
@@ -164,18 +165,47 @@ __device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a
     (void)PARTS;
 }
 
-// PF = k-chunks per group; it divides the number of k-chunks, so the unrolled group body has no branches.
-// A fragments are double-buffered by group and the request stream runs on across row tiles (the first
-// fragments of the next tile are requested while the current tile finishes and stores).
-template <bool BF16, int NT, int PF, bool SCORES, bool MSG, bool ADD>
-__global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
-    constexpr int SPARTS = BF16 ? 2 : 1;  // B fragments of the score tile per chunk (bf16: hi and lo part)
-    extern __shared__ uint4 wlds[];
+// ---------------------------------------------------------------------------------------------------------
+// The fragment layout of the matrix cores puts 32 different rows into adjacent lanes, so loading
+// A fragments (and storing C fragments) straight from/to global memory gives the vector cache one 16-byte (or
+// 8-byte) access per lane: measured, this costs four times the cache accesses of row-contiguous traffic.  Here every
+// wavefront owns a staging area in LDS: it loads its 32 rows x 32*PF bytes with 2*PF adjacent lanes on one
+// row (full 64-byte accesses), writes them to LDS, and reads the fragments from there; the finished 32 x 32*NT
+// tile goes back through the same area so that it leaves as row-contiguous 16-byte stores.  Staging is private
+// to a wavefront (LDS operations of one wavefront execute in program order), so the row-tile loop needs no
+// block-level synchronisation.  Loads run two k-groups ahead in registers.
+// Staging layout for A: 16-byte unit (row r, piece c) at r*LPR + (c ^ swz(r)), LPR = 2*PF pieces per row,
+// swz(r) = (r / (16/LPR)) % LPR: both the row-major writes and the column-wise fragment reads touch 64 distinct
+// banks per 16 lanes.
+template <int LPR>
+__device__ __forceinline__ int stage_swz(int r) { return (r / (16 / LPR)) % LPR; }
+
+// RAGGED: d_out is not a multiple of the 16-byte store width; the epilogue then stores element by element (a small
+// loop, kept out of the vector variant because memory operations inside a loop of unknown length make the
+// compiler's wait counts for the prefetched rows conservative).
+// GTS > 0: the number of k-groups per row tile is this compile-time constant (even); the tile body is then one
+// straight line of code and the wait counts for the rows in flight are exact.  GTS == 0: any number of groups.
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS>
+__global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a) {
+    constexpr int SPARTS = BF16 ? 2 : 1;
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
+    constexpr int LPR = 2 * PF;              // lanes (16-byte pieces) per row and group
+    constexpr int RPL = 64 / LPR;            // rows per load instruction
+    constexpr int STG_VECS = (32 * LPR > 256) ? 32 * LPR : 256;  // per wavefront: the A group, at least 4 KB for the epilogue
+    constexpr int ENT = STG_VECS / 256;      // 32-column tiles the epilogue stages at a time (fp32): 2 or 1
+    constexpr int W = ENT * 32;              // dwords per staged output row
+    constexpr int VE = BF16 ? 8 : 4;         // output elements per 16-byte store
+    constexpr int UPL = VE / 4;              // 16-byte fp32 units a lane reads back
+    constexpr int LPRO = (W / 4) / UPL;      // lanes per output row
+    constexpr int RPI = 64 / LPRO;           // output rows per store instruction
+    extern __shared__ uint4 wlds[];
     const int col0 = blockIdx.y * BN;
     load_weight_panel<BF16, NT>(wlds, a, col0);
-    uint4 *slds = wlds + (int64_t)(a.d_in / KC) * (a.h_self ? 2 : 1) * 2 * BN;  // score panel behind the weight panel
+    const int chunks = a.d_in / KC;
+    const int phases = a.h_self ? 2 : 1;
+    const int total = phases * chunks;
+    uint4 *slds = wlds + (int64_t)total * 2 * BN;
     if constexpr (SCORES) load_score_panel<BF16>(slds, a);
     __syncthreads();
 
@@ -183,243 +213,207 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
     const int w = threadIdx.x / kWave;
     const int i = lane & 31;
     const int kh = lane >> 5;
-    const int chunks = a.d_in / KC;
-    const int chunks_self = a.h_self ? chunks : 0;
-    const int total = chunks_self + chunks;
+    uint4 *stage = slds + (SCORES ? (int64_t)total * 64 * SPARTS : 0) + (int64_t)w * STG_VECS;
+    uint32_t *stage32 = reinterpret_cast<uint32_t *>(stage);
+    const int gpp = chunks / PF;             // groups per phase (PF divides chunks)
+    const int GT = GTS > 0 ? GTS : phases * gpp;  // groups per row tile
     const int64_t row_vecs = 2 * chunks;
     const uint4 *wbase = wlds + kh * BN + i;
-    const uint4 *sbase = slds + kh * 32 + i;   // score panel: [part][chunk][kh][32]
+    const uint4 *sbase = slds + kh * 32 + i;
+    const int lr = lane / LPR, lc = lane % LPR;
+    const int frag_swz = stage_swz<LPR>(i);
 
-    auto tile_rowoff = [&](int64_t tile) -> int64_t {
-        int64_t r = tile * kRowsPerBlockTile + (int64_t)w * 32 + i;
-        r = r < a.n ? r : a.n - 1;  // clamped rows are computed but never stored
-        return r * row_vecs + kh;
-    };
-    // 16-byte fragment c of the concatenated [h_self | agg] row at vector offset `rowoff`
-    auto frag_ptr = [&](int64_t rowoff, int c) -> const uint4 * {
-        const bool in_self = c < chunks_self;
-        const uint4 *base = in_self ? a.h_self : a.agg;
-        const int ci = in_self ? c : c - chunks_self;
-        return base + rowoff + 2 * ci;
-    };
-
-    float bias_v[NT];  // this lane's bias per column tile, fetched once
+    float bias_v[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int col = col0 + nt * 32 + i;
         bias_v[nt] = (a.bias && col < a.d_out) ? a.bias[col] : 0.f;
     }
 
+    // fetch cursor: the next group to request (runs two groups ahead of the compute cursor)
+    int64_t f_tile = blockIdx.x;
+    int f_g = 0;
+    // Always issues its PF loads, so that the number of requests in flight at every point of the loop is the same
+    // on every path and the compiler's wait counts stay exact (a conditional request made it wait for everything
+    // outstanding).  Past the block's last tile the requests go to the first rows of `agg` (cache hits, never used).
+    auto issue = [&](uint4(&R)[PF]) __attribute__((always_inline)) {
+        const bool live = f_tile < a.n_row_tiles;
+        const int phase = (f_g >= gpp) ? 1 : 0;
+        const uint4 *base = (live && phases == 2 && phase == 0) ? a.h_self : a.agg;
+        const int gi = live ? f_g - phase * gpp : 0;
+        const int64_t row0 = live ? f_tile * kRowsPerBlockTile + (int64_t)w * 32 + lr : 0;
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            int64_t row = row0 + q * RPL;
+            row = row < a.n ? row : a.n - 1;  // clamped rows are computed but never stored
+            R[q] = base[row * row_vecs + gi * LPR + lc];
+        }
+        if (++f_g == GT) {
+            f_g = 0;
+            f_tile += gridDim.x;
+        }
+    };
+    auto stage_write = [&](const uint4(&R)[PF]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int r = q * RPL + lr;
+            stage[r * LPR + (lc ^ stage_swz<LPR>(r))] = R[q];
+        }
+    };
+
+    v16f acc[NT];
+    v16f sacc;
     int64_t tile = blockIdx.x;
-    if (tile >= a.n_row_tiles) return;
-    int64_t rowoff = tile_rowoff(tile);
-    uint4 cur[PF];
-#pragma unroll
-    for (int p = 0; p < PF; ++p) cur[p] = *frag_ptr(rowoff, p);
-    uint4 bcur[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) bcur[nt] = wbase[nt * 32];
-    uint4 scur[SCORES ? SPARTS : 1];
-    if constexpr (SCORES) {
-#pragma unroll
-        for (int q = 0; q < SPARTS; ++q) scur[q] = sbase[(int64_t)q * total * 64];
-    }
+    int g = 0;
 
-    for (; tile < a.n_row_tiles; tile += gridDim.x) {
-        const int64_t next_tile = tile + gridDim.x;
-        const int64_t rowoff_next = next_tile < a.n_row_tiles ? tile_rowoff(next_tile) : rowoff;
-        v16f acc[NT];
+    auto compute = [&]() __attribute__((always_inline)) {
+        const int cb = g * PF;
+        uint4 av = stage[i * LPR + (kh ^ frag_swz)];
+        uint4 bv[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt) bv[nt] = wbase[(int64_t)cb * 2 * BN + nt * 32];
+        uint4 sv[SCORES ? SPARTS : 1];
+        if constexpr (SCORES) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
-        v16f sacc;
+            for (int q = 0; q < SPARTS; ++q) sv[q] = sbase[(int64_t)q * total * 64 + (int64_t)cb * 64];
+        }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-
-        for (int c0 = 0; c0 < total; c0 += PF) {
-            // Double-buffered A: the PF fragments of the NEXT k-group (running on into the next row tile) are
-            // requested first and are only touched a whole group of MFMAs later.
-            uint4 nxt[PF];
-            {
-                const int s0 = c0 + PF;
-                const bool wrap = s0 >= total;  // PF divides total: a group never straddles two tiles
-                const int64_t ro = wrap ? rowoff_next : rowoff;
-                const int sb = wrap ? s0 - total : s0;
+        for (int p = 0; p < PF; ++p) {
+            uint4 an = av;
+            uint4 bn[NT];
+            uint4 sn[SCORES ? SPARTS : 1];
+            if (p + 1 < PF) {  // fragments of the next chunk, read under the current MFMAs
+                an = stage[i * LPR + ((2 * (p + 1) + kh) ^ frag_swz)];
 #pragma unroll
-                for (int p = 0; p < PF; ++p) nxt[p] = *frag_ptr(ro, sb + p);
+                for (int nt = 0; nt < NT; ++nt) bn[nt] = wbase[(int64_t)(cb + p + 1) * 2 * BN + nt * 32];
+                if constexpr (SCORES) {
+#pragma unroll
+                    for (int q = 0; q < SPARTS; ++q) sn[q] = sbase[(int64_t)q * total * 64 + (int64_t)(cb + p + 1) * 64];
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
+            mfma_chunk<BF16, NT>(acc, av, bv);
+            if constexpr (SCORES) {
 #pragma unroll
-            for (int p = 0; p < PF; ++p) {
-                const int c = c0 + p;
-                const int cn = (c + 1 == total) ? 0 : c + 1;
-                uint4 bnext[NT];  // B fragments of the next chunk, read from LDS under the current MFMAs
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) bnext[nt] = wbase[(int64_t)cn * 2 * BN + nt * 32];
-                uint4 snext[SCORES ? SPARTS : 1];
-                if constexpr (SCORES) {
-#pragma unroll
-                    for (int q = 0; q < SPARTS; ++q) snext[q] = sbase[(int64_t)q * total * 64 + (int64_t)cn * 64];
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_chunk<BF16, NT>(acc, cur[p], bcur);
-                if constexpr (SCORES) {
-#pragma unroll
-                    for (int q = 0; q < SPARTS; ++q) {
-                        v16f one[1] = {sacc};
-                        const uint4 bq[1] = {scur[q]};
-                        mfma_chunk<BF16, 1>(one, cur[p], bq);
-                        sacc = one[0];
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) bcur[nt] = bnext[nt];
-                if constexpr (SCORES) {
-#pragma unroll
-                    for (int q = 0; q < SPARTS; ++q) scur[q] = snext[q];
+                for (int q = 0; q < SPARTS; ++q) {
+                    v16f one[1] = {sacc};
+                    const uint4 bq[1] = {sv[q]};
+                    mfma_chunk<BF16, 1>(one, av, bq);
+                    sacc = one[0];
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
+            if (p + 1 < PF) {
+                av = an;
 #pragma unroll
-            for (int p = 0; p < PF; ++p) cur[p] = nxt[p];
+                for (int nt = 0; nt < NT; ++nt) bv[nt] = bn[nt];
+                if constexpr (SCORES) {
+#pragma unroll
+                    for (int q = 0; q < SPARTS; ++q) sv[q] = sn[q];
+                }
+            }
         }
+    };
 
-        // Epilogue.  Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of the tile.
+    // Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of its 32-column tile.
+    auto epilogue = [&]() __attribute__((always_inline)) {
         const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
-        const bool full = (m0 + 32 <= a.n) && (col0 + BN <= a.d_out) && (a.d_out % 4 == 0);
-        if (full) {
-            // 4x4 transposes inside lane quads (two butterfly steps, lanes ^1 then ^2) turn "4 rows of one column"
-            // into "4 consecutive columns of one row", so a lane stores 16 bytes (fp32) / 8 bytes (bf16) at once:
-            // lane i ends up with row 8*b + 4*kh + (i&3) and columns 4*(i>>2) .. +3 of the tile.
-            const bool odd = (i & 1) != 0, hi = (i & 2) != 0;
-            const int64_t row_q = m0 + 4 * kh + (i & 3);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const float b = bias_v[nt];
-                const float b1 = __shfl_xor(b, 1, kWave);   // bias of the neighbouring column
-                const float blo = odd ? b1 : b, bhi = odd ? b : b1;   // biases of columns (pair start, pair start + 1)
-                const int colq = col0 + nt * 32 + 4 * (i >> 2);
+        for (int nt0 = 0; nt0 < NT; nt0 += ENT) {
+            constexpr int dummy = 0;
+            (void)dummy;
+            const int npass = (NT - nt0 < ENT) ? NT - nt0 : ENT;
+            // fp32 tile (+bias) into the staging area; rows 4 apart (kh = 0 / 1) are kept in different bank halves:
+            // with two tiles per row by flipping the tile half, with one tile per row by swapping the row pair
 #pragma unroll
-                for (int bq = 0; bq < 4; ++bq) {
-                    float p0[2], p1[2];  // after step 1: pair jj holds two adjacent columns of one row
+            for (int e = 0; e < ENT; ++e) {
+                if (e < npass) {
+                    const int nt = nt0 + e;
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        const float va = acc[nt][4 * bq + 2 * jj], vb = acc[nt][4 * bq + 2 * jj + 1];
-                        const float got = __shfl_xor(odd ? va : vb, 1, kWave);
-                        p0[jj] = odd ? got : va;   // even lane: row 2jj, cols (c, c+1); odd lane: row 2jj+1, cols (c-1, c)
-                        p1[jj] = odd ? vb : got;
-                        p0[jj] += blo;
-                        p1[jj] += bhi;
-                        if (!ADD && a.act == ITB_ACT_RELU) {
-                            p0[jj] = fmaxf(p0[jj], 0.f);
-                            p1[jj] = fmaxf(p1[jj], 0.f);
-                        }
+                    for (int r = 0; r < 16; ++r) {
+                        const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                        const int col = e * 32 + i;
+                        const int unit = (ENT == 2) ? ((col >> 2) ^ (kh * 8)) : (col >> 2);
+                        const int slot = (ENT == 2) ? rho : (rho ^ kh);
+                        stage32[slot * W + unit * 4 + (col & 3)] = __float_as_uint(acc[nt][r] + bias_v[nt]);
                     }
-                    const int64_t off = (row_q + 8 * bq) * a.d_out + colq;
-                    if constexpr (ADD) {
-                        // finish the transpose in fp32, add the addend's four columns of this lane's row, then the
-                        // activation, rounding and stores
-                        const float g0 = __shfl_xor(hi ? p0[0] : p0[1], 2, kWave);
-                        const float g1 = __shfl_xor(hi ? p1[0] : p1[1], 2, kWave);
-                        float o[4] = {hi ? g0 : p0[0], hi ? g1 : p1[0], hi ? p0[1] : g0, hi ? p1[1] : g1};
-                        if constexpr (BF16) {
-                            const uint2 ad = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(a.addend) + off);
-                            o[0] += bf16_lo(ad.x); o[1] += bf16_hi(ad.x); o[2] += bf16_lo(ad.y); o[3] += bf16_hi(ad.y);
-                        } else {
-                            const float4 ad = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.addend) + off);
-                            o[0] += ad.x; o[1] += ad.y; o[2] += ad.z; o[3] += ad.w;
+                }
+            }
+            // back as rows: a lane takes VE consecutive columns of one row
+#pragma unroll
+            for (int t = 0; t < 32 / RPI; ++t) {
+                const int rho = t * RPI + lane / LPRO;
+                const int u0 = (lane % LPRO) * UPL;
+                const int khr = (rho >> 2) & 1;
+                const int slot = (ENT == 2) ? rho : (rho ^ khr);
+                const int uswz = (ENT == 2) ? khr * 8 : 0;
+                float v[VE];
+#pragma unroll
+                for (int j = 0; j < UPL; ++j) {
+                    const uint4 x = stage[(slot * W) / 4 + ((u0 + j) ^ uswz)];
+                    v[4 * j + 0] = __uint_as_float(x.x);
+                    v[4 * j + 1] = __uint_as_float(x.y);
+                    v[4 * j + 2] = __uint_as_float(x.z);
+                    v[4 * j + 3] = __uint_as_float(x.w);
+                }
+                const int64_t row = m0 + rho;
+                const int col = col0 + nt0 * 32 + u0 * 4;
+                if (row < a.n && u0 * 4 < npass * 32 && col < a.d_out) {
+                    const int64_t off = row * a.d_out + col;
+                    const float ms = a.msg_out ? a.msg_scale[row] : 0.f;
+                    if constexpr (!RAGGED) {  // d_out % VE == 0: every vector is whole and 16-byte aligned
+                        if (a.addend) {
+                            if constexpr (BF16) {
+                                const uint4 ad = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.addend) + off);
+                                v[0] += bf16_lo(ad.x); v[1] += bf16_hi(ad.x); v[2] += bf16_lo(ad.y); v[3] += bf16_hi(ad.y);
+                                v[4] += bf16_lo(ad.z); v[5] += bf16_hi(ad.z); v[6] += bf16_lo(ad.w); v[7] += bf16_hi(ad.w);
+                            } else {
+                                const float4 ad = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.addend) + off);
+                                v[0] += ad.x; v[1] += ad.y; v[2] += ad.z; v[3] += ad.w;
+                            }
                         }
                         if (a.act == ITB_ACT_RELU) {
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) o[t] = fmaxf(o[t], 0.f);
+                            for (int e = 0; e < VE; ++e) v[e] = fmaxf(v[e], 0.f);
                         }
-                        float ms = 0.f;
-                        if constexpr (MSG) ms = a.msg_scale[row_q + 8 * bq];
                         if constexpr (BF16) {
-                            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + off) =
-                                make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
-                            if constexpr (MSG)
-                                *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.msg_out) + off) =
-                                    make_uint2(pack_bf16x2(o[0] * ms, o[1] * ms), pack_bf16x2(o[2] * ms, o[3] * ms));
+                            *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.out) + off) =
+                                make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                            if (a.msg_out)
+                                *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.msg_out) + off) =
+                                    make_uint4(pack_bf16x2(v[0] * ms, v[1] * ms), pack_bf16x2(v[2] * ms, v[3] * ms),
+                                               pack_bf16x2(v[4] * ms, v[5] * ms), pack_bf16x2(v[6] * ms, v[7] * ms));
                         } else {
-                            *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + off) = make_float4(o[0], o[1], o[2], o[3]);
-                            if constexpr (MSG)
+                            *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + off) = make_float4(v[0], v[1], v[2], v[3]);
+                            if (a.msg_out)
                                 *reinterpret_cast<float4 *>(static_cast<float *>(a.msg_out) + off) =
-                                    make_float4(o[0] * ms, o[1] * ms, o[2] * ms, o[3] * ms);
-                        }
-                        continue;
-                    }
-                    // after step 1 pair jj of a lane belongs to row 8*bq + 4*kh + 2*jj + (i&1) of the tile
-                    float ms0 = 0.f, ms1 = 0.f;
-                    if constexpr (MSG) {
-                        ms0 = a.msg_scale[m0 + 8 * bq + 4 * kh + (i & 1)];
-                        ms1 = a.msg_scale[m0 + 8 * bq + 4 * kh + 2 + (i & 1)];
-                    }
-                    if constexpr (BF16) {
-                        const uint32_t k0 = pack_bf16x2(p0[0], p1[0]), k1 = pack_bf16x2(p0[1], p1[1]);
-                        const uint32_t got = (uint32_t)__shfl_xor((int)(hi ? k0 : k1), 2, kWave);
-                        uint2 o;
-                        o.x = hi ? got : k0;   // lanes with bit1 clear keep pair 0 (their row), receive columns +2,+3
-                        o.y = hi ? k1 : got;
-                        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.out) + off) = o;
-                        if constexpr (MSG) {
-                            const uint32_t q0 = pack_bf16x2(p0[0] * ms0, p1[0] * ms0), q1 = pack_bf16x2(p0[1] * ms1, p1[1] * ms1);
-                            const uint32_t gq = (uint32_t)__shfl_xor((int)(hi ? q0 : q1), 2, kWave);
-                            uint2 m;
-                            m.x = hi ? gq : q0;
-                            m.y = hi ? q1 : gq;
-                            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.msg_out) + off) = m;
+                                    make_float4(v[0] * ms, v[1] * ms, v[2] * ms, v[3] * ms);
                         }
                     } else {
-                        const float g0 = __shfl_xor(hi ? p0[0] : p0[1], 2, kWave);
-                        const float g1 = __shfl_xor(hi ? p1[0] : p1[1], 2, kWave);
-                        float4 o;
-                        o.x = hi ? g0 : p0[0];
-                        o.y = hi ? g1 : p1[0];
-                        o.z = hi ? p0[1] : g0;
-                        o.w = hi ? p1[1] : g1;
-                        *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + off) = o;
-                        if constexpr (MSG) {
-                            const float ms = hi ? ms1 : ms0;  // this lane's final row is 8*bq + 4*kh + (i&3)
-                            *reinterpret_cast<float4 *>(static_cast<float *>(a.msg_out) + off) =
-                                make_float4(o.x * ms, o.y * ms, o.z * ms, o.w * ms);
-                        }
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int col = col0 + nt * 32 + i;
-                const bool col_ok = col < a.d_out;
-                const float b = bias_v[nt];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t orow = m0 + 8 * (r / 4) + 4 * kh + (r % 4);
-                    float y = acc[nt][r] + b;
-                    if constexpr (ADD) {
-                        if (col_ok && orow < a.n) {
-                            if constexpr (BF16) y += __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.addend)[orow * a.d_out + col] << 16);
-                            else y += static_cast<const float *>(a.addend)[orow * a.d_out + col];
-                        }
-                    }
-                    if (a.act == ITB_ACT_RELU) y = fmaxf(y, 0.f);
-                    if (col_ok && orow < a.n) {
-                        if constexpr (BF16) {
-                            static_cast<uint16_t *>(a.out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y);
-                            if constexpr (MSG)
-                                static_cast<uint16_t *>(a.msg_out)[orow * a.d_out + col] = (uint16_t)f32_to_bf16(y * a.msg_scale[orow]);
-                        } else {
-                            static_cast<float *>(a.out)[orow * a.d_out + col] = y;
-                            if constexpr (MSG) static_cast<float *>(a.msg_out)[orow * a.d_out + col] = y * a.msg_scale[orow];
+                        // element by element, read again from the staging area so that the path stays a small loop
+#pragma unroll 1
+                        for (int e = 0; e < VE; ++e) {
+                            if (col + e < a.d_out) {
+                                float y = __uint_as_float(stage32[slot * W + ((u0 + e / 4) ^ uswz) * 4 + (e & 3)]);
+                                if (a.addend) {
+                                    if constexpr (BF16) y += __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.addend)[off + e] << 16);
+                                    else y += static_cast<const float *>(a.addend)[off + e];
+                                }
+                                if (a.act == ITB_ACT_RELU) y = fmaxf(y, 0.f);
+                                if constexpr (BF16) {
+                                    static_cast<uint16_t *>(a.out)[off + e] = (uint16_t)f32_to_bf16(y);
+                                    if (a.msg_out) static_cast<uint16_t *>(a.msg_out)[off + e] = (uint16_t)f32_to_bf16(y * ms);
+                                } else {
+                                    static_cast<float *>(a.out)[off + e] = y;
+                                    if (a.msg_out) static_cast<float *>(a.msg_out)[off + e] = y * ms;
+                                }
+                            }
                         }
                     }
                 }
             }
         }
         if constexpr (SCORES) {
-            // column i of the score tile: source score of head i, or destination score of head i - heads
             if (blockIdx.y == 0 && i < 2 * a.heads) {
                 float *dst = i < a.heads ? a.s_src : a.s_dst;
                 const int hd = i < a.heads ? i : i - a.heads;
@@ -430,19 +424,69 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(ApplyArgs a) {
                 }
             }
         }
-        rowoff = rowoff_next;
+    };
+
+    auto item = [&](uint4(&R)[PF]) __attribute__((always_inline)) {
+        stage_write(R);   // this group's rows (requested two groups ago) into the staging area
+        __builtin_amdgcn_sched_barrier(0);
+        issue(R);         // and its registers carry the request two groups ahead
+        __builtin_amdgcn_sched_barrier(0);
+        if (g == 0) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        }
+        compute();
+        if (++g == GT) {
+            epilogue();
+            g = 0;
+            tile += gridDim.x;
+        }
+    };
+
+    if (tile >= a.n_row_tiles) return;
+    uint4 R0[PF], R1[PF];
+#pragma unroll
+    for (int q = 0; q < PF; ++q) R0[q] = R1[q] = make_uint4(0, 0, 0, 0);
+    // (the barriers keep the two request batches in program order: the wait counts assume R0's rows were asked
+    // for before R1's)
+    issue(R0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(R1);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (GTS > 0) {
+        static_assert(GTS % 2 == 0, "static group count must be even");
+        while (tile < a.n_row_tiles) {
+#pragma unroll
+            for (int gg = 0; gg < GTS; gg += 2) {
+                g = gg;
+                item(R0);
+                g = gg + 1;
+                item(R1);
+            }
+        }
+    } else {
+        while (tile < a.n_row_tiles) {
+            item(R0);
+            if (tile >= a.n_row_tiles) break;
+            item(R1);
+        }
     }
 }
 
-template <bool BF16, int NT, int PF, bool SCORES, bool MSG, bool ADD>
-int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS = 0>
+int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
+    constexpr size_t stage_bytes = (size_t)kApplyWaves * ((32 * 2 * PF > 256) ? 32 * 2 * PF : 256) * 16;
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
-    const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4);
+    const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4) + stage_bytes;
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     static bool attr_set = false;
     if (!attr_set) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_kernel<BF16, NT, PF, SCORES, MSG, ADD>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set = true;
     }
@@ -454,52 +498,48 @@ int32_t launch_apply_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_kernel<BF16, NT, PF, SCORES, MSG, ADD><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
 
-template <bool BF16, int NT, int PF, bool SCORES>
-int32_t launch_apply_pf(const ApplyArgs &a, int n_cus, hipStream_t st) {
-    if constexpr (!SCORES) {
-        if (a.msg_out && a.addend) return launch_apply_cfg<BF16, NT, PF, false, true, true>(a, n_cus, st);
-        if (a.msg_out) return launch_apply_cfg<BF16, NT, PF, false, true, false>(a, n_cus, st);
-        if (a.addend) return launch_apply_cfg<BF16, NT, PF, false, false, true>(a, n_cus, st);
-    }
-    return launch_apply_cfg<BF16, NT, PF, SCORES, false, false>(a, n_cus, st);
-}
-
-template <bool BF16, int NT>
-int32_t launch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
-    const int total = (a.d_in / (BF16 ? 16 : 8)) * (a.h_self ? 2 : 1);
-    if (a.heads > 0) {
-        if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, true>(a, n_cus, st);
-        if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, true>(a, n_cus, st);
-        return launch_apply_pf<BF16, NT, 1, true>(a, n_cus, st);
-    }
-    if (total % 8 == 0) return launch_apply_pf<BF16, NT, 8, false>(a, n_cus, st);
-    if (total % 4 == 0) return launch_apply_pf<BF16, NT, 4, false>(a, n_cus, st);
-    if (total % 2 == 0) return launch_apply_pf<BF16, NT, 2, false>(a, n_cus, st);
-    return launch_apply_pf<BF16, NT, 1, false>(a, n_cus, st);
-}
-
-template <bool BF16>
-int32_t dispatch_apply(const ApplyArgs &a, int n_cus, hipStream_t st) {
+// Widest column tile first (fewer re-reads of A), then the largest k-group whose staging still fits the LDS.
+template <bool BF16, bool SCORES>
+int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    const int chunks = a.d_in / (BF16 ? 16 : 8);
     const int k_total = a.d_in * (a.h_self ? 2 : 1);
-    const size_t per_tile = (size_t)k_total * 32 * (BF16 ? 2 : 4);
-    int nt = 4;  // 8 accumulator tiles per wave would not leave registers for the prefetch buffers
-    while (nt > 1 && (per_tile * nt > kMaxWeightLds || 32 * (nt / 2) >= a.d_out)) nt /= 2;
-    if (per_tile * nt > kMaxWeightLds) return ITB_ERR_UNSUPPORTED;
-    if (a.heads > 0) {  // leave room for the score panel
-        const size_t score = (size_t)k_total * 32 * (BF16 ? 4 : 4);
-        while (nt > 1 && per_tile * nt + score > kMaxLds) nt /= 2;
-        if (per_tile * nt + score > kMaxLds) return ITB_ERR_UNSUPPORTED;
+    const size_t esz = BF16 ? 2 : 4;
+    const size_t score = SCORES ? (size_t)k_total * 32 * (BF16 ? 2 : 1) * esz : 0;
+    const bool ragged = a.d_out % (BF16 ? 8 : 4) != 0;
+    for (int nt = 4; nt >= 1; nt /= 2) {
+        if (nt > 1 && 32 * (nt / 2) >= a.d_out) continue;  // narrower tile already covers every column
+        const size_t panel = (size_t)k_total * 32 * nt * esz + score;
+        if (ragged) {  // rare widths: one instantiation per tile width, smallest k-group
+            if (panel + (size_t)kApplyWaves * 256 * 16 > kMaxLds) continue;
+            if (nt == 4) return launch_staged_cfg<BF16, 4, 1, SCORES, true>(a, n_cus, st);
+            if (nt == 2) return launch_staged_cfg<BF16, 2, 1, SCORES, true>(a, n_cus, st);
+            return launch_staged_cfg<BF16, 1, 1, SCORES, true>(a, n_cus, st);
+        }
+        for (int pf = 8; pf >= 1; pf /= 2) {
+            if (chunks % pf != 0) continue;
+            const size_t stage = (size_t)kApplyWaves * ((64 * pf > 256) ? 64 * pf : 256) * 16;
+            if (panel + stage > kMaxLds) continue;
+            // frequent shapes with a compile-time group count
+            const int gt = (chunks / pf) * (a.h_self ? 2 : 1);
+            if constexpr (!SCORES) {  // (with the score tile the straight-line body runs out of registers)
+                if (BF16 && nt == 4 && pf == 8 && gt == 2) return launch_staged_cfg<BF16, 4, 8, false, false, 2>(a, n_cus, st);
+                if (!BF16 && nt == 4 && pf == 4 && gt == 8) return launch_staged_cfg<BF16, 4, 4, false, false, 8>(a, n_cus, st);
+                if (!BF16 && nt == 2 && pf == 8 && gt == 2) return launch_staged_cfg<BF16, 2, 8, false, false, 2>(a, n_cus, st);
+            }
+#define ITB_STAGED_CASE(NT_, PF_) \
+    if (nt == NT_ && pf == PF_) return launch_staged_cfg<BF16, NT_, PF_, SCORES, false>(a, n_cus, st);
+            ITB_STAGED_CASE(4, 8) ITB_STAGED_CASE(4, 4) ITB_STAGED_CASE(4, 2) ITB_STAGED_CASE(4, 1)
+            ITB_STAGED_CASE(2, 8) ITB_STAGED_CASE(2, 4) ITB_STAGED_CASE(2, 2) ITB_STAGED_CASE(2, 1)
+            ITB_STAGED_CASE(1, 8) ITB_STAGED_CASE(1, 4) ITB_STAGED_CASE(1, 2) ITB_STAGED_CASE(1, 1)
+#undef ITB_STAGED_CASE
+        }
     }
-    switch (nt) {
-        case 4: return launch_apply<BF16, 4>(a, n_cus, st);
-        case 2: return launch_apply<BF16, 2>(a, n_cus, st);
-        default: return launch_apply<BF16, 1>(a, n_cus, st);
-    }
+    return ITB_ERR_UNSUPPORTED;
 }
 
 int cached_cu_count() {
@@ -560,6 +600,7 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     a.msg_out = msg_out;
     a.addend = addend;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    return desc->dtype == ITB_BF16 ? dispatch_apply<true>(a, cached_cu_count(), st)
-                                   : dispatch_apply<false>(a, cached_cu_count(), st);
+    const int cus = cached_cu_count();
+    if (desc->dtype == ITB_BF16) return a.heads > 0 ? dispatch_staged<true, true>(a, cus, st) : dispatch_staged<true, false>(a, cus, st);
+    return a.heads > 0 ? dispatch_staged<false, true>(a, cus, st) : dispatch_staged<false, false>(a, cus, st);
 }
