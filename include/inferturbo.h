@@ -24,9 +24,12 @@
  *    too small -> ITB_ERR_WORKSPACE.  Workspace must be 256-byte aligned.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    gather_layer, apply_layer, gcn_norm_scales and infer_full_graph only
- *    enqueue work and return without synchronising.  build_csr_by_dst and
- *    split_hubs synchronise the stream before returning (they report range
- *    errors / counts to the host).
+ *    enqueue work and return without synchronising.  build_csr_by_dst
+ *    synchronises the stream before returning (it reports range errors to
+ *    the host); split_hubs synchronises once to read the two counts, the
+ *    arrays it fills afterwards are ordered on the stream like any output.
+ *    gather_layer runs its hub passes on a helper stream of its own and
+ *    joins it back into `stream` before returning.
  *  - Return value: ITB_OK (0) or a negative itb_status.  Argument errors are
  *    detected on the host before any launch.  Nothing throws, aborts or prints.
  *  - Dense tensors are row-major.  ITB_BF16 tensors hold IEEE bfloat16
