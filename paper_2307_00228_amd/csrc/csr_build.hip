@@ -48,6 +48,38 @@ __device__ __forceinline__ uint32_t partition_digit(uint32_t key, int shift, int
     return d < (uint32_t)radix ? d : (uint32_t)radix - 1u;
 }
 
+// LDS counter update of one wavefront: h[d] += 1 for every valid lane; returns the lane's slot (the counter value
+// it would have seen), which only the unstable partition uses.  Popular digits -- the ids of hubs -- would make
+// dozens of lanes hit one counter and serialise, so up to two rounds first fold all lanes that share the digit of
+// the first pending lane into one atomic (worth it from four lanes on); what is left goes lane by lane.
+// `fold` (wave-uniform, in/out): folding is tried only while it is set; a wavefront whose probe finds nothing to fold
+// clears it and pays one atomic per lane from then on -- on uniform ids the votes would be pure overhead.
+__device__ __forceinline__ uint32_t wave_count(uint32_t *h, uint32_t d, bool valid, bool &fold) {
+    if (!fold) return valid ? atomicAdd(&h[d], 1u) : 0u;
+    bool folded = false;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
+    uint64_t pending = __ballot(valid);
+    uint32_t slot = 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        if (pending == 0) break;  // wave-uniform
+        const int leader = __ffsll((unsigned long long)pending) - 1;
+        const uint32_t dl = (uint32_t)__shfl((int)d, leader, kWave);
+        const uint64_t same = __ballot(valid && d == dl) & pending;
+        if (__popcll(same) < 4) break;
+        folded = true;
+        uint32_t base = 0;
+        if (lane == leader) base = atomicAdd(&h[dl], (uint32_t)__popcll(same));
+        base = (uint32_t)__shfl((int)base, leader, kWave);
+        if ((same >> lane) & 1ull) slot = base + (uint32_t)__popcll(same & lower);
+        pending &= ~same;
+    }
+    if ((pending >> lane) & 1ull) slot = atomicAdd(&h[d], 1u);
+    fold = folded;
+    return slot;
+}
+
 __global__ void fill_i64_kernel(int64_t *p, int64_t n, int64_t v) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -77,6 +109,7 @@ __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, u
     __syncthreads();
     const int64_t base = tile * kTile;
     bool bad = false;
+    bool fold_d = true, fold_s = true;
     uint32_t kd[kItems], ks[kItems];
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
@@ -87,12 +120,11 @@ __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, u
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const int64_t idx = base + i * kThreads + threadIdx.x;
-        if (idx < n_edges) {
-            bad = bad || kd[i] >= n_nodes || ks[i] >= n_nodes;
-            atomicAdd(&hd[kd[i] & mask], 1u);
-            if constexpr (SRC_MODE == 1) atomicAdd(&hs[ks[i] & (uint32_t)(src_radix - 1)], 1u);
-            if constexpr (SRC_MODE == 2) atomicAdd(&hs[partition_digit(ks[i], src_shift, src_radix)], 1u);
-        }
+        const bool valid = idx < n_edges;
+        if (valid) bad = bad || kd[i] >= n_nodes || ks[i] >= n_nodes;
+        wave_count(hd, kd[i] & mask, valid, fold_d);
+        if constexpr (SRC_MODE == 1) wave_count(hs, ks[i] & (uint32_t)(src_radix - 1), valid, fold_s);
+        if constexpr (SRC_MODE == 2) wave_count(hs, partition_digit(ks[i], src_shift, src_radix), valid, fold_s);
     }
     if (bad) atomicOr(bad_flag, 1u);
     __syncthreads();
@@ -126,6 +158,7 @@ __global__ __launch_bounds__(kThreads) void partition_scatter_kernel(const uint3
     const int64_t base = tile * kTile;
     const uint32_t low_mask = (1u << shift) - 1u;
     uint32_t key[kItems], slot[kItems];
+    bool fold = true;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const int64_t idx = base + i * kThreads + threadIdx.x;
@@ -134,8 +167,7 @@ __global__ __launch_bounds__(kThreads) void partition_scatter_kernel(const uint3
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const int64_t idx = base + i * kThreads + threadIdx.x;
-        slot[i] = 0;
-        if (idx < n) slot[i] = atomicAdd(&cnt[partition_digit(key[i], shift, radix)], 1u);
+        slot[i] = wave_count(cnt, partition_digit(key[i], shift, radix), idx < n, fold);
     }
     __syncthreads();
     // exclusive prefix over the digits, two digits per thread (radix <= 2 * kThreads)
@@ -189,12 +221,15 @@ __global__ __launch_bounds__(kDegThreads) void bucket_degree_kernel(const uint16
         for (int64_t i = a1 + threadIdx.x; i < s1; i += kDegThreads) atomicAdd(&h[low_keys[i]], 1u);
         const uint4 *body = reinterpret_cast<const uint4 *>(low_keys + a0);
         const int64_t n_vec = (a1 - a0) / 8;
-        for (int64_t i = threadIdx.x; i < n_vec; i += kDegThreads) {
-            const uint4 v = body[i];
-            atomicAdd(&h[v.x & 0xffffu], 1u); atomicAdd(&h[v.x >> 16], 1u);
-            atomicAdd(&h[v.y & 0xffffu], 1u); atomicAdd(&h[v.y >> 16], 1u);
-            atomicAdd(&h[v.z & 0xffffu], 1u); atomicAdd(&h[v.z >> 16], 1u);
-            atomicAdd(&h[v.w & 0xffffu], 1u); atomicAdd(&h[v.w >> 16], 1u);
+        for (int64_t i0 = 0; i0 < n_vec; i0 += kDegThreads) {  // block-uniform trip count: wave_count votes
+            const int64_t i = i0 + threadIdx.x;
+            const bool valid = i < n_vec;
+            const uint4 v = valid ? body[i] : make_uint4(0, 0, 0, 0);
+            bool fold = true;  // probed again for every 16-byte vector
+            wave_count(h, v.x & 0xffffu, valid, fold); wave_count(h, v.x >> 16, valid, fold);
+            wave_count(h, v.y & 0xffffu, valid, fold); wave_count(h, v.y >> 16, valid, fold);
+            wave_count(h, v.z & 0xffffu, valid, fold); wave_count(h, v.z >> 16, valid, fold);
+            wave_count(h, v.w & 0xffffu, valid, fold); wave_count(h, v.w >> 16, valid, fold);
         }
     }
     __syncthreads();
@@ -218,10 +253,12 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *ke
     for (int d = threadIdx.x; d < radix; d += kThreads) h[d] = 0;
     __syncthreads();
     const int64_t base = tile * kTile;
+    bool fold = true;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         int64_t idx = base + i * kThreads + threadIdx.x;
-        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & mask], 1u);
+        const bool valid = idx < n;
+        wave_count(h, valid ? (keys[idx] >> shift) & mask : 0u, valid, fold);
     }
     __syncthreads();
     for (int d = threadIdx.x; d < radix; d += kThreads) hist[(int64_t)d * nblocks + tile] = h[d];

@@ -597,7 +597,9 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     int G = 1;
     while (G < a.row_vecs && G < kWave) G <<= 1;
     const int ng = kWave / G;
-    a.small_limit = g_small_limit >= 0 ? g_small_limit : 2 * ng;
+    // one lane group per row up to 32 in-edges (measured on 256-byte rows: 4 % faster than handing rows of 9-32
+    // edges to the whole wavefront, whose last load batch is mostly masked), never below two batches of groups
+    a.small_limit = g_small_limit >= 0 ? g_small_limit : (2 * ng > 32 ? 2 * ng : 32);
     a.long_limit = g_long_row > a.small_limit ? g_long_row : a.small_limit;
     a.long_list = long_list;
     a.long_count = long_count;
