@@ -74,10 +74,10 @@ def main():
 
     from paper_2307_00228_amd import compose
     is_gat = [l.agg == W.AGG_GAT for l in w.layers]
-    projected = [compose.project_before_gather(l, tdt) for l in layers]
+    projected = compose.plan(layers, tdt)
     buffers = {}                       # intermediates reused by every step
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    stamps = {"gather": [], "apply": [], "csr": [], "split": []}
+    stamps = {"gather": [], "apply": [], "project": [], "csr": [], "split": []}
 
     def step(record: bool):
         e0 = ev(); e0.record()
@@ -96,6 +96,10 @@ def main():
             for i in range(L):
                 stamps["gather"].append((marks[("gather_begin", i)], marks[("gather_end", i)]))
                 stamps["apply"].append((marks[("apply_begin", i)], marks[("apply_end", i)]))
+                if ("project_begin", i) in marks:
+                    stamps["project"].append((marks[("project_begin", i)], marks[("project_end", i)]))
+                else:
+                    stamps["project"].append(None)
         return rowptr, col, deg_out, split
 
     for _ in range(args.warmup):
@@ -109,13 +113,14 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
 
     def avg_ms(pairs, sel=None):
-        v = [a.elapsed_time(b) for a, b in pairs]
+        v = [p[0].elapsed_time(p[1]) if p is not None else 0.0 for p in pairs]
         if sel is not None:
             v = v[sel::L]
         return float(np.mean(v)) if v else 0.0
 
     g_ms = [avg_ms(stamps["gather"], i) for i in range(L)]
     a_ms = [avg_ms(stamps["apply"], i) for i in range(L)]
+    p_ms = [avg_ms(stamps["project"], i) for i in range(L)]   # projection before the gather (0 where there is none)
     # algorithmic traffic of one gather launch: every in-edge reads its column index and its source row once,
     # every vertex reads its row pointer and writes its aggregate row once
     # (GAT: the row is the projected state of width d_out; plus the 4-byte source score of each head per edge, and per
@@ -175,7 +180,7 @@ def main():
             "gather_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(g_bytes, g_ms)],
             "apply_TFLOPs": [f / (t * 1e-3) / 1e12 for f, t in zip(a_flops, a_ms)],
             "apply_frac_of_mfma_peak": [f / (t * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype] for f, t in zip(a_flops, a_ms)],
-            "projected_before_gather": projected,
+            "projected_before_gather": projected, "project_ms": p_ms,
             "nodes_per_s_per_layer": [N / ((g + a) * 1e-3) for g, a in zip(g_ms, a_ms)],
             "n_hubs": split.n_hubs, "n_shadows": split.n_shadows,
         },

@@ -253,7 +253,8 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  *              issued per range of `edge_chunk` edge offsets (see gather_layer).
  * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
  * gather(h . W_nbr) (see apply_layer's addend); a GCN layer reads per-vertex
- * message rows h * deg_out^-1/2 written by the previous update (or scale_rows).
+ * message rows h * deg_out^-1/2 written by the previous update (or, where there
+ * is none -- first layer, after a GAT layer -- by scale_rows).
  * An ITB_AGG_NONE layer is h' = act(h . w_nbr + bias) per vertex, no edges
  * touched (w_self must be NULL).
  * ------------------------------------------------------------------------- */

@@ -198,17 +198,27 @@ def round_store(x64, dtype):
 
 
 # ------------------------------------------------------------------ whole layers
-def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None):
+def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=True):
     """One SAGE/GCN-style layer: gather (sum, mean, degree-normalised sum, max or min), store agg, apply.
     Returns (agg_stored, y64).  A layer without a gather (NONE: encoder before the first round, prediction
-    head after the last, Sec. IV-C) is the update of the vertex's own state alone: (None, y64)."""
+    head after the last, Sec. IV-C) is the update of the vertex's own state alone: (None, y64).
+    ``round_agg``: the aggregate is a stored tensor between the two steps and is rounded to the storage dtype;
+    with False the layer is Eq. (1) in fp64 with no intermediate rounding at all (the yardstick for evaluation
+    orders that never store agg(h), such as applying W_nbr before the aggregate)."""
     if layer.agg == NONE:
         hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
         return None, apply(None, hs, None, layer.w_nbr, layer.bias, layer.act)
     a64 = gather(layer.agg, rowptr, col, h, deg_out=deg_out, verts=verts)
     a_st = round_store(a64, dtype)
     hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
-    y64 = apply(hs, a_st, layer.w_self, layer.w_nbr, layer.bias, layer.act)
+    if round_agg:
+        y64 = apply(hs, a_st, layer.w_self, layer.w_nbr, layer.bias, layer.act)
+    else:
+        # same update on the unrounded aggregate; apply() takes fp32 storage, so the neighbour product is done here
+        y64 = apply(hs, np.zeros_like(_f32(a_st)), layer.w_self, layer.w_nbr, layer.bias, ACT_NONE)
+        y64 = y64 + a64 @ _f32(layer.w_nbr).astype(np.float64)
+        if layer.act == ACT_RELU:
+            y64 = np.maximum(y64, 0.0)
     return a_st, y64
 
 

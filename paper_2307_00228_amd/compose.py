@@ -24,16 +24,23 @@ class LayerTrace:
     scores: Optional[tuple] = None  # GAT: (s_src, s_dst)
 
 
-def project_before_gather(layer: B.DeviceLayer, dtype: torch.dtype) -> bool:
-    elem = 2 if dtype == torch.bfloat16 else 4
+def project_before_gather(layer, dtype) -> bool:
+    """Same rule as the library's layer loop: narrowing sum / mean / GCN layers apply W_nbr before the gather."""
+    elem = 2 if dtype in (torch.bfloat16, "bf16") else 4
     linear = layer.agg in (B.AGG_SUM, B.AGG_MEAN, B.AGG_GCN)
     return linear and layer.w_self is not None and layer.d_out < layer.d_in and (layer.d_out * elem) % 16 == 0
+
+
+def plan(layers, dtype) -> List[bool]:
+    """Which layers apply W_nbr before their gather."""
+    return [project_before_gather(l, dtype) for l in layers]
 
 
 def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torch.Tensor,
                mark: Optional[Callable[[str, int], None]] = None, buffers: Optional[dict] = None) -> List[LayerTrace]:
     """``mark(tag, layer)`` is called right before/after the gather and the update of every layer
-    (tags: gather_begin, gather_end, apply_begin, apply_end).  ``buffers`` caches the intermediates across calls."""
+    (tags: gather_begin, gather_end, apply_begin, apply_end; for sum/mean/GCN layers also project_begin, project_end around
+    the optional projection before the gather).  ``buffers`` caches the intermediates across calls."""
     mark = mark or (lambda tag, i: None)
     buffers = buffers if buffers is not None else {}
     n = x.shape[0]
@@ -77,13 +84,15 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
             h, msg = out, None
             continue
         src_rows = h
+        pf = project_before_gather(l, x.dtype)
         if gcn:
             if msg is None:
                 msg = B.scale_rows(h, ss, out=buf(("msg", i), l.d_in))
             src_rows = msg
-        pf = project_before_gather(l, x.dtype)
+        mark("project_begin", i)
         if pf:
             src_rows = B.apply_layer(None, src_rows, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out))
+        mark("project_end", i)
         mark("gather_begin", i)
         agg = B.gather_layer(l.agg, rowptr, col, src_rows, split, None, sd if gcn else None, out=buf(("agg", i), src_rows.shape[1]))
         mark("gather_end", i)

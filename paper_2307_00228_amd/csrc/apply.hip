@@ -520,17 +520,30 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
             if (nt == 2) return launch_staged_cfg<BF16, 2, 1, SCORES, true>(a, n_cus, st);
             return launch_staged_cfg<BF16, 1, 1, SCORES, true>(a, n_cus, st);
         }
-        for (int pf = 8; pf >= 1; pf /= 2) {
-            if (chunks % pf != 0) continue;
+        auto fits = [&](int pf) {
             const size_t stage = (size_t)kApplyWaves * ((64 * pf > 256) ? 64 * pf : 256) * 16;
-            if (panel + stage > kMaxLds) continue;
-            // frequent shapes with a compile-time group count
-            const int gt = (chunks / pf) * (a.h_self ? 2 : 1);
-            if constexpr (!SCORES) {  // (with the score tile the straight-line body runs out of registers)
-                if (BF16 && nt == 4 && pf == 8 && gt == 2) return launch_staged_cfg<BF16, 4, 8, false, false, 2>(a, n_cus, st);
-                if (!BF16 && nt == 4 && pf == 4 && gt == 8) return launch_staged_cfg<BF16, 4, 4, false, false, 8>(a, n_cus, st);
-                if (!BF16 && nt == 2 && pf == 8 && gt == 2) return launch_staged_cfg<BF16, 2, 8, false, false, 2>(a, n_cus, st);
+            return chunks % pf == 0 && panel + stage <= kMaxLds;
+        };
+        // First choice: a k-group size (8 or 4 chunks) that cuts the row tile into 2, 4, 8 or 16 groups -- those have
+        // variants with a compile-time group count (straight-line tile body, exact wait counts; measured 1.5-2x on
+        // shapes whose run-time variant waits for every outstanding request at the loop head).
+        if constexpr (!SCORES) {  // (with the score tile the straight-line body runs out of registers)
+            if (nt >= 2) {
+                for (int pf = 8; pf >= 4; pf /= 2) {
+                    if (!fits(pf)) continue;
+                    const int gt = (chunks / pf) * (a.h_self ? 2 : 1);
+#define ITB_STATIC_CASE(NT_, PF_, GT_) \
+    if (nt == NT_ && pf == PF_ && gt == GT_) return launch_staged_cfg<BF16, NT_, PF_, false, false, GT_>(a, n_cus, st);
+                    ITB_STATIC_CASE(4, 8, 2) ITB_STATIC_CASE(4, 8, 4) ITB_STATIC_CASE(4, 8, 8) ITB_STATIC_CASE(4, 8, 16)
+                    ITB_STATIC_CASE(4, 4, 2) ITB_STATIC_CASE(4, 4, 4) ITB_STATIC_CASE(4, 4, 8) ITB_STATIC_CASE(4, 4, 16)
+                    ITB_STATIC_CASE(2, 8, 2) ITB_STATIC_CASE(2, 8, 4) ITB_STATIC_CASE(2, 8, 8) ITB_STATIC_CASE(2, 8, 16)
+                    ITB_STATIC_CASE(2, 4, 2) ITB_STATIC_CASE(2, 4, 4) ITB_STATIC_CASE(2, 4, 8) ITB_STATIC_CASE(2, 4, 16)
+#undef ITB_STATIC_CASE
+                }
             }
+        }
+        for (int pf = 8; pf >= 1; pf /= 2) {
+            if (!fits(pf)) continue;
 #define ITB_STAGED_CASE(NT_, PF_) \
     if (nt == NT_ && pf == PF_) return launch_staged_cfg<BF16, NT_, PF_, SCORES, false>(a, n_cus, st);
             ITB_STAGED_CASE(4, 8) ITB_STAGED_CASE(4, 4) ITB_STAGED_CASE(4, 2) ITB_STAGED_CASE(4, 1)

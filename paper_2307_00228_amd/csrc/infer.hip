@@ -89,11 +89,15 @@ extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const
 // Sum, mean and the degree-normalised sum are linear in the source rows, so W_nbr can be applied before the gather
 // (the computation flow may be reorganised around the aggregate, Sec. IV-B "Inference"): when a layer narrows
 // (d_out < d_in) the edges then carry d_out instead of d_in elements.
+// (For a layer of equal width the split into projection + update was measured slower than the fused update, even
+// where it would save the pass that writes the GCN message rows: both launches are bound by their memory traffic,
+// not by the matrix cores.)
 static bool project_before_gather(const itb_layer &L, int32_t dtype) {
     const int elem = dtype == ITB_BF16 ? 2 : 4;
     const bool linear = L.agg == ITB_AGG_SUM || L.agg == ITB_AGG_MEAN || L.agg == ITB_AGG_GCN;
     return linear && L.w_self != nullptr && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
 }
+
 
 extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
                                     const int32_t *deg_out, const itb_split *split, int32_t dtype, int32_t n_layers,
@@ -180,6 +184,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         const float *gs = nullptr, *gd_scale = gcn ? dst_scale : nullptr;
         void *gather_out = aggbuf;
         itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr};
+        const bool pf = project_before_gather(L, dtype);
         if (gcn) {
             // The message of a GCN edge is the source state times the source's coefficient (apply_edge on the
             // scatter side): it is produced once per vertex -- by the previous layer's epilogue, or here for the
@@ -203,7 +208,6 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             gather_out = dst;
             gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias};
         }
-        const bool pf = project_before_gather(L, dtype);
         if (pf) {
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
             int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, L.w_nbr, nullptr, projbuf, nullptr, nullptr, nullptr,

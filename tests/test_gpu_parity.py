@@ -367,6 +367,34 @@ def test_apply_message_output_and_scale_rows(B, dtype, d_in, d_out, n):
     check_features(B.to_numpy(xs), W.as_f32(h).astype(np.float64) * scale[:, None].astype(np.float64), dtype)
 
 
+@pytest.mark.parametrize("dtype,dims", [(W.F32, (64, 32, 32)), (W.F32, (48, 48, 16)), (W.BF16, (128, 64, 32)), (W.BF16, (64, 128, 128))])
+def test_gcn_stack(B, dtype, dims):
+    """GCN layers: the first one has no message rows yet (scale_rows makes them), later ones read the rows the previous
+    update left; narrowing layers apply W_nbr before the gather."""
+    import torch
+    from paper_2307_00228_amd import compose
+    n, e = 6000, 90000
+    src, dst, x = W.random_small_graph(sum(dims), n, e, dims[0], dtype, 0.3)
+    layers = W.dense_layers(np.random.default_rng(dims[1]), W.AGG_GCN, dims, dtype, bias_random=True)
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    dl, xd = B.device_layers(layers), B.to_device(x)
+    assert compose.plan(dl, xd.dtype) == [dims[i + 1] < dims[i] for i in range(len(dims) - 1)]
+    for T in (None, 60):
+        split = B.split_hubs(rowptr, T) if T else None
+        steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd)
+        out = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd)
+        view = torch.int16 if dtype == W.BF16 else torch.int32
+        assert torch.equal(out.view(view), steps[-1].out.view(view))
+        h = x
+        for i, (lay, tr) in enumerate(zip(layers, steps)):
+            # a projected layer never stores agg(h): it is held to Eq. (1) without the intermediate rounding (on the hub,
+            # whose aggregate is ~20, rounding agg(h) to bf16 alone moves the oracle by more than the tolerance)
+            y64 = oracle.dense_layer(r, c, d, h, lay, dtype, round_agg=not tr.projected)[1]
+            check_features(B.to_numpy(tr.out), y64, dtype, f"T={T} layer {i}")
+            h = B.to_numpy(tr.out)
+
+
 @pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 64, 16), (W.F32, 128, 64), (W.BF16, 64, 32), (W.BF16, 128, 40)])
 @pytest.mark.parametrize("n", [7, 1000, 4100])
 def test_apply_with_addend(B, dtype, d_in, d_out, n):

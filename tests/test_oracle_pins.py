@@ -518,3 +518,22 @@ def test_infer_rounds_between_layers_and_uses_relu_only_between():
     agg_st = W.bf16_bits_to_f32(oracle.round_store(agg, "bf16")).astype(np.float64)
     y = xf @ W.as_f32(layers[1].w_self).astype(np.float64) + agg_st @ W.as_f32(layers[1].w_nbr).astype(np.float64) + layers[1].bias
     assert np.array_equal(oracle.round_store(y, "bf16"), outs[1])
+
+
+def test_dense_layer_without_intermediate_rounding_is_plain_matmul():
+    """round_agg=False: Eq. (1) in fp64, no stored aggregate; equals act(h W_self + (A h) W_nbr + b) by scipy/numpy,
+    and differs from the rounded-aggregate form exactly by (agg - round(agg)) W_nbr."""
+    n, e, d = 50, 600, 16
+    src, dst, x = small_graph(160, n, e, d, hub=0.4, dtype=W.BF16)
+    lay = W.dense_layers(np.random.default_rng(161), W.AGG_SUM, (d, 8, 8), W.BF16, bias_random=True)[0]
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    xf = W.as_f32(x).astype(np.float64)
+    A = sp.csr_matrix((np.ones(e), (dst, src)), shape=(n, n))
+    ws, wn = W.as_f32(lay.w_self).astype(np.float64), W.as_f32(lay.w_nbr).astype(np.float64)
+    want = np.maximum(xf @ ws + (A @ xf) @ wn + lay.bias, 0.0)
+    a_st, got = oracle.dense_layer(rowptr, col, deg_out, x, lay, W.BF16, round_agg=False)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    _, rounded = oracle.dense_layer(rowptr, col, deg_out, x, lay, W.BF16)
+    want_r = np.maximum(xf @ ws + W.as_f32(a_st).astype(np.float64) @ wn + lay.bias, 0.0)
+    np.testing.assert_allclose(rounded, want_r, rtol=1e-12, atol=1e-12)
+    assert np.abs(rounded - got).max() > 0                       # the hub's aggregate does not fit bf16 exactly
