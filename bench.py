@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="medium_uniform")
     ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--threshold", default=None,
+                    help="hub threshold override: an integer, or 'heuristic' = 0.1 * E / #CUs (Sec. IV-D rule of thumb)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-s", type=float, default=25.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -64,6 +66,11 @@ def main():
     src, dst = torch.from_numpy(w.src).cuda(), torch.from_numpy(w.dst).cuda()
     x = B.to_device(w.x)
     layers = B.device_layers(w.layers)
+    if args.threshold is not None:
+        if args.threshold == "heuristic":
+            w.threshold = B.hub_threshold_heuristic(E, torch.cuda.get_device_properties(0).multi_processor_count, 0.1)
+        else:
+            w.threshold = int(args.threshold)
     use_split = w.threshold < W.NO_SPLIT
     thr = w.threshold if use_split else (1 << 62)
     tdt = x.dtype

@@ -110,6 +110,17 @@ int32_t split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t threshold,
                    int64_t *shadow_begin, int64_t *shadow_end, int32_t *shadow_owner,
                    void *workspace, size_t *workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------
+ * hub_threshold_heuristic -- the paper's rule of thumb for the threshold
+ * (Sec. IV-D, closing paragraph; Sec. V, strategy analysis: 1e9 edges on 1000
+ * workers with lambda = 0.1 give 100,000): threshold = lambda * total_edges /
+ * total_workers, returned as floor (degrees are integers), at least 1.  Host
+ * only; `threshold` is a host pointer.  On one GPU a "worker" is a compute
+ * unit; the measured sensitivity to the choice is small.
+ * ------------------------------------------------------------------------- */
+int32_t hub_threshold_heuristic(int64_t total_edges, int64_t total_workers, double lambda,
+                                int64_t *threshold);
+
 /* The split as consumed by gather_layer / infer_full_graph.  `threshold` must
  * be the value given to split_hubs: rows with in-degree > threshold are
  * skipped by the per-row pass and produced by the partial/combine passes. */

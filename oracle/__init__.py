@@ -71,6 +71,16 @@ def set_threads(n: int = 0) -> int:
 
 
 # ------------------------------------------------------------------ integer steps
+def hub_threshold(total_edges, total_workers, lam=(1, 10)):
+    """floor(lambda * E / W) with lambda = num/den (Sec. IV-D heuristic), at least 1."""
+    t = C.c_int64(0)
+    rc = lib().oracle_hub_threshold(C.c_int64(total_edges), C.c_int64(total_workers), C.c_int64(lam[0]), C.c_int64(lam[1]),
+                                    C.byref(t))
+    if rc != 0:
+        raise ValueError("oracle_hub_threshold: bad arguments")
+    return t.value
+
+
 def build_csr(n_nodes, src, dst):
     src, dst = _i32(src), _i32(dst)
     e = len(src)

@@ -41,6 +41,24 @@ int oracle_set_threads(int n)
 }
 
 /* ---------------------------------------------------------------------------
+ * Threshold heuristic (Sec. IV-D, closing paragraph): a vertex counts as a hub
+ * when its edge count exceeds the fraction lambda of the edges one worker
+ * holds, threshold = lambda * total_edges / total_workers (lambda = 0.1 in the
+ * paper's runs).  Degrees are integers, so "exceeds the real number t" is
+ * "exceeds floor(t)"; the quotient is formed exactly in integers where
+ * lambda is given as the rational num/den.
+ * ------------------------------------------------------------------------- */
+int oracle_hub_threshold(int64_t total_edges, int64_t total_workers, int64_t lambda_num, int64_t lambda_den,
+                         int64_t *threshold)
+{
+    if (total_edges < 0 || total_workers <= 0 || lambda_num <= 0 || lambda_den <= 0 || !threshold) return -1;
+    __int128 t = ((__int128)lambda_num * (__int128)total_edges) / ((__int128)lambda_den * (__int128)total_workers);
+    if (t < 1) t = 1;
+    *threshold = (int64_t)t;
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
  * In-edge grouping (Sec. IV-B gather_nbrs: a vertex receives messages via its
  * in-edges; Sec. IV-C: the edge table is a list of (source, destination)).
  * rowptr[v+1]-rowptr[v] = in-degree of v; col holds, for each v, the sources of

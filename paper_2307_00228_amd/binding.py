@@ -70,10 +70,11 @@ def _load():
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
                                      vp, vp, i64, vp, szp, vp]
+    lib.hub_threshold_heuristic.argtypes = [i64, i64, C.c_double, C.POINTER(i64)]
     lib.itb_set_tuning.argtypes = [i32, i32]
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
-              "infer_full_graph", "itb_set_tuning"):
+              "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -135,6 +136,12 @@ def build_csr_by_dst(n_nodes: int, src: torch.Tensor, dst: torch.Tensor, want_de
     _check("build_csr_by_dst", lib.build_csr_by_dst(n_nodes, e, _ptr(src), _ptr(dst), _ptr(rowptr), _ptr(col),
                                                     _ptr(deg_out), _ptr(ws), C.byref(size), _stream()))
     return rowptr, col, deg_out
+
+
+def hub_threshold_heuristic(total_edges: int, total_workers: int, lam: float = 0.1) -> int:
+    t = C.c_int64(0)
+    _check("hub_threshold_heuristic", lib.hub_threshold_heuristic(total_edges, total_workers, lam, C.byref(t)))
+    return t.value
 
 
 @dataclass

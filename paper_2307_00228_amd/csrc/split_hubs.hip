@@ -7,6 +7,8 @@
 // Integer only; the output is unique.
 #include "common.h"
 
+#include <cmath>
+
 namespace {
 using namespace itb;
 
@@ -115,6 +117,19 @@ __global__ void segment_emit_kernel(const int64_t *rowptr, int64_t n_hubs, int64
 }
 
 }  // namespace
+
+extern "C" int32_t hub_threshold_heuristic(int64_t total_edges, int64_t total_workers, double lambda, int64_t *threshold) {
+    if (!threshold) return ITB_ERR_NULL;
+    if (total_edges < 0 || total_workers <= 0 || !(lambda > 0.0) || lambda > 1.0e6) return ITB_ERR_SIZE;
+    // floor of the real quotient, formed in long double and nudged up by one part in 2^52: a lambda like 0.1, which a
+    // double holds up to 2^-53 off, still lands on the integer it means (0.1 * 1e9 / 1000 = 100000, not 99999)
+    const long double t = (long double)lambda * (long double)total_edges / (long double)total_workers;
+    long double f = floorl(t * (1.0L + 0x1p-52L));
+    if (f < 1.0L) f = 1.0L;
+    if (f > 9.0e18L) f = 9.0e18L;
+    *threshold = (int64_t)f;
+    return ITB_OK;
+}
 
 extern "C" int32_t split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t threshold, int64_t *n_hubs,
                               int64_t *n_shadows, int32_t *hub_ids, int64_t *hub_shadow_off, int64_t *shadow_begin,

@@ -537,3 +537,26 @@ def test_dense_layer_without_intermediate_rounding_is_plain_matmul():
     want_r = np.maximum(xf @ ws + W.as_f32(a_st).astype(np.float64) @ wn + lay.bias, 0.0)
     np.testing.assert_allclose(rounded, want_r, rtol=1e-12, atol=1e-12)
     assert np.abs(rounded - got).max() > 0                       # the hub's aggregate does not fit bf16 exactly
+
+
+# ---------------------------------------------------------------- threshold heuristic (Sec. IV-D / Sec. V)
+def test_hub_threshold_golden_and_exact_rational():
+    import os
+    from fractions import Fraction
+    path = os.path.join(os.path.dirname(__file__), "golden", "hub_threshold_heuristic.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert rows
+    for e, w, num, den, want in rows:
+        assert oracle.hub_threshold(int(e), int(w), (int(num), int(den))) == int(want)
+    rng = np.random.default_rng(170)
+    for _ in range(200):
+        e, w = int(rng.integers(0, 1 << 40)), int(rng.integers(1, 5000))
+        num, den = int(rng.integers(1, 50)), int(rng.integers(1, 1000))
+        t = oracle.hub_threshold(e, w, (num, den))
+        exact = Fraction(num * e, den * w)
+        assert t == max(1, exact.numerator // exact.denominator)
+        # "exceeds the real threshold" and "exceeds its floor" are the same statement about integer degrees
+        if t > 1:
+            assert (t + 1 > exact) and not (t > exact)
+    with pytest.raises(ValueError):
+        oracle.hub_threshold(10, 0)
