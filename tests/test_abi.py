@@ -116,3 +116,34 @@ def test_hub_threshold_heuristic_matches_golden_and_oracle(B):
     assert B.lib.hub_threshold_heuristic(10, 4, -1.0, C.byref(t)) == -2
     assert B.lib.hub_threshold_heuristic(10, 4, 0.1, None) == -1
     assert B.hub_threshold_heuristic(0, 7, 0.1) == 1
+
+
+def test_missing_library_fails_loudly(B, monkeypatch):
+    """No CPU fallback: without the built shared library the binding refuses to load."""
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "paper_2307_00228_amd", "no_such_library.so"))
+    with pytest.raises(ImportError, match="no CPU fallback"):
+        B._load()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "exactly one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_product_package_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing under the package, and not the product path of bench.py, may
+    import it (bench.py only inside its cpu_baseline leg)."""
+    pkg = os.path.join(ROOT, "paper_2307_00228_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            text = open(os.path.join(pkg, name)).read()
+            assert not re.search(r"^\s*(import oracle|from oracle)", text, flags=re.M), name
+    for name in os.listdir(os.path.join(pkg, "csrc")):
+        assert "oracle" not in open(os.path.join(pkg, "csrc", name)).read(), name
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    hits = [m.start() for m in re.finditer(r"^\s*import oracle", bench, flags=re.M)]
+    assert len(hits) == 1 and bench.rfind("if not args.no_cpu_baseline:", 0, hits[0]) != -1
+    assert "oracle" not in bench[:bench.index("if not args.no_cpu_baseline:")]
