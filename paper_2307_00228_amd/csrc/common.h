@@ -15,6 +15,8 @@
         if (hipGetLastError() != hipSuccess) return ITB_ERR_DEVICE; \
     } while (0)
 
+#include <mutex>
+
 namespace itb {
 
 // A helper stream per device on which gather_layer runs the hub passes (segment partials + combine) next to the
@@ -23,6 +25,7 @@ namespace itb {
 struct SideStream {
     hipStream_t stream;
     hipEvent_t fork, join;
+    std::mutex mu;  // held from the fork record to the join wait: host threads sharing the device must not interleave them
 };
 SideStream *side_stream();  // nullptr if it cannot be created (callers then stay on the one stream)
 extern int g_overlap_hubs;  // tuning hook (key 6): 0 = everything on the caller's stream

@@ -568,6 +568,8 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
     const unsigned gy = (unsigned)((a.row_vecs + G - 1) / G);
     // hub passes first, on the helper stream when there is one (see gather_layer)
     itb::SideStream *side = (hubs && itb::g_overlap_hubs) ? itb::side_stream() : nullptr;
+    std::unique_lock<std::mutex> side_lock;
+    if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
     if (hubs) {
         hipStream_t hst = side ? side->stream : st;
         if (side) {

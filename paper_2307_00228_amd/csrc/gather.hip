@@ -32,12 +32,11 @@ SideStream *side_stream() {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
     std::lock_guard<std::mutex> lock(mu);
     if (!made[dev]) {
-        SideStream s{};
+        SideStream &s = table[dev];
         if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
             hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess)
             return nullptr;
-        table[dev] = s;
         made[dev] = true;
     }
     return &table[dev];
@@ -609,6 +608,8 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     // The hub passes touch other rows and other workspace than the row passes: they go first and, when the helper
     // stream exists, run beside the row passes, whose many small blocks fill the gaps the large segment blocks leave.
     SideStream *side = (hubs && g_overlap_hubs) ? side_stream() : nullptr;
+    std::unique_lock<std::mutex> side_lock;
+    if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
     if (hubs) {
         hipStream_t hst = side ? side->stream : st;
         if (side) {
