@@ -241,6 +241,46 @@ def test_gather_chunked_equals_unchunked_and_is_deterministic(B):
     check_features(full, want, W.F32)
 
 
+def test_gather_from_two_host_threads(B):
+    """Two host threads, each on its own stream, call gather_layer with a hub split at the same time: the helper
+    stream's fork/join sequences must not interleave (bitwise the single-threaded results)."""
+    import threading
+    import torch
+    n, e, dim = 20000, 400000, 64
+    graphs = []
+    for seed in (41, 42):
+        src, dst, x = W.random_small_graph(seed, n, e, dim, W.F32, 0.3)
+        r, c, d = oracle.build_csr(n, src, dst)
+        rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+        sp = B.split_hubs(rp, 64)
+        h = B.to_device(x)
+        ref = B.gather_layer(W.AGG_MEAN, rp, cl, h, sp)
+        graphs.append((rp, cl, sp, h, ref))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(k):
+        rp, cl, sp, h, ref = graphs[k]
+        st = torch.cuda.Stream()
+        try:
+            with torch.cuda.stream(st):
+                for _ in range(25):
+                    out = B.gather_layer(W.AGG_MEAN, rp, cl, h, sp)
+                    st.synchronize()
+                    if not torch.equal(out.view(torch.int32), ref.view(torch.int32)):
+                        errors.append(k)
+                        return
+        except Exception as ex:          # noqa: BLE001 - reported below
+            errors.append(repr(ex))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in (0, 1)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 # ------------------------------------------------------------------------------------------ max / min
 def assert_same_values(got_st, want64, what=""):
     """Extrema select one of the stored inputs: the result must equal the oracle's value exactly (as numbers:
