@@ -153,6 +153,15 @@ extern "C" int32_t split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t th
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t host_totals[2] = {0, 0};
+    // An in-degree is at most the edge count, which is below 2^31: a threshold from there on selects no vertex, and
+    // the answer needs neither a kernel nor a round trip to the host.
+    const bool nothing_can_exceed = threshold >= ((int64_t)1 << 31);
+    if (nothing_can_exceed) {
+        *n_hubs = 0;
+        *n_shadows = 0;
+        if (fill) ITB_HIP(hipMemsetAsync(hub_shadow_off, 0, sizeof(int64_t), st));
+        return ITB_OK;
+    }
     if (nblocks > 0) {
         hub_count_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(rowptr, n_nodes, threshold, blk_hubs, blk_segs);
         ITB_LAUNCH_CHECK();

@@ -119,7 +119,7 @@ def assert_split_equal(sp, want):
     assert np.array_equal(sp.shadow_owner.cpu().numpy(), want["shadow_owner"])
 
 
-@pytest.mark.parametrize("T", [1, 2, 3, 7, 64, 999, 1000, 1001, 10 ** 9])
+@pytest.mark.parametrize("T", [1, 2, 3, 7, 64, 999, 1000, 1001, 10 ** 9, 1 << 31, 1 << 62])
 def test_split_hubs_bit_exact(B, T):
     import torch
     n, e = 5000, 60000
