@@ -122,7 +122,6 @@ template <bool BF16>
 __device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a) {
     constexpr int KC = BF16 ? 16 : 8;
     constexpr int KH = KC / 2;
-    constexpr int PARTS = BF16 ? 2 : 1;
     const int chunks = a.d_in / KC;
     const int dh = a.d_out / a.heads;
     const int total = chunks * 2 * 32;
@@ -162,7 +161,6 @@ __device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a
             slds[idx] = make_uint4(__float_as_uint(u[0]), __float_as_uint(u[1]), __float_as_uint(u[2]), __float_as_uint(u[3]));
         }
     }
-    (void)PARTS;
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -320,8 +318,6 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
         const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
 #pragma unroll
         for (int nt0 = 0; nt0 < NT; nt0 += ENT) {
-            constexpr int dummy = 0;
-            (void)dummy;
             const int npass = (NT - nt0 < ENT) ? NT - nt0 : ENT;
             // fp32 tile (+bias) into the staging area; rows 4 apart (kh = 0 / 1) are kept in different bank halves:
             // with two tiles per row by flipping the tile half, with one tile per row by swapping the row pair

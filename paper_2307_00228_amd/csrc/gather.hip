@@ -44,7 +44,6 @@ SideStream *side_stream() {
 extern int g_csr_xcd_remap;
 extern int g_csr_deg_by_sort;
 int g_small_limit = -1;   // tuning hook (key 0): rows with in-degree <= limit use one lane group per row (-1 = auto)
-int g_gather_unroll = 4;  // reserved
 int g_long_row = 512;     // tuning hook (key 3): rows with more in-edges get a whole block
 int g_rows_waves_per_simd = -1;  // tuning hook (key 4): cap on resident wavefronts per SIMD of the row kernels
                                  // (0 = no cap, -1 = built-in choice)
@@ -648,7 +647,6 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
 
 extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 0) { itb::g_small_limit = value; return ITB_OK; }
-    if (key == 1) { itb::g_gather_unroll = value; return ITB_OK; }
     if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
     if (key == 3 && value > 0) { itb::g_long_row = value; return ITB_OK; }
     if (key == 4) { itb::g_rows_waves_per_simd = value; return ITB_OK; }
