@@ -281,6 +281,32 @@ def test_gather_from_two_host_threads(B):
     assert not errors, errors
 
 
+def test_bf16_store_rounding_is_nearest_even_bit_exact(B):
+    """Stores to bf16 go through the hardware float-pair conversion: with W = identity the update's accumulator is
+    exactly x + bias (one fp32 addition), so the stored bits must equal round-to-nearest-even of that sum, ties included."""
+    import torch
+    d, n = 64, 4096
+    rng = np.random.default_rng(77)
+    x = W.store(rng.standard_normal((n, d)).astype(np.float32), W.BF16)
+    bias = rng.standard_normal(d).astype(np.float32) * np.float32(0.37)
+    xf = W.as_f32(x).copy()
+    # exact ties: 1 + 2^-8 -> 1 (even), 1.0078125 + 2^-8 -> 1.015625 (odd mantissa rounds up), and their negatives
+    xf[0, :] = 1.0
+    xf[1, :] = 1.0078125
+    xf[2, :] = -1.0
+    xf[3, :] = -1.0078125
+    bias[:8] = np.float32(2.0 ** -8)
+    bias[8:16] = np.float32(-(2.0 ** -8))
+    x = W.store(xf, W.BF16)
+    eye = W.store(np.eye(d, dtype=np.float32), W.BF16)
+    out = B.apply_layer(None, B.to_device(x), None, B.to_device(eye), torch.from_numpy(bias).cuda(), W.ACT_NONE)
+    want = oracle.round_store((W.as_f32(x) + bias[None, :]).astype(np.float64), W.BF16)   # fp32 sum, then RNE
+    got = B.to_numpy(out)
+    assert np.array_equal(got, want), np.argwhere(got != want)[:5]
+    assert W.as_f32(got)[0, 0] == 1.0 and W.as_f32(got)[1, 0] == 1.015625
+    assert W.as_f32(got)[2, 8] == -1.0 and W.as_f32(got)[3, 8] == -1.015625
+
+
 # ------------------------------------------------------------------------------------------ max / min
 def assert_same_values(got_st, want64, what=""):
     """Extrema select one of the stored inputs: the result must equal the oracle's value exactly (as numbers:
