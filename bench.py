@@ -6,7 +6,9 @@ synthetic graph whose edge list, features and weights are already resident in HB
 issued through the same C-ABI calls that infer_full_graph makes, so that HIP events can bracket the
 gather kernel inside the timed region; `infer_ms` additionally reports infer_full_graph itself.
 
-Prints ONE JSON line (see the design doc for the field definitions)."""
+Prints ONE JSON line: metric / value (edges per second and layer over the whole step), `roofline` (the gather launch
+with the longest duration: algorithmic bytes / measured time against the HBM peak, plus the hardware byte count recorded
+under profiles/), `breakdown` (per-stage times and rates) and `cpu_baseline` (the CPU oracle timed on the host)."""
 import argparse
 import json
 import os

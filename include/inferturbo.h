@@ -116,7 +116,8 @@ int32_t split_hubs(int64_t n_nodes, const int64_t *rowptr, int64_t threshold,
  * workers with lambda = 0.1 give 100,000): threshold = lambda * total_edges /
  * total_workers, returned as floor (degrees are integers), at least 1.  Host
  * only; `threshold` is a host pointer.  On one GPU a "worker" is a compute
- * unit; the measured sensitivity to the choice is small.
+ * unit; measured on two hub-dominated graphs the gather time is flat over
+ * more than a decade of thresholds around the value this returns.
  * ------------------------------------------------------------------------- */
 int32_t hub_threshold_heuristic(int64_t total_edges, int64_t total_workers, double lambda,
                                 int64_t *threshold);

@@ -1,4 +1,4 @@
-"""Parity at the full BASELINE sizes, in the launch configuration bench.py times.
+"""Parity at the full workload sizes, in the launch configuration bench.py times.
 
 Integer structures are compared in full (the oracle's counting sort handles 6e7 edges in seconds);
 features are compared on sampled vertices -- every hub plus a few thousand random ones -- which the oracle
