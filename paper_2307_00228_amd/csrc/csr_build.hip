@@ -483,6 +483,9 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     uint32_t *hist_src = cv.take<uint32_t>((size_t)part_hist_elems);  // histograms of the source sort (reserved whether or not
                                                                   // deg_out is asked for: the size query passes no pointers)
     uint32_t *scan_ws = cv.take<uint32_t>(scan_workspace_elems(part_hist_elems) + 64);
+    // buffers of the out-degree branch, separate so that it can run beside the pair sort
+    uint32_t *scan_ws_deg = cv.take<uint32_t>(scan_workspace_elems(part_hist_elems) + 64);
+    uint16_t *low_keys = cv.take<uint16_t>((size_t)n_edges);
     uint32_t *bounds = cv.take<uint32_t>((size_t)n_nodes + 1);
     if (!workspace) {
         *workspace_bytes = cv.off;
@@ -533,19 +536,30 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
                                                                              nullptr, nblocks, itb::g_csr_xcd_remap, flag);
         ITB_LAUNCH_CHECK();
     }
+    // The out-degree branch shares nothing with the pair sort but the raw table and the first-pass histograms: it is
+    // enqueued on the helper stream (when there is one) and joins before the final synchronisation.
+    itb::SideStream *side = (deg_by_partition && itb::g_overlap_hubs) ? itb::side_stream() : nullptr;
+    std::unique_lock<std::mutex> side_lock;
+    if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
     if (deg_by_partition) {
+        hipStream_t dst_stream = side ? side->stream : st;
+        if (side) {
+            ITB_HIP(hipEventRecord(side->fork, st));
+            ITB_HIP(hipStreamWaitEvent(dst_stream, side->fork, 0));
+        }
         const int radix = 1 << part_high;
-        int32_t rc = exclusive_scan_u32(hist_src, (int64_t)radix * nblocks, scan_ws, st);
+        int32_t rc = exclusive_scan_u32(hist_src, (int64_t)radix * nblocks, scan_ws_deg, dst_stream);
         if (rc != ITB_OK) return rc;
-        uint16_t *low_keys = reinterpret_cast<uint16_t *>(kbuf0);
-        partition_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(reinterpret_cast<const uint32_t *>(src), low_keys, n_edges,
-                                                                         part_low, radix, hist_src, nblocks, itb::g_csr_xcd_remap);
+        partition_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, dst_stream>>>(reinterpret_cast<const uint32_t *>(src), low_keys,
+                                                                                 n_edges, part_low, radix, hist_src, nblocks,
+                                                                                 itb::g_csr_xcd_remap);
         ITB_LAUNCH_CHECK();
-        fill_u32_kernel<<<grid_for(n_nodes, 256), 256, 0, st>>>(reinterpret_cast<uint32_t *>(deg_out), n_nodes, 0u);
+        fill_u32_kernel<<<grid_for(n_nodes, 256), 256, 0, dst_stream>>>(reinterpret_cast<uint32_t *>(deg_out), n_nodes, 0u);
         ITB_LAUNCH_CHECK();
-        bucket_degree_kernel<<<dim3((unsigned)radix, kDegSlicesY), kDegThreads, 0, st>>>(low_keys, n_edges, hist_src, nblocks, radix,
-                                                                                         part_low, n_nodes, deg_out);
+        bucket_degree_kernel<<<dim3((unsigned)radix, kDegSlicesY), kDegThreads, 0, dst_stream>>>(low_keys, n_edges, hist_src, nblocks,
+                                                                                                 radix, part_low, n_nodes, deg_out);
         ITB_LAUNCH_CHECK();
+        if (side) ITB_HIP(hipEventRecord(side->join, dst_stream));
     }
 
     // One radix sort, run once or twice: keys only over the sources (their run lengths are the out-degrees;
@@ -590,6 +604,10 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     rowptr_from_sorted_kernel<int64_t><<<grid_for(n_edges, 256), 256, 0, st>>>(kin, n_edges, n_nodes, rowptr);
     ITB_LAUNCH_CHECK();
 
+    if (side) {
+        ITB_HIP(hipStreamWaitEvent(st, side->join, 0));
+        side_lock.unlock();
+    }
     uint32_t host_flag = 0;
     ITB_HIP(hipMemcpyAsync(&host_flag, flag, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     ITB_HIP(hipStreamSynchronize(st));
