@@ -208,9 +208,12 @@ int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
  *   h_self [n x d_in] or NULL together with w_self (no self term).
  *   agg    [n x d_in];  w_self, w_nbr [d_in x d_out];  all of `dtype`.
  *   bias   [d_out] fp32 or NULL.   h_out [n x d_out] of `dtype`.
- *   dtype ITB_F32: fp32 matrix-core path (d_in % 8 == 0);
- *   dtype ITB_BF16: bf16 matrix-core path, fp32 accumulate (d_in % 16 == 0).
- *   1 <= d_out <= 256, d_in <= 512 (else ITB_ERR_UNSUPPORTED).
+ *   dtype ITB_F32: fp32 matrix-core path; dtype ITB_BF16: bf16 matrix-core
+ *   path with fp32 accumulation.  Rows are read as 16-byte pieces: d_in must
+ *   be a multiple of 4 (fp32) / 8 (bf16); any d_out >= 1.  The weights of one
+ *   32-column tile over the whole k range (d_in, twice that with a self term,
+ *   rounded up to 8 / 16 values) must fit the LDS next to the staging areas:
+ *   about 1000 fp32 or 2000 bf16 values of k; beyond that ITB_ERR_UNSUPPORTED.
  *   att_src/att_dst/s_src/s_dst: optional attention-score epilogue for the GAT
  *   projection: s_src[v,k] = sum_d att_src[k,d] * y[v,k,d] (fp32, from the fp32
  *   accumulators before rounding), heads dividing d_out, heads <= 16, no self

@@ -52,13 +52,13 @@ struct ApplyArgs {
 
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
 // 4 (fp32) or 8 (bf16) consecutive-k weights W[kc*KC + kh*KC/2 + t][col0 + j].
+// `chunks_per_phase` may exceed d_in / KC (the k range is padded to whole k-groups): weights of k >= d_in are zero.
 template <bool BF16, int NT>
-__device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &a, int col0) {
+__device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &a, int col0, int chunks_per_phase) {
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
     constexpr int KH = KC / 2;
     const int phases = a.h_self ? 2 : 1;
-    const int chunks_per_phase = a.d_in / KC;
     const int total = phases * chunks_per_phase * 2 * BN;
 #pragma unroll 4
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
@@ -76,17 +76,19 @@ __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &
                 const uint16_t *w = static_cast<const uint16_t *>(wbase);
                 uint32_t e[8];
 #pragma unroll
-                for (int t = 0; t < 8; ++t) e[t] = w[(int64_t)(k0 + t) * a.d_out + col];
+                for (int t = 0; t < 8; ++t) e[t] = (k0 + t < a.d_in) ? w[(int64_t)(k0 + t) * a.d_out + col] : 0u;
                 v.x = e[0] | (e[1] << 16);
                 v.y = e[2] | (e[3] << 16);
                 v.z = e[4] | (e[5] << 16);
                 v.w = e[6] | (e[7] << 16);
             } else {
                 const uint32_t *w = static_cast<const uint32_t *>(wbase);
-                v.x = w[(int64_t)(k0 + 0) * a.d_out + col];
-                v.y = w[(int64_t)(k0 + 1) * a.d_out + col];
-                v.z = w[(int64_t)(k0 + 2) * a.d_out + col];
-                v.w = w[(int64_t)(k0 + 3) * a.d_out + col];
+                if (k0 < a.d_in) {  // d_in is a multiple of 4: a 4-value piece is whole or absent
+                    v.x = w[(int64_t)(k0 + 0) * a.d_out + col];
+                    v.y = w[(int64_t)(k0 + 1) * a.d_out + col];
+                    v.z = w[(int64_t)(k0 + 2) * a.d_out + col];
+                    v.w = w[(int64_t)(k0 + 3) * a.d_out + col];
+                }
             }
         }
         wlds[idx] = v;
@@ -119,10 +121,9 @@ __device__ __forceinline__ void mfma_chunk(v16f (&acc)[NT], const uint4 &av, con
 // bf16: U is split into hi + lo bf16 parts (two B fragments per chunk, same accumulator), which keeps it
 // accurate to ~2^-17 relative.
 template <bool BF16>
-__device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a) {
+__device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a, int chunks) {
     constexpr int KC = BF16 ? 16 : 8;
     constexpr int KH = KC / 2;
-    const int chunks = a.d_in / KC;
     const int dh = a.d_out / a.heads;
     const int total = chunks * 2 * 32;
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
@@ -140,11 +141,13 @@ __device__ __forceinline__ void load_score_panel(uint4 *slds, const ApplyArgs &a
                 const float av = att[d];
 #pragma unroll
                 for (int t = 0; t < KH; ++t) {
-                    const int64_t wi = (int64_t)(k0 + t) * a.d_out + hd * dh + d;
-                    float wv;
-                    if constexpr (BF16) wv = __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.w_nbr)[wi] << 16);
-                    else wv = static_cast<const float *>(a.w_nbr)[wi];
-                    u[t] = fmaf(wv, av, u[t]);
+                    if (k0 + t < a.d_in) {  // padded k range: nothing beyond d_in
+                        const int64_t wi = (int64_t)(k0 + t) * a.d_out + hd * dh + d;
+                        float wv;
+                        if constexpr (BF16) wv = __uint_as_float((uint32_t)static_cast<const uint16_t *>(a.w_nbr)[wi] << 16);
+                        else wv = static_cast<const float *>(a.w_nbr)[wi];
+                        u[t] = fmaf(wv, av, u[t]);
+                    }
                 }
             }
         }
@@ -199,12 +202,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     constexpr int RPI = 64 / LPRO;           // output rows per store instruction
     extern __shared__ uint4 wlds[];
     const int col0 = blockIdx.y * BN;
-    load_weight_panel<BF16, NT>(wlds, a, col0);
-    const int chunks = a.d_in / KC;
+    // k range of a phase: d_in values = row_vecs 16-byte pieces per row, padded up to whole groups of PF chunks (the
+    // padding reads as zeros on both operands)
+    const int gpp = ((a.d_in + KC - 1) / KC + PF - 1) / PF;   // groups per phase
+    const int chunks = gpp * PF;                                // padded chunks per phase
     const int phases = a.h_self ? 2 : 1;
     const int total = phases * chunks;
+    load_weight_panel<BF16, NT>(wlds, a, col0, chunks);
     uint4 *slds = wlds + (int64_t)total * 2 * BN;
-    if constexpr (SCORES) load_score_panel<BF16>(slds, a);
+    if constexpr (SCORES) load_score_panel<BF16>(slds, a, chunks);
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -213,9 +219,8 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     const int kh = lane >> 5;
     uint4 *stage = slds + (SCORES ? (int64_t)total * 64 * SPARTS : 0) + (int64_t)w * STG_VECS;
     uint32_t *stage32 = reinterpret_cast<uint32_t *>(stage);
-    const int gpp = chunks / PF;             // groups per phase (PF divides chunks)
     const int GT = GTS > 0 ? GTS : phases * gpp;  // groups per row tile
-    const int64_t row_vecs = 2 * chunks;
+    const int64_t row_vecs = a.d_in / (KC / 2);    // 16-byte pieces of a stored row (2 * chunks unless the k range is padded)
     const uint4 *wbase = wlds + kh * BN + i;
     const uint4 *sbase = slds + kh * 32 + i;
     const int lr = lane / LPR, lc = lane % LPR;
@@ -240,11 +245,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
         const uint4 *base = (live && phases == 2 && phase == 0) ? a.h_self : a.agg;
         const int gi = live ? f_g - phase * gpp : 0;
         const int64_t row0 = live ? f_tile * kRowsPerBlockTile + (int64_t)w * 32 + lr : 0;
+        // A piece of the padded k range past the row's end re-reads the row's last piece: it meets zero weights, so it
+        // adds exactly nothing (for finite data) and the load needs no predicate.
+        int piece = gi * LPR + lc;
+        piece = piece < (int)row_vecs ? piece : (int)row_vecs - 1;
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
             int64_t row = row0 + q * RPL;
             row = row < a.n ? row : a.n - 1;  // clamped rows are computed but never stored
-            R[q] = base[row * row_vecs + gi * LPR + lc];
+            R[q] = base[row * row_vecs + piece];
         }
         if (++f_g == GT) {
             f_g = 0;
@@ -473,11 +482,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     }
 }
 
+// chunks of KC values per phase, rounded up to whole groups of pf chunks
+int padded_chunks(int d_in, int kc, int pf) { return ((d_in + kc - 1) / kc + pf - 1) / pf * pf; }
+
 template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS = 0>
 int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     constexpr size_t stage_bytes = (size_t)kApplyWaves * ((32 * 2 * PF > 256) ? 32 * 2 * PF : 256) * 16;
-    const int k_total = a.d_in * (a.h_self ? 2 : 1);
+    constexpr int KC = BF16 ? 16 : 8;
+    const int k_total = padded_chunks(a.d_in, KC, PF) * KC * (a.h_self ? 2 : 1);
     const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4) + stage_bytes;
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     static bool attr_set = false;
@@ -502,24 +515,28 @@ int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
 // Widest column tile first (fewer re-reads of A), then the largest k-group whose staging still fits the LDS.
 template <bool BF16, bool SCORES>
 int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
-    const int chunks = a.d_in / (BF16 ? 16 : 8);
-    const int k_total = a.d_in * (a.h_self ? 2 : 1);
+    constexpr int KC = BF16 ? 16 : 8;
+    const int phases = a.h_self ? 2 : 1;
     const size_t esz = BF16 ? 2 : 4;
-    const size_t score = SCORES ? (size_t)k_total * 32 * (BF16 ? 2 : 1) * esz : 0;
+    const int real_chunks = (a.d_in + KC - 1) / KC;
     const bool ragged = a.d_out % (BF16 ? 8 : 4) != 0;
     for (int nt = 4; nt >= 1; nt /= 2) {
         if (nt > 1 && 32 * (nt / 2) >= a.d_out) continue;  // narrower tile already covers every column
-        const size_t panel = (size_t)k_total * 32 * nt * esz + score;
+        // LDS of a configuration: weight panel (+ score panel) over the padded k range, plus the staging areas
+        auto fits = [&](int pf) {
+            const int chunks = padded_chunks(a.d_in, KC, pf);
+            if (pf > 1 && 4 * (chunks - real_chunks) > real_chunks) return false;  // more than 25 % padding: smaller groups
+            const size_t k_total = (size_t)chunks * KC * phases;
+            const size_t panel = k_total * 32 * nt * esz + (SCORES ? k_total * 32 * (BF16 ? 2 : 1) * esz : 0);
+            const size_t stage = (size_t)kApplyWaves * ((64 * pf > 256) ? 64 * pf : 256) * 16;
+            return panel + stage <= kMaxLds;
+        };
         if (ragged) {  // rare widths: one instantiation per tile width, smallest k-group
-            if (panel + (size_t)kApplyWaves * 256 * 16 > kMaxLds) continue;
+            if (!fits(1)) continue;
             if (nt == 4) return launch_staged_cfg<BF16, 4, 1, SCORES, true>(a, n_cus, st);
             if (nt == 2) return launch_staged_cfg<BF16, 2, 1, SCORES, true>(a, n_cus, st);
             return launch_staged_cfg<BF16, 1, 1, SCORES, true>(a, n_cus, st);
         }
-        auto fits = [&](int pf) {
-            const size_t stage = (size_t)kApplyWaves * ((64 * pf > 256) ? 64 * pf : 256) * 16;
-            return chunks % pf == 0 && panel + stage <= kMaxLds;
-        };
         // First choice: a k-group size (8 or 4 chunks) that cuts the row tile into 2, 4, 8 or 16 groups -- those have
         // variants with a compile-time group count (straight-line tile body, exact wait counts; measured 1.5-2x on
         // shapes whose run-time variant waits for every outstanding request at the loop head).
@@ -527,7 +544,7 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
             if (nt >= 2) {
                 for (int pf = 8; pf >= 4; pf /= 2) {
                     if (!fits(pf)) continue;
-                    const int gt = (chunks / pf) * (a.h_self ? 2 : 1);
+                    const int gt = (padded_chunks(a.d_in, KC, pf) / pf) * phases;
 #define ITB_STATIC_CASE(NT_, PF_, GT_) \
     if (nt == NT_ && pf == PF_ && gt == GT_) return launch_staged_cfg<BF16, NT_, PF_, false, false, GT_>(a, n_cus, st);
                     ITB_STATIC_CASE(4, 8, 2) ITB_STATIC_CASE(4, 8, 4) ITB_STATIC_CASE(4, 8, 8) ITB_STATIC_CASE(4, 8, 16)
@@ -573,8 +590,8 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if (desc->dtype != ITB_F32 && desc->dtype != ITB_BF16) return ITB_ERR_DTYPE;
     if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
     if (desc->d_in <= 0 || desc->d_out <= 0) return ITB_ERR_SIZE;
-    const int kc = desc->dtype == ITB_BF16 ? 16 : 8;
-    if (desc->d_in % kc != 0 || desc->d_in > 512 || desc->d_out > 256) return ITB_ERR_UNSUPPORTED;
+    const int piece = desc->dtype == ITB_BF16 ? 8 : 4;  // elements of one 16-byte piece of a row
+    if (desc->d_in % piece != 0) return ITB_ERR_UNSUPPORTED;  // rows are read as 16-byte pieces
     if (desc->heads < 0) return ITB_ERR_SIZE;
     if (desc->heads == 0 && (att_src || att_dst || s_src || s_dst)) return ITB_ERR_SIZE;
     if (desc->heads > 0) {

@@ -79,7 +79,7 @@ def test_argument_errors_are_reported_on_the_host(B):
     a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
     assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
     assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
-    a7 = B.itb_apply_desc(B.ITB_F32, 60, 16, B.ACT_RELU, 0)
+    a7 = B.itb_apply_desc(B.ITB_F32, 62, 16, B.ACT_RELU, 0)     # rows of 248 bytes: not whole 16-byte pieces
     assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
     a9 = B.itb_apply_desc(B.ITB_F32, 64, 16, 5, 0)
     assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4

@@ -394,7 +394,10 @@ def test_infer_with_encoder_extremum_layers_and_head(B, dtype):
 # ------------------------------------------------------------------------------------------ apply
 APPLY_CASES = [(W.F32, 64, 64), (W.F32, 64, 16), (W.F32, 128, 128), (W.F32, 128, 64), (W.F32, 8, 1), (W.F32, 256, 256),
                (W.F32, 40, 100), (W.BF16, 128, 128), (W.BF16, 64, 64), (W.BF16, 64, 32), (W.BF16, 256, 256),
-               (W.BF16, 16, 7), (W.BF16, 48, 200)]
+               (W.BF16, 16, 7), (W.BF16, 48, 200),
+               # widths that are not whole k-chunks (padded k range), and output widths beyond one pass of column tiles
+               (W.F32, 100, 47), (W.F32, 200, 64), (W.F32, 12, 300), (W.F32, 52, 8), (W.BF16, 200, 64), (W.BF16, 40, 24),
+               (W.BF16, 104, 512), (W.BF16, 8, 8)]
 
 
 @pytest.mark.parametrize("dtype,d_in,d_out", APPLY_CASES)
@@ -411,6 +414,27 @@ def test_apply_layer(B, dtype, d_in, d_out, n):
         want = oracle.apply(h if with_self else None, a, lay.w_self if with_self else None, lay.w_nbr,
                             lay.bias if with_bias else None, act)
         check_features(B.to_numpy(out), want, dtype, f"act={act} self={with_self}")
+
+
+@pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 768, 96), (W.BF16, 768, 256), (W.BF16, 1000, 40), (W.F32, 600, 7)])
+def test_apply_wide_input_without_self_term(B, dtype, d_in, d_out):
+    """Encoder-style layers: input widths of raw features (hundreds), no self matrix; and the widths that do not fit are
+    refused with a status, not attempted."""
+    n = 3000
+    rng = np.random.default_rng(d_in + d_out)
+    a = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    lay = W.dense_layers(rng, W.AGG_NONE, (d_in, d_out, d_out), dtype, bias_random=True)[0]
+    out = B.apply_layer(None, B.to_device(a), None, B.to_device(lay.w_nbr), B.to_device(lay.bias), W.ACT_RELU)
+    want = oracle.apply(None, a, None, lay.w_nbr, lay.bias, W.ACT_RELU)
+    check_features(B.to_numpy(out), want, dtype)
+    if dtype == W.F32 and d_in == 768:      # with a self matrix the 2 x 768 x 32 fp32 panel alone exceeds the LDS
+        wide = W.dense_layers(rng, W.AGG_MEAN, (d_in, d_out, d_out), dtype)[0]
+        with pytest.raises(B.InferTurboError, match="UNSUPPORTED"):
+            B.apply_layer(B.to_device(a), B.to_device(a), B.to_device(wide.w_self), B.to_device(wide.w_nbr), None, W.ACT_NONE)
+    with pytest.raises(B.InferTurboError, match="UNSUPPORTED"):      # rows must be whole 16-byte pieces
+        bad = 6 if dtype == W.F32 else 12
+        x = B.to_device(W.store(np.zeros((4, bad), np.float32), dtype))
+        B.apply_layer(None, x, None, B.to_device(W.store(np.zeros((bad, 8), np.float32), dtype)), None, W.ACT_NONE)
 
 
 @pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 64, 64), (W.F32, 128, 40), (W.BF16, 64, 128), (W.BF16, 32, 16)])
