@@ -218,6 +218,17 @@ def main():
                                   "cores": cores, "kind": "oracle",
                                   "sample": f"same workload at scale {args.scale * frac:.4g} "
                                             f"({sw.n_nodes} nodes, {sw.n_edges} edges, all {L} layers), {cpu_s:.1f} s"}
+        # the same on one thread, on a sample sized for a few seconds
+        one = W.make(args.workload, args.scale * frac / max(1.0, 0.25 * cores * cpu_s))
+        oracle.set_threads(1)
+        t = time.perf_counter()
+        r, c, d = oracle.build_csr(one.n_nodes, one.src, one.dst)
+        oracle.split_hubs(r, thr)
+        oracle.infer_full_graph(r, c, d, one.x, one.layers, one.dtype)
+        one_s = time.perf_counter() - t
+        oracle.set_threads(cores)
+        result["cpu_baseline"]["value_1_thread"] = one.n_edges * L / one_s
+        result["cpu_baseline"]["sample_1_thread"] = f"{one.n_nodes} nodes, {one.n_edges} edges, {one_s:.1f} s"
     print(json.dumps(result))
 
 
