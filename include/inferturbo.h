@@ -301,7 +301,9 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
  * (-1 = built-in choice); 2 = XCD-contiguous tile order in the radix passes
  * (1 = on); 3 = in-degree above which a non-hub row gets a whole block (512);
  * 4 = resident wavefronts per SIMD of the row gather (-1 = built-in choice);
- * 5 = out-degrees from a keys-only sort instead of partition + bucket counts.
+ * 5 = out-degrees from a keys-only sort instead of partition + bucket counts;
+ * 6 = helper-stream overlap (hub passes of a gather, out-degree branch of the
+ * CSR build; 1 = on).
  * ------------------------------------------------------------------------- */
 int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream);
 int32_t itb_set_tuning(int32_t key, int32_t value);
