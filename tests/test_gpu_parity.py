@@ -613,3 +613,81 @@ def test_infer_split_equals_unsplit(B):
     for T in (64, 4096):
         parts = B.infer_full_graph(rowptr, col, deg_out, B.split_hubs(rowptr, T), layers, x)
         assert (whole - parts).abs().max().item() <= 1e-5
+
+
+# ------------------------------------------------------------------------------------------ randomised sweep
+@pytest.mark.parametrize("seed", range(48))
+def test_random_configurations(B, seed):
+    """Random small graphs, widths, aggregators, thresholds and chunk sizes through the whole path step by step:
+    CSR and split bit-exact, every aggregate to its bar (extrema exactly), chunked == unchunked bitwise."""
+    import torch
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([1, 2, 63, 64, 65, 500, 3000, 7000]))
+    e = int(rng.choice([0, 1, 5, 100, 4096, 4097, 30000, 70000]))
+    dtype = W.F32 if rng.random() < 0.5 else W.BF16
+    dim = int(rng.choice([4, 8, 20, 64, 100, 128, 132, 260] if dtype == W.F32 else [8, 16, 40, 64, 128, 200, 256, 264]))
+    hub = float(rng.choice([0.0, 0.1, 0.5, 0.95]))
+    kind = int(rng.choice([W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN, W.AGG_MAX, W.AGG_MIN]))
+    T = [None, 1, 3, 17, 100, 700][int(rng.integers(0, 6))]
+    src, dst, x = W.random_small_graph(5000 + seed, n, e, dim, dtype, hub)
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    assert np.array_equal(rowptr.cpu().numpy(), r) and np.array_equal(col.cpu().numpy(), c)
+    assert np.array_equal(deg_out.cpu().numpy(), d)
+    if T is not None:
+        assert_split_equal(B.split_hubs(rowptr, T), oracle.split_hubs(r, T))
+    got, want, _ = run_gather(B, kind, n, src, dst, x, dtype, T=T)
+    what = f"n={n} e={e} dim={dim} {dtype} kind={kind} T={T} hub={hub}"
+    if kind in (W.AGG_MAX, W.AGG_MIN):
+        assert_same_values(got, want, what)
+    else:
+        check_features(got, want, dtype, what, magnitude_scaled=kind == W.AGG_SUM)
+    if e > 10:
+        chunk = int(rng.integers(1, e))
+        chunked, _, _ = run_gather(B, kind, n, src, dst, x, dtype, T=T, chunk=chunk)
+        assert np.array_equal(np.asarray(got).view(np.uint8), np.asarray(chunked).view(np.uint8)), what + f" chunk={chunk}"
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_layer_stacks(B, seed):
+    """Random stacks of every layer kind (no-gather, mean, GCN, max, min, GAT) and widths through infer_full_graph:
+    bitwise equal to the call-by-call loop, chunked or not, and every layer within its bar of the oracle evaluated
+    from the state the GPU stored for the previous layer."""
+    import torch
+    from dataclasses import replace
+    from paper_2307_00228_amd import compose
+    rng = np.random.default_rng(2000 + seed)
+    dtype = W.F32 if seed % 2 == 0 else W.BF16
+    n, e = int(rng.choice([300, 2000, 6000])), int(rng.choice([2000, 30000, 60000]))
+    hub = float(rng.choice([0.0, 0.3]))
+    L = int(rng.integers(1, 5))
+    widths = [int(rng.choice([16, 32, 64, 128])) for _ in range(L + 1)]
+    kinds = [int(rng.choice([W.AGG_NONE, W.AGG_MEAN, W.AGG_GCN, W.AGG_MAX, W.AGG_MIN, W.AGG_GAT])) for _ in range(L)]
+    layers = []
+    for i, kind in enumerate(kinds):
+        dims = (widths[i], widths[i + 1], widths[i + 1])
+        if kind == W.AGG_GAT:
+            lay = W.gat_layers(rng, dims, int(rng.choice([1, 2])), dtype, bias_random=True)[0]
+        else:
+            lay = W.dense_layers(rng, kind, dims, dtype, bias_random=True)[0]
+        layers.append(replace(lay, act=W.ACT_RELU if i < L - 1 else W.ACT_NONE))
+    src, dst, x = W.random_small_graph(7000 + seed, n, e, widths[0], dtype, hub)
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    T = [None, 9, 200][seed % 3]
+    split = B.split_hubs(rowptr, T) if T else None
+    dl, xd = B.device_layers(layers), B.to_device(x)
+    out = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd)
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    chunked = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd, edge_chunk=max(1, e // 3))
+    assert torch.equal(out.view(view), chunked.view(view))
+    steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd)
+    assert torch.equal(out.view(view), steps[-1].out.view(view))
+    h = x
+    for i, (lay, tr) in enumerate(zip(layers, steps)):
+        if lay.agg == W.AGG_GAT:
+            y64 = oracle.gat_layer(r, c, h, lay, dtype)[3]
+        else:
+            y64 = oracle.dense_layer(r, c, d, h, lay, dtype, round_agg=not tr.projected)[1]
+        check_features(B.to_numpy(tr.out), y64, dtype, f"layer {i} kinds={kinds} widths={widths} T={T}")
+        h = B.to_numpy(tr.out)
