@@ -83,6 +83,7 @@ def main():
 
     from paper_2307_00228_amd import compose
     is_gat = [l.agg == W.AGG_GAT for l in w.layers]
+    needs_deg_out = any(l.agg == W.AGG_GCN for l in w.layers)   # out-degrees enter the GCN coefficients only
     projected = compose.plan(layers, tdt)
     buffers = {}                       # intermediates reused by every step
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -90,7 +91,7 @@ def main():
 
     def step(record: bool):
         e0 = ev(); e0.record()
-        rowptr, col, deg_out = B.build_csr_by_dst(N, src, dst)
+        rowptr, col, deg_out = B.build_csr_by_dst(N, src, dst, want_deg_out=needs_deg_out)
         e1 = ev(); e1.record()
         split = B.split_hubs(rowptr, thr)
         e2 = ev(); e2.record()
