@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the whole hot path on one MI355X.
 
-A step = build_csr_by_dst + split_hubs + (gcn_norm_scales) + L x (gather_layer + apply_layer) over one
+A step = build_csr_by_dst + split_hubs + (gcn_norm_scales + gcn_edge_coefficients) + L x (gather_layer + apply_layer) over one
 synthetic graph whose edge list, features and weights are already resident in HBM.  The layer loop is
 issued through the same C-ABI calls that infer_full_graph makes, so that HIP events can bracket the
 gather kernel inside the timed region; `infer_ms` additionally reports infer_full_graph itself.
@@ -138,8 +138,10 @@ def main():
     # (a narrowing layer gathers rows already multiplied by W_nbr: width d_out)
     def gather_width(l, g, pf):
         return l.d_out if (g or pf) else l.d_in
+    # (a GCN layer also reads the 4-byte source coefficient of each in-edge and the 4-byte destination scale of each vertex)
     g_bytes = [E * (4 + 4 * l.heads + l.d_out * esz) + N * (8 + 2 * l.d_out * esz + 8 * l.heads) if g
-               else E * (4 + gather_width(l, g, pf) * esz) + N * (8 + gather_width(l, g, pf) * esz)
+               else E * (4 + (4 if l.agg == W.AGG_GCN else 0) + gather_width(l, g, pf) * esz)
+               + N * (8 + (4 if l.agg == W.AGG_GCN else 0) + gather_width(l, g, pf) * esz)
                for l, g, pf in zip(w.layers, is_gat, projected)]
     # flops of the final update launch of the layer (GAT: the projection; projected layers: the self product)
     a_flops = [(2.0 if (g or pf) else 4.0) * l.d_in * l.d_out * N for l, g, pf in zip(w.layers, is_gat, projected)]

@@ -144,6 +144,16 @@ int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *d
                         float *src_scale, float *dst_scale, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * gcn_edge_coefficients -- apply_edge of the degree normalisation (Sec. IV-B:
+ * the message of an edge is generated from the source's state; here its
+ * coefficient): coef[e] = src_scale[col[e]] for every in-edge e in CSR order.
+ * Done once per graph; gather_layer then reads the coefficient sequentially
+ * beside the column index instead of looking it up per edge.
+ * ------------------------------------------------------------------------- */
+int32_t gcn_edge_coefficients(int64_t n_edges, const int32_t *col, const float *src_scale,
+                              float *coef, void *stream);
+
+/* ---------------------------------------------------------------------------
  * gather_layer -- gather_nbrs + aggregate (Sec. IV-B), i.e. the reduce R of
  * Eq. (1) with the source's hidden state as the message (Sec. II-B).  The
  * aggregate is commutative and associative, which is what makes the hub
@@ -151,9 +161,13 @@ int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *d
  *
  *   ITB_AGG_SUM : agg[v] = sum over in-edges of h[col]
  *   ITB_AGG_MEAN: the sum divided by the in-degree; 0 for an isolated vertex
- *   ITB_AGG_GCN : dst_scale[v] * sum of src_scale[col] * h[col]; dst_scale is
- *                 required; src_scale == NULL means the rows of h_src already
- *                 carry their source coefficient (see scale_rows / msg_out)
+ *   ITB_AGG_GCN : dst_scale[v] * sum of c_e * h[col]; dst_scale is required.
+ *                 The source coefficient c_e of an in-edge comes from
+ *                 desc->edge_coef[e] ([n_edges] fp32 in CSR order, read beside
+ *                 col: see gcn_edge_coefficients) if given, else from
+ *                 src_scale[col[e]] ([n_nodes], one random look-up per edge);
+ *                 both NULL means the rows of h_src already carry it (see
+ *                 scale_rows / msg_out)
  *   ITB_AGG_MAX / ITB_AGG_MIN: element-wise maximum / minimum of h[col] over
  *                 the in-edges, exactly (no rounding: the result is one of
  *                 the stored values); 0 for an isolated vertex; hub partials
@@ -190,6 +204,7 @@ typedef struct {
     float leaky_slope;  /* GAT only */
     int32_t act;        /* GAT only: activation applied after the bias; else ITB_ACT_NONE */
     const float *bias;  /* GAT only: [dim] fp32 added to the reduced row, or NULL; else NULL */
+    const float *edge_coef; /* GCN only, optional: [n_edges] fp32 coefficient of every in-edge, CSR order */
 } itb_gather_desc;
 
 int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
@@ -267,9 +282,8 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  *   edge_chunk 0 = one gather launch set per layer; else each layer's gather is
  *              issued per range of `edge_chunk` edge offsets (see gather_layer).
  * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
- * gather(h . W_nbr) (see apply_layer's addend); a GCN layer reads per-vertex
- * message rows h * deg_out^-1/2 written by the previous update (or, where there
- * is none -- first layer, after a GAT layer -- by scale_rows).
+ * gather(h . W_nbr) (see apply_layer's addend); GCN layers share one array of
+ * per-edge source coefficients (gcn_edge_coefficients) built at the start.
  * An ITB_AGG_NONE layer is h' = act(h . w_nbr + bias) per vertex, no edges
  * touched (w_self must be NULL).
  * ------------------------------------------------------------------------- */

@@ -40,7 +40,8 @@ class itb_split(C.Structure):
 
 class itb_gather_desc(C.Structure):
     _fields_ = [("agg", C.c_int32), ("dtype_in", C.c_int32), ("dtype_out", C.c_int32), ("dim", C.c_int32),
-                ("heads", C.c_int32), ("leaky_slope", C.c_float), ("act", C.c_int32), ("bias", C.c_void_p)]
+                ("heads", C.c_int32), ("leaky_slope", C.c_float), ("act", C.c_int32), ("bias", C.c_void_p),
+                ("edge_coef", C.c_void_p)]
 
 
 class itb_apply_desc(C.Structure):
@@ -64,6 +65,7 @@ def _load():
     lib.build_csr_by_dst.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp, szp, vp]
     lib.split_hubs.argtypes = [i64, vp, i64, C.POINTER(i64), C.POINTER(i64), vp, vp, vp, vp, vp, vp, szp, vp]
     lib.gcn_norm_scales.argtypes = [i64, vp, vp, vp, vp, vp]
+    lib.gcn_edge_coefficients.argtypes = [i64, vp, vp, vp, vp]
     lib.gather_layer.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                  i64, i64, vp, szp, vp]
     lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -74,7 +76,7 @@ def _load():
     lib.itb_set_tuning.argtypes = [i32, i32]
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
-              "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic"):
+              "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -193,16 +195,25 @@ def gcn_norm_scales(rowptr: torch.Tensor, deg_out: torch.Tensor):
     return s_src, s_dst
 
 
+def gcn_edge_coefficients(col: torch.Tensor, src_scale: torch.Tensor, out: Optional[torch.Tensor] = None):
+    e = col.numel()
+    if out is None:
+        out = torch.empty(e, dtype=torch.float32, device="cuda")
+    _check("gcn_edge_coefficients", lib.gcn_edge_coefficients(e, _ptr(col), _ptr(src_scale), _ptr(out), _stream()))
+    return out
+
+
 def gather_layer(agg: int, rowptr, col, h, split: Optional[Split] = None, src_scale=None, dst_scale=None,
                  out_dtype=None, heads: int = 1, leaky_slope: float = 0.2, edge_lo: int = 0, edge_hi: int = INT64_MAX,
                  out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                 act: int = ACT_NONE, bias: Optional[torch.Tensor] = None):
+                 act: int = ACT_NONE, bias: Optional[torch.Tensor] = None, edge_coef: Optional[torch.Tensor] = None):
     n, dim = h.shape
     out_dtype = out_dtype or h.dtype
     if out is None:
         out = torch.empty((n, dim), dtype=out_dtype, device="cuda")
     desc = itb_gather_desc(agg, dtype_code(h), dtype_code(out), dim, heads, leaky_slope, act,
-                           bias.data_ptr() if bias is not None else None)
+                           bias.data_ptr() if bias is not None else None,
+                           edge_coef.data_ptr() if edge_coef is not None else None)
     sp = split.c_struct() if split is not None else None
     spp = C.byref(sp) if sp is not None else None
     need = C.c_size_t(0)

@@ -52,24 +52,25 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
             buffers[key] = t
         return t
 
-    ss = sd = None
+    sd = coef = None
     if any(l.agg == B.AGG_GCN for l in layers):
         ss, sd = B.gcn_norm_scales(rowptr, deg_out)
+        cb = buffers.get("edge_coef")
+        coef = B.gcn_edge_coefficients(col, ss, out=cb if cb is not None and cb.numel() == col.numel() else None)
+        buffers["edge_coef"] = coef
     traces = []
-    h, msg = x, None
+    h = x
     for i, l in enumerate(layers):
         gcn, gat = l.agg == B.AGG_GCN, l.agg == B.AGG_GAT
-        next_gcn = i + 1 < len(layers) and layers[i + 1].agg == B.AGG_GCN
         out = buf(("out", i), l.d_out)
         if l.agg == B.AGG_NONE:       # encoder / prediction head: the update alone
-            nmsg = buf(("msg", i + 1), l.d_out) if next_gcn else None
             mark("gather_begin", i)
             mark("gather_end", i)
             mark("apply_begin", i)
-            B.apply_layer(None, h, None, l.w_nbr, l.bias, l.act, out=out, msg_scale=ss if next_gcn else None, msg_out=nmsg)
+            B.apply_layer(None, h, None, l.w_nbr, l.bias, l.act, out=out)
             mark("apply_end", i)
             traces.append(LayerTrace(h, h, out, False))
-            h, msg = out, nmsg
+            h = out
             continue
         if gat:
             mark("apply_begin", i)
@@ -81,28 +82,24 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
                            bias=l.bias, out=out)
             mark("gather_end", i)
             traces.append(LayerTrace(z, out, out, False, (s_src, s_dst)))
-            h, msg = out, None
+            h = out
             continue
         src_rows = h
         pf = project_before_gather(l, x.dtype)
-        if gcn:
-            if msg is None:
-                msg = B.scale_rows(h, ss, out=buf(("msg", i), l.d_in))
-            src_rows = msg
         mark("project_begin", i)
         if pf:
             src_rows = B.apply_layer(None, src_rows, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out))
         mark("project_end", i)
         mark("gather_begin", i)
-        agg = B.gather_layer(l.agg, rowptr, col, src_rows, split, None, sd if gcn else None, out=buf(("agg", i), src_rows.shape[1]))
+        agg = B.gather_layer(l.agg, rowptr, col, src_rows, split, None, sd if gcn else None, out=buf(("agg", i), src_rows.shape[1]),
+                             edge_coef=coef if gcn else None)
         mark("gather_end", i)
-        nmsg = buf(("msg", i + 1), l.d_out) if next_gcn else None
         mark("apply_begin", i)
         if pf:
-            B.apply_layer(None, h, None, l.w_self, l.bias, l.act, out=out, msg_scale=ss if next_gcn else None, msg_out=nmsg, addend=agg)
+            B.apply_layer(None, h, None, l.w_self, l.bias, l.act, out=out, addend=agg)
         else:
-            B.apply_layer(h, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out, msg_scale=ss if next_gcn else None, msg_out=nmsg)
+            B.apply_layer(h, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
         mark("apply_end", i)
         traces.append(LayerTrace(src_rows, agg, out, pf))
-        h, msg = out, nmsg
+        h = out
     return traces

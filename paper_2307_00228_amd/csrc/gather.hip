@@ -73,7 +73,8 @@ struct GatherArgs {
     const int64_t *rowptr;
     const int32_t *col;
     const uint4 *h;          // [n_nodes x row_vecs] 16-byte vectors
-    const float *src_scale;  // nullable
+    const float *src_scale;  // nullable: per-source coefficient, looked up per edge
+    const float *edge_coef;  // nullable: per-edge coefficient in CSR order (read beside the column index); wins over src_scale
     const float *dst_scale;  // kModeScaleDst only
     void *out;               // agg rows, or fp32 partial rows in the segment kernel
     int64_t threshold;       // rows with in-degree > threshold are hubs (skipped by the row kernel)
@@ -200,7 +201,7 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
     constexpr int U = 4;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
-    const bool has_scale = !EXT && a.src_scale != nullptr;
+    const bool has_scale = !EXT && (a.src_scale != nullptr || a.edge_coef != nullptr);
     const float unit = EXT ? ext_sign(a.mode) : 1.f;  // scale of an edge without a source coefficient
     const float idle_s = EXT ? unit : 0.f;
     const uint32_t idle = idle_word<BF16, EXT>(unit);
@@ -211,7 +212,7 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
         float mys = unit;
         if (c + lane < deg) {
             myc = a.col[start + c + lane];
-            if (has_scale) mys = a.src_scale[myc];
+            if (has_scale) mys = a.edge_coef ? a.edge_coef[start + c + lane] : a.src_scale[myc];
         }
         const int cnt = (deg - c < kWave) ? (int)(deg - c) : kWave;  // wave-uniform
         const int steps = (cnt + NG - 1) / NG;
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     if (r0 >= a.n_nodes) return;
     const int vec = blockIdx.y * G + li;
     const bool lane_on = vec < a.row_vecs;
-    const bool has_scale = !EXT && a.src_scale != nullptr;
+    const bool has_scale = !EXT && (a.src_scale != nullptr || a.edge_coef != nullptr);
     const float unit = EXT ? ext_sign(a.mode) : 1.f;
     const float idle_s = EXT ? unit : 0.f;
     const uint32_t idle = idle_word<BF16_IN, EXT>(unit);
@@ -298,7 +299,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
                 float mys = unit;
                 if (j + li < d) {
                     myc = a.col[st + j + li];
-                    if (has_scale) mys = a.src_scale[myc];
+                    if (has_scale) mys = a.edge_coef ? a.edge_coef[st + j + li] : a.src_scale[myc];
                 }
                 const int cnt = d - j;  // edges left for this group (may be <= 0)
                 for (int t = 0; t < G; t += U) {
@@ -580,6 +581,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     a.col = col;
     a.h = static_cast<const uint4 *>(h_src);
     a.src_scale = (desc->agg == ITB_AGG_GCN) ? src_scale : nullptr;
+    a.edge_coef = (desc->agg == ITB_AGG_GCN) ? desc->edge_coef : nullptr;
     a.dst_scale = (desc->agg == ITB_AGG_GCN) ? dst_scale : nullptr;
     a.out = agg_out;
     a.threshold = split ? split->threshold : INT64_MAX;

@@ -15,6 +15,12 @@ __global__ void gcn_scales_kernel(int64_t n, const int64_t *rowptr, const int32_
     }
 }
 
+// coef[e] = src_scale[col[e]]: the per-source coefficient laid out per in-edge, in CSR order.
+__global__ void edge_coef_kernel(int64_t n_edges, const int32_t *col, const float *src_scale, float *coef) {
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n_edges; e += (int64_t)gridDim.x * blockDim.x)
+        coef[e] = src_scale[col[e]];
+}
+
 // Plain 16-byte-per-lane copy: the known-size reference against which hardware byte counters are scaled.
 __global__ void copy_kernel(const uint4 *src, uint4 *dst, int64_t n_vec) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x) dst[i] = src[i];
@@ -74,6 +80,17 @@ extern "C" int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, v
     return ITB_OK;
 }
 
+extern "C" int32_t gcn_edge_coefficients(int64_t n_edges, const int32_t *col, const float *src_scale, float *coef, void *stream) {
+    if (n_edges < 0 || n_edges >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
+    if (n_edges > 0 && (!col || !src_scale || !coef)) return ITB_ERR_NULL;
+    if (n_edges == 0) return ITB_OK;
+    int64_t g = (n_edges + 255) / 256;
+    if (g > 65536) g = 65536;
+    edge_coef_kernel<<<(unsigned)g, 256, 0, static_cast<hipStream_t>(stream)>>>(n_edges, col, src_scale, coef);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
+
 extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const int32_t *deg_out, float *src_scale,
                                    float *dst_scale, void *stream) {
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
@@ -129,7 +146,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (gat && L.heads > max_heads) max_heads = L.heads;
         const bool pf = project_before_gather(L, dtype);
         any_project = any_project || pf;
-        itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr};
+        itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr, nullptr};
         size_t need = 0;
         int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
                                   &need, nullptr);
@@ -141,7 +158,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     char *state0 = cv.take<char>(n_layers > 1 ? state_bytes : 0);
     char *state1 = cv.take<char>(n_layers > 2 ? state_bytes : 0);
     char *aggbuf = cv.take<char>(state_bytes);
-    char *msgbuf = cv.take<char>(any_gcn ? state_bytes : 0);  // source-scaled copy of the state a GCN gather reads
+    float *edge_coef = cv.take<float>(any_gcn ? (size_t)n_edges : 0);  // source coefficient of every in-edge (GCN layers)
     char *projbuf = cv.take<char>(any_project ? state_bytes : 0);  // W_nbr-projected rows of a narrowing layer
     float *src_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *dst_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
@@ -157,24 +174,25 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     if (n_nodes == 0) return ITB_OK;
 
     if (any_gcn) {
+        // The coefficient of a GCN edge factors into a per-source and a per-destination part.  The source part is
+        // laid out once per in-edge (apply_edge, done in preprocessing) so that every GCN gather reads it beside the
+        // column index: a sequential 4 bytes per edge instead of a random look-up, and no scaled copy of the state.
         int32_t rc = gcn_norm_scales(n_nodes, rowptr, deg_out, src_scale, dst_scale, stream);
+        if (rc != ITB_OK) return rc;
+        rc = gcn_edge_coefficients(n_edges, col, src_scale, edge_coef, stream);
         if (rc != ITB_OK) return rc;
     }
     char *state[2] = {state0, state1};
     const void *cur = x;
-    bool msg_ready = false;
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
         if (L.agg == ITB_AGG_NONE) {
             // encoder / prediction head (Sec. IV-C): the update alone, on the vertex's own state
-            const bool next_gcn = (l + 1 < n_layers) && layers[l + 1].agg == ITB_AGG_GCN;
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
             int32_t rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
-                                     next_gcn ? src_scale : nullptr, next_gcn ? static_cast<void *>(msgbuf) : nullptr, nullptr,
-                                     stream);
+                                     nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
-            msg_ready = next_gcn;
             cur = dst;
             continue;
         }
@@ -183,18 +201,8 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         const void *gather_src = cur;
         const float *gs = nullptr, *gd_scale = gcn ? dst_scale : nullptr;
         void *gather_out = aggbuf;
-        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr};
+        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr, gcn ? edge_coef : nullptr};
         const bool pf = project_before_gather(L, dtype);
-        if (gcn) {
-            // The message of a GCN edge is the source state times the source's coefficient (apply_edge on the
-            // scatter side): it is produced once per vertex -- by the previous layer's epilogue, or here for the
-            // input features -- instead of being looked up once per edge.
-            if (!msg_ready) {
-                int32_t rc = scale_rows(dtype, n_nodes, L.d_in, cur, src_scale, msgbuf, stream);
-                if (rc != ITB_OK) return rc;
-            }
-            gather_src = msgbuf;
-        }
         if (gat) {
             // project first (z and the per-head scores), then the attention reduce writes the new state directly
             if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
@@ -206,7 +214,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             gs = att_s_src;
             gd_scale = att_s_dst;
             gather_out = dst;
-            gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias};
+            gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias, nullptr};
         }
         if (pf) {
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
@@ -224,24 +232,18 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws, stream);
             if (rc != ITB_OK) return rc;
         }
-        msg_ready = false;
         if (!gat) {
-            // if the next layer is a GCN layer, its messages are written by this update's epilogue
-            const bool next_gcn = (l + 1 < n_layers) && layers[l + 1].agg == ITB_AGG_GCN;
-            const float *ms = next_gcn ? src_scale : nullptr;
-            void *mo = next_gcn ? static_cast<void *>(msgbuf) : nullptr;
             int32_t rc;
             if (pf) {  // the gathered projection enters the update as an addend to the self product
                 itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-                rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_self, L.bias, dst, nullptr, nullptr, nullptr, nullptr, ms, mo,
-                                 aggbuf, stream);
+                rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_self, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
+                                 nullptr, nullptr, aggbuf, stream);
             } else {
                 itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-                rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr, ms, mo,
-                                 nullptr, stream);
+                rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
+                                 nullptr, nullptr, nullptr, stream);
             }
             if (rc != ITB_OK) return rc;
-            msg_ready = next_gcn;
         }
         cur = dst;
     }

@@ -38,7 +38,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_struct_layouts_match_header(B):
     assert C.sizeof(B.itb_split) == 8 * 8
-    assert C.sizeof(B.itb_gather_desc) == 8 * 4 + 8
+    assert C.sizeof(B.itb_gather_desc) == 8 * 4 + 8 + 8
     assert C.sizeof(B.itb_apply_desc) == 5 * 4
     assert C.sizeof(B.itb_layer) == 6 * 4 + 5 * 8
 
@@ -58,14 +58,14 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert lib.split_hubs(-1, None, 4, C.byref(nh), C.byref(ns), None, None, None, None, None, None, C.byref(need), None) == -2
     assert lib.split_hubs(10, None, 4, C.byref(nh), C.byref(ns), None, None, None, None, None, None, C.byref(need), None) == 0
     # gather_layer
-    d = B.itb_gather_desc(B.AGG_SUM, B.ITB_F32, B.ITB_F32, 64, 1, 0.2, 0, None)
+    d = B.itb_gather_desc(B.AGG_SUM, B.ITB_F32, B.ITB_F32, 64, 1, 0.2, 0, None, None)
     assert lib.gather_layer(None, 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -1
     assert lib.gather_layer(C.byref(d), -5, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -2
-    bad = B.itb_gather_desc(9, B.ITB_F32, B.ITB_F32, 64, 1, 0.2, 0, None)
+    bad = B.itb_gather_desc(9, B.ITB_F32, B.ITB_F32, 64, 1, 0.2, 0, None, None)
     assert lib.gather_layer(C.byref(bad), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -4
-    bad = B.itb_gather_desc(B.AGG_SUM, 7, B.ITB_F32, 64, 1, 0.2, 0, None)
+    bad = B.itb_gather_desc(B.AGG_SUM, 7, B.ITB_F32, 64, 1, 0.2, 0, None, None)
     assert lib.gather_layer(C.byref(bad), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -4
-    odd = B.itb_gather_desc(B.AGG_SUM, B.ITB_F32, B.ITB_F32, 7, 1, 0.2, 0, None)        # 28-byte rows
+    odd = B.itb_gather_desc(B.AGG_SUM, B.ITB_F32, B.ITB_F32, 7, 1, 0.2, 0, None, None)        # 28-byte rows
     assert lib.gather_layer(C.byref(odd), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -5
     assert lib.gather_layer(C.byref(d), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == 0
     no_split = need.value

@@ -88,12 +88,9 @@ def test_full_size_dense_workloads(B, name):
             assert ok, f"layer {i + 1} apply: {worst}"
         else:
             # W_nbr was applied before the gather: the gather itself is a plain aggregate of the projected rows
-            kind = lay.agg
-            p64 = oracle.gather(kind, r, c, B.to_numpy(tr.gather_src), deg_out=None if kind != W.AGG_GCN else d, verts=verts) \
-                if kind != W.AGG_GCN else None
-            if p64 is not None:
-                ok, worst = tolerance_ok(B.to_numpy(tr.agg[vt]), p64, w.dtype)
-                assert ok, f"layer {i + 1} gather of projected rows: {worst}"
+            p64 = oracle.gather(lay.agg, r, c, B.to_numpy(tr.gather_src), deg_out=d, verts=verts)
+            ok, worst = tolerance_ok(B.to_numpy(tr.agg[vt]), p64, w.dtype)
+            assert ok, f"layer {i + 1} gather of projected rows: {worst}"
         h_host = B.to_numpy(tr.out)
     h_dev = traces[-1].out
 

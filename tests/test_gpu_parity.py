@@ -241,6 +241,33 @@ def test_gather_chunked_equals_unchunked_and_is_deterministic(B):
     check_features(full, want, W.F32)
 
 
+@pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.F32, 128), (W.BF16, 128), (W.BF16, 40)])
+@pytest.mark.parametrize("T", [None, 50])
+def test_gcn_gather_with_per_edge_coefficients(B, dtype, dim, T):
+    """The source coefficient laid out per in-edge (read beside the column index) gives bitwise the result of the
+    per-source look-up, and both match the oracle; the layout itself is col-gathered src_scale."""
+    import torch
+    n, e = 5000, 80000
+    src, dst, x = W.random_small_graph(dim + 9, n, e, dim, dtype, 0.3)
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    ss, sd = B.gcn_norm_scales(rp, torch.from_numpy(d).cuda())
+    coef = B.gcn_edge_coefficients(cl, ss)
+    assert np.array_equal(coef.cpu().numpy(), ss.cpu().numpy()[c])
+    split = B.split_hubs(rp, T) if T else None
+    h = B.to_device(x)
+    by_lookup = B.gather_layer(W.AGG_GCN, rp, cl, h, split, ss, sd)
+    by_edge = B.gather_layer(W.AGG_GCN, rp, cl, h, split, None, sd, edge_coef=coef)
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    assert torch.equal(by_lookup.view(view), by_edge.view(view))
+    check_features(B.to_numpy(by_edge), oracle.gather(W.AGG_GCN, r, c, x, deg_out=d), dtype)
+    chunked = torch.full_like(by_edge, float("nan"))
+    for lo in range(0, e, 9001):
+        B.gather_layer(W.AGG_GCN, rp, cl, h, split, None, sd, edge_coef=coef, edge_lo=lo,
+                       edge_hi=B.INT64_MAX if lo + 9001 >= e else lo + 9001, out=chunked)
+    assert torch.equal(chunked.view(view), by_edge.view(view))
+
+
 def test_gather_from_two_host_threads(B):
     """Two host threads, each on its own stream, call gather_layer with a hub split at the same time: the helper
     stream's fork/join sequences must not interleave (bitwise the single-threaded results)."""
