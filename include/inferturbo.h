@@ -28,8 +28,12 @@
  *    synchronises the stream before returning (it reports range errors to
  *    the host); split_hubs synchronises once to read the two counts, the
  *    arrays it fills afterwards are ordered on the stream like any output.
- *    gather_layer runs its hub passes on a helper stream of its own and
- *    joins it back into `stream` before returning.
+ *    gather_layer (hub passes) and build_csr_by_dst (out-degrees) put part of
+ *    their work on a helper stream the library owns and join it back into
+ *    `stream` before returning; host threads calling on different streams are
+ *    serialised around that fork and join.  Nothing the calls enqueue uses a
+ *    memset node or a synchronisation, so infer_full_graph, gather_layer and
+ *    apply_layer can be captured into a HIP graph.
  *  - Return value: ITB_OK (0) or a negative itb_status.  Argument errors are
  *    detected on the host before any launch.  Nothing throws, aborts or prints.
  *  - Dense tensors are row-major.  ITB_BF16 tensors hold IEEE bfloat16
