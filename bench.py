@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the whole hot path on one MI355X.
 
-A step = build_csr_by_dst + split_hubs + (gcn_norm_scales + gcn_edge_coefficients) + L x (gather_layer + apply_layer) over one
-synthetic graph whose edge list, features and weights are already resident in HBM.  The layer loop is
-issued through the same C-ABI calls that infer_full_graph makes, so that HIP events can bracket the
-gather kernel inside the timed region; `infer_ms` additionally reports infer_full_graph itself.
+A step = build_csr_by_dst + split_hubs + infer_full_graph (which is gcn_norm_scales + gcn_edge_coefficients + L x
+(gather_layer + apply_layer)) over one synthetic graph whose edge list, features and weights are already resident in
+HBM.  The layer loop records caller-provided HIP events at its stage boundaries (itb_set_layer_events), so the gather
+kernel is timed live inside the timed region; `infer_full_graph_ms` additionally times the call back to back.
 
 Prints ONE JSON line: metric / value (edges per second and layer over the whole step), `roofline` (the gather launch
 with the longest duration: algorithmic bytes / measured time against the HBM peak, plus the hardware byte count recorded
@@ -85,42 +85,63 @@ def main():
     is_gat = [l.agg == W.AGG_GAT for l in w.layers]
     needs_deg_out = any(l.agg == W.AGG_GCN for l in w.layers)   # out-degrees enter the GCN coefficients only
     projected = compose.plan(layers, tdt)
-    buffers = {}                       # intermediates reused by every step
     ev = lambda: torch.cuda.Event(enable_timing=True)
     stamps = {"gather": [], "apply": [], "project": [], "csr": [], "split": []}
+    out = torch.empty((N, w.layers[-1].d_out), dtype=tdt, device="cuda")
+    state = {"ws": None}
 
-    def step(record: bool):
-        e0 = ev(); e0.record()
+    def fresh_events(k):
+        evs = [ev() for _ in range(k)]
+        for e in evs:
+            e.record()              # creates the handle; the library records it again at its mark
+        return evs
+
+    # Events for every timed step are made beforehand: inside the timed region a step costs the three calls below
+    # plus one call that hands the step's events to the library.
+    layer_events = [fresh_events(4 * L) for _ in range(args.steps)]
+    outer_events = [fresh_events(3) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+
+    def step(k):
+        """k: index of the timed step, or None for a warm-up step."""
+        if k is not None:
+            outer_events[k][0].record()
         rowptr, col, deg_out = B.build_csr_by_dst(N, src, dst, want_deg_out=needs_deg_out)
-        e1 = ev(); e1.record()
+        if k is not None:
+            outer_events[k][1].record()
         split = B.split_hubs(rowptr, thr)
-        e2 = ev(); e2.record()
-        marks = {}
-
-        def mark(tag, i):
-            e = ev(); e.record(); marks[(tag, i)] = e
-
-        compose.run_layers(rowptr, col, deg_out, split if use_split else None, layers, x, mark, buffers)
-        if record:
-            stamps["csr"].append((e0, e1)); stamps["split"].append((e1, e2))
-            for i in range(L):
-                stamps["gather"].append((marks[("gather_begin", i)], marks[("gather_end", i)]))
-                stamps["apply"].append((marks[("apply_begin", i)], marks[("apply_end", i)]))
-                if ("project_begin", i) in marks:
-                    stamps["project"].append((marks[("project_begin", i)], marks[("project_end", i)]))
-                else:
-                    stamps["project"].append(None)
+        if k is not None:
+            outer_events[k][2].record()
+        sp = split if use_split else None
+        if state["ws"] is None:
+            state["ws"] = torch.empty(max(256, B.infer_workspace_bytes(N, E, sp, tdt, layers)), dtype=torch.uint8, device="cuda")
+        B.set_layer_events(layer_events[k] if k is not None else [])
+        B.infer_full_graph(rowptr, col, deg_out, sp, layers, x, out=out, workspace=state["ws"])
         return rowptr, col, deg_out, split
 
     for _ in range(args.warmup):
-        graph = step(False)
+        graph = step(None)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        graph = step(True)
+    for k in range(args.steps):
+        graph = step(k)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    B.set_layer_events([])
     ms_per_step = elapsed * 1e3 / args.steps
+    for k in range(args.steps):
+        o, le = outer_events[k], layer_events[k]
+        stamps["csr"].append((o[0], o[1]))
+        stamps["split"].append((o[1], o[2]))
+        for i in range(L):
+            b, g0, g1, e1 = le[4 * i: 4 * i + 4]
+            stamps["gather"].append((g0, g1))
+            if is_gat[i]:               # projection first, the attention reduce ends the layer
+                stamps["apply"].append((b, g0))
+                stamps["project"].append(None)
+            else:                       # optional projection, gather, update
+                stamps["project"].append((b, g0))
+                stamps["apply"].append((g1, e1))
 
     def avg_ms(pairs, sel=None):
         v = [p[0].elapsed_time(p[1]) if p is not None else 0.0 for p in pairs]
@@ -150,9 +171,7 @@ def main():
 
     # infer_full_graph itself (same kernels, one call)
     rowptr, col, deg_out, split = graph
-    ws = torch.empty(max(256, B.infer_workspace_bytes(N, E, split if use_split else None, tdt, layers)),
-                     dtype=torch.uint8, device="cuda")
-    out = torch.empty((N, w.layers[-1].d_out), dtype=tdt, device="cuda")
+    ws = state["ws"]
     for _ in range(2):
         B.infer_full_graph(rowptr, col, deg_out, split if use_split else None, layers, x, out=out, workspace=ws)
     i0, i1 = ev(), ev()

@@ -322,7 +322,12 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
  * 5 = out-degrees from a keys-only sort instead of partition + bucket counts;
  * 6 = helper-stream overlap (hub passes of a gather, out-degree branch of the
  * CSR build; 1 = on).
+ * itb_set_layer_events: `events` is a HOST array of hipEvent_t handles, four per
+ * layer; infer_full_graph records events[4l + 0..3] on its stream at layer l's
+ * begin, before its gather, after its gather and at its end (NULL entries are
+ * skipped; n_events = 0 switches the recording off).  Process-wide.
  * ------------------------------------------------------------------------- */
+int32_t itb_set_layer_events(void **events, int32_t n_events);
 int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream);
 int32_t itb_set_tuning(int32_t key, int32_t value);
 

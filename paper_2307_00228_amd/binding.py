@@ -74,9 +74,11 @@ def _load():
                                      vp, vp, i64, vp, szp, vp]
     lib.hub_threshold_heuristic.argtypes = [i64, i64, C.c_double, C.POINTER(i64)]
     lib.itb_set_tuning.argtypes = [i32, i32]
+    lib.itb_set_layer_events.argtypes = [C.POINTER(C.c_void_p), i32]
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
-              "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients"):
+              "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients",
+              "itb_set_layer_events"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -116,6 +118,13 @@ def copy_bytes(src: torch.Tensor, dst: torch.Tensor):
     n = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == n
     _check("itb_copy_bytes", lib.itb_copy_bytes(_ptr(src), _ptr(dst), n, _stream()))
+
+
+def set_layer_events(events):
+    """``events``: torch.cuda.Event objects (timing enabled, each recorded once so that its handle exists), four per
+    layer, which infer_full_graph records at layer begin / before gather / after gather / layer end; [] switches it off."""
+    arr = (C.c_void_p * max(1, len(events)))(*[e.cuda_event for e in events])
+    _check("itb_set_layer_events", lib.itb_set_layer_events(arr, len(events)))
 
 
 def set_tuning(key: int, value: int):

@@ -3,8 +3,23 @@
 // Only enqueues work on the caller's stream.
 #include "common.h"
 
+#include <vector>
+
+namespace itb {
+// Measurement aid: events the layer loop records on its stream, four per layer (layer begin, before the gather, after
+// the gather, layer end), so that a caller can time the stages of the single call without issuing them one by one.
+std::vector<hipEvent_t> g_layer_events;
+}
+
 namespace {
 using namespace itb;
+
+int32_t mark(int layer, int which, void *stream) {
+    const size_t k = (size_t)layer * 4 + which;
+    if (k < itb::g_layer_events.size() && itb::g_layer_events[k])
+        if (hipEventRecord(itb::g_layer_events[k], static_cast<hipStream_t>(stream)) != hipSuccess) return ITB_ERR_DEVICE;
+    return ITB_OK;
+}
 
 __global__ void gcn_scales_kernel(int64_t n, const int64_t *rowptr, const int32_t *deg_out, float *src_scale, float *dst_scale) {
     for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
@@ -84,6 +99,12 @@ extern "C" int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, v
     if (n_bytes == 0) return ITB_OK;
     copy_kernel<<<8192, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n_bytes / 16);
     ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
+
+extern "C" int32_t itb_set_layer_events(void **events, int32_t n_events) {
+    if (n_events < 0 || (n_events > 0 && !events)) return ITB_ERR_SIZE;
+    itb::g_layer_events.assign(reinterpret_cast<hipEvent_t *>(events), reinterpret_cast<hipEvent_t *>(events) + n_events);
     return ITB_OK;
 }
 
@@ -194,12 +215,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
+        if (mark(l, 0, stream) != ITB_OK) return ITB_ERR_DEVICE;
         if (L.agg == ITB_AGG_NONE) {
+            if (mark(l, 1, stream) != ITB_OK || mark(l, 2, stream) != ITB_OK) return ITB_ERR_DEVICE;
             // encoder / prediction head (Sec. IV-C): the update alone, on the vertex's own state
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
             int32_t rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
                                      nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
+            if (mark(l, 3, stream) != ITB_OK) return ITB_ERR_DEVICE;
             cur = dst;
             continue;
         }
@@ -231,6 +255,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             gather_src = projbuf;
             gd.dim = L.d_out;
         }
+        if (mark(l, 1, stream) != ITB_OK) return ITB_ERR_DEVICE;
         const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
         for (int64_t c = 0; c < n_chunks; ++c) {
             const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
@@ -239,6 +264,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws, stream);
             if (rc != ITB_OK) return rc;
         }
+        if (mark(l, 2, stream) != ITB_OK) return ITB_ERR_DEVICE;
         if (!gat) {
             int32_t rc;
             if (pf) {  // the gathered projection enters the update as an addend to the self product
@@ -252,6 +278,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             }
             if (rc != ITB_OK) return rc;
         }
+        if (mark(l, 3, stream) != ITB_OK) return ITB_ERR_DEVICE;
         cur = dst;
     }
     return ITB_OK;

@@ -718,3 +718,32 @@ def test_random_layer_stacks(B, seed):
             y64 = oracle.dense_layer(r, c, d, h, lay, dtype, round_agg=not tr.projected)[1]
         check_features(B.to_numpy(tr.out), y64, dtype, f"layer {i} kinds={kinds} widths={widths} T={T}")
         h = B.to_numpy(tr.out)
+
+
+def test_layer_events_bracket_the_stages(B):
+    """itb_set_layer_events: four events per layer recorded by infer_full_graph on its stream, in order; the result is
+    unchanged and switching the recording off leaves the events alone."""
+    import torch
+    w = W.make("medium_uniform", 0.02)
+    rowptr, col, deg_out = B.build_csr_by_dst(w.n_nodes, dev_i32(w.src), dev_i32(w.dst))
+    layers, x = B.device_layers(w.layers), B.to_device(w.x)
+    ref = B.infer_full_graph(rowptr, col, deg_out, None, layers, x)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(4 * len(layers))]
+    for e in evs:
+        e.record()
+    torch.cuda.synchronize()
+    B.set_layer_events(evs)
+    try:
+        out = B.infer_full_graph(rowptr, col, deg_out, None, layers, x)
+    finally:
+        B.set_layer_events([])
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
+    times = [evs[k].elapsed_time(evs[k + 1]) for k in range(len(evs) - 1)]
+    assert all(t >= 0.0 for t in times)
+    gather = [evs[4 * i + 1].elapsed_time(evs[4 * i + 2]) for i in range(len(layers))]
+    assert all(g > 0.0 for g in gather)                      # every layer of this workload has a gather
+    again = B.infer_full_graph(rowptr, col, deg_out, None, layers, x)    # recording off: same result, events untouched
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int32), ref.view(torch.int32))
+    assert [evs[k].elapsed_time(evs[k + 1]) for k in range(len(evs) - 1)] == times
