@@ -198,7 +198,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         return ITB_OK;
     }
     if (*workspace_bytes < cv.off || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return ITB_ERR_WORKSPACE;
-    if (!rowptr || (n_nodes > 0 && (!x || !out)) || (n_edges > 0 && !col) || (any_gcn && !deg_out)) return ITB_ERR_NULL;
+    if (!rowptr || (n_nodes > 0 && (!x || !out)) || (n_edges > 0 && !col) || (any_gcn && n_nodes > 0 && !deg_out)) return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;
 
     if (any_gcn) {

@@ -747,3 +747,32 @@ def test_layer_events_bracket_the_stages(B):
     torch.cuda.synchronize()
     assert torch.equal(again.view(torch.int32), ref.view(torch.int32))
     assert [evs[k].elapsed_time(evs[k + 1]) for k in range(len(evs) - 1)] == times
+
+
+@pytest.mark.parametrize("kind", [W.AGG_MEAN, W.AGG_GCN, W.AGG_MAX, W.AGG_GAT])
+def test_infer_degenerate_graphs(B, kind):
+    """No edges at all (every vertex keeps its self term; GAT returns the projected row), a single vertex with
+    self-loops, and an empty vertex set."""
+    import torch
+    rng = np.random.default_rng(kind)
+    for n, e in [(300, 0), (1, 0), (1, 7), (2, 1)]:
+        src, dst, x = W.random_small_graph(n + e, n, e, 32, W.F32, 0.0)
+        layers = (W.gat_layers(rng, (32, 32, 16), 2, W.F32, bias_random=True) if kind == W.AGG_GAT
+                  else W.dense_layers(rng, kind, (32, 32, 16), W.F32, bias_random=True))
+        rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+        r, c, d = oracle.build_csr(n, src, dst)
+        out = B.infer_full_graph(rowptr, col, deg_out, B.split_hubs(rowptr, 2), B.device_layers(layers), B.to_device(x))
+        check_features(B.to_numpy(out), W.as_f32(oracle.infer_full_graph(r, c, d, x, layers, W.F32)), W.F32, f"n={n} e={e}")
+        if e == 0 and kind != W.AGG_GAT:
+            # isolated vertices: the aggregate is zero, so only the self term is left (the paper-independent invariant)
+            h = W.as_f32(x).astype(np.float64)
+            for i, lay in enumerate(layers):
+                h = h @ W.as_f32(lay.w_self).astype(np.float64) + lay.bias
+                h = np.maximum(h, 0) if i == 0 else h
+                h = h.astype(np.float32).astype(np.float64)
+            assert np.abs(B.to_numpy(out) - h).max() <= 1e-4
+    # empty vertex set: nothing to do, no error
+    empty = B.infer_full_graph(torch.zeros(1, dtype=torch.int64, device="cuda"), torch.zeros(0, dtype=torch.int32, device="cuda"),
+                               torch.zeros(0, dtype=torch.int32, device="cuda"), None, B.device_layers(layers),
+                               torch.zeros((0, 32), dtype=torch.float32, device="cuda"))
+    assert empty.shape == (0, 16)
