@@ -593,6 +593,7 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     const int piece = desc->dtype == ITB_BF16 ? 8 : 4;  // elements of one 16-byte piece of a row
     if (desc->d_in % piece != 0) return ITB_ERR_UNSUPPORTED;  // rows are read as 16-byte pieces
     if (desc->heads < 0) return ITB_ERR_SIZE;
+    if (n_nodes == 0) return ITB_OK;  // nothing to read or write: the per-vertex pointers may all be NULL
     if (desc->heads == 0 && (att_src || att_dst || s_src || s_dst)) return ITB_ERR_SIZE;
     if (desc->heads > 0) {
         if (!att_src || !att_dst || !s_src || !s_dst) return ITB_ERR_NULL;
@@ -602,8 +603,7 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
     if ((msg_scale == nullptr) != (msg_out == nullptr)) return ITB_ERR_NULL;
     if ((msg_out || addend) && desc->heads > 0) return ITB_ERR_UNSUPPORTED;
-    if (!w_nbr || (n_nodes > 0 && (!agg || !h_out))) return ITB_ERR_NULL;
-    if (n_nodes == 0) return ITB_OK;
+    if (!w_nbr || !agg || !h_out) return ITB_ERR_NULL;
 
     ApplyArgs a{};
     a.n = n_nodes;

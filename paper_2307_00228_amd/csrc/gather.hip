@@ -568,8 +568,8 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         return ITB_OK;
     }
     if (*workspace_bytes < cv.off || (cv.off > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u))) return ITB_ERR_WORKSPACE;
-    if (!rowptr || !agg_out || (n_nodes > 0 && !h_src)) return ITB_ERR_NULL;
-    if (desc->agg == ITB_AGG_GCN && !dst_scale) return ITB_ERR_NULL;  // src_scale NULL: rows already carry it
+    if (!rowptr || (n_nodes > 0 && (!h_src || !agg_out))) return ITB_ERR_NULL;
+    if (desc->agg == ITB_AGG_GCN && n_nodes > 0 && !dst_scale) return ITB_ERR_NULL;  // src_scale NULL: rows already carry it
     if (hubs && (!split->hub_ids || !split->hub_shadow_off || !split->shadow_begin || !split->shadow_end || !split->shadow_owner))
         return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;

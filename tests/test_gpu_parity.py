@@ -776,3 +776,29 @@ def test_infer_degenerate_graphs(B, kind):
                                torch.zeros(0, dtype=torch.int32, device="cuda"), None, B.device_layers(layers),
                                torch.zeros((0, 32), dtype=torch.float32, device="cuda"))
     assert empty.shape == (0, 16)
+
+
+def test_zero_sized_calls_are_accepted(B):
+    """Every entry point with an empty vertex or edge set: no launch, no error, outputs of the right (empty) shape."""
+    import torch
+    z64 = torch.zeros(1, dtype=torch.int64, device="cuda")
+    e32 = torch.zeros(0, dtype=torch.int32, device="cuda")
+    x0 = torch.zeros((0, 64), dtype=torch.float32, device="cuda")
+    rowptr, col, deg_out = B.build_csr_by_dst(0, e32, e32)
+    assert rowptr.cpu().tolist() == [0] and col.numel() == 0 and deg_out.numel() == 0
+    sp = B.split_hubs(rowptr, 4)
+    assert sp.n_hubs == 0 and sp.n_shadows == 0
+    for kind in (W.AGG_SUM, W.AGG_MEAN, W.AGG_MAX):
+        assert B.gather_layer(kind, z64, e32, x0, sp).shape == (0, 64)
+    ss, sd = B.gcn_norm_scales(z64, e32)
+    assert ss.numel() == 0 and B.gcn_edge_coefficients(e32, ss).numel() == 0
+    assert B.gather_layer(W.AGG_GCN, z64, e32, x0, None, ss, sd).shape == (0, 64)
+    wt = torch.zeros((64, 16), dtype=torch.float32, device="cuda")
+    assert B.apply_layer(x0, x0, wt, wt, None, W.ACT_RELU).shape == (0, 16)
+    assert B.scale_rows(x0, ss).shape == (0, 64)
+    # vertices without any edge
+    rowptr, col, deg_out = B.build_csr_by_dst(5, e32, e32)
+    assert rowptr.cpu().tolist() == [0] * 6 and deg_out.cpu().tolist() == [0] * 5
+    x5 = torch.ones((5, 64), dtype=torch.float32, device="cuda")
+    assert not B.gather_layer(W.AGG_MEAN, rowptr, col, x5, B.split_hubs(rowptr, 1)).any()
+    assert not B.gather_layer(W.AGG_MIN, rowptr, col, x5).any()
