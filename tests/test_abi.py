@@ -147,3 +147,25 @@ def test_product_package_never_imports_the_oracle():
     hits = [m.start() for m in re.finditer(r"^\s*import oracle", bench, flags=re.M)]
     assert len(hits) == 1 and bench.rfind("if not args.no_cpu_baseline:", 0, hits[0]) != -1
     assert not re.search(r"\boracle\.", bench[:bench.index("if not args.no_cpu_baseline:")])   # no use before that leg
+
+
+def test_workspace_errors_are_reported_before_anything_is_touched(B):
+    """Too small or misaligned workspace: ITB_ERR_WORKSPACE from the host-side checks (the pointers here are never
+    dereferenced, so fake addresses do)."""
+    lib = B.lib
+    fake, odd = C.c_void_p(1 << 20), C.c_void_p((1 << 20) + 8)
+    small, big = C.c_size_t(8), C.c_size_t(1 << 40)
+    assert lib.build_csr_by_dst(1000, 5000, None, None, None, None, None, fake, C.byref(small), None) == -6
+    assert lib.build_csr_by_dst(1000, 5000, None, None, None, None, None, odd, C.byref(big), None) == -6
+    nh, ns = C.c_int64(0), C.c_int64(0)
+    assert lib.split_hubs(5000, None, 4, C.byref(nh), C.byref(ns), None, None, None, None, None, fake, C.byref(small), None) == -6
+    assert lib.split_hubs(5000, None, 4, C.byref(nh), C.byref(ns), None, None, None, None, None, odd, C.byref(big), None) == -6
+    d = B.itb_gather_desc(B.AGG_MEAN, B.ITB_F32, B.ITB_F32, 64, 1, 0.2, 0, None, None)
+    assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, fake, C.byref(small), None) == -6
+    assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, odd, C.byref(big), None) == -6
+    lay = (B.itb_layer * 1)()
+    lay[0] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
+    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, fake, C.byref(small), None) == -6
+    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, odd, C.byref(big), None) == -6
+    # with enough (fake) workspace the next check is the missing inputs
+    assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, fake, C.byref(big), None) == -1
