@@ -169,3 +169,27 @@ def test_workspace_errors_are_reported_before_anything_is_touched(B):
     assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, odd, C.byref(big), None) == -6
     # with enough (fake) workspace the next check is the missing inputs
     assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, fake, C.byref(big), None) == -1
+
+
+def test_gat_and_layer_descriptor_validation(B):
+    lib = B.lib
+    need = C.c_size_t(0)
+    def gat(dt_in, dt_out, dim, heads, bias=None):
+        d = B.itb_gather_desc(B.AGG_GAT, dt_in, dt_out, dim, heads, 0.2, 0, bias, None)
+        return lib.gather_layer(C.byref(d), 100, None, None, None, None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None)
+    assert gat(B.ITB_F32, B.ITB_F32, 64, 4) == 0 and need.value > 0
+    assert gat(B.ITB_F32, B.ITB_F32, 64, 0) == -2            # heads
+    assert gat(B.ITB_F32, B.ITB_F32, 64, 3) == -2            # heads does not divide dim
+    assert gat(B.ITB_BF16, B.ITB_BF16, 64, 16) == -5         # 4 values per head: not a whole 16-byte vector of bf16
+    assert gat(B.ITB_BF16, B.ITB_F32, 64, 4) == -5           # the attention reduce keeps the dtype
+    assert gat(B.ITB_F32, B.ITB_F32, 64, 4, bias=C.c_void_p(4100)) == -5     # bias is read as 16-byte vectors
+    def infer(layer):
+        lay = (B.itb_layer * 1)()
+        lay[0] = layer
+        return lib.infer_full_graph(100, 500, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, C.byref(need), None)
+    assert infer(B.itb_layer(B.AGG_MAX, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == 0
+    assert infer(B.itb_layer(B.AGG_NONE, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == 0
+    assert infer(B.itb_layer(B.AGG_NONE, 64, 32, B.ACT_NONE, 1, 0.2, C.c_void_p(256), None, None, None, None)) == -5   # no self matrix there
+    assert infer(B.itb_layer(7, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == -4
+    assert infer(B.itb_layer(B.AGG_MEAN, 0, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == -2
+    assert infer(B.itb_layer(B.AGG_MEAN, 62, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == -5            # 248-byte rows
