@@ -221,6 +221,8 @@ def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=Tru
     a64 = gather(layer.agg, rowptr, col, h, deg_out=deg_out, verts=verts)
     a_st = round_store(a64, dtype)
     hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
+    if layer.w_self is None:      # no self matrix: the update sees the aggregate only
+        hs = None
     if round_agg:
         y64 = apply(hs, a_st, layer.w_self, layer.w_nbr, layer.bias, layer.act)
     else:

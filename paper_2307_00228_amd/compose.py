@@ -98,7 +98,7 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         if pf:
             B.apply_layer(None, h, None, l.w_self, l.bias, l.act, out=out, addend=agg)
         else:
-            B.apply_layer(h, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
+            B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
         mark("apply_end", i)
         traces.append(LayerTrace(src_rows, agg, out, pf))
         h = out

@@ -568,6 +568,38 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
     return ITB_ERR_UNSUPPORTED;
 }
 
+}  // namespace
+
+namespace itb {
+// Whether some configuration of the update kernel holds this shape in LDS (the same walk as dispatch_staged): lets
+// the layer loop refuse a model before it has enqueued anything.
+bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t heads) {
+    const bool bf16 = dtype == ITB_BF16;
+    const int kc = bf16 ? 16 : 8;
+    if (d_in <= 0 || d_out <= 0 || d_in % (kc / 2) != 0) return false;
+    if (heads > 0 && (has_self || heads > 16 || d_out % heads != 0)) return false;
+    const size_t esz = bf16 ? 2 : 4;
+    const int phases = has_self ? 2 : 1;
+    const int real_chunks = (d_in + kc - 1) / kc;
+    const bool ragged = d_out % (bf16 ? 8 : 4) != 0;
+    for (int nt = 4; nt >= 1; nt /= 2) {
+        if (nt > 1 && 32 * (nt / 2) >= d_out) continue;
+        for (int pf = ragged ? 1 : 8; pf >= 1; pf /= 2) {
+            const int chunks = padded_chunks(d_in, kc, pf);
+            if (pf > 1 && 4 * (chunks - real_chunks) > real_chunks) continue;
+            const size_t k_total = (size_t)chunks * kc * phases;
+            const size_t panel = k_total * 32 * nt * esz + (heads > 0 ? k_total * 32 * (bf16 ? 2 : 1) * esz : 0);
+            const size_t stage = (size_t)kApplyWaves * ((64 * pf > 256) ? 64 * pf : 256) * 16;
+            if (panel + stage <= kMaxLds) return true;
+        }
+    }
+    return false;
+}
+}  // namespace itb
+
+namespace {
+using namespace itb;
+
 int cached_cu_count() {
     static int cus = 0;
     if (cus == 0) {

@@ -6,6 +6,7 @@
 #include <vector>
 
 namespace itb {
+bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t heads);
 // Measurement aid: events the layer loop records on its stream, four per layer (layer begin, before the gather, after
 // the gather, layer end), so that a caller can time the stages of the single call without issuing them one by one.
 std::vector<hipEvent_t> g_layer_events;
@@ -167,6 +168,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (L.d_out > max_d) max_d = L.d_out;
         if (L.agg == ITB_AGG_NONE) {  // per-vertex layer: no gather, no gather workspace
             if (L.w_self) return ITB_ERR_UNSUPPORTED;
+            if (!apply_shape_supported(dtype, L.d_in, L.d_out, false, 0)) return ITB_ERR_UNSUPPORTED;
             continue;
         }
         any_gcn = any_gcn || L.agg == ITB_AGG_GCN;
@@ -174,6 +176,11 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (gat && L.heads > max_heads) max_heads = L.heads;
         const bool pf = project_before_gather(L, dtype);
         any_project = any_project || pf;
+        // every update launch of the layer must have a kernel configuration: refuse the model before enqueueing anything
+        if (gat ? !apply_shape_supported(dtype, L.d_in, L.d_out, false, L.heads)
+                : (pf ? !apply_shape_supported(dtype, L.d_in, L.d_out, false, 0)
+                      : !apply_shape_supported(dtype, L.d_in, L.d_out, L.w_self != nullptr, 0)))
+            return ITB_ERR_UNSUPPORTED;
         itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr, nullptr};
         size_t need = 0;
         int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
@@ -273,8 +280,8 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
                                  nullptr, nullptr, aggbuf, stream);
             } else {
                 itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-                rc = apply_layer(&ad, n_nodes, cur, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
-                                 nullptr, nullptr, nullptr, stream);
+                rc = apply_layer(&ad, n_nodes, L.w_self ? cur : nullptr, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr,
+                                 nullptr, nullptr, nullptr, nullptr, nullptr, stream);   // no self matrix: no self term
             }
             if (rc != ITB_OK) return rc;
         }

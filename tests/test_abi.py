@@ -193,3 +193,6 @@ def test_gat_and_layer_descriptor_validation(B):
     assert infer(B.itb_layer(7, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == -4
     assert infer(B.itb_layer(B.AGG_MEAN, 0, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == -2
     assert infer(B.itb_layer(B.AGG_MEAN, 62, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == -5            # 248-byte rows
+    # an update whose weights cannot be held in LDS is refused up front (2 x 768 x 32 fp32 with the self matrix)
+    assert infer(B.itb_layer(B.AGG_MEAN, 768, 768, B.ACT_NONE, 1, 0.2, C.c_void_p(256), C.c_void_p(256), None, None, None)) == -5
+    assert infer(B.itb_layer(B.AGG_NONE, 768, 96, B.ACT_NONE, 1, 0.2, None, C.c_void_p(256), None, None, None)) == 0

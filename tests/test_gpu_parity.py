@@ -802,3 +802,21 @@ def test_zero_sized_calls_are_accepted(B):
     x5 = torch.ones((5, 64), dtype=torch.float32, device="cuda")
     assert not B.gather_layer(W.AGG_MEAN, rowptr, col, x5, B.split_hubs(rowptr, 1)).any()
     assert not B.gather_layer(W.AGG_MIN, rowptr, col, x5).any()
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_layers_without_a_self_matrix(B, dtype):
+    """h' = act(agg(h) W_nbr + b): dense layers whose self matrix is absent (the vertex's own state does not enter)."""
+    import torch
+    from dataclasses import replace
+    n, e = 4000, 50000
+    src, dst, x = W.random_small_graph(61, n, e, 64, dtype, 0.2)
+    layers = [replace(l, w_self=None) for l in W.dense_layers(np.random.default_rng(62), [W.AGG_MEAN, W.AGG_MAX], (64, 64, 32), dtype,
+                                                              bias_random=True)]
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    out = B.infer_full_graph(rowptr, col, deg_out, B.split_hubs(rowptr, 100), B.device_layers(layers), B.to_device(x))
+    check_features(B.to_numpy(out), W.as_f32(oracle.infer_full_graph(r, c, d, x, layers, dtype)), dtype)
+    iso = np.nonzero(np.diff(r) == 0)[0]
+    if len(iso):                                  # no in-edges, no self term: bias only
+        assert np.abs(W.as_f32(B.to_numpy(out))[iso] - layers[-1].bias).max() <= (1e-6 if dtype == W.F32 else 2e-3)
