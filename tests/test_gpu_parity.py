@@ -820,3 +820,26 @@ def test_layers_without_a_self_matrix(B, dtype):
     iso = np.nonzero(np.diff(r) == 0)[0]
     if len(iso):                                  # no in-edges, no self term: bias only
         assert np.abs(W.as_f32(B.to_numpy(out))[iso] - layers[-1].bias).max() <= (1e-6 if dtype == W.F32 else 2e-3)
+
+
+def test_very_wide_rows_with_hubs(B):
+    """Rows wider than one pass of the combine kernels (more than 1024 16-byte columns of fp32 partials) and than one
+    wavefront of lane groups: dense and attention gathers with hub partials."""
+    import torch
+    n, e, dim = 400, 6000, 4352
+    src, dst, x = W.random_small_graph(71, n, e, dim, W.F32, 0.4)
+    for kind in (W.AGG_MEAN, W.AGG_MAX):
+        got, want, _ = run_gather(B, kind, n, src, dst, x, W.F32, T=16)
+        if kind == W.AGG_MAX:
+            assert_same_values(got, want)
+        else:
+            check_features(got, want, W.F32)
+    heads = 4
+    rng = np.random.default_rng(72)
+    s_src = rng.standard_normal((n, heads)).astype(np.float32)
+    s_dst = rng.standard_normal((n, heads)).astype(np.float32)
+    r, c, _ = oracle.build_csr(n, src, dst)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    out = B.gather_layer(W.AGG_GAT, rp, cl, B.to_device(x), B.split_hubs(rp, 16), torch.from_numpy(s_src).cuda(),
+                         torch.from_numpy(s_dst).cuda(), heads=heads, leaky_slope=0.2)
+    check_features(B.to_numpy(out), oracle.gat_gather(r, c, x, s_src, s_dst, heads, 0.2), W.F32)
