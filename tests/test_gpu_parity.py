@@ -512,7 +512,8 @@ def test_gcn_stack(B, dtype, dims):
             h = B.to_numpy(tr.out)
 
 
-@pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 64, 16), (W.F32, 128, 64), (W.BF16, 64, 32), (W.BF16, 128, 40)])
+@pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 64, 16), (W.F32, 128, 64), (W.BF16, 64, 32), (W.BF16, 128, 40),
+                                              (W.F32, 64, 47), (W.BF16, 64, 20), (W.BF16, 200, 300)])
 @pytest.mark.parametrize("n", [7, 1000, 4100])
 def test_apply_with_addend(B, dtype, d_in, d_out, n):
     """h_out = act(h . W + addend + bias), optionally with the message output."""
