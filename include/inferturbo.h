@@ -36,8 +36,10 @@
  *    apply_layer can be captured into a HIP graph.
  *  - Return value: ITB_OK (0) or a negative itb_status.  Argument errors are
  *    detected on the host before any launch.  Nothing throws, aborts or prints.
- *  - Dense tensors are row-major.  ITB_BF16 tensors hold IEEE bfloat16
- *    (round-to-nearest-even on store); all sums accumulate in fp32.
+ *  - Dense tensors are row-major and 16-byte aligned (they are moved as
+ *    16-byte vectors; a misaligned feature tensor is ITB_ERR_UNSUPPORTED).
+ *    ITB_BF16 tensors hold IEEE bfloat16 (round-to-nearest-even on store); all
+ *    sums accumulate in fp32.
  *  - Sizes: 0 <= n_nodes < 2^31, 0 <= n_edges < 2^31.
  *  - Results are bitwise reproducible run to run: no floating-point atomics,
  *    every summation order is fixed by the inputs and sizes (the paper's

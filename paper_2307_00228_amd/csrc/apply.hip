@@ -636,6 +636,9 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if ((msg_scale == nullptr) != (msg_out == nullptr)) return ITB_ERR_NULL;
     if ((msg_out || addend) && desc->heads > 0) return ITB_ERR_UNSUPPORTED;
     if (!w_nbr || !agg || !h_out) return ITB_ERR_NULL;
+    if (!aligned16(h_self) || !aligned16(agg) || !aligned16(h_out) || !aligned16(addend) || !aligned16(msg_out))
+        return ITB_ERR_UNSUPPORTED;  // rows are moved as 16-byte vectors (a ragged d_out is stored element by element,
+                                     // its base must still be aligned)
 
     ApplyArgs a{};
     a.n = n_nodes;

@@ -22,6 +22,9 @@ namespace itb {
 // A helper stream per device on which gather_layer runs the hub passes (segment partials + combine) next to the
 // row passes of the caller's stream: fork = event recorded on the caller's stream that the helper waits for,
 // join = event recorded on the helper that the caller's stream waits for.  Default priority, non-blocking.
+// Feature tensors are read and written as 16-byte vectors.
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
 struct SideStream {
     hipStream_t stream;
     hipEvent_t fork, join;

@@ -637,6 +637,7 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     }
     if (*workspace_bytes < cv.off || (cv.off > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u))) return ITB_ERR_WORKSPACE;
     if (!rowptr || (n_nodes > 0 && (!out || !z || !s_src || !s_dst))) return ITB_ERR_NULL;
+    if (!aligned16(z) || !aligned16(out)) return ITB_ERR_UNSUPPORTED;
     if (hubs && (!split->hub_ids || !split->hub_shadow_off || !split->shadow_begin || !split->shadow_end || !split->shadow_owner))
         return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;

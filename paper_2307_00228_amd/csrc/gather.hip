@@ -569,6 +569,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     }
     if (*workspace_bytes < cv.off || (cv.off > 0 && (reinterpret_cast<uintptr_t>(workspace) & 255u))) return ITB_ERR_WORKSPACE;
     if (!rowptr || (n_nodes > 0 && (!h_src || !agg_out))) return ITB_ERR_NULL;
+    if (!aligned16(h_src) || !aligned16(agg_out)) return ITB_ERR_UNSUPPORTED;
     if (desc->agg == ITB_AGG_GCN && n_nodes > 0 && !dst_scale) return ITB_ERR_NULL;  // src_scale NULL: rows already carry it
     if (hubs && (!split->hub_ids || !split->hub_shadow_off || !split->shadow_begin || !split->shadow_end || !split->shadow_owner))
         return ITB_ERR_NULL;

@@ -80,6 +80,7 @@ extern "C" int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const
     const int elem = dtype == ITB_BF16 ? 2 : 4;
     if ((dim * elem) % 16 != 0) return ITB_ERR_UNSUPPORTED;
     if (n_nodes > 0 && (!x || !row_scale || !out)) return ITB_ERR_NULL;
+    if (!aligned16(x) || !aligned16(out)) return ITB_ERR_UNSUPPORTED;
     if (n_nodes == 0) return ITB_OK;
     const int32_t row_vecs = dim * elem / 16;
     const int64_t n_vec = n_nodes * row_vecs;

@@ -196,3 +196,19 @@ def test_gat_and_layer_descriptor_validation(B):
     # an update whose weights cannot be held in LDS is refused up front (2 x 768 x 32 fp32 with the self matrix)
     assert infer(B.itb_layer(B.AGG_MEAN, 768, 768, B.ACT_NONE, 1, 0.2, C.c_void_p(256), C.c_void_p(256), None, None, None)) == -5
     assert infer(B.itb_layer(B.AGG_NONE, 768, 96, B.ACT_NONE, 1, 0.2, None, C.c_void_p(256), None, None, None)) == 0
+
+
+def test_misaligned_feature_tensors_are_refused(B):
+    """Feature tensors move as 16-byte vectors: a base address that is not 16-byte aligned is refused on the host."""
+    lib = B.lib
+    ok, off = C.c_void_p(1 << 20), C.c_void_p((1 << 20) + 4)
+    big = C.c_size_t(1 << 40)
+    d = B.itb_gather_desc(B.AGG_MEAN, B.ITB_F32, B.ITB_F32, 64, 1, 0.2, 0, None, None)
+    args = lambda h, o: (C.byref(d), 100, ok, ok, None, h, None, None, o, 0, B.INT64_MAX, ok, C.byref(big), None)
+    assert lib.gather_layer(*args(off, ok)) == -5 and lib.gather_layer(*args(ok, off)) == -5
+    a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
+    ap = lambda hs, ag, out, add: lib.apply_layer(C.byref(a), 10, hs, ag, ok if hs else None, ok, None, out, None, None, None, None,
+                                                   None, None, add, None)
+    assert ap(None, off, ok, None) == -5 and ap(None, ok, off, None) == -5
+    assert ap(off, ok, ok, None) == -5 and ap(None, ok, ok, off) == -5
+    assert lib.scale_rows(B.ITB_F32, 10, 64, off, ok, ok, None) == -5
