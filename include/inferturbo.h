@@ -180,6 +180,9 @@ int32_t gcn_edge_coefficients(int64_t n_edges, const int32_t *col, const float *
  *                 are merged by the same operator
  *   ITB_AGG_GAT : attention-weighted sum, see below.
  *
+ *   rowptr/col the CSR by destination as build_csr_by_dst writes it (rowptr
+ *              non-decreasing, rowptr[n_nodes] = number of edges, every col
+ *              entry in [0, n_nodes)); trusted, not validated again.
  *   dim        feature width; dim * sizeof(element) must be a multiple of 16.
  *   h_src      [n_nodes x dim] dtype_in.
  *   agg_out    [n_nodes x dim] dtype_out (f32->f32, bf16->bf16, bf16->f32).
