@@ -110,16 +110,27 @@ __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, u
     const int64_t base = tile * kTile;
     bool bad = false;
     bool fold_d = true, fold_s = true;
+    // 16-byte loads where the caller's arrays allow them (counting does not care about the order inside the tile)
+    const bool vec = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0;
     uint32_t kd[kItems], ks[kItems];
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        const int64_t idx = base + i * kThreads + threadIdx.x;
-        kd[i] = idx < n_edges ? (uint32_t)dst[idx] : 0u;
-        ks[i] = idx < n_edges ? (uint32_t)src[idx] : 0u;
+    for (int i = 0; i < kItems / 4; ++i) {
+        const int64_t idx = base + ((int64_t)i * kThreads + threadIdx.x) * 4;
+        if (vec && idx + 3 < n_edges) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(dst + idx), b = *reinterpret_cast<const uint4 *>(src + idx);
+            kd[4 * i] = a.x; kd[4 * i + 1] = a.y; kd[4 * i + 2] = a.z; kd[4 * i + 3] = a.w;
+            ks[4 * i] = b.x; ks[4 * i + 1] = b.y; ks[4 * i + 2] = b.z; ks[4 * i + 3] = b.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                kd[4 * i + j] = idx + j < n_edges ? (uint32_t)dst[idx + j] : 0u;
+                ks[4 * i + j] = idx + j < n_edges ? (uint32_t)src[idx + j] : 0u;
+            }
+        }
     }
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        const int64_t idx = base + i * kThreads + threadIdx.x;
+        const int64_t idx = base + ((int64_t)(i / 4) * kThreads + threadIdx.x) * 4 + (i & 3);
         const bool valid = idx < n_edges;
         if (valid) bad = bad || kd[i] >= n_nodes || ks[i] >= n_nodes;
         wave_count(hd, kd[i] & mask, valid, fold_d);
@@ -254,11 +265,25 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *ke
     __syncthreads();
     const int64_t base = tile * kTile;
     bool fold = true;
+    // counting does not care about the order inside the tile: 16-byte loads (the key buffers are 16-byte aligned and a
+    // tile starts at a multiple of 4096 keys); only the last tile can be ragged
+    uint32_t k[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems / 4; ++i) {
+        const int64_t idx = base + ((int64_t)i * kThreads + threadIdx.x) * 4;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (idx + 3 < n) v = *reinterpret_cast<const uint4 *>(keys + idx);
+        else {
+            if (idx < n) v.x = keys[idx];
+            if (idx + 1 < n) v.y = keys[idx + 1];
+            if (idx + 2 < n) v.z = keys[idx + 2];
+        }
+        k[4 * i] = v.x; k[4 * i + 1] = v.y; k[4 * i + 2] = v.z; k[4 * i + 3] = v.w;
+    }
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        int64_t idx = base + i * kThreads + threadIdx.x;
-        const bool valid = idx < n;
-        wave_count(h, valid ? (keys[idx] >> shift) & mask : 0u, valid, fold);
+        const int64_t idx = base + ((int64_t)(i / 4) * kThreads + threadIdx.x) * 4 + (i & 3);
+        wave_count(h, (k[i] >> shift) & mask, idx < n, fold);
     }
     __syncthreads();
     for (int d = threadIdx.x; d < radix; d += kThreads) hist[(int64_t)d * nblocks + tile] = h[d];
