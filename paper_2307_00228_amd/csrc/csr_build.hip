@@ -170,16 +170,23 @@ __global__ __launch_bounds__(kThreads) void partition_scatter_kernel(const uint3
     const uint32_t low_mask = (1u << shift) - 1u;
     uint32_t key[kItems], slot[kItems];
     bool fold = true;
+    // any order inside the tile will do: 16-byte loads where the caller's array allows them
+    const bool vec = (reinterpret_cast<uintptr_t>(keys_in) & 15u) == 0;
+    auto item_index = [&](int i) { return base + ((int64_t)(i / 4) * kThreads + threadIdx.x) * 4 + (i & 3); };
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        const int64_t idx = base + i * kThreads + threadIdx.x;
-        key[i] = idx < n ? keys_in[idx] : 0u;
+    for (int i = 0; i < kItems / 4; ++i) {
+        const int64_t idx = item_index(4 * i);
+        if (vec && idx + 3 < n) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(keys_in + idx);
+            key[4 * i] = v.x; key[4 * i + 1] = v.y; key[4 * i + 2] = v.z; key[4 * i + 3] = v.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) key[4 * i + j] = idx + j < n ? keys_in[idx + j] : 0u;
+        }
     }
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        const int64_t idx = base + i * kThreads + threadIdx.x;
-        slot[i] = wave_count(cnt, partition_digit(key[i], shift, radix), idx < n, fold);
-    }
+    for (int i = 0; i < kItems; ++i)
+        slot[i] = wave_count(cnt, partition_digit(key[i], shift, radix), item_index(i) < n, fold);
     __syncthreads();
     // exclusive prefix over the digits, two digits per thread (radix <= 2 * kThreads)
     const int d0 = 2 * threadIdx.x, d1 = d0 + 1;
@@ -191,8 +198,7 @@ __global__ __launch_bounds__(kThreads) void partition_scatter_kernel(const uint3
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
-        const int64_t idx = base + i * kThreads + threadIdx.x;
-        if (idx < n) {
+        if (item_index(i) < n) {
             const uint32_t d = partition_digit(key[i], shift, radix);
             skey[lstart[d] + slot[i]] = (d << 16) | (key[i] & low_mask);
         }
