@@ -14,7 +14,7 @@
 
 namespace itb {
 extern int g_rows_waves_per_simd;
-size_t lds_for_occupancy(int waves, int lanes_per_row);
+size_t lds_for_occupancy(int waves, int lanes_per_row, bool beside_hub_passes);
 }  // namespace itb
 
 namespace {
@@ -584,7 +584,7 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
     }
     zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
     ITB_LAUNCH_CHECK();
-    gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, itb::lds_for_occupancy(itb::g_rows_waves_per_simd == -1 ? 0 : itb::g_rows_waves_per_simd, G), st>>>(a);
+    gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, itb::lds_for_occupancy(itb::g_rows_waves_per_simd == -1 ? 0 : itb::g_rows_waves_per_simd, G, hubs), st>>>(a);
     ITB_LAUNCH_CHECK();
     int64_t lg = waves > 2048 ? 2048 : waves;  // fixed grid over the device-side work list
     gat_long_rows_kernel<BF16, G><<<dim3((unsigned)lg, gy), kRangeWaves * kWave, 0, st>>>(a);

@@ -49,11 +49,12 @@ int g_rows_waves_per_simd = -1;  // tuning hook (key 4): cap on resident wavefro
                                  // (0 = no cap, -1 = built-in choice)
 // Dynamic LDS that limits a 256-thread (4-wave) block to `waves` wavefronts per SIMD: a CU has 4 SIMDs and
 // 160 KB of LDS, so `waves` blocks fit when each asks for 160 KB / waves.
-size_t lds_for_occupancy(int waves, int lanes_per_row) {
+size_t lds_for_occupancy(int waves, int lanes_per_row, bool beside_hub_passes) {
     // Measured on MI355X: with rows of 512 bytes and more (32+ lanes per row) the random row gather runs ~10 %
-    // faster with 4 resident wavefronts per SIMD than with 8 (fewer requests queued per memory channel); with
-    // shorter rows the extra wavefronts pay off.
-    if (waves < 0) waves = lanes_per_row >= 32 ? 4 : 0;
+    // faster with 4 resident wavefronts per SIMD than with 8 (fewer requests queued per memory channel); 256-byte
+    // rows gain 2-3 % from a cap of 5 when the kernel has the chip to itself and lose 5 % when the hub passes run
+    // beside it (the LDS request then keeps segment blocks off the CU); shorter rows want every wavefront.
+    if (waves < 0) waves = lanes_per_row >= 32 ? 4 : (lanes_per_row == 16 && !beside_hub_passes ? 5 : 0);
     if (waves <= 0 || waves >= 8) return 0;
     return (size_t)(160 * 1024 / waves) - 512;
 }
@@ -486,7 +487,7 @@ int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
     if (a.n_nodes > 0) {
         zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
         ITB_LAUNCH_CHECK();
-        gather_rows_kernel<BF16_IN, BF16_OUT, G, EXT><<<grid, 256, lds_for_occupancy(g_rows_waves_per_simd, G), st>>>(a);
+        gather_rows_kernel<BF16_IN, BF16_OUT, G, EXT><<<grid, 256, lds_for_occupancy(g_rows_waves_per_simd, G, a.n_shadows > 0), st>>>(a);
         ITB_LAUNCH_CHECK();
         // the list length is only known on the device: a fixed grid walks it (blocks beyond the length exit)
         int64_t lg = (a.n_nodes + 63) / 64;
@@ -604,6 +605,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     a.long_limit = g_long_row > a.small_limit ? g_long_row : a.small_limit;
     a.long_list = long_list;
     a.long_count = long_count;
+    a.n_shadows = hubs ? split->n_shadows : 0;  // > 0: hub passes run beside the row passes
 
     const bool bin = desc->dtype_in == ITB_BF16, bout = desc->dtype_out == ITB_BF16;
     int32_t rc;
