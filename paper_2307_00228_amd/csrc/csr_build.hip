@@ -416,6 +416,35 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(uint32_t *data
     }
 }
 
+// Second level folded into the first: with at most kScanTile partial sums every block adds up the partials of the
+// blocks before it by itself (one 8-item read per thread), which saves the launch of a one-block scan in between.
+__global__ __launch_bounds__(kScanThreads) void scan_apply_self_offset_kernel(uint32_t *data, int64_t n, const uint32_t *partial) {
+    __shared__ uint32_t sm[17];
+    uint32_t before = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        const int j = threadIdx.x * kScanItems + i;
+        if (j < (int)blockIdx.x) before += partial[j];
+    }
+    uint32_t offset;
+    block_exclusive_scan<uint32_t>(before, sm, &offset);   // offset = sum over the whole block = sum of partial[0 .. blockIdx)
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    uint32_t v[kScanItems];
+    uint32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        v[i] = (base + i < n) ? data[base + i] : 0u;
+        s += v[i];
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan<uint32_t>(s, sm, &total) + offset;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        if (base + i < n) data[base + i] = run;
+        run += v[i];
+    }
+}
+
 size_t scan_workspace_elems(int64_t n) {
     size_t total = 0;
     while (n > kScanTile) {
@@ -435,6 +464,11 @@ int32_t exclusive_scan_u32(uint32_t *data, int64_t n, uint32_t *ws, hipStream_t 
     }
     scan_reduce_kernel<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, ws);
     ITB_LAUNCH_CHECK();
+    if (nb <= kScanTile) {
+        scan_apply_self_offset_kernel<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, ws);
+        ITB_LAUNCH_CHECK();
+        return ITB_OK;
+    }
     int32_t rc = exclusive_scan_u32(ws, nb, ws + align_up((size_t)nb * sizeof(uint32_t)) / sizeof(uint32_t), st);
     if (rc != ITB_OK) return rc;
     scan_apply_kernel<<<(unsigned)nb, kScanThreads, 0, st>>>(data, n, ws);
