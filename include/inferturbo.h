@@ -167,6 +167,10 @@ int32_t gcn_edge_coefficients(int64_t n_edges, const int32_t *col, const float *
  *
  *   ITB_AGG_SUM : agg[v] = sum over in-edges of h[col]
  *   ITB_AGG_MEAN: the sum divided by the in-degree; 0 for an isolated vertex
+ *                 With desc->edge_coef ([n_edges] fp32, CSR order) both take
+ *                 edge-weighted messages w_e * h[col[e]] (apply_edge with a
+ *                 scalar edge feature, Sec. IV-B); the mean still divides by
+ *                 the number of in-edges.
  *   ITB_AGG_GCN : dst_scale[v] * sum of c_e * h[col]; dst_scale is required.
  *                 The source coefficient c_e of an in-edge comes from
  *                 desc->edge_coef[e] ([n_edges] fp32 in CSR order, read beside
@@ -213,7 +217,7 @@ typedef struct {
     float leaky_slope;  /* GAT only */
     int32_t act;        /* GAT only: activation applied after the bias; else ITB_ACT_NONE */
     const float *bias;  /* GAT only: [dim] fp32 added to the reduced row, or NULL; else NULL */
-    const float *edge_coef; /* GCN only, optional: [n_edges] fp32 coefficient of every in-edge, CSR order */
+    const float *edge_coef; /* SUM / MEAN / GCN, optional: [n_edges] fp32 scalar of every in-edge, CSR order */
 } itb_gather_desc;
 
 int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,

@@ -131,6 +131,22 @@ def gather(agg, rowptr, col, h, deg_out=None, verts=None):
     return out
 
 
+def gather_weighted(agg, rowptr, col, h, edge_w, verts=None):
+    """fp64 aggregate of edge-weighted messages w_e * h[col[e]] (SUM or MEAN); ``edge_w`` is [E] fp32 in CSR order."""
+    rowptr, col, hf = _i64(rowptr), _i32(col), _f32(h)
+    n, d = hf.shape
+    w = np.ascontiguousarray(edge_w, dtype=np.float32)
+    assert len(w) == len(col)
+    vs = None if verts is None else _i64(verts)
+    out = np.zeros((n if vs is None else len(vs), d), dtype=np.float64)
+    rc = lib().oracle_gather_weighted(C.c_int(agg), C.c_int64(n), _p(rowptr, C.c_int64), _p(col, C.c_int32),
+                                      C.c_int64(d), _p(hf, C.c_float), _p(w, C.c_float),
+                                      _p(vs, C.c_int64), C.c_int64(0 if vs is None else len(vs)), _p(out, C.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_gather_weighted failed: {rc}")
+    return out
+
+
 def gather_split(agg, rowptr, col, h, split, deg_out=None):
     """Same aggregate computed through the shadow segments; returns (agg, edge_count)."""
     rowptr, col, hf = _i64(rowptr), _i32(col), _f32(h)

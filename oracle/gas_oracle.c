@@ -174,6 +174,37 @@ int oracle_gather(int agg, int64_t n_nodes, const int64_t *rowptr, const int32_t
 }
 
 /* ---------------------------------------------------------------------------
+ * Gather of edge-weighted messages (Sec. IV-B apply_edge: the message of an
+ * edge is generated from the source's state and the edge's own feature; here
+ * the feature is one scalar w_e per edge, stored in CSR order):
+ *   sum : agg[v] = sum_{e in in(v)} w_e * h[col[e]]
+ *   mean: that sum divided by the in-degree (the number of messages), 0 for an
+ *         isolated vertex.
+ * ------------------------------------------------------------------------- */
+int oracle_gather_weighted(int agg, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                           int64_t dim, const float *h, const float *edge_w,
+                           const int64_t *verts, int64_t n_verts, double *out)
+{
+    if ((agg != ORC_SUM && agg != ORC_MEAN) || !edge_w) return -1;
+    int64_t n_out = verts ? n_verts : n_nodes;
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < n_out; ++i) {
+        int64_t v = verts ? verts[i] : i;
+        double *acc = out + i * dim;
+        for (int64_t k = 0; k < dim; ++k) acc[k] = 0.0;
+        int64_t b = rowptr[v], e = rowptr[v + 1];
+        for (int64_t j = b; j < e; ++j) {
+            const float *hu = h + (int64_t)col[j] * dim;
+            double w = (double)edge_w[j];
+            for (int64_t k = 0; k < dim; ++k) acc[k] += w * (double)hu[k];
+        }
+        if (agg == ORC_MEAN && e > b)
+            for (int64_t k = 0; k < dim; ++k) acc[k] /= (double)(e - b);
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
  * Partial-gather over shadow segments (Sec. IV-D "Partial-Gather": aggregate
  * runs on partially available messages, the receiver aggregates the partials;
  * exact because aggregate is commutative and associative).  Non-hub vertices

@@ -583,7 +583,8 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     a.col = col;
     a.h = static_cast<const uint4 *>(h_src);
     a.src_scale = (desc->agg == ITB_AGG_GCN) ? src_scale : nullptr;
-    a.edge_coef = (desc->agg == ITB_AGG_GCN) ? desc->edge_coef : nullptr;
+    // per-edge scalar: the source coefficient of a GCN edge, or the weight of an edge-weighted sum / mean
+    a.edge_coef = (desc->agg == ITB_AGG_GCN || desc->agg == ITB_AGG_SUM || desc->agg == ITB_AGG_MEAN) ? desc->edge_coef : nullptr;
     a.dst_scale = (desc->agg == ITB_AGG_GCN) ? dst_scale : nullptr;
     a.out = agg_out;
     a.threshold = split ? split->threshold : INT64_MAX;

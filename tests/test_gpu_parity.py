@@ -268,6 +268,27 @@ def test_gcn_gather_with_per_edge_coefficients(B, dtype, dim, T):
     assert torch.equal(chunked.view(view), by_edge.view(view))
 
 
+@pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN])
+@pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.BF16, 128), (W.F32, 260)])
+@pytest.mark.parametrize("T", [None, 40])
+def test_edge_weighted_gather(B, kind, dtype, dim, T):
+    """Messages w_e * h[u] with one scalar per in-edge (CSR order), through rows, long rows and hub partials."""
+    import torch
+    n, e = 3000, 50000
+    src, dst, x = W.random_small_graph(dim + 13, n, e, dim, dtype, 0.3)
+    r, c, _ = oracle.build_csr(n, src, dst)
+    w = np.random.default_rng(dim).uniform(-1.0, 1.0, e).astype(np.float32)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    split = B.split_hubs(rp, T) if T else None
+    out = B.gather_layer(kind, rp, cl, B.to_device(x), split, edge_coef=torch.from_numpy(w).cuda())
+    want = oracle.gather_weighted(kind, r, c, x, w)
+    check_features(B.to_numpy(out), want, dtype, magnitude_scaled=kind == W.AGG_SUM)
+    ones = torch.ones(e, dtype=torch.float32, device="cuda")
+    plain = B.gather_layer(kind, rp, cl, B.to_device(x), split)
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    assert torch.equal(B.gather_layer(kind, rp, cl, B.to_device(x), split, edge_coef=ones).view(view), plain.view(view))
+
+
 def test_gather_from_two_host_threads(B):
     """Two host threads, each on its own stream, call gather_layer with a hub split at the same time: the helper
     stream's fork/join sequences must not interleave (bitwise the single-threaded results)."""

@@ -560,3 +560,33 @@ def test_hub_threshold_golden_and_exact_rational():
             assert (t + 1 > exact) and not (t > exact)
     with pytest.raises(ValueError):
         oracle.hub_threshold(10, 0)
+
+
+# ---------------------------------------------------------------- edge-weighted messages (Sec. IV-B apply_edge)
+def test_weighted_gather_is_weighted_spmm_and_reduces_to_the_plain_forms():
+    n, e, d = 60, 900, 5
+    src, dst, x = small_graph(180, n, e, d, hub=0.3)
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    order = np.argsort(dst, kind="stable")                     # CSR position -> original edge
+    w_edge = np.random.default_rng(181).standard_normal(e).astype(np.float32)   # per original edge
+    w_csr = w_edge[order]
+    A = sp.csr_matrix((w_edge.astype(np.float64), (dst, src)), shape=(n, n))      # duplicates are summed
+    want = A @ x.astype(np.float64)
+    got = oracle.gather_weighted(oracle.SUM, rowptr, col, x, w_csr)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    deg = np.diff(rowptr)
+    mean = oracle.gather_weighted(oracle.MEAN, rowptr, col, x, w_csr)
+    np.testing.assert_allclose(mean[deg > 0], want[deg > 0] / deg[deg > 0, None], rtol=1e-12, atol=1e-12)
+    assert not mean[deg == 0].any()
+    ones = np.ones(e, dtype=np.float32)
+    assert np.array_equal(oracle.gather_weighted(oracle.SUM, rowptr, col, x, ones), oracle.gather(oracle.SUM, rowptr, col, x))
+    assert np.array_equal(oracle.gather_weighted(oracle.MEAN, rowptr, col, x, ones), oracle.gather(oracle.MEAN, rowptr, col, x))
+    # the GCN aggregate is the weighted sum with w_e = (deg_out(u) deg_in(v))^-1/2
+    dv = np.repeat(np.maximum(deg, 1), deg)
+    w_gcn = (1.0 / np.sqrt(np.maximum(deg_out[col], 1).astype(np.float64) * dv)).astype(np.float32)
+    np.testing.assert_allclose(oracle.gather_weighted(oracle.SUM, rowptr, col, x, w_gcn),
+                               oracle.gather(oracle.GCN, rowptr, col, x, deg_out=deg_out), rtol=1e-5, atol=1e-6)
+    verts = np.array([3, 0, 59, 3], dtype=np.int64)
+    assert np.array_equal(oracle.gather_weighted(oracle.SUM, rowptr, col, x, w_csr, verts=verts), got[verts])
+    with pytest.raises(ValueError):
+        oracle.gather_weighted(oracle.MAX, rowptr, col, x, w_csr)
