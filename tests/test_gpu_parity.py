@@ -865,3 +865,17 @@ def test_very_wide_rows_with_hubs(B):
     out = B.gather_layer(W.AGG_GAT, rp, cl, B.to_device(x), B.split_hubs(rp, 16), torch.from_numpy(s_src).cuda(),
                          torch.from_numpy(s_dst).cuda(), heads=heads, leaky_slope=0.2)
     check_features(B.to_numpy(out), oracle.gat_gather(r, c, x, s_src, s_dst, heads, 0.2), W.F32)
+
+
+def test_readme_example_runs(B):
+    """The call sequence shown in README.md, executed as written there."""
+    import os
+    import re
+    text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "README.md")).read()
+    code = re.search(r"```python\n(.*?)```", text, flags=re.S).group(1)
+    scope = {}
+    exec(compile(code, "README.md", "exec"), scope)
+    w, out, agg = scope["w"], scope["out"], scope["agg"]
+    assert tuple(out.shape) == (w.n_nodes, w.layers[-1].d_out) and tuple(agg.shape) == (w.n_nodes, w.layers[0].d_in)
+    r, c, d = oracle.build_csr(w.n_nodes, w.src, w.dst)
+    check_features(B.to_numpy(out), W.as_f32(oracle.infer_full_graph(r, c, d, w.x, w.layers, w.dtype)), w.dtype)
