@@ -140,6 +140,7 @@ __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPer
     constexpr int U = 4;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
+    const int vec_c = lane_on ? vec : 0;   // lanes beyond the row's width read its first vector (never used)
     for (int64_t c = (int64_t)first_chunk * kWave; c < deg; c += (int64_t)chunk_stride * kWave) {
         int myc = 0;
         if (c + lane < deg) myc = a.col[start + c + lane];
@@ -151,11 +152,14 @@ __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPer
             bool on[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) {
+                // A slot past the end of the chunk re-reads the chunk's last edge and enters with weight zero (its row
+                // is a row this segment sums anyway): the loads need no predicate and no select.
                 const int ei = (t + q) * NG + g;
-                const int u = __shfl(myc, ei & (kWave - 1), kWave);
+                const int eic = ei < cnt ? ei : cnt - 1;
+                const int u = __shfl(myc, eic, kWave);
                 on[q] = lane_on && ei < cnt;
-                raw[q] = on[q] ? a.z[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
-                e[q] = on[q] ? a.s_src[(int64_t)u * a.heads + hk] : 0.f;
+                raw[q] = a.z[(int64_t)u * a.row_vecs + vec_c];
+                e[q] = a.s_src[(int64_t)u * a.heads + hk];
             }
 #pragma unroll
             for (int q = 0; q < U; ++q) e[q] = leaky(e[q] + sd, a.slope);
