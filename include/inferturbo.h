@@ -16,8 +16,13 @@
  * Conventions for every call
  *  - Every pointer is a DEVICE pointer unless marked "host".  All buffers
  *    (inputs, outputs, workspace) are allocated, owned and freed by the
- *    caller; the library keeps no allocation and no pointer after return and
- *    never modifies an input.
+ *    caller; the library never modifies an input and keeps no pointer to a
+ *    caller's buffer or handle after return.
+ *  - What the library itself owns, per device, from the first call that needs
+ *    it until itb_shutdown() or the end of the process: one helper stream
+ *    (default priority, non-blocking) with two events, on which gather_layer
+ *    runs the hub passes and build_csr_by_dst the out-degree branch; and
+ *    the launch attributes of its kernels.  Nothing else outlives a call.
  *  - Workspace protocol: if `workspace` is NULL the call only writes the
  *    number of bytes it needs for these sizes to *workspace_bytes (host) and
  *    returns ITB_OK.  Otherwise *workspace_bytes is the size provided;
@@ -29,17 +34,21 @@
  *    the host); split_hubs synchronises once to read the two counts, the
  *    arrays it fills afterwards are ordered on the stream like any output.
  *    gather_layer (hub passes) and build_csr_by_dst (out-degrees) put part of
- *    their work on a helper stream the library owns and join it back into
- *    `stream` before returning; host threads calling on different streams are
- *    serialised around that fork and join.  Nothing the calls enqueue uses a
- *    memset node or a synchronisation, so infer_full_graph, gather_layer and
- *    apply_layer can be captured into a HIP graph.
+ *    their work on the helper stream and join it back into `stream` before
+ *    returning, on error returns too; host threads calling on different
+ *    streams are serialised around that fork and join.  Nothing the calls
+ *    enqueue uses a memset node or a synchronisation, so infer_full_graph,
+ *    gather_layer and apply_layer can be captured into a HIP graph (after one
+ *    uncaptured call on the device, which creates the helper stream).
  *  - Return value: ITB_OK (0) or a negative itb_status.  Argument errors are
  *    detected on the host before any launch.  Nothing throws, aborts or prints.
  *  - Dense tensors are row-major and 16-byte aligned (they are moved as
  *    16-byte vectors; a misaligned feature tensor is ITB_ERR_UNSUPPORTED).
  *    ITB_BF16 tensors hold IEEE bfloat16 (round-to-nearest-even on store); all
- *    sums accumulate in fp32.
+ *    sums accumulate in fp32.  Feature data is expected to be finite: the
+ *    attention gather feeds the tail of an edge chunk with weight zero, so an
+ *    infinity in a source row can surface as NaN in a destination whose exact
+ *    result is infinite.
  *  - Sizes: 0 <= n_nodes < 2^31, 0 <= n_edges < 2^31.
  *  - Results are bitwise reproducible run to run: no floating-point atomics,
  *    every summation order is fixed by the inputs and sizes (the paper's
@@ -299,6 +308,11 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  * per-edge source coefficients (gcn_edge_coefficients) built at the start.
  * An ITB_AGG_NONE layer is h' = act(h . w_nbr + bias) per vertex, no edges
  * touched (w_self must be NULL).
+ *   events     NULL, or a host struct naming a host array of hipEvent_t
+ *              handles, four per layer: the call records events[4l + 0..3] on
+ *              `stream` at layer l's begin, before its gather, after its
+ *              gather and at its end (NULL entries and layers beyond n_events
+ *              are skipped).  The handles are used during the call only.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t agg;        /* ITB_AGG_* */
@@ -312,33 +326,25 @@ typedef struct {
     const float *att_src, *att_dst; /* GAT: [heads x d_out/heads] */
 } itb_layer;
 
+typedef struct {
+    void **events;      /* host array of hipEvent_t */
+    int32_t n_events;
+} itb_stage_events;
+
 int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
                          const int32_t *deg_out, const itb_split *split,
                          int32_t dtype, int32_t n_layers, const itb_layer *layers,
                          const void *x, void *out, int64_t edge_chunk,
-                         void *workspace, size_t *workspace_bytes, void *stream);
+                         void *workspace, size_t *workspace_bytes,
+                         const itb_stage_events *events, void *stream);
 
 /* ---------------------------------------------------------------------------
- * Measurement aids (not part of the method).
- * itb_copy_bytes: plain device copy of n_bytes (multiple of 16) with one
- * 16-byte load and store per lane; the known-size kernel that hardware byte
- * counters are scaled against.
- * itb_set_tuning: process-wide switches for A/B measurements.  key 0 = in-degree
- * up to which gather processes one row per lane group instead of per wavefront
- * (-1 = built-in choice); 2 = XCD-contiguous tile order in the radix passes
- * (1 = on); 3 = in-degree above which a non-hub row gets a whole block (512);
- * 4 = resident wavefronts per SIMD of the row gather (-1 = built-in choice);
- * 5 = out-degrees from a keys-only sort instead of partition + bucket counts;
- * 6 = helper-stream overlap (hub passes of a gather, out-degree branch of the
- * CSR build; 1 = on).
- * itb_set_layer_events: `events` is a HOST array of hipEvent_t handles, four per
- * layer; infer_full_graph records events[4l + 0..3] on its stream at layer l's
- * begin, before its gather, after its gather and at its end (NULL entries are
- * skipped; n_events = 0 switches the recording off).  Process-wide.
+ * itb_shutdown -- destroys what the library owns (the helper stream and its
+ * events on every device that has them), after synchronising the helper
+ * stream.  Call it when no call is in flight; a later call creates the state
+ * again.  Optional: the objects are otherwise released with the process.
  * ------------------------------------------------------------------------- */
-int32_t itb_set_layer_events(void **events, int32_t n_events);
-int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream);
-int32_t itb_set_tuning(int32_t key, int32_t value);
+int32_t itb_shutdown(void);
 
 #ifdef __cplusplus
 }

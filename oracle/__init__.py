@@ -224,16 +224,19 @@ def round_store(x64, dtype):
 
 
 # ------------------------------------------------------------------ whole layers
-def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=True):
-    """One SAGE/GCN-style layer: gather (sum, mean, degree-normalised sum, max or min), store agg, apply.
-    Returns (agg_stored, y64).  A layer without a gather (NONE: encoder before the first round, prediction
-    head after the last, Sec. IV-C) is the update of the vertex's own state alone: (None, y64).
-    ``round_agg``: the aggregate is a stored tensor between the two steps and is rounded to the storage dtype;
-    with False the layer is Eq. (1) in fp64 with no intermediate rounding at all (the yardstick for evaluation
-    orders that never store agg(h), such as applying W_nbr before the aggregate)."""
+def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=False, return_agg64=False):
+    """One SAGE/GCN-style layer: gather (sum, mean, degree-normalised sum, max or min), then apply: Eq. (1) in fp64
+    with no intermediate rounding, whatever order or storage an implementation uses between the two steps.
+    Returns (agg_stored, y64) -- agg_stored is the aggregate rounded to the storage dtype, for stage-wise checks --
+    and with ``return_agg64`` also the unrounded aggregate.  A layer without a gather (NONE: encoder before the first
+    round, prediction head after the last, Sec. IV-C) is the update of the vertex's own state alone: (None, y64).
+    ``round_agg=True`` evaluates the update on the ROUNDED aggregate instead: the arithmetic of an implementation
+    that stores agg(h) in the storage dtype between gather and update (kept for stage-wise comparisons; it is not
+    the yardstick of a layer)."""
     if layer.agg == NONE:
         hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
-        return None, apply(None, hs, None, layer.w_nbr, layer.bias, layer.act)
+        y = apply(None, hs, None, layer.w_nbr, layer.bias, layer.act)
+        return (None, y, None) if return_agg64 else (None, y)
     a64 = gather(layer.agg, rowptr, col, h, deg_out=deg_out, verts=verts)
     a_st = round_store(a64, dtype)
     hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
@@ -247,7 +250,7 @@ def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=Tru
         y64 = y64 + a64 @ _f32(layer.w_nbr).astype(np.float64)
         if layer.act == ACT_RELU:
             y64 = np.maximum(y64, 0.0)
-    return a_st, y64
+    return (a_st, y64, a64) if return_agg64 else (a_st, y64)
 
 
 def gat_layer(rowptr, col, h, layer, dtype, verts=None):

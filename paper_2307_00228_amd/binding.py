@@ -56,6 +56,10 @@ class itb_layer(C.Structure):
                 ("att_src", C.c_void_p), ("att_dst", C.c_void_p)]
 
 
+class itb_stage_events(C.Structure):
+    _fields_ = [("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int32)]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -71,14 +75,15 @@ def _load():
     lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
-                                     vp, vp, i64, vp, szp, vp]
+                                     vp, vp, i64, vp, szp, C.POINTER(itb_stage_events), vp]
+    lib.itb_shutdown.argtypes = []
+    lib.itb_random_row_read.argtypes = [vp, i64, i32, vp, i64, vp, i64, vp]
     lib.hub_threshold_heuristic.argtypes = [i64, i64, C.c_double, C.POINTER(i64)]
     lib.itb_set_tuning.argtypes = [i32, i32]
-    lib.itb_set_layer_events.argtypes = [C.POINTER(C.c_void_p), i32]
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients",
-              "itb_set_layer_events"):
+              "itb_shutdown", "itb_random_row_read"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -120,11 +125,20 @@ def copy_bytes(src: torch.Tensor, dst: torch.Tensor):
     _check("itb_copy_bytes", lib.itb_copy_bytes(_ptr(src), _ptr(dst), n, _stream()))
 
 
-def set_layer_events(events):
-    """``events``: torch.cuda.Event objects (timing enabled, each recorded once so that its handle exists), four per
-    layer, which infer_full_graph records at layer begin / before gather / after gather / layer end; [] switches it off."""
-    arr = (C.c_void_p * max(1, len(events)))(*[e.cuda_event for e in events])
-    _check("itb_set_layer_events", lib.itb_set_layer_events(arr, len(events)))
+def random_row_read(table: torch.Tensor, idx: torch.Tensor, sink: Optional[torch.Tensor] = None):
+    """Measurement aid: reads row idx[i] of ``table`` ([rows x row_bytes] as any dtype) for every i; returns the sink."""
+    n_rows = table.shape[0]
+    row_bytes = table.shape[1] * table.element_size()
+    assert idx.dtype == torch.int32
+    if sink is None:
+        sink = torch.empty(2048 * 256, dtype=torch.int32, device="cuda")
+    _check("itb_random_row_read", lib.itb_random_row_read(_ptr(table), n_rows, row_bytes, _ptr(idx), idx.numel(), _ptr(sink),
+                                                          sink.numel() * 4, _stream()))
+    return sink
+
+
+def shutdown():
+    _check("itb_shutdown", lib.itb_shutdown())
 
 
 def set_tuning(key: int, value: int):
@@ -293,12 +307,15 @@ def infer_workspace_bytes(n_nodes, n_edges, split: Optional[Split], dtype, layer
     _check("infer_full_graph(size)", lib.infer_full_graph(n_nodes, n_edges, None, None, None,
                                                           C.byref(sp) if sp is not None else None,
                                                           ITB_BF16 if dtype == torch.bfloat16 else ITB_F32, len(layers), arr,
-                                                          None, None, edge_chunk, None, C.byref(need), None))
+                                                          None, None, edge_chunk, None, C.byref(need), None, None))
     return need.value
 
 
 def infer_full_graph(rowptr, col, deg_out, split: Optional[Split], layers: List[DeviceLayer], x,
-                     out: Optional[torch.Tensor] = None, edge_chunk: int = 0, workspace: Optional[torch.Tensor] = None):
+                     out: Optional[torch.Tensor] = None, edge_chunk: int = 0, workspace: Optional[torch.Tensor] = None,
+                     events=None):
+    """``events``: optional list of torch.cuda.Event objects (timing enabled, each recorded once so that its handle
+    exists), four per layer, which the call records at layer begin / before gather / after gather / layer end."""
     n = x.shape[0]
     e = col.numel()
     if out is None:
@@ -309,9 +326,14 @@ def infer_full_graph(rowptr, col, deg_out, split: Optional[Split], layers: List[
     if workspace is None:
         workspace = _workspace(infer_workspace_bytes(n, e, split, x.dtype, layers, edge_chunk))
     size = C.c_size_t(workspace.numel())
+    evp = None
+    if events:
+        handles = (C.c_void_p * len(events))(*[ev.cuda_event for ev in events])
+        evs = itb_stage_events(handles, len(events))
+        evp = C.byref(evs)
     _check("infer_full_graph", lib.infer_full_graph(n, e, _ptr(rowptr), _ptr(col), _ptr(deg_out), spp, dtype_code(x),
                                                     len(layers), arr, _ptr(x), _ptr(out), edge_chunk, _ptr(workspace),
-                                                    C.byref(size), _stream()))
+                                                    C.byref(size), evp, _stream()))
     return out
 
 

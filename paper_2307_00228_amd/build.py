@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libinferturbo_hip.so")
 BUILD_DIR = os.path.join(HERE, "_build")
-SOURCES = ["csr_build.hip", "split_hubs.hip", "gather.hip", "gat.hip", "apply.hip", "infer.hip"]
+SOURCES = ["csr_build.hip", "split_hubs.hip", "gather.hip", "gat.hip", "apply.hip", "infer.hip", "aids.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-fno-strict-aliasing",

@@ -221,6 +221,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     uint32_t *stage32 = reinterpret_cast<uint32_t *>(stage);
     const int GT = GTS > 0 ? GTS : phases * gpp;  // groups per row tile
     const int64_t row_vecs = a.d_in / (KC / 2);    // 16-byte pieces of a stored row (2 * chunks unless the k range is padded)
+    const bool padded_k = (int64_t)2 * chunks != row_vecs;
     const uint4 *wbase = wlds + kh * BN + i;
     const uint4 *sbase = slds + kh * 32 + i;
     const int lr = lane / LPR, lc = lane % LPR;
@@ -245,8 +246,8 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
         const uint4 *base = (live && phases == 2 && phase == 0) ? a.h_self : a.agg;
         const int gi = live ? f_g - phase * gpp : 0;
         const int64_t row0 = live ? f_tile * kRowsPerBlockTile + (int64_t)w * 32 + lr : 0;
-        // A piece of the padded k range past the row's end re-reads the row's last piece: it meets zero weights, so it
-        // adds exactly nothing (for finite data) and the load needs no predicate.
+        // A piece of the padded k range past the row's end re-reads the row's last piece, so that the load needs no
+        // predicate; stage_write replaces it by zeros (the zero weights it meets would cancel finite values only).
         int piece = gi * LPR + lc;
         piece = piece < (int)row_vecs ? piece : (int)row_vecs - 1;
 #pragma unroll
@@ -260,18 +261,21 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
             f_tile += gridDim.x;
         }
     };
-    auto stage_write = [&](const uint4(&R)[PF]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < PF; ++q) {
-            const int r = q * RPL + lr;
-            stage[r * LPR + (lc ^ stage_swz<LPR>(r))] = R[q];
-        }
-    };
-
     v16f acc[NT];
     v16f sacc;
     int64_t tile = blockIdx.x;
-    int g = 0;
+    int g = 0;   // compute cursor: the group whose rows are written to the staging area and multiplied next
+
+    auto stage_write = [&](const uint4(&R)[PF]) __attribute__((always_inline)) {
+        // pieces of group g beyond the row's width (padded k range only) enter as zeros
+        const int gi = (g >= gpp) ? g - gpp : g;
+        const bool pad = padded_k && gi * LPR + lc >= (int)row_vecs;
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int r = q * RPL + lr;
+            stage[r * LPR + (lc ^ stage_swz<LPR>(r))] = pad ? make_uint4(0, 0, 0, 0) : R[q];
+        }
+    };
 
     auto compute = [&]() __attribute__((always_inline)) {
         const int cb = g * PF;
@@ -493,11 +497,12 @@ int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     const int k_total = padded_chunks(a.d_in, KC, PF) * KC * (a.h_self ? 2 : 1);
     const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4) + stage_bytes;
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // once per kernel variant (setting it again is harmless, so a race between two first callers is too)
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int col_tiles = (a.d_out + BN - 1) / BN;
     int blocks_per_cu = (int)((160 * 1024) / (lds + 1024));

@@ -15,23 +15,81 @@
         if (hipGetLastError() != hipSuccess) return ITB_ERR_DEVICE; \
     } while (0)
 
+#include <atomic>
 #include <mutex>
 
 namespace itb {
 
-// A helper stream per device on which gather_layer runs the hub passes (segment partials + combine) next to the
-// row passes of the caller's stream: fork = event recorded on the caller's stream that the helper waits for,
-// join = event recorded on the helper that the caller's stream waits for.  Default priority, non-blocking.
 // Feature tensors are read and written as 16-byte vectors.
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Library-owned state, one per device, created at the first call that uses it and destroyed by itb_shutdown():
+// a helper stream on which gather_layer runs the hub passes (segment partials + combine) and build_csr_by_dst the
+// out-degree branch, next to the work on the caller's stream.  fork = event recorded on the caller's stream that
+// the helper waits for, join = event recorded on the helper that the caller's stream waits for.  Default
+// priority, non-blocking.
 struct SideStream {
     hipStream_t stream;
     hipEvent_t fork, join;
     std::mutex mu;  // held from the fork record to the join wait: host threads sharing the device must not interleave them
 };
 SideStream *side_stream();  // nullptr if it cannot be created (callers then stay on the one stream)
-extern int g_overlap_hubs;  // tuning hook (key 6): 0 = everything on the caller's stream
+void destroy_side_streams();
+
+// Process-wide A/B switches of the measurement aids (itb_set_tuning, keys in brackets); atomics because a caller may
+// flip one while another host thread is inside a call.
+struct Tuning {
+    std::atomic<int> small_limit{-1};         // [0] rows with in-degree <= limit use one lane group per row (-1 = built-in)
+    std::atomic<int> csr_xcd_remap{1};        // [2] XCD-contiguous tile order in the radix passes
+    std::atomic<int> long_row{512};           // [3] rows with more in-edges get a whole block
+    std::atomic<int> rows_waves_per_simd{-1}; // [4] resident wavefronts per SIMD of the row gather (0 = no cap, -1 = built-in)
+    std::atomic<int> csr_deg_by_sort{0};      // [5] out-degrees always from a keys-only run of the stable sort
+    std::atomic<int> overlap_hubs{1};         // [6] 0 = everything on the caller's stream
+    std::atomic<int> gather_unroll{-1};       // [7] row loads in flight per lane of the gather loops (-1 = built-in)
+};
+extern Tuning g_tuning;
+
+// One fork/join of the helper stream.  Whatever path a call takes after begin() -- an error return included --
+// the destructor records the join on the helper stream and makes the caller's stream wait for it, so that no
+// call leaves the caller's stream (or a stream capture) with an open fork.
+class SideFork {
+   public:
+    SideFork() = default;
+    SideFork(const SideFork &) = delete;
+    SideFork &operator=(const SideFork &) = delete;
+    ~SideFork() { finish(); }
+    // `side` may be nullptr: everything then stays on `main`.
+    int32_t begin(SideStream *side, hipStream_t main) {
+        main_ = main;
+        if (!side) return ITB_OK;
+        lock_ = std::unique_lock<std::mutex>(side->mu);
+        if (hipEventRecord(side->fork, main) != hipSuccess) { lock_.unlock(); return ITB_ERR_DEVICE; }
+        side_ = side;  // from here on the helper stream depends on `main`: it must be joined back
+        if (hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) return ITB_ERR_DEVICE;
+        return ITB_OK;
+    }
+    hipStream_t stream() const { return side_ ? side_->stream : main_; }
+    // The helper's work is enqueued: record the join point (the caller's stream waits for it in finish()).
+    int32_t mark_done() {
+        if (!side_ || recorded_) return ITB_OK;
+        recorded_ = true;
+        return hipEventRecord(side_->join, side_->stream) == hipSuccess ? ITB_OK : ITB_ERR_DEVICE;
+    }
+    int32_t finish() {
+        if (!side_) return ITB_OK;
+        int32_t rc = mark_done();
+        if (hipStreamWaitEvent(main_, side_->join, 0) != hipSuccess) rc = ITB_ERR_DEVICE;
+        side_ = nullptr;
+        lock_.unlock();
+        return rc;
+    }
+
+   private:
+    SideStream *side_ = nullptr;
+    hipStream_t main_ = nullptr;
+    bool recorded_ = false;
+    std::unique_lock<std::mutex> lock_;
+};
 
 constexpr int kWave = 64;
 

@@ -7,11 +7,6 @@
 // ordering, so the result is the unique stable grouping.
 #include "common.h"
 
-namespace itb {
-int g_csr_xcd_remap = 1;  // tuning hook (key 2): 0 = tiles in launch order
-int g_csr_deg_by_sort = 0;  // tuning hook (key 5): 1 = out-degrees always from a keys-only run of the stable sort
-}
-
 namespace {
 using namespace itb;
 
@@ -584,47 +579,47 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     if (part_high > 9) part_high = 9;
     if (part_high > bits_total) part_high = bits_total;
     const int part_low = bits_total - part_high;
-    const bool deg_by_partition = deg_out && part_low <= kMaxLowBits && itb::g_csr_deg_by_sort == 0;
+    const bool deg_by_partition = deg_out && part_low <= kMaxLowBits && itb::g_tuning.csr_deg_by_sort.load() == 0;
 
+    const int xcd_remap = itb::g_tuning.csr_xcd_remap.load();
     fill_u32_kernel<<<1, 64, 0, st>>>(flag, 64, 0u);
     ITB_LAUNCH_CHECK();
     {
         const int bits0 = base_bits + (0 < extra ? 1 : 0);
         if (deg_by_partition)
             first_pass_kernel<2><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, part_low,
-                                                                         1 << part_high, hist_src, nblocks, itb::g_csr_xcd_remap, flag);
+                                                                         1 << part_high, hist_src, nblocks, xcd_remap, flag);
         else if (deg_out)
             first_pass_kernel<1><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, 0, 1 << bits0,
-                                                                         hist_src, nblocks, itb::g_csr_xcd_remap, flag);
+                                                                         hist_src, nblocks, xcd_remap, flag);
         else
             first_pass_kernel<0><<<(unsigned)nblocks, kThreads, 0, st>>>(n_edges, (uint32_t)n_nodes, src, dst, bits0, hist, 0, 1,
-                                                                             nullptr, nblocks, itb::g_csr_xcd_remap, flag);
+                                                                             nullptr, nblocks, xcd_remap, flag);
         ITB_LAUNCH_CHECK();
     }
     // The out-degree branch shares nothing with the pair sort but the raw table and the first-pass histograms: it is
     // enqueued on the helper stream (when there is one) and joins before the final synchronisation.
-    itb::SideStream *side = (deg_by_partition && itb::g_overlap_hubs) ? itb::side_stream() : nullptr;
-    std::unique_lock<std::mutex> side_lock;
-    if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
+    itb::SideFork fork;
+    {
+        const int32_t rc = fork.begin((deg_by_partition && itb::g_tuning.overlap_hubs.load()) ? itb::side_stream() : nullptr, st);
+        if (rc != ITB_OK) return rc;
+    }
     if (deg_by_partition) {
-        hipStream_t dst_stream = side ? side->stream : st;
-        if (side) {
-            ITB_HIP(hipEventRecord(side->fork, st));
-            ITB_HIP(hipStreamWaitEvent(dst_stream, side->fork, 0));
-        }
+        hipStream_t dst_stream = fork.stream();
         const int radix = 1 << part_high;
         int32_t rc = exclusive_scan_u32(hist_src, (int64_t)radix * nblocks, scan_ws_deg, dst_stream);
         if (rc != ITB_OK) return rc;
         partition_scatter_kernel<<<(unsigned)nblocks, kThreads, 0, dst_stream>>>(reinterpret_cast<const uint32_t *>(src), low_keys,
                                                                                  n_edges, part_low, radix, hist_src, nblocks,
-                                                                                 itb::g_csr_xcd_remap);
+                                                                                 xcd_remap);
         ITB_LAUNCH_CHECK();
         fill_u32_kernel<<<grid_for(n_nodes, 256), 256, 0, dst_stream>>>(reinterpret_cast<uint32_t *>(deg_out), n_nodes, 0u);
         ITB_LAUNCH_CHECK();
         bucket_degree_kernel<<<dim3((unsigned)radix, kDegSlicesY), kDegThreads, 0, dst_stream>>>(low_keys, n_edges, hist_src, nblocks,
                                                                                                  radix, part_low, n_nodes, deg_out);
         ITB_LAUNCH_CHECK();
-        if (side) ITB_HIP(hipEventRecord(side->join, dst_stream));
+        rc = fork.mark_done();
+        if (rc != ITB_OK) return rc;
     }
 
     // One radix sort, run once or twice: keys only over the sources (their run lengths are the out-degrees;
@@ -643,17 +638,17 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
             // the first digit of both sorts was counted while the raw table was range-checked
             uint32_t *h = pairs ? hist : hist_src;  // separate buffers: the pairs' first histogram must survive the source sort
             if (p > 0) {
-                radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, h, nblocks, itb::g_csr_xcd_remap);
+                radix_hist_kernel<<<(unsigned)nblocks, kThreads, 0, st>>>(kin, n_edges, shift, bits, h, nblocks, xcd_remap);
                 ITB_LAUNCH_CHECK();
             }
             int32_t rc = exclusive_scan_u32(h, hist_n, scan_ws, st);
             if (rc != ITB_OK) return rc;
             if (pairs)
                 radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, h,
-                                                                                   nblocks, itb::g_csr_xcd_remap);
+                                                                                   nblocks, xcd_remap);
             else
                 radix_scatter_kernel<false><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, nullptr, kout, nullptr, n_edges, shift, bits,
-                                                                                    h, nblocks, itb::g_csr_xcd_remap);
+                                                                                    h, nblocks, xcd_remap);
             ITB_LAUNCH_CHECK();
             kin = kout;
             vin = vout;
@@ -669,9 +664,9 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     rowptr_from_sorted_kernel<int64_t><<<grid_for(n_edges, 256), 256, 0, st>>>(kin, n_edges, n_nodes, rowptr);
     ITB_LAUNCH_CHECK();
 
-    if (side) {
-        ITB_HIP(hipStreamWaitEvent(st, side->join, 0));
-        side_lock.unlock();
+    {
+        const int32_t rc = fork.finish();
+        if (rc != ITB_OK) return rc;
     }
     uint32_t host_flag = 0;
     ITB_HIP(hipMemcpyAsync(&host_flag, flag, sizeof(uint32_t), hipMemcpyDeviceToHost, st));

@@ -13,7 +13,6 @@
 #include "common.h"
 
 namespace itb {
-extern int g_rows_waves_per_simd;
 size_t lds_for_occupancy(int waves, int lanes_per_row, bool beside_hub_passes);
 }  // namespace itb
 
@@ -253,7 +252,9 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
     const uint64_t small_mask = __ballot(mine && deg > 0 && deg <= a.small_limit);
     uint64_t large_mask = __ballot(mine && deg > a.small_limit && deg <= a.long_limit);
     const uint64_t long_mask = __ballot(mine && deg > a.long_limit);
-    if (long_mask) {  // hand the long rows to the block-per-row kernel (the list order enters no result)
+    // hand the long rows to the block-per-row kernel (the list order enters no result); one entry per row: only the
+    // first of the column blocks (blockIdx.y) that share these rows appends
+    if (long_mask && blockIdx.y == 0) {
         uint32_t base = 0;
         if (lane == 0) base = atomicAdd(a.long_count, (uint32_t)__popcll(long_mask));
         base = __shfl(base, 0, kWave);
@@ -567,59 +568,57 @@ __global__ __launch_bounds__(1024) void gat_combine_kernel(GatArgs a, int64_t n_
 
 template <bool BF16, int G>
 int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *hub_ids, const int64_t *hub_shadow_off,
-                   hipStream_t st) {
+                   bool allow_side, hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
     const unsigned gy = (unsigned)((a.row_vecs + G - 1) / G);
     // hub passes first, on the helper stream when there is one (see gather_layer)
-    itb::SideStream *side = (hubs && itb::g_overlap_hubs) ? itb::side_stream() : nullptr;
-    std::unique_lock<std::mutex> side_lock;
-    if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
+    itb::SideFork fork;
+    {
+        const int32_t rc = fork.begin((hubs && allow_side && itb::g_tuning.overlap_hubs.load()) ? itb::side_stream() : nullptr, st);
+        if (rc != ITB_OK) return rc;
+    }
     if (hubs) {
-        hipStream_t hst = side ? side->stream : st;
-        if (side) {
-            ITB_HIP(hipEventRecord(side->fork, st));
-            ITB_HIP(hipStreamWaitEvent(hst, side->fork, 0));
-        }
+        hipStream_t hst = fork.stream();
         gat_segments_kernel<BF16, G><<<dim3((unsigned)a.n_shadows, gy), kRangeWaves * kWave, 0, hst>>>(a);
         ITB_LAUNCH_CHECK();
         gat_combine_kernel<BF16><<<(unsigned)n_hubs, 1024, 0, hst>>>(a, n_hubs, hub_ids, hub_shadow_off);
         ITB_LAUNCH_CHECK();
-        if (side) ITB_HIP(hipEventRecord(side->join, hst));
+        const int32_t rc = fork.mark_done();
+        if (rc != ITB_OK) return rc;
     }
     zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
     ITB_LAUNCH_CHECK();
-    gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, itb::lds_for_occupancy(itb::g_rows_waves_per_simd == -1 ? 0 : itb::g_rows_waves_per_simd, G, hubs), st>>>(a);
+    const int cap = itb::g_tuning.rows_waves_per_simd.load();
+    gat_rows_kernel<BF16, G><<<dim3((unsigned)((waves + 3) / 4), gy), 256, itb::lds_for_occupancy(cap == -1 ? 0 : cap, G, hubs), st>>>(a);
     ITB_LAUNCH_CHECK();
     int64_t lg = waves > 2048 ? 2048 : waves;  // fixed grid over the device-side work list
     gat_long_rows_kernel<BF16, G><<<dim3((unsigned)lg, gy), kRangeWaves * kWave, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
-    if (side) ITB_HIP(hipStreamWaitEvent(st, side->join, 0));
-    return ITB_OK;
+    return fork.finish();
 }
 
 template <bool BF16>
 int32_t dispatch(int G, const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *hub_ids, const int64_t *hub_shadow_off,
-                 hipStream_t st) {
+                 bool allow_side, hipStream_t st) {
     switch (G) {
-        case 1: return launch_all<BF16, 1>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
-        case 2: return launch_all<BF16, 2>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
-        case 4: return launch_all<BF16, 4>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
-        case 8: return launch_all<BF16, 8>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
-        case 16: return launch_all<BF16, 16>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
-        case 32: return launch_all<BF16, 32>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
-        default: return launch_all<BF16, 64>(a, hubs, n_hubs, hub_ids, hub_shadow_off, st);
+        case 1: return launch_all<BF16, 1>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        case 2: return launch_all<BF16, 2>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        case 4: return launch_all<BF16, 4>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        case 8: return launch_all<BF16, 8>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        case 16: return launch_all<BF16, 16>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        case 32: return launch_all<BF16, 32>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        default: return launch_all<BF16, 64>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
     }
 }
 
 }  // namespace
 
 namespace itb {
-extern int g_small_limit;
-extern int g_long_row;
 
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
-                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, hipStream_t st) {
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, bool allow_side,
+                        hipStream_t st) {
     const bool bf16 = desc->dtype_in == ITB_BF16;
     if (desc->dtype_out != desc->dtype_in) return ITB_ERR_UNSUPPORTED;
     if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
@@ -665,8 +664,9 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     a.slope = desc->leaky_slope;
     int G = 1;
     while (G < a.row_vecs && G < kWave) G <<= 1;
-    a.small_limit = g_small_limit >= 0 ? g_small_limit : 2 * (kWave / G);
-    a.long_limit = g_long_row > a.small_limit ? g_long_row : a.small_limit;
+    const int tuned_small = g_tuning.small_limit.load(), tuned_long = g_tuning.long_row.load();
+    a.small_limit = tuned_small >= 0 ? tuned_small : 2 * (kWave / G);
+    a.long_limit = tuned_long > a.small_limit ? tuned_long : a.small_limit;
     a.long_list = long_list;
     a.long_count = long_count;
     if (hubs) {
@@ -679,8 +679,8 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
         a.part_l = part_l;
     }
     return bf16 ? dispatch<true>(G, a, hubs, hubs ? split->n_hubs : 0, hubs ? split->hub_ids : nullptr,
-                                 hubs ? split->hub_shadow_off : nullptr, st)
+                                 hubs ? split->hub_shadow_off : nullptr, allow_side, st)
                 : dispatch<false>(G, a, hubs, hubs ? split->n_hubs : 0, hubs ? split->hub_ids : nullptr,
-                                  hubs ? split->hub_shadow_off : nullptr, st);
+                                  hubs ? split->hub_shadow_off : nullptr, allow_side, st);
 }
 }  // namespace itb

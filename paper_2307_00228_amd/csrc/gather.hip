@@ -19,34 +19,51 @@
 // No floating-point atomics anywhere: every summation order is a function of the sizes only.
 #include "common.h"
 
-#include <mutex>
-
 namespace itb {
-int g_overlap_hubs = 1;
+namespace {
+constexpr int kMaxDevices = 64;
+SideStream g_side[kMaxDevices];
+bool g_side_made[kMaxDevices];
+std::mutex g_side_mu;
+}  // namespace
 SideStream *side_stream() {
-    constexpr int kMaxDevices = 64;
-    static SideStream table[kMaxDevices];
-    static bool made[kMaxDevices];
-    static std::mutex mu;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    std::lock_guard<std::mutex> lock(mu);
-    if (!made[dev]) {
-        SideStream &s = table[dev];
+    std::lock_guard<std::mutex> lock(g_side_mu);
+    if (!g_side_made[dev]) {
+        SideStream &s = g_side[dev];
         if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess)
+        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) {
+            (void)hipStreamDestroy(s.stream);
             return nullptr;
-        made[dev] = true;
+        }
+        if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) {
+            (void)hipEventDestroy(s.fork);
+            (void)hipStreamDestroy(s.stream);
+            return nullptr;
+        }
+        g_side_made[dev] = true;
     }
-    return &table[dev];
+    return &g_side[dev];
 }
-extern int g_csr_xcd_remap;
-extern int g_csr_deg_by_sort;
-int g_small_limit = -1;   // tuning hook (key 0): rows with in-degree <= limit use one lane group per row (-1 = auto)
-int g_long_row = 512;     // tuning hook (key 3): rows with more in-edges get a whole block
-int g_rows_waves_per_simd = -1;  // tuning hook (key 4): cap on resident wavefronts per SIMD of the row kernels
-                                 // (0 = no cap, -1 = built-in choice)
+// Destroys the helper stream and events of every device that has them (the next call that wants one makes it again).
+void destroy_side_streams() {
+    std::lock_guard<std::mutex> lock(g_side_mu);
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    for (int dev = 0; dev < kMaxDevices; ++dev) {
+        if (!g_side_made[dev]) continue;
+        if (hipSetDevice(dev) == hipSuccess) {
+            std::lock_guard<std::mutex> in_use(g_side[dev].mu);
+            (void)hipStreamSynchronize(g_side[dev].stream);
+            (void)hipEventDestroy(g_side[dev].fork);
+            (void)hipEventDestroy(g_side[dev].join);
+            (void)hipStreamDestroy(g_side[dev].stream);
+        }
+        g_side_made[dev] = false;
+    }
+    if (cur >= 0) (void)hipSetDevice(cur);
+}
 // Dynamic LDS that limits a 256-thread (4-wave) block to `waves` wavefronts per SIMD: a CU has 4 SIMDs and
 // 160 KB of LDS, so `waves` blocks fit when each asks for 160 KB / waves.
 size_t lds_for_occupancy(int waves, int lanes_per_row, bool beside_hub_passes) {
@@ -272,7 +289,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     const uint64_t small_mask = __ballot(mine && deg <= a.small_limit);
     uint64_t large_mask = __ballot(mine && deg > a.small_limit && deg <= a.long_limit);
     const uint64_t long_mask = __ballot(mine && deg > a.long_limit);
-    if (long_mask) {  // hand the long rows to the block-per-row kernel
+    // hand the long rows to the block-per-row kernel; one entry per row: of the blocks that share these rows
+    // (blockIdx.y walks the row's width) only the first appends, every column block of the long-rows kernel
+    // reads the same list
+    if (long_mask && blockIdx.y == 0) {
         uint32_t base = 0;
         if (lane == 0) base = atomicAdd(a.long_count, (uint32_t)__popcll(long_mask));
         base = __shfl(base, 0, kWave);
@@ -487,7 +507,7 @@ int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
     if (a.n_nodes > 0) {
         zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
         ITB_LAUNCH_CHECK();
-        gather_rows_kernel<BF16_IN, BF16_OUT, G, EXT><<<grid, 256, lds_for_occupancy(g_rows_waves_per_simd, G, a.n_shadows > 0), st>>>(a);
+        gather_rows_kernel<BF16_IN, BF16_OUT, G, EXT><<<grid, 256, lds_for_occupancy(g_tuning.rows_waves_per_simd.load(), G, a.n_shadows > 0), st>>>(a);
         ITB_LAUNCH_CHECK();
         // the list length is only known on the device: a fixed grid walks it (blocks beyond the length exit)
         int64_t lg = (a.n_nodes + 63) / 64;
@@ -537,13 +557,17 @@ int32_t dispatch_segments(int G, const GatherArgs &a, hipStream_t st) {
 namespace itb {
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
-                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, hipStream_t st);
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, bool allow_side,
+                        hipStream_t st);
 }
 
-extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
-                                const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
-                                void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
-                                void *stream) {
+namespace {
+// `allow_side`: the hub passes may run on the library's helper stream (false: everything on the caller's stream, no
+// library-owned object is created or touched).
+int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                          const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
+                          void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
+                          bool allow_side, void *stream) {
     if (!desc || !workspace_bytes) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_MIN) return ITB_ERR_DTYPE;
@@ -556,7 +580,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     if (split && (split->threshold <= 0 || split->n_hubs < 0 || split->n_shadows < 0)) return ITB_ERR_SIZE;
     if (desc->agg == ITB_AGG_GAT)
         return gat_gather_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
-                               workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+                               workspace, workspace_bytes, allow_side, static_cast<hipStream_t>(stream));
 
     if (desc->bias || desc->act != ITB_ACT_NONE) return ITB_ERR_UNSUPPORTED;  // epilogue exists for the GAT reduce only
     const bool hubs = split && split->n_hubs > 0;
@@ -602,8 +626,9 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     const int ng = kWave / G;
     // one lane group per row up to 32 in-edges (measured on 256-byte rows: 4 % faster than handing rows of 9-32
     // edges to the whole wavefront, whose last load batch is mostly masked), never below two batches of groups
-    a.small_limit = g_small_limit >= 0 ? g_small_limit : (2 * ng > 32 ? 2 * ng : 32);
-    a.long_limit = g_long_row > a.small_limit ? g_long_row : a.small_limit;
+    const int tuned_small = g_tuning.small_limit.load(), tuned_long = g_tuning.long_row.load();
+    a.small_limit = tuned_small >= 0 ? tuned_small : (2 * ng > 32 ? 2 * ng : 32);
+    a.long_limit = tuned_long > a.small_limit ? tuned_long : a.small_limit;
     a.long_list = long_list;
     a.long_count = long_count;
     a.n_shadows = hubs ? split->n_shadows : 0;  // > 0: hub passes run beside the row passes
@@ -612,15 +637,11 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
     int32_t rc;
     // The hub passes touch other rows and other workspace than the row passes: they go first and, when the helper
     // stream exists, run beside the row passes, whose many small blocks fill the gaps the large segment blocks leave.
-    SideStream *side = (hubs && g_overlap_hubs) ? side_stream() : nullptr;
-    std::unique_lock<std::mutex> side_lock;
-    if (side) side_lock = std::unique_lock<std::mutex>(side->mu);
+    SideFork fork;
+    rc = fork.begin((hubs && allow_side && g_tuning.overlap_hubs.load()) ? side_stream() : nullptr, st);
+    if (rc != ITB_OK) return rc;
     if (hubs) {
-        hipStream_t hst = side ? side->stream : st;
-        if (side) {
-            ITB_HIP(hipEventRecord(side->fork, st));
-            ITB_HIP(hipStreamWaitEvent(hst, side->fork, 0));
-        }
+        hipStream_t hst = fork.stream();
         GatherArgs s = a;
         s.out = part;
         s.n_shadows = split->n_shadows;
@@ -635,7 +656,8 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         combine<<<(unsigned)split->n_hubs, 1024, 0, hst>>>(part, desc->dim, split->n_hubs, split->hub_ids, split->hub_shadow_off,
                                                            rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out);
         ITB_LAUNCH_CHECK();
-        if (side) ITB_HIP(hipEventRecord(side->join, hst));
+        rc = fork.mark_done();
+        if (rc != ITB_OK) return rc;
     }
     if (ext) {
         if (!bin) rc = dispatch_rows<false, false, true>(G, a, st);
@@ -647,16 +669,20 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
         else rc = dispatch_rows<true, false, false>(G, a, st);
     }
     if (rc != ITB_OK) return rc;
-    if (side) ITB_HIP(hipStreamWaitEvent(st, side->join, 0));
-    return ITB_OK;
+    return fork.finish();
 }
 
-extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
-    if (key == 0) { itb::g_small_limit = value; return ITB_OK; }
-    if (key == 2) { itb::g_csr_xcd_remap = value; return ITB_OK; }
-    if (key == 3 && value > 0) { itb::g_long_row = value; return ITB_OK; }
-    if (key == 4) { itb::g_rows_waves_per_simd = value; return ITB_OK; }
-    if (key == 5) { itb::g_csr_deg_by_sort = value; return ITB_OK; }
-    if (key == 6) { itb::g_overlap_hubs = value; return ITB_OK; }
-    return ITB_ERR_UNSUPPORTED;
+}  // namespace
+
+extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                                const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
+                                void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
+                                void *stream) {
+    return gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, workspace,
+                             workspace_bytes, true, stream);
+}
+
+extern "C" int32_t itb_shutdown(void) {
+    itb::destroy_side_streams();
+    return ITB_OK;
 }

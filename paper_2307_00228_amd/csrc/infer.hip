@@ -3,24 +3,26 @@
 // Only enqueues work on the caller's stream.
 #include "common.h"
 
-#include <vector>
-
 namespace itb {
 bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t heads);
-// Measurement aid: events the layer loop records on its stream, four per layer (layer begin, before the gather, after
-// the gather, layer end), so that a caller can time the stages of the single call without issuing them one by one.
-std::vector<hipEvent_t> g_layer_events;
 }
 
 namespace {
 using namespace itb;
 
-int32_t mark(int layer, int which, void *stream) {
-    const size_t k = (size_t)layer * 4 + which;
-    if (k < itb::g_layer_events.size() && itb::g_layer_events[k])
-        if (hipEventRecord(itb::g_layer_events[k], static_cast<hipStream_t>(stream)) != hipSuccess) return ITB_ERR_DEVICE;
-    return ITB_OK;
-}
+// Stage events of the caller (four per layer: layer begin, before the gather, after the gather, layer end), recorded
+// on the launch stream so that the stages of the single call can be timed without issuing them one by one.
+struct Marks {
+    const itb_stage_events *ev;
+    void *stream;
+    int32_t operator()(int layer, int which) const {
+        if (!ev || !ev->events) return ITB_OK;
+        const int64_t k = (int64_t)layer * 4 + which;
+        if (k >= ev->n_events || !ev->events[k]) return ITB_OK;
+        return hipEventRecord(static_cast<hipEvent_t>(ev->events[k]), static_cast<hipStream_t>(stream)) == hipSuccess ? ITB_OK
+                                                                                                                      : ITB_ERR_DEVICE;
+    }
+};
 
 __global__ void gcn_scales_kernel(int64_t n, const int64_t *rowptr, const int32_t *deg_out, float *src_scale, float *dst_scale) {
     for (int64_t v = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; v < n; v += (int64_t)gridDim.x * blockDim.x) {
@@ -42,11 +44,6 @@ __global__ void edge_coef_kernel(int64_t n_edges, const int32_t *col, const floa
     }
     for (int64_t e = 4 * n4 + blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n_edges; e += (int64_t)gridDim.x * blockDim.x)
         coef[e] = src_scale[col[e]];
-}
-
-// Plain 16-byte-per-lane copy: the known-size reference against which hardware byte counters are scaled.
-__global__ void copy_kernel(const uint4 *src, uint4 *dst, int64_t n_vec) {
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x) dst[i] = src[i];
 }
 
 // out[v][:] = x[v][:] * scale[v]; one 16-byte vector per thread.
@@ -95,21 +92,6 @@ extern "C" int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const
     return ITB_OK;
 }
 
-extern "C" int32_t itb_copy_bytes(const void *src, void *dst, int64_t n_bytes, void *stream) {
-    if (n_bytes < 0 || (n_bytes & 15)) return ITB_ERR_SIZE;
-    if (n_bytes > 0 && (!src || !dst)) return ITB_ERR_NULL;
-    if (n_bytes == 0) return ITB_OK;
-    copy_kernel<<<8192, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n_bytes / 16);
-    ITB_LAUNCH_CHECK();
-    return ITB_OK;
-}
-
-extern "C" int32_t itb_set_layer_events(void **events, int32_t n_events) {
-    if (n_events < 0 || (n_events > 0 && !events)) return ITB_ERR_SIZE;
-    itb::g_layer_events.assign(reinterpret_cast<hipEvent_t *>(events), reinterpret_cast<hipEvent_t *>(events) + n_events);
-    return ITB_OK;
-}
-
 extern "C" int32_t gcn_edge_coefficients(int64_t n_edges, const int32_t *col, const float *src_scale, float *coef, void *stream) {
     if (n_edges < 0 || n_edges >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (n_edges > 0 && (!col || !src_scale || !coef)) return ITB_ERR_NULL;
@@ -149,7 +131,7 @@ static bool project_before_gather(const itb_layer &L, int32_t dtype) {
 extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
                                     const int32_t *deg_out, const itb_split *split, int32_t dtype, int32_t n_layers,
                                     const itb_layer *layers, const void *x, void *out, int64_t edge_chunk, void *workspace,
-                                    size_t *workspace_bytes, void *stream) {
+                                    size_t *workspace_bytes, const itb_stage_events *events, void *stream) {
     if (!workspace_bytes || !layers) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || n_edges < 0 || n_edges >= ((int64_t)1 << 31) || n_layers <= 0 ||
         edge_chunk < 0)
@@ -218,20 +200,22 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         rc = gcn_edge_coefficients(n_edges, col, src_scale, edge_coef, stream);
         if (rc != ITB_OK) return rc;
     }
+    if (events && events->n_events < 0) return ITB_ERR_SIZE;
+    const Marks mark{events, stream};
     char *state[2] = {state0, state1};
     const void *cur = x;
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
-        if (mark(l, 0, stream) != ITB_OK) return ITB_ERR_DEVICE;
+        if (mark(l, 0) != ITB_OK) return ITB_ERR_DEVICE;
         if (L.agg == ITB_AGG_NONE) {
-            if (mark(l, 1, stream) != ITB_OK || mark(l, 2, stream) != ITB_OK) return ITB_ERR_DEVICE;
+            if (mark(l, 1) != ITB_OK || mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;
             // encoder / prediction head (Sec. IV-C): the update alone, on the vertex's own state
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
             int32_t rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
                                      nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
-            if (mark(l, 3, stream) != ITB_OK) return ITB_ERR_DEVICE;
+            if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;
             cur = dst;
             continue;
         }
@@ -263,7 +247,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             gather_src = projbuf;
             gd.dim = L.d_out;
         }
-        if (mark(l, 1, stream) != ITB_OK) return ITB_ERR_DEVICE;
+        if (mark(l, 1) != ITB_OK) return ITB_ERR_DEVICE;
         const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
         for (int64_t c = 0; c < n_chunks; ++c) {
             const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
@@ -272,7 +256,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws, stream);
             if (rc != ITB_OK) return rc;
         }
-        if (mark(l, 2, stream) != ITB_OK) return ITB_ERR_DEVICE;
+        if (mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;
         if (!gat) {
             int32_t rc;
             if (pf) {  // the gathered projection enters the update as an addend to the self product
@@ -286,7 +270,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             }
             if (rc != ITB_OK) return rc;
         }
-        if (mark(l, 3, stream) != ITB_OK) return ITB_ERR_DEVICE;
+        if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;
         cur = dst;
     }
     return ITB_OK;

@@ -12,16 +12,35 @@ Tab. I are not reproduced.
 
 All randomness: numpy ``Generator(PCG64(SeedSequence([seed, tag])))`` with one
 sub-stream per purpose (topology, features, weights), so a workload is a pure
-function of (name, scale, seed).
+function of (name, scale, seed).  Large arrays are drawn in fixed-size chunks,
+each from its own child stream (``Generator.spawn``), by a small thread pool:
+the result does not depend on the number of threads, and the 2e9-edge workload
+is generated in about a minute instead of several.
 
 bf16 tensors are carried as ``uint16`` bit patterns (numpy has no bf16).
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import List, Optional
 
 import numpy as np
+
+_POOL = None
+
+
+def _pool() -> ThreadPoolExecutor:
+    """Worker threads for the chunked draws (numpy releases the GIL in its fill, sort and gather loops)."""
+    global _POOL
+    if _POOL is None:
+        _POOL = ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1)))
+    return _POOL
+
+
+def _chunks(n: int, step: int):
+    return [(i, min(i + step, n)) for i in range(0, n, step)]
 
 F32 = "f32"
 BF16 = "bf16"
@@ -115,7 +134,14 @@ def power_law_degree_sequence(rng, n_nodes: int, total: int, exponent: float, d_
     d = np.arange(1, d_max + 1, dtype=np.float64)
     cdf = np.cumsum(d ** (-exponent))
     cdf /= cdf[-1]
-    deg = 1 + np.searchsorted(cdf, rng.random(n_nodes), side="right").astype(np.int64)
+    u = rng.random(n_nodes)
+    deg = np.empty(n_nodes, dtype=np.int64)
+
+    def look_up(span):
+        deg[span[0]:span[1]] = 1 + np.searchsorted(cdf, u[span[0]:span[1]], side="right")
+
+    list(_pool().map(look_up, _chunks(n_nodes, 1 << 22)))
+    del u
     deg = np.minimum(deg, d_max)
     s = int(deg.sum())
     if s > 0 and s != total:
@@ -137,7 +163,22 @@ def power_law_degree_sequence(rng, n_nodes: int, total: int, exponent: float, d_
 def destinations_from_degrees(rng, deg_by_slot: np.ndarray, n_nodes: int) -> np.ndarray:
     """Expand a degree sequence into a dst list; slot -> node id by a random permutation."""
     ids = rng.permutation(n_nodes).astype(np.int32)[: len(deg_by_slot)]
-    return np.repeat(ids, deg_by_slot)
+    total = int(deg_by_slot.sum())
+    if total <= (1 << 27):
+        return np.repeat(ids, deg_by_slot)
+    # slot ranges of roughly equal output size, expanded side by side
+    ends = np.cumsum(deg_by_slot)
+    cuts = np.searchsorted(ends, np.linspace(0, total, 65)[1:-1], side="left")
+    bounds = np.unique(np.concatenate([[0], cuts, [len(deg_by_slot)]]))
+    out = np.empty(total, dtype=np.int32)
+
+    def expand(k):
+        a, b = int(bounds[k]), int(bounds[k + 1])
+        o0 = int(ends[a - 1]) if a > 0 else 0
+        out[o0:int(ends[b - 1])] = np.repeat(ids[a:b], deg_by_slot[a:b])
+
+    list(_pool().map(expand, range(len(bounds) - 1)))
+    return out
 
 
 def shuffle_edges(rng, src: np.ndarray, dst: np.ndarray, log=None):
@@ -150,15 +191,21 @@ def shuffle_edges(rng, src: np.ndarray, dst: np.ndarray, log=None):
         return np.ascontiguousarray(src[p]), np.ascontiguousarray(dst[p])
     parts = 64
     out_s, out_d = np.empty_like(src), np.empty_like(dst)
-    pos = 0
-    for k in range(parts):
+    sizes = [len(range(k, e, parts)) for k in range(parts)]
+    starts = np.concatenate([[0], np.cumsum(sizes)])
+    streams = rng.spawn(parts)
+    done = []
+
+    def one(k):
         s_k, d_k = src[k::parts], dst[k::parts]
-        p = rng.permutation(len(s_k))
-        out_s[pos:pos + len(s_k)] = s_k[p]
-        out_d[pos:pos + len(d_k)] = d_k[p]
-        pos += len(s_k)
-        if log and k % 8 == 7:
-            log(f"  shuffle: part {k + 1}/{parts}")
+        p = streams[k].permutation(len(s_k))
+        out_s[starts[k]:starts[k + 1]] = s_k[p]
+        out_d[starts[k]:starts[k + 1]] = d_k[p]
+        done.append(k)
+        if log and len(done) % 16 == 0:
+            log(f"  shuffle: {len(done)}/{parts} parts")
+
+    list(_pool().map(one, range(parts)))
     return out_s, out_d
 
 
@@ -168,11 +215,18 @@ def shuffle_edges(rng, src: np.ndarray, dst: np.ndarray, log=None):
 def normal_features(rng, n: int, d: int, dtype: str, log=None) -> np.ndarray:
     """N(0,1) features in the storage dtype, drawn and rounded chunk by chunk (bounded temporary memory)."""
     out = np.empty((n, d), dtype=np.uint16 if dtype == BF16 else np.float32)
-    step = max(1, (1 << 24) // max(d, 1))
-    for k, i in enumerate(range(0, n, step)):
-        out[i:i + step] = store(rng.standard_normal((min(step, n - i), d), dtype=np.float32), dtype)
-        if log and k % 64 == 63:
-            log(f"  features: {min(i + step, n)}/{n} rows")
+    spans = _chunks(n, max(1, (1 << 22) // max(d, 1)))
+    streams = rng.spawn(len(spans))
+    done = []
+
+    def fill(k):
+        a, b = spans[k]
+        out[a:b] = store(streams[k].standard_normal((b - a, d), dtype=np.float32), dtype)
+        done.append(k)
+        if log and len(done) % 256 == 0:
+            log(f"  features: {len(done)}/{len(spans)} chunks")
+
+    list(_pool().map(fill, range(len(spans))))
     return out
 
 
@@ -223,7 +277,7 @@ def gat_layers(rng, dims, heads: int, dtype: str, bias_random: bool = False) -> 
 NO_SPLIT = 1 << 62
 
 NAMES = ("tiny_powerlaw", "medium_uniform", "hub_heavy", "hub_heavy_uniform_control",
-         "attention", "huge_share")
+         "attention", "huge_share", "huge_share_slice")
 
 
 def make(name: str, scale: float = 1.0, seed: int = 0, bias_random: bool = False,
@@ -274,24 +328,36 @@ def make(name: str, scale: float = 1.0, seed: int = 0, bias_random: bool = False
         dtype, dims, agg = BF16, (256, 256, 256, 256), AGG_GAT
         thr = max(4, sz(8192)) if scale < 1.0 else 8192
         recipe = "rank-Zipf(1.5) in-degree, 3-layer GAT 4x64 bf16, T=8192"
-    elif name == "huge_share":
-        n, e = sz(100_000_000, 64), sz(2_000_000_000, 1024)
-        d_max = max(2, sz(10_000_000))
-        say(f"huge_share: degree sequence for {n} vertices")
+    elif name in ("huge_share", "huge_share_slice"):
+        if name == "huge_share":
+            n, e = sz(100_000_000, 64), sz(2_000_000_000, 1024)
+            d_max = max(2, sz(10_000_000))
+        else:
+            # the shape of huge_share that matters to the address arithmetic -- a state buffer beyond 4 GiB, tens of
+            # millions of rows, a hub far above the threshold -- with an edge count that a test can afford
+            n, e = sz(50_000_000, 64), sz(250_000_000, 1024)
+            d_max = max(2, sz(1_000_000))
+        say(f"{name}: degree sequence for {n} vertices")
         deg = power_law_degree_sequence(topo, n, e - d_max, 2.0, d_max)
         deg[0] += d_max
-        say(f"huge_share: expanding {e} destinations")
+        say(f"{name}: expanding {e} destinations")
         dst = destinations_from_degrees(topo, deg, n)
         del deg
-        say("huge_share: drawing sources")
+        say(f"{name}: drawing sources")
         src = np.empty(e, dtype=np.int32)
-        for i in range(0, e, 1 << 27):
-            src[i:i + (1 << 27)] = topo.integers(0, n, size=min(1 << 27, e - i), dtype=np.int32)
-        say("huge_share: shuffling the edge list")
+        spans = _chunks(e, 1 << 25)
+        streams = topo.spawn(len(spans))
+
+        def draw(k):
+            src[spans[k][0]:spans[k][1]] = streams[k].integers(0, n, size=spans[k][1] - spans[k][0], dtype=np.int32)
+
+        list(_pool().map(draw, range(len(spans))))
+        say(f"{name}: shuffling the edge list")
         src, dst = shuffle_edges(topo, src, dst, log)
         dtype, dims, agg = BF16, (64, 64, 32), AGG_MEAN
         thr = max(4, sz(16384)) if scale < 1.0 else 16384
-        recipe = "power-law(2.0) in-degree with one ~1e7 hub, SAGE-mean 64-64-32 bf16, T=16384"
+        recipe = (f"power-law(2.0) in-degree with one ~{d_max:.0e} hub, SAGE-mean 64-64-32 bf16, T=16384"
+                  + (" (half the vertices and an eighth of the edges of huge_share)" if name == "huge_share_slice" else ""))
     else:
         raise ValueError(f"unknown workload {name!r}")
 

@@ -20,15 +20,21 @@ def B():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "inferturbo.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"\bint32_t\s+(\w+)\s*\(", text)
+    names = []
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\bint32_t\s+(\w+)\s*\(", text)
+    return names
 
 
 def test_header_declares_the_five_entry_points():
     names = declared_functions()
     for f in ("build_csr_by_dst", "split_hubs", "gather_layer", "apply_layer", "infer_full_graph"):
         assert f in names
+    # the measurement aids live in a header of their own
+    main = open(os.path.join(ROOT, "include", "inferturbo.h")).read()
+    assert "itb_set_tuning" not in main and "itb_copy_bytes" not in main
 
 
 def test_library_exports_every_declared_symbol(B):
@@ -84,14 +90,22 @@ def test_argument_errors_are_reported_on_the_host(B):
     a9 = B.itb_apply_desc(B.ITB_F32, 64, 16, 5, 0)
     assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
     # infer_full_graph
-    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, C.byref(need), None) == -1
+    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, C.byref(need), None, None) == -1
     lay = (B.itb_layer * 2)()
     lay[0] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_RELU, 1, 0.2, None, None, None, None, None)
     lay[1] = B.itb_layer(B.AGG_MEAN, 48, 16, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
-    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None) == -2
+    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None, None) == -2
     lay[1] = B.itb_layer(B.AGG_MEAN, 32, 16, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
-    assert lib.infer_full_graph(1000, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None) == 0
+    assert lib.infer_full_graph(1000, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None, None) == 0
     assert need.value >= 2 * 1000 * 64 * 4
+    # stage events: a negative count is refused before any launch; the handles are per call (no process-wide setter)
+    assert C.sizeof(B.itb_stage_events) == 16
+    assert not hasattr(lib, "itb_set_layer_events")
+    # the aids
+    assert lib.itb_random_row_read(None, 10, 48, None, 0, None, 0, None) == -5
+    assert lib.itb_random_row_read(None, 0, 64, None, 0, None, 0, None) == -2
+    assert lib.itb_set_tuning(99, 0) == -5
+    assert lib.itb_shutdown() == 0          # nothing to destroy: no call has made the helper stream
 
 
 def test_hub_threshold_heuristic_matches_golden_and_oracle(B):
@@ -165,8 +179,8 @@ def test_workspace_errors_are_reported_before_anything_is_touched(B):
     assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, odd, C.byref(big), None) == -6
     lay = (B.itb_layer * 1)()
     lay[0] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
-    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, fake, C.byref(small), None) == -6
-    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, odd, C.byref(big), None) == -6
+    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, fake, C.byref(small), None, None) == -6
+    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, odd, C.byref(big), None, None) == -6
     # with enough (fake) workspace the next check is the missing inputs
     assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, fake, C.byref(big), None) == -1
 
@@ -186,7 +200,7 @@ def test_gat_and_layer_descriptor_validation(B):
     def infer(layer):
         lay = (B.itb_layer * 1)()
         lay[0] = layer
-        return lib.infer_full_graph(100, 500, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, C.byref(need), None)
+        return lib.infer_full_graph(100, 500, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, C.byref(need), None, None)
     assert infer(B.itb_layer(B.AGG_MAX, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == 0
     assert infer(B.itb_layer(B.AGG_NONE, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == 0
     assert infer(B.itb_layer(B.AGG_NONE, 64, 32, B.ACT_NONE, 1, 0.2, C.c_void_p(256), None, None, None, None)) == -5   # no self matrix there

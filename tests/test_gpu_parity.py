@@ -1,9 +1,12 @@
 """Parity of the HIP path against the CPU oracle, through the C ABI (needs an MI355X).
 
 Integer results (CSR, hub split) must be bit-exact.  Features: fp32 within max-abs 1e-4
-(for the un-normalised SUM aggregator, whose outputs grow with the in-degree, 1e-4 times
-max(1, largest |oracle value|): fp32 cannot hold 1e-4 absolute on values in the hundreds);
-bf16 storage with fp32 accumulation within |g-o| <= 2e-2 * (|o| + rms(o))."""
+(for the un-normalised SUM aggregator, whose outputs grow with the in-degree, element by
+element 1e-4 * max(1, |oracle value|): fp32 cannot hold 1e-4 absolute on a value in the
+hundreds); bf16 storage with fp32 accumulation within |g-o| <= 2e-2 * (|o| + rms(o)).
+Whole layers are held to Eq. (1) without intermediate rounding; where the path under test
+stores agg(h) in bf16 between gather and update, the bound is widened by what that one
+rounding can move the result at most (agg_rounding_slack)."""
 import numpy as np
 import pytest
 
@@ -29,7 +32,7 @@ def dev_i32(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
 
 
-def check_features(got_st, want64, dtype, what="", magnitude_scaled=False):
+def check_features(got_st, want64, dtype, what="", magnitude_scaled=False, slack=0.0):
     got = W.as_f32(got_st).astype(np.float64)
     want64 = np.asarray(want64, dtype=np.float64)
     assert got.shape == want64.shape, (got.shape, want64.shape)
@@ -37,12 +40,28 @@ def check_features(got_st, want64, dtype, what="", magnitude_scaled=False):
         return
     err = np.abs(got - want64)
     if dtype == W.F32:
-        atol = FP32_ATOL * (max(1.0, np.abs(want64).max()) if magnitude_scaled else 1.0)
-        assert err.max() <= atol, f"{what}: fp32 max abs err {err.max():.3e} (tol {atol:.1e})"
+        atol = FP32_ATOL * (np.maximum(1.0, np.abs(want64)) if magnitude_scaled else np.ones_like(want64))
+        bad = err > atol
+        assert not bad.any(), f"{what}: fp32 abs err {err[bad].max():.3e} at {np.argwhere(bad)[0]} (tol {atol[bad].min():.1e})"
     else:
-        tol = BF16_RTOL * (np.abs(want64) + np.sqrt(np.mean(want64 ** 2)))
+        tol = BF16_RTOL * (np.abs(want64) + np.sqrt(np.mean(want64 ** 2))) + slack
         bad = err > tol
         assert not bad.any(), f"{what}: bf16 err {err[bad].max():.3e} at {np.argwhere(bad)[0]} (tol {tol[bad].min():.3e})"
+
+
+def agg_rounding_slack(a64, w_nbr, dtype):
+    """What storing agg(h) in bf16 between gather and update can move the update by: round-to-nearest-even changes
+    an element by at most 2^-9 relative, so output j moves by at most 2^-9 * sum_k |agg_k| |W_kj|."""
+    if dtype == W.F32 or a64 is None:
+        return 0.0
+    return 2.0 ** -9 * (np.abs(a64) @ np.abs(W.as_f32(w_nbr).astype(np.float64)))
+
+
+def check_layer(B, tr, r, c, d, h, lay, dtype, what):
+    """One dense layer's stored output against Eq. (1) evaluated from the stored input `h`."""
+    _, y64, a64 = oracle.dense_layer(r, c, d, h, lay, dtype, return_agg64=True)
+    exact_agg = tr.projected or lay.agg in (W.AGG_MAX, W.AGG_MIN, W.AGG_NONE)     # nothing rounded between the steps
+    check_features(B.to_numpy(tr.out), y64, dtype, what, slack=0.0 if exact_agg else agg_rounding_slack(a64, lay.w_nbr, dtype))
 
 
 # ------------------------------------------------------------------------------------------ CSR build
@@ -432,8 +451,7 @@ def test_infer_with_encoder_extremum_layers_and_head(B, dtype):
         # two of them through an extremum that picks the worst case, do not average out end to end)
         h = x
         for i, (lay, tr) in enumerate(zip(layers, steps)):
-            y64 = oracle.dense_layer(r, c, d, h, lay, dtype)[1]
-            check_features(B.to_numpy(tr.out), y64, dtype, f"T={T} layer {i}")
+            check_layer(B, tr, r, c, d, h, lay, dtype, f"T={T} layer {i}")
             if lay.agg in (W.AGG_MAX, W.AGG_MIN):
                 assert_same_values(B.to_numpy(tr.agg), oracle.gather(lay.agg, r, c, h), f"T={T} layer {i} aggregate")
             h = B.to_numpy(tr.out)
@@ -526,10 +544,7 @@ def test_gcn_stack(B, dtype, dims):
         assert torch.equal(out.view(view), steps[-1].out.view(view))
         h = x
         for i, (lay, tr) in enumerate(zip(layers, steps)):
-            # a projected layer never stores agg(h): it is held to Eq. (1) without the intermediate rounding (on the hub,
-            # whose aggregate is ~20, rounding agg(h) to bf16 alone moves the oracle by more than the tolerance)
-            y64 = oracle.dense_layer(r, c, d, h, lay, dtype, round_agg=not tr.projected)[1]
-            check_features(B.to_numpy(tr.out), y64, dtype, f"T={T} layer {i}")
+            check_layer(B, tr, r, c, d, h, lay, dtype, f"T={T} layer {i}")
             h = B.to_numpy(tr.out)
 
 
@@ -734,17 +749,17 @@ def test_random_layer_stacks(B, seed):
     assert torch.equal(out.view(view), steps[-1].out.view(view))
     h = x
     for i, (lay, tr) in enumerate(zip(layers, steps)):
+        what = f"layer {i} kinds={kinds} widths={widths} T={T}"
         if lay.agg == W.AGG_GAT:
-            y64 = oracle.gat_layer(r, c, h, lay, dtype)[3]
+            check_features(B.to_numpy(tr.out), oracle.gat_layer(r, c, h, lay, dtype)[3], dtype, what)
         else:
-            y64 = oracle.dense_layer(r, c, d, h, lay, dtype, round_agg=not tr.projected)[1]
-        check_features(B.to_numpy(tr.out), y64, dtype, f"layer {i} kinds={kinds} widths={widths} T={T}")
+            check_layer(B, tr, r, c, d, h, lay, dtype, what)
         h = B.to_numpy(tr.out)
 
 
 def test_layer_events_bracket_the_stages(B):
-    """itb_set_layer_events: four events per layer recorded by infer_full_graph on its stream, in order; the result is
-    unchanged and switching the recording off leaves the events alone."""
+    """Stage events: four events per layer recorded by infer_full_graph on its stream, in order; the result is
+    unchanged and a call without them leaves the events alone (the library keeps no handle after the call)."""
     import torch
     w = W.make("medium_uniform", 0.02)
     rowptr, col, deg_out = B.build_csr_by_dst(w.n_nodes, dev_i32(w.src), dev_i32(w.dst))
@@ -754,11 +769,7 @@ def test_layer_events_bracket_the_stages(B):
     for e in evs:
         e.record()
     torch.cuda.synchronize()
-    B.set_layer_events(evs)
-    try:
-        out = B.infer_full_graph(rowptr, col, deg_out, None, layers, x)
-    finally:
-        B.set_layer_events([])
+    out = B.infer_full_graph(rowptr, col, deg_out, None, layers, x, events=evs)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
     times = [evs[k].elapsed_time(evs[k + 1]) for k in range(len(evs) - 1)]
@@ -865,6 +876,37 @@ def test_very_wide_rows_with_hubs(B):
     out = B.gather_layer(W.AGG_GAT, rp, cl, B.to_device(x), B.split_hubs(rp, 16), torch.from_numpy(s_src).cuda(),
                          torch.from_numpy(s_dst).cuda(), heads=heads, leaky_slope=0.2)
     check_features(B.to_numpy(out), oracle.gat_gather(r, c, x, s_src, s_dst, heads, 0.2), W.F32)
+
+
+@pytest.mark.parametrize("kind", [W.AGG_MEAN, W.AGG_MAX, W.AGG_GAT])
+def test_many_long_rows_wider_than_a_wavefront(B, kind):
+    """Rows wider than 64 lanes are covered by several column blocks per row; most rows here lie above the (lowered)
+    long-row limit and there is no split: every long row must enter the work list once, whatever the number of column
+    blocks (the list holds one entry per vertex)."""
+    import torch
+    n, e, dim = 1000, 60000, 1040                        # 130 16-byte vectors of bf16: three column blocks
+    src, dst, x = W.random_small_graph(91, n, e, dim, W.BF16, 0.0)
+    r, c, _ = oracle.build_csr(n, src, dst)
+    assert (np.diff(r) > 33).sum() > 0.9 * n
+    B.set_tuning(3, 33)
+    try:
+        if kind == W.AGG_GAT:
+            rng = np.random.default_rng(92)
+            s_src = rng.standard_normal((n, 2)).astype(np.float32)
+            s_dst = rng.standard_normal((n, 2)).astype(np.float32)
+            out = B.gather_layer(kind, torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda(), B.to_device(x), None,
+                                 torch.from_numpy(s_src).cuda(), torch.from_numpy(s_dst).cuda(), heads=2)
+            torch.cuda.synchronize()
+            check_features(B.to_numpy(out), oracle.gat_gather(r, c, x, s_src, s_dst, 2, 0.2), W.BF16)
+        else:
+            got, want, _ = run_gather(B, kind, n, src, dst, x, W.BF16)
+            torch.cuda.synchronize()
+            if kind == W.AGG_MAX:
+                assert_same_values(got, want)
+            else:
+                check_features(got, want, W.BF16)
+    finally:
+        B.set_tuning(3, 512)
 
 
 def test_readme_example_runs(B):
