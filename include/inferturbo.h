@@ -21,8 +21,10 @@
  *  - What the library itself owns, per device, from the first call that needs
  *    it until itb_shutdown() or the end of the process: one helper stream
  *    (default priority, non-blocking) with two events, on which gather_layer
- *    runs the hub passes and build_csr_by_dst the out-degree branch; and
- *    the launch attributes of its kernels.  Nothing else outlives a call.
+ *    runs the hub passes and build_csr_by_dst the out-degree branch; the
+ *    launch attributes of its kernels; and the fixed scratch array of
+ *    gather_layer_noalloc, which is part of the loaded code object.  Nothing
+ *    else outlives a call.
  *  - Workspace protocol: if `workspace` is NULL the call only writes the
  *    number of bytes it needs for these sizes to *workspace_bytes (host) and
  *    returns ITB_OK.  Otherwise *workspace_bytes is the size provided;
@@ -234,6 +236,26 @@ int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
                      const void *h_src, const float *src_scale, const float *dst_scale,
                      void *agg_out, int64_t edge_lo, int64_t edge_hi,
                      void *workspace, size_t *workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * gather_layer_noalloc -- gather_layer for callers that cannot allocate or
+ * size a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results (bitwise) as
+ * gather_layer without the workspace pair; the work list of long rows and the
+ * hub partials live in a fixed scratch array inside the library's code object,
+ * ITB_NOALLOC_SCRATCH_BYTES per GPU, held until the process ends.  The call
+ * allocates nothing, creates no stream or event and runs every pass on
+ * `stream`.  Sizes whose workspace (what gather_layer's size query reports)
+ * exceeds the array return ITB_ERR_WORKSPACE before anything is enqueued:
+ * roughly 4 * n_nodes + 4 * dim * n_shadows bytes must fit.  All calls on one
+ * GPU share the array: calls that overlap in time on one GPU (different
+ * streams, different host threads) race and must be serialised by the caller.
+ * ------------------------------------------------------------------------- */
+#define ITB_NOALLOC_SCRATCH_BYTES (16u << 20)
+int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes,
+                             const int64_t *rowptr, const int32_t *col, const itb_split *split,
+                             const void *h_src, const float *src_scale, const float *dst_scale,
+                             void *agg_out, int64_t edge_lo, int64_t edge_hi, void *stream);
 
 /* ---------------------------------------------------------------------------
  * apply_layer -- apply_node (Sec. IV-B), the update U of Eq. (1): combine the

@@ -74,6 +74,8 @@ def _load():
                                  i64, i64, vp, szp, vp]
     lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
+    lib.gather_layer_noalloc.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
+                                         i64, i64, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
                                      vp, vp, i64, vp, szp, C.POINTER(itb_stage_events), vp]
     lib.itb_shutdown.argtypes = []
@@ -83,7 +85,7 @@ def _load():
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients",
-              "itb_shutdown", "itb_random_row_read"):
+              "gather_layer_noalloc", "itb_shutdown", "itb_random_row_read"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -246,6 +248,22 @@ def gather_layer(agg: int, rowptr, col, h, split: Optional[Split] = None, src_sc
     size = C.c_size_t(ws.numel())
     _check("gather_layer", lib.gather_layer(C.byref(desc), n, _ptr(rowptr), _ptr(col), spp, _ptr(h), _ptr(src_scale),
                                             _ptr(dst_scale), _ptr(out), edge_lo, edge_hi, _ptr(ws), C.byref(size), _stream()))
+    return out
+
+
+def gather_layer_noalloc(agg: int, rowptr, col, h, out: torch.Tensor, split: Optional[Split] = None, src_scale=None,
+                         dst_scale=None, heads: int = 1, leaky_slope: float = 0.2, edge_lo: int = 0, edge_hi: int = INT64_MAX,
+                         act: int = ACT_NONE, bias: Optional[torch.Tensor] = None, edge_coef: Optional[torch.Tensor] = None):
+    """gather_layer on the library's built-in scratch: the caller passes inputs and the output, nothing is allocated."""
+    n, dim = h.shape
+    desc = itb_gather_desc(agg, dtype_code(h), dtype_code(out), dim, heads, leaky_slope, act,
+                           bias.data_ptr() if bias is not None else None,
+                           edge_coef.data_ptr() if edge_coef is not None else None)
+    sp = split.c_struct() if split is not None else None
+    spp = C.byref(sp) if sp is not None else None
+    _check("gather_layer_noalloc", lib.gather_layer_noalloc(C.byref(desc), n, _ptr(rowptr), _ptr(col), spp, _ptr(h),
+                                                            _ptr(src_scale), _ptr(dst_scale), _ptr(out), edge_lo, edge_hi,
+                                                            _stream()))
     return out
 
 

@@ -672,6 +672,26 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     return fork.finish();
 }
 
+// Scratch of gather_layer_noalloc: device memory that belongs to the library image, one copy per GPU, held until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels and memory
+// operations get the per-device address looked up below.
+constexpr size_t kStaticScratchBytes = (size_t)ITB_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+void *static_scratch_of_current_device() {
+    constexpr int kMaxDev = 64;
+    static void *table[kMaxDev];
+    static std::mutex mu;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!table[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        table[dev] = ptr;
+    }
+    return table[dev];
+}
 }  // namespace
 
 extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
@@ -680,6 +700,21 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
                                 void *stream) {
     return gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, workspace,
                              workspace_bytes, true, stream);
+}
+
+extern "C" int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                                        const itb_split *split, const void *h_src, const float *src_scale,
+                                        const float *dst_scale, void *agg_out, int64_t edge_lo, int64_t edge_hi, void *stream) {
+    size_t need = 0;
+    int32_t rc = gather_layer_impl(desc, n_nodes, nullptr, nullptr, split, nullptr, nullptr, nullptr, nullptr, edge_lo, edge_hi,
+                                   nullptr, &need, false, nullptr);
+    if (rc != ITB_OK) return rc;
+    if (need > kStaticScratchBytes) return ITB_ERR_WORKSPACE;  // sizes beyond the built-in scratch: use gather_layer
+    void *ptr = static_scratch_of_current_device();
+    if (!ptr) return ITB_ERR_DEVICE;
+    size_t have = kStaticScratchBytes;
+    return gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, ptr, &have,
+                             false, stream);
 }
 
 extern "C" int32_t itb_shutdown(void) {

@@ -101,6 +101,12 @@ def test_argument_errors_are_reported_on_the_host(B):
     # stage events: a negative count is refused before any launch; the handles are per call (no process-wide setter)
     assert C.sizeof(B.itb_stage_events) == 16
     assert not hasattr(lib, "itb_set_layer_events")
+    # gather_layer_noalloc: same argument checks, and sizes beyond the built-in scratch are refused on the host
+    assert lib.gather_layer_noalloc(None, 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None) == -1
+    assert lib.gather_layer_noalloc(C.byref(odd), 10, None, None, None, None, None, None, None, 0, B.INT64_MAX, None) == -5
+    assert lib.gather_layer_noalloc(C.byref(d), 1 << 23, None, None, None, None, None, None, None, 0, B.INT64_MAX, None) == -6
+    sp = B.itb_split(16, 2, 1 << 17, None, None, None, None, None)
+    assert lib.gather_layer_noalloc(C.byref(d), 10, None, None, C.byref(sp), None, None, None, None, 0, B.INT64_MAX, None) == -6
     # the aids
     assert lib.itb_random_row_read(None, 10, 48, None, 0, None, 0, None) == -5
     assert lib.itb_random_row_read(None, 0, 64, None, 0, None, 0, None) == -2
