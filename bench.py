@@ -84,7 +84,8 @@ def measure(name, scale, steps, warmup, threshold=None, edge_chunk=None, keep=Fa
             outer_events[k][2].record()
         sp = split if use_split else None
         if state["ws"] is None:
-            state["ws"] = torch.empty(max(256, B.infer_workspace_bytes(N, E, sp, tdt, layers)), dtype=torch.uint8, device="cuda")
+            state["ws"] = torch.empty(max(256, B.infer_workspace_bytes(N, E, sp, tdt, layers, edge_chunk)), dtype=torch.uint8,
+                                      device="cuda")
         B.infer_full_graph(rowptr, col, deg_out, sp, layers, x, out=out, workspace=state["ws"], edge_chunk=edge_chunk,
                            events=layer_events[k] if k is not None else None)
         return rowptr, col, deg_out, split
@@ -105,35 +106,36 @@ def measure(name, scale, steps, warmup, threshold=None, edge_chunk=None, keep=Fa
 
     csr_ms = avg([(o[0], o[1]) for o in outer_events])
     split_ms = avg([(o[1], o[2]) for o in outer_events])
-    g_ms, a_ms, p_ms = [], [], []
+    # stage events of a layer: begin, before the gather, after the gather, end.  The dense launches of a layer are what
+    # lies before the gather (GAT: projection with scores; narrowing layers: h . [W_nbr | W_self]) plus what lies after it
+    # (the update of the other layers).
+    g_ms, d_ms = [], []
     for i in range(L):
         b, g0, g1, e1 = ([le[4 * i + j] for le in layer_events] for j in range(4))
         g_ms.append(avg(zip(g0, g1)))
-        if is_gat[i]:               # projection first, the attention reduce ends the layer
-            a_ms.append(avg(zip(b, g0)))
-            p_ms.append(0.0)
-        else:                       # optional projection, gather, update
-            p_ms.append(avg(zip(b, g0)))
-            a_ms.append(avg(zip(g1, e1)))
+        d_ms.append(avg(zip(b, g0)) + avg(zip(g1, e1)))
 
     # Algorithmic traffic of one layer's gather: every in-edge reads its column index and its source row once, every
     # vertex reads its row pointer and writes its aggregate row once.  GAT: the row is the projected state of width
     # d_out, plus the 4-byte source score of each head per edge, and per vertex its own row and scores for the implicit
-    # self edge.  A narrowing layer gathers rows already multiplied by W_nbr (width d_out).  A GCN layer also reads the
-    # 4-byte source coefficient of each in-edge and the 4-byte destination scale of each vertex.
+    # self edge.  A narrowing layer gathers rows already multiplied by W_nbr (width d_out) and its row epilogue reads
+    # the self product (one more row per vertex).  A GCN layer also reads the 4-byte source coefficient of each in-edge
+    # and the 4-byte destination scale of each vertex.
     def gather_width(l, g, pf):
         return l.d_out if (g or pf) else l.d_in
 
     g_bytes = [E * (4 + 4 * l.heads + l.d_out * esz) + N * (8 + 2 * l.d_out * esz + 8 * l.heads) if g
                else E * (4 + (4 if l.agg == W.AGG_GCN else 0) + gather_width(l, g, pf) * esz)
-               + N * (8 + (4 if l.agg == W.AGG_GCN else 0) + gather_width(l, g, pf) * esz)
+               + N * (8 + (4 if l.agg == W.AGG_GCN else 0) + (2 if pf else 1) * gather_width(l, g, pf) * esz)
                for l, g, pf in zip(w.layers, is_gat, projected)]
     # what a gather must move at the very least: the source table once, the column indices, row pointers, the output
     g_compulsory = [N * gather_width(l, g, pf) * esz * 2 + E * 4 + N * 8 for l, g, pf in zip(w.layers, is_gat, projected)]
-    # the final update launch of the layer (GAT: the projection; projected layers: the self product + addend)
-    a_flops = [(2.0 if (g or pf) else 4.0) * l.d_in * l.d_out * N for l, g, pf in zip(w.layers, is_gat, projected)]
-    a_bytes = [N * esz * ((l.d_in + 2 * l.d_out) if pf else (l.d_in + l.d_out) if g else (2 * l.d_in + l.d_out))
-               for l, g, pf in zip(w.layers, is_gat, projected)]
+    # dense work of the layer: 2 * d_in * d_out flops per vertex and matrix (GAT: one matrix, the others two); bytes per
+    # vertex: GAT reads h, writes z and the scores; a narrowing layer reads h once and writes two products; the others
+    # read h and agg and write the new state
+    a_flops = [(2.0 if g else 4.0) * l.d_in * l.d_out * N for l, g in zip(w.layers, is_gat)]
+    a_bytes = [N * ((l.d_in + l.d_out) * esz + 8 * l.heads if g else (l.d_in + 2 * l.d_out) * esz if pf
+                    else (2 * l.d_in + l.d_out) * esz) for l, g, pf in zip(w.layers, is_gat, projected)]
     peak_tf = PEAK_TFLOPS[w.dtype]
     a_attainable = [min(peak_tf, f / b * HBM_PEAK_GBS / 1e3) for f, b in zip(a_flops, a_bytes)]   # TFLOP/s
     dom = int(np.argmax(g_ms))
@@ -143,19 +145,19 @@ def measure(name, scale, steps, warmup, threshold=None, edge_chunk=None, keep=Fa
         "hub_threshold": w.threshold if use_split else None, "recipe": w.recipe,
         "edge_chunk": edge_chunk or None, "chunks_per_gather": n_chunks,
         "ms_per_step": ms_per_step, "edges_per_s_per_layer": E * L / (ms_per_step * 1e-3),
-        "csr_build_ms": csr_ms, "split_hubs_ms": split_ms, "gather_ms": g_ms, "apply_ms": a_ms, "project_ms": p_ms,
+        "csr_build_ms": csr_ms, "split_hubs_ms": split_ms, "gather_ms": g_ms, "apply_ms": d_ms,
         "projected_before_gather": projected,
         "gather_width": [gather_width(l, g, pf) for l, g, pf in zip(w.layers, is_gat, projected)],
         "gather_algorithmic_bytes": g_bytes, "gather_compulsory_bytes": g_compulsory,
         "gather_edges_per_s": [E / (t * 1e-3) for t in g_ms],
         "gather_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(g_bytes, g_ms)],
         "gather_frac_of_hbm_peak": [b / (t * 1e-3) / 1e9 / HBM_PEAK_GBS for b, t in zip(g_bytes, g_ms)],
-        "apply_TFLOPs": [f / (t * 1e-3) / 1e12 for f, t in zip(a_flops, a_ms)],
-        "apply_frac_of_mfma_peak": [f / (t * 1e-3) / 1e12 / peak_tf for f, t in zip(a_flops, a_ms)],
+        "apply_TFLOPs": [f / (t * 1e-3) / 1e12 for f, t in zip(a_flops, d_ms)],
+        "apply_frac_of_mfma_peak": [f / (t * 1e-3) / 1e12 / peak_tf for f, t in zip(a_flops, d_ms)],
         "apply_attainable_TFLOPs": a_attainable,
-        "apply_frac_of_attainable_roofline": [f / (t * 1e-3) / 1e12 / at for f, t, at in zip(a_flops, a_ms, a_attainable)],
-        "apply_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(a_bytes, a_ms)],
-        "nodes_per_s_per_layer": [N / ((g + a + p) * 1e-3) for g, a, p in zip(g_ms, a_ms, p_ms)],
+        "apply_frac_of_attainable_roofline": [f / (t * 1e-3) / 1e12 / at for f, t, at in zip(a_flops, d_ms, a_attainable)],
+        "apply_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(a_bytes, d_ms)],
+        "nodes_per_s_per_layer": [N / ((g + a) * 1e-3) for g, a in zip(g_ms, d_ms)],
         "n_hubs": graph[3].n_hubs, "n_shadows": graph[3].n_shadows, "dominant_gather": dom,
     }
     if keep:
@@ -328,7 +330,7 @@ def main():
             say(f"side workload {name}")
             r = measure(name, 1.0, steps=5, warmup=2)
             others[name] = {k: r[k] for k in ("n_nodes", "n_edges", "dtype", "dims", "ms_per_step", "edges_per_s_per_layer",
-                                              "csr_build_ms", "gather_ms", "apply_ms", "project_ms", "gather_GBps",
+                                              "csr_build_ms", "gather_ms", "apply_ms", "projected_before_gather", "gather_GBps",
                                               "gather_frac_of_hbm_peak", "apply_TFLOPs", "apply_frac_of_mfma_peak",
                                               "apply_frac_of_attainable_roofline", "n_hubs", "n_shadows")}
             torch.cuda.empty_cache()

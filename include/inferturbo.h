@@ -209,6 +209,14 @@ int32_t gcn_edge_coefficients(int64_t n_edges, const int32_t *col, const float *
  *              INT64_MAX for the whole graph.  Rows with no in-edge belong to
  *              the range that contains their rowptr value.
  *
+ * The update fused into the reduce (Sec. IV-B "Inference": the computation may
+ * be reorganised around the aggregate): with desc->addend, desc->bias and
+ * desc->act the stored row is act(agg[v] + addend[v] + bias) instead of agg[v].
+ * A narrowing layer uses it: W_nbr and W_self are applied to h first (one
+ * launch, apply_layer's second product), the gather runs over h.W_nbr with
+ * addend = h.W_self, and no update launch follows.  Hub rows get the epilogue
+ * in the combine pass.
+ *
  * ITB_AGG_GAT (Sec. II-B: GAT's reduce is an attention-weighted sum; Sec. IV-B:
  * it runs after the messages are collected): h_src is the projected state z,
  * heads divides dim, src_scale = s_src [n_nodes x heads], dst_scale = s_dst
@@ -226,9 +234,10 @@ typedef struct {
     int32_t dim;
     int32_t heads;      /* GAT only, else 1 */
     float leaky_slope;  /* GAT only */
-    int32_t act;        /* GAT only: activation applied after the bias; else ITB_ACT_NONE */
-    const float *bias;  /* GAT only: [dim] fp32 added to the reduced row, or NULL; else NULL */
+    int32_t act;        /* activation of the update fused into the reduce (below); ITB_ACT_NONE for a plain aggregate */
+    const float *bias;  /* [dim] fp32 added to the reduced row (16-byte aligned), or NULL */
     const float *edge_coef; /* SUM / MEAN / GCN, optional: [n_edges] fp32 scalar of every in-edge, CSR order */
+    const void *addend; /* not GAT, optional: [n_nodes x dim] of dtype_out added to the reduced row before the bias */
 } itb_gather_desc;
 
 int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes,
@@ -286,6 +295,12 @@ int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes,
  *   projection when W_nbr was applied before the gather (sum, mean and the
  *   degree-normalised sum are linear, so a narrowing layer can gather d_out
  *   instead of d_in elements per edge); NULL to skip.
+ *   w_second/out_second: optional second product of the same rows in the same
+ *   launch: out_second[v] = agg[v] . w_second ([d_in x d_out] of `dtype`, no
+ *   bias, no activation; bias, addend, activation and messages apply to h_out
+ *   only).  A narrowing layer uses it for h . [W_nbr | W_self]: h is read once.
+ *   Needs d_out to be a multiple of 4 (fp32) / 8 (bf16), no self term and no
+ *   score epilogue; both NULL to skip.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t dtype;
@@ -301,6 +316,7 @@ int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes,
                     const float *att_src, const float *att_dst, float *s_src, float *s_dst,
                     const float *msg_scale, void *msg_out,
                     const void *addend,
+                    const void *w_second, void *out_second,
                     void *stream);
 
 /* ---------------------------------------------------------------------------
@@ -326,8 +342,12 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  *   edge_chunk 0 = one gather launch set per layer; else each layer's gather is
  *              issued per range of `edge_chunk` edge offsets (see gather_layer).
  * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
- * gather(h . W_nbr) (see apply_layer's addend); GCN layers share one array of
- * per-edge source coefficients (gcn_edge_coefficients) built at the start.
+ * act(gather(h . W_nbr) + h . W_self + bias): one matrix launch with two
+ * products, then the gather with the update fused into its row epilogue (see
+ * gather_layer); infer_layer_plan reports which layers take that form.  GCN
+ * layers share one array of per-edge source coefficients
+ * (gcn_edge_coefficients) built at the start.  With edge_chunk > 0 there may be
+ * at most 65536 ranges.
  * An ITB_AGG_NONE layer is h' = act(h . w_nbr + bias) per vertex, no edges
  * touched (w_self must be NULL).
  *   events     NULL, or a host struct naming a host array of hipEvent_t
@@ -359,6 +379,19 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
                          const void *x, void *out, int64_t edge_chunk,
                          void *workspace, size_t *workspace_bytes,
                          const itb_stage_events *events, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * infer_layer_plan -- the evaluation order infer_full_graph takes for every
+ * layer of a model (host only; `layers` and `plan` are host arrays, the weight
+ * pointers are not dereferenced): plan[l] is one of ITB_PLAN_*.
+ * ------------------------------------------------------------------------- */
+enum {
+    ITB_PLAN_GATHER_UPDATE = 0,   /* gather_layer on the state, then apply_layer */
+    ITB_PLAN_PROJECT_GATHER = 1,  /* apply_layer with two products, then gather_layer with the fused update */
+    ITB_PLAN_ATTENTION = 2,       /* projection with scores, then the attention reduce */
+    ITB_PLAN_UPDATE_ONLY = 3      /* ITB_AGG_NONE: apply_layer alone */
+};
+int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_layer *layers, int32_t *plan);
 
 /* ---------------------------------------------------------------------------
  * itb_shutdown -- destroys what the library owns (the helper stream and its

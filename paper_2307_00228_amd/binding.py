@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libinferturbo_hip.so")
 ITB_F32, ITB_BF16 = 0, 1
 AGG_SUM, AGG_MEAN, AGG_GCN, AGG_GAT, AGG_MAX, AGG_MIN, AGG_NONE = 0, 1, 2, 3, 4, 5, 6
 ACT_NONE, ACT_RELU = 0, 1
+PLAN_GATHER_UPDATE, PLAN_PROJECT_GATHER, PLAN_ATTENTION, PLAN_UPDATE_ONLY = 0, 1, 2, 3
 INT64_MAX = (1 << 63) - 1
 
 STATUS = {0: "ITB_OK", -1: "ITB_ERR_NULL", -2: "ITB_ERR_SIZE", -3: "ITB_ERR_RANGE", -4: "ITB_ERR_DTYPE",
@@ -41,7 +42,7 @@ class itb_split(C.Structure):
 class itb_gather_desc(C.Structure):
     _fields_ = [("agg", C.c_int32), ("dtype_in", C.c_int32), ("dtype_out", C.c_int32), ("dim", C.c_int32),
                 ("heads", C.c_int32), ("leaky_slope", C.c_float), ("act", C.c_int32), ("bias", C.c_void_p),
-                ("edge_coef", C.c_void_p)]
+                ("edge_coef", C.c_void_p), ("addend", C.c_void_p)]
 
 
 class itb_apply_desc(C.Structure):
@@ -72,7 +73,8 @@ def _load():
     lib.gcn_edge_coefficients.argtypes = [i64, vp, vp, vp, vp]
     lib.gather_layer.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                  i64, i64, vp, szp, vp]
-    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.infer_layer_plan.argtypes = [i32, i32, C.POINTER(itb_layer), C.POINTER(i32)]
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
     lib.gather_layer_noalloc.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                          i64, i64, vp]
@@ -85,7 +87,7 @@ def _load():
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients",
-              "gather_layer_noalloc", "itb_shutdown", "itb_random_row_read"):
+              "gather_layer_noalloc", "itb_shutdown", "itb_random_row_read", "infer_layer_plan"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -231,14 +233,17 @@ def gcn_edge_coefficients(col: torch.Tensor, src_scale: torch.Tensor, out: Optio
 def gather_layer(agg: int, rowptr, col, h, split: Optional[Split] = None, src_scale=None, dst_scale=None,
                  out_dtype=None, heads: int = 1, leaky_slope: float = 0.2, edge_lo: int = 0, edge_hi: int = INT64_MAX,
                  out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                 act: int = ACT_NONE, bias: Optional[torch.Tensor] = None, edge_coef: Optional[torch.Tensor] = None):
+                 act: int = ACT_NONE, bias: Optional[torch.Tensor] = None, edge_coef: Optional[torch.Tensor] = None,
+                 addend: Optional[torch.Tensor] = None):
     n, dim = h.shape
     out_dtype = out_dtype or h.dtype
     if out is None:
         out = torch.empty((n, dim), dtype=out_dtype, device="cuda")
+    assert addend is None or (addend.shape == out.shape and addend.dtype == out.dtype and addend.is_contiguous())
     desc = itb_gather_desc(agg, dtype_code(h), dtype_code(out), dim, heads, leaky_slope, act,
                            bias.data_ptr() if bias is not None else None,
-                           edge_coef.data_ptr() if edge_coef is not None else None)
+                           edge_coef.data_ptr() if edge_coef is not None else None,
+                           addend.data_ptr() if addend is not None else None)
     sp = split.c_struct() if split is not None else None
     spp = C.byref(sp) if sp is not None else None
     need = C.c_size_t(0)
@@ -253,12 +258,14 @@ def gather_layer(agg: int, rowptr, col, h, split: Optional[Split] = None, src_sc
 
 def gather_layer_noalloc(agg: int, rowptr, col, h, out: torch.Tensor, split: Optional[Split] = None, src_scale=None,
                          dst_scale=None, heads: int = 1, leaky_slope: float = 0.2, edge_lo: int = 0, edge_hi: int = INT64_MAX,
-                         act: int = ACT_NONE, bias: Optional[torch.Tensor] = None, edge_coef: Optional[torch.Tensor] = None):
+                         act: int = ACT_NONE, bias: Optional[torch.Tensor] = None, edge_coef: Optional[torch.Tensor] = None,
+                         addend: Optional[torch.Tensor] = None):
     """gather_layer on the library's built-in scratch: the caller passes inputs and the output, nothing is allocated."""
     n, dim = h.shape
     desc = itb_gather_desc(agg, dtype_code(h), dtype_code(out), dim, heads, leaky_slope, act,
                            bias.data_ptr() if bias is not None else None,
-                           edge_coef.data_ptr() if edge_coef is not None else None)
+                           edge_coef.data_ptr() if edge_coef is not None else None,
+                           addend.data_ptr() if addend is not None else None)
     sp = split.c_struct() if split is not None else None
     spp = C.byref(sp) if sp is not None else None
     _check("gather_layer_noalloc", lib.gather_layer_noalloc(C.byref(desc), n, _ptr(rowptr), _ptr(col), spp, _ptr(h),
@@ -276,7 +283,9 @@ def scale_rows(x: torch.Tensor, row_scale: torch.Tensor, out: Optional[torch.Ten
 
 
 def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.Tensor] = None,
-                heads: int = 0, att_src=None, att_dst=None, msg_scale=None, msg_out=None, addend=None):
+                heads: int = 0, att_src=None, att_dst=None, msg_scale=None, msg_out=None, addend=None,
+                w_second=None, out_second=None):
+    """Returns out; with heads > 0 (out, s_src, s_dst); with w_second (out, out_second)."""
     n, d_in = agg.shape
     d_out = w_nbr.shape[1]
     if out is None:
@@ -286,9 +295,14 @@ def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.
     if heads:
         s_src = torch.empty((n, heads), dtype=torch.float32, device="cuda")
         s_dst = torch.empty((n, heads), dtype=torch.float32, device="cuda")
+    if w_second is not None and out_second is None:
+        out_second = torch.empty((n, d_out), dtype=agg.dtype, device="cuda")
     _check("apply_layer", lib.apply_layer(C.byref(desc), n, _ptr(h_self), _ptr(agg), _ptr(w_self), _ptr(w_nbr), _ptr(bias),
                                           _ptr(out), _ptr(att_src), _ptr(att_dst), _ptr(s_src), _ptr(s_dst),
-                                          _ptr(msg_scale), _ptr(msg_out), _ptr(addend), _stream()))
+                                          _ptr(msg_scale), _ptr(msg_out), _ptr(addend), _ptr(w_second), _ptr(out_second),
+                                          _stream()))
+    if w_second is not None:
+        return out, out_second
     return (out, s_src, s_dst) if heads else out
 
 
@@ -316,6 +330,14 @@ def _layer_array(layers: List[DeviceLayer]):
                            l.att_src.data_ptr() if l.att_src is not None else None,
                            l.att_dst.data_ptr() if l.att_dst is not None else None)
     return arr
+
+
+def infer_layer_plan(layers: List["DeviceLayer"], dtype) -> List[int]:
+    """The evaluation order the library takes for every layer (PLAN_* codes)."""
+    arr = _layer_array(layers)
+    plan = (C.c_int32 * len(layers))()
+    _check("infer_layer_plan", lib.infer_layer_plan(ITB_BF16 if dtype in (torch.bfloat16, "bf16") else ITB_F32, len(layers), arr, plan))
+    return list(plan)
 
 
 def infer_workspace_bytes(n_nodes, n_edges, split: Optional[Split], dtype, layers: List[DeviceLayer], edge_chunk=0) -> int:

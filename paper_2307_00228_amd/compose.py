@@ -18,22 +18,16 @@ from . import binding as B
 @dataclass
 class LayerTrace:
     gather_src: torch.Tensor        # rows the gather read (state, message rows, or projected rows)
-    agg: torch.Tensor               # gather output (GAT: the new state)
+    agg: torch.Tensor               # gather output (GAT and projected layers: the new state)
     out: torch.Tensor               # new state
-    projected: bool                 # W_nbr applied before the gather
+    projected: bool                 # W_nbr applied before the gather, update fused into the gather's epilogue
     scores: Optional[tuple] = None  # GAT: (s_src, s_dst)
-
-
-def project_before_gather(layer, dtype) -> bool:
-    """Same rule as the library's layer loop: narrowing sum / mean / GCN layers apply W_nbr before the gather."""
-    elem = 2 if dtype in (torch.bfloat16, "bf16") else 4
-    linear = layer.agg in (B.AGG_SUM, B.AGG_MEAN, B.AGG_GCN)
-    return linear and layer.w_self is not None and layer.d_out < layer.d_in and (layer.d_out * elem) % 16 == 0
+    self_product: Optional[torch.Tensor] = None   # projected layers: h . W_self, the addend of the gather's epilogue
 
 
 def plan(layers, dtype) -> List[bool]:
-    """Which layers apply W_nbr before their gather."""
-    return [project_before_gather(l, dtype) for l in layers]
+    """Which layers apply W_nbr before their gather: asked of the library (infer_layer_plan), not decided here."""
+    return [p == B.PLAN_PROJECT_GATHER for p in B.infer_layer_plan(layers, dtype)]
 
 
 def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torch.Tensor,
@@ -60,6 +54,7 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         buffers["edge_coef"] = coef
     traces = []
     h = x
+    projected = plan(layers, x.dtype)
     for i, l in enumerate(layers):
         gcn, gat = l.agg == B.AGG_GCN, l.agg == B.AGG_GAT
         out = buf(("out", i), l.d_out)
@@ -84,22 +79,30 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
             traces.append(LayerTrace(z, out, out, False, (s_src, s_dst)))
             h = out
             continue
-        src_rows = h
-        pf = project_before_gather(l, x.dtype)
+        if projected[i]:
+            # h . [W_nbr | W_self] in one launch, then the gather of the first product with the update in its epilogue
+            mark("project_begin", i)
+            proj, selfp = B.apply_layer(None, h, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out),
+                                        w_second=l.w_self, out_second=buf(("selfp", i), l.d_out))
+            mark("project_end", i)
+            mark("gather_begin", i)
+            B.gather_layer(l.agg, rowptr, col, proj, split, None, sd if gcn else None, out=out,
+                           edge_coef=coef if gcn else None, addend=selfp, bias=l.bias, act=l.act)
+            mark("gather_end", i)
+            mark("apply_begin", i)
+            mark("apply_end", i)
+            traces.append(LayerTrace(proj, out, out, True, None, selfp))
+            h = out
+            continue
         mark("project_begin", i)
-        if pf:
-            src_rows = B.apply_layer(None, src_rows, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out))
         mark("project_end", i)
         mark("gather_begin", i)
-        agg = B.gather_layer(l.agg, rowptr, col, src_rows, split, None, sd if gcn else None, out=buf(("agg", i), src_rows.shape[1]),
+        agg = B.gather_layer(l.agg, rowptr, col, h, split, None, sd if gcn else None, out=buf(("agg", i), h.shape[1]),
                              edge_coef=coef if gcn else None)
         mark("gather_end", i)
         mark("apply_begin", i)
-        if pf:
-            B.apply_layer(None, h, None, l.w_self, l.bias, l.act, out=out, addend=agg)
-        else:
-            B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
+        B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
         mark("apply_end", i)
-        traces.append(LayerTrace(src_rows, agg, out, pf))
+        traces.append(LayerTrace(h, agg, out, False))
         h = out
     return traces

@@ -48,7 +48,14 @@ __global__ __launch_bounds__(256) void random_rows_kernel(const uint4 *table, co
 template <int G>
 int32_t launch_probe(const void *table, const int32_t *idx, int64_t n_idx, void *sink, int blocks, hipStream_t st) {
     constexpr int U = G < 4 ? G : 4;
-    random_rows_kernel<G, U><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
+    constexpr int U8 = G < 8 ? G : 8;
+    const int want = itb::g_tuning.gather_unroll.load();  // A/B switch 7: row loads in flight per lane
+    if (want == 8)
+        random_rows_kernel<G, U8><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
+    else if (want == 1)
+        random_rows_kernel<G, 1><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
+    else
+        random_rows_kernel<G, U><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }

@@ -48,6 +48,12 @@ struct ApplyArgs {
     // optional addend [n x d_out] of the storage dtype, added before the activation (the gathered projection when
     // the neighbour product was taken before the gather)
     const void *addend;
+    // optional second product of the same rows: out2 = agg . w2 ([d_in x d_out], no bias, no activation).  The kernel
+    // then runs over n_cols = 2 * d_out logical columns: column c < d_out belongs to (w_nbr, out), column c >= d_out
+    // to (w2, out2) at c - d_out.
+    const void *w2;
+    void *out2;
+    int32_t n_cols;
 };
 
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
@@ -67,11 +73,13 @@ __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &
         const int kcg = idx / (2 * BN);
         const int phase = kcg / chunks_per_phase;
         const int kc = kcg % chunks_per_phase;
-        const void *wbase = (phases == 2 && phase == 0) ? a.w_self : a.w_nbr;
-        const int col = col0 + j;
+        const int lcol = col0 + j;                       // logical column
+        const bool second = lcol >= a.d_out;             // (only with a second product)
+        const void *wbase = second ? a.w2 : ((phases == 2 && phase == 0) ? a.w_self : a.w_nbr);
+        const int col = second ? lcol - a.d_out : lcol;
         const int k0 = kc * KC + kh * KH;
         uint4 v = make_uint4(0, 0, 0, 0);
-        if (col < a.d_out) {
+        if (lcol < a.n_cols) {
             if constexpr (BF16) {
                 const uint16_t *w = static_cast<const uint16_t *>(wbase);
                 uint32_t e[8];
@@ -231,7 +239,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int col = col0 + nt * 32 + i;
-        bias_v[nt] = (a.bias && col < a.d_out) ? a.bias[col] : 0.f;
+        bias_v[nt] = (a.bias && col < a.d_out) ? a.bias[col] : 0.f;   // (the second product carries no bias)
     }
 
     // fetch cursor: the next group to request (runs two groups ahead of the compute cursor)
@@ -367,7 +375,15 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
                 }
                 const int64_t row = m0 + rho;
                 const int col = col0 + nt0 * 32 + u0 * 4;
-                if (row < a.n && u0 * 4 < npass * 32 && col < a.d_out) {
+                if (row < a.n && u0 * 4 < npass * 32 && col >= a.d_out && col < a.n_cols) {
+                    // the second product: plain rows of out2 (d_out is a multiple of the vector width here)
+                    const int64_t off = row * a.d_out + (col - a.d_out);
+                    if constexpr (BF16)
+                        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.out2) + off) =
+                            make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                    else
+                        *reinterpret_cast<float4 *>(static_cast<float *>(a.out2) + off) = make_float4(v[0], v[1], v[2], v[3]);
+                } else if (row < a.n && u0 * 4 < npass * 32 && col < a.d_out) {
                     const int64_t off = row * a.d_out + col;
                     const float ms = a.msg_out ? a.msg_scale[row] : 0.f;
                     if constexpr (!RAGGED) {  // d_out % VE == 0: every vector is whole and 16-byte aligned
@@ -504,7 +520,7 @@ int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set.store(true, std::memory_order_release);
     }
-    const int col_tiles = (a.d_out + BN - 1) / BN;
+    const int col_tiles = (a.n_cols + BN - 1) / BN;
     int blocks_per_cu = (int)((160 * 1024) / (lds + 1024));
     if (blocks_per_cu < 1) blocks_per_cu = 1;
     if (blocks_per_cu > 2) blocks_per_cu = 2;
@@ -526,7 +542,7 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
     const int real_chunks = (a.d_in + KC - 1) / KC;
     const bool ragged = a.d_out % (BF16 ? 8 : 4) != 0;
     for (int nt = 4; nt >= 1; nt /= 2) {
-        if (nt > 1 && 32 * (nt / 2) >= a.d_out) continue;  // narrower tile already covers every column
+        if (nt > 1 && 32 * (nt / 2) >= a.n_cols) continue;  // narrower tile already covers every column
         // LDS of a configuration: weight panel (+ score panel) over the padded k range, plus the staging areas
         auto fits = [&](int pf) {
             const int chunks = padded_chunks(a.d_in, KC, pf);
@@ -621,7 +637,7 @@ int cached_cu_count() {
 extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, const void *h_self, const void *agg,
                                const void *w_self, const void *w_nbr, const float *bias, void *h_out, const float *att_src,
                                const float *att_dst, float *s_src, float *s_dst, const float *msg_scale, void *msg_out,
-                               const void *addend, void *stream) {
+                               const void *addend, const void *w_second, void *out_second, void *stream) {
     if (!desc) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->dtype != ITB_F32 && desc->dtype != ITB_BF16) return ITB_ERR_DTYPE;
@@ -640,8 +656,12 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if ((h_self == nullptr) != (w_self == nullptr)) return ITB_ERR_NULL;
     if ((msg_scale == nullptr) != (msg_out == nullptr)) return ITB_ERR_NULL;
     if ((msg_out || addend) && desc->heads > 0) return ITB_ERR_UNSUPPORTED;
+    if ((w_second == nullptr) != (out_second == nullptr)) return ITB_ERR_NULL;
+    // the second product shares the rows of `agg`: no self term, no score columns, whole 16-byte vectors per row
+    if (w_second && (h_self || desc->heads > 0 || desc->d_out % piece != 0)) return ITB_ERR_UNSUPPORTED;
     if (!w_nbr || !agg || !h_out) return ITB_ERR_NULL;
-    if (!aligned16(h_self) || !aligned16(agg) || !aligned16(h_out) || !aligned16(addend) || !aligned16(msg_out))
+    if (!aligned16(h_self) || !aligned16(agg) || !aligned16(h_out) || !aligned16(addend) || !aligned16(msg_out) ||
+        !aligned16(out_second))
         return ITB_ERR_UNSUPPORTED;  // rows are moved as 16-byte vectors (a ragged d_out is stored element by element,
                                      // its base must still be aligned)
 
@@ -665,6 +685,9 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     a.msg_scale = msg_scale;
     a.msg_out = msg_out;
     a.addend = addend;
+    a.w2 = w_second;
+    a.out2 = out_second;
+    a.n_cols = w_second ? 2 * desc->d_out : desc->d_out;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int cus = cached_cu_count();
     if (desc->dtype == ITB_BF16) return a.heads > 0 ? dispatch_staged<true, true>(a, cus, st) : dispatch_staged<true, false>(a, cus, st);

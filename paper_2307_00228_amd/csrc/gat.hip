@@ -14,6 +14,8 @@
 
 namespace itb {
 size_t lds_for_occupancy(int waves, int lanes_per_row, bool beside_hub_passes);
+int32_t enqueue_range_bounds(int64_t n_ranges, int64_t edge_step, int64_t edge_lo, int64_t edge_hi, int64_t n_nodes,
+                             const int64_t *rowptr, const itb_split *split, int64_t *out, hipStream_t st);
 }  // namespace itb
 
 namespace {
@@ -30,6 +32,7 @@ struct GatArgs {
     void *out;
     int64_t threshold;
     int64_t edge_lo, edge_hi;
+    const int64_t *bounds;   // nullable: {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi} of the edge range (see gather_layer)
     int32_t row_vecs, heads, dh, act;
     float slope;
     int32_t small_limit;
@@ -208,6 +211,7 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
     const int li = lane % G;
     const int64_t r0 = ((int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave)) * kWave;
     if (r0 >= a.n_nodes) return;
+    if (a.bounds && (r0 + kWave <= a.bounds[0] || r0 >= a.bounds[1])) return;  // no row of this wavefront starts in the range
     const int vec = blockIdx.y * G + li;
     const bool lane_on = vec < a.row_vecs;
     const int hk = lane_on ? (vec * VE) / a.dh : 0;
@@ -403,6 +407,7 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gat_segments_kernel(GatAr
     const int lane = threadIdx.x & (kWave - 1);
     const int li = lane % G;
     const int64_t s = blockIdx.x;
+    if (a.bounds && (s < a.bounds[2] || s >= a.bounds[3])) return;
     const int64_t v = a.shadow_owner[s];
     const int64_t owner_start = a.rowptr[v];
     if (owner_start < a.edge_lo || owner_start >= a.edge_hi) return;
@@ -468,6 +473,7 @@ __global__ __launch_bounds__(1024) void gat_combine_kernel(GatArgs a, int64_t n_
     __shared__ float sm_l[1024];
     __shared__ float sm_max[64];
     constexpr int VE = Elems<BF16>::kPerVec;
+    if (a.bounds && ((int64_t)blockIdx.x < a.bounds[4] || (int64_t)blockIdx.x >= a.bounds[5])) return;
     const int64_t v = hub_ids[blockIdx.x];
     const int64_t rs = a.rowptr[v];
     if (rs < a.edge_lo || rs >= a.edge_hi) return;
@@ -617,8 +623,8 @@ namespace itb {
 
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
-                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, bool allow_side,
-                        hipStream_t st) {
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, const int64_t *bounds,
+                        bool allow_side, hipStream_t st) {
     const bool bf16 = desc->dtype_in == ITB_BF16;
     if (desc->dtype_out != desc->dtype_in) return ITB_ERR_UNSUPPORTED;
     if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
@@ -630,6 +636,7 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     const bool hubs = split && split->n_hubs > 0;
     Carver cv(workspace);
     uint32_t *long_count = cv.take<uint32_t>(64);
+    int64_t *own_bounds = cv.take<int64_t>(32);
     int32_t *long_list = cv.take<int32_t>((size_t)n_nodes);
     float *part_acc = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
     float *part_m = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->heads : 0);
@@ -657,6 +664,12 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     a.threshold = split ? split->threshold : INT64_MAX;
     a.edge_lo = edge_lo;
     a.edge_hi = edge_hi;
+    if (!bounds && (edge_lo > 0 || edge_hi < INT64_MAX)) {   // a partial range: find its rows, segments and hubs once
+        const int32_t brc = enqueue_range_bounds(1, 0, edge_lo, edge_hi, n_nodes, rowptr, split, own_bounds, st);
+        if (brc != ITB_OK) return brc;
+        bounds = own_bounds;
+    }
+    a.bounds = bounds;
     a.row_vecs = desc->dim * (bf16 ? 2 : 4) / 16;
     a.heads = desc->heads;
     a.dh = dh;

@@ -95,8 +95,15 @@ struct GatherArgs {
     const float *edge_coef;  // nullable: per-edge coefficient in CSR order (read beside the column index); wins over src_scale
     const float *dst_scale;  // kModeScaleDst only
     void *out;               // agg rows, or fp32 partial rows in the segment kernel
+    // update epilogue (all nullable / 0): out = act(agg + addend + bias), applied when a row is finished
+    const void *addend;      // [n_nodes x dim] of the output dtype
+    const float *bias;       // [dim]
+    int32_t act;
     int64_t threshold;       // rows with in-degree > threshold are hubs (skipped by the row kernel)
     int64_t edge_lo, edge_hi;
+    // nullable: {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi} = the rows, shadow segments and hubs whose first edge
+    // offset can lie in [edge_lo, edge_hi); wavefronts and blocks outside leave after one scalar load
+    const int64_t *bounds;
     int32_t row_vecs;        // 16-byte vectors per input row
     int32_t mode;
     int32_t small_limit;
@@ -201,6 +208,42 @@ __device__ __forceinline__ void finish_row(float (&acc)[VE], int mode, int64_t d
     }
 }
 
+// The update fused into the gather (a layer whose neighbour matrix was applied before the gather): the finished
+// aggregate of a lane's VE columns gets the lane's slice of the addend row and of the bias, then the activation.
+template <bool BF16_OUT, int VE>
+__device__ __forceinline__ void update_epilogue(float (&acc)[VE], const void *addend, const float *bias, int act, int64_t row,
+                                                int32_t row_vecs, int vec) {
+    if (!addend && !bias && act == ITB_ACT_NONE) return;
+    if (addend) {
+        const int64_t elem0 = (row * row_vecs + vec) * VE;
+        if constexpr (BF16_OUT) {
+            static_assert(VE == 8, "bf16 output rows come from bf16 input rows");
+            const uint4 ad = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(addend) + elem0);
+            acc[0] += bf16_lo(ad.x); acc[1] += bf16_hi(ad.x); acc[2] += bf16_lo(ad.y); acc[3] += bf16_hi(ad.y);
+            acc[4] += bf16_lo(ad.z); acc[5] += bf16_hi(ad.z); acc[6] += bf16_lo(ad.w); acc[7] += bf16_hi(ad.w);
+        } else {
+            const float4 *ad = reinterpret_cast<const float4 *>(static_cast<const float *>(addend) + elem0);
+#pragma unroll
+            for (int k = 0; k < VE / 4; ++k) {
+                const float4 x = ad[k];
+                acc[4 * k + 0] += x.x; acc[4 * k + 1] += x.y; acc[4 * k + 2] += x.z; acc[4 * k + 3] += x.w;
+            }
+        }
+    }
+    if (bias) {
+        const float4 *b4 = reinterpret_cast<const float4 *>(bias + (int64_t)vec * VE);
+#pragma unroll
+        for (int k = 0; k < VE / 4; ++k) {
+            const float4 b = b4[k];
+            acc[4 * k + 0] += b.x; acc[4 * k + 1] += b.y; acc[4 * k + 2] += b.z; acc[4 * k + 3] += b.w;
+        }
+    }
+    if (act == ITB_ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) acc[i] = fmaxf(acc[i], 0.f);
+    }
+}
+
 __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
     int lo = __shfl((int)(v & 0xffffffff), src, kWave);
     int hi = __shfl((int)(v >> 32), src, kWave);
@@ -270,6 +313,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
     const int li = lane % G;
     const int64_t r0 = ((int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave)) * kWave;
     if (r0 >= a.n_nodes) return;
+    if (a.bounds && (r0 + kWave <= a.bounds[0] || r0 >= a.bounds[1])) return;  // no row of this wavefront starts in the range
     const int vec = blockIdx.y * G + li;
     const bool lane_on = vec < a.row_vecs;
     const bool has_scale = !EXT && (a.src_scale != nullptr || a.edge_coef != nullptr);
@@ -342,6 +386,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
             }
             if (act && lane_on) {
                 finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
+                update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, r0 + rl, a.row_vecs, vec);
                 store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
             }
         }
@@ -357,6 +402,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
         wave_segment_sum<BF16_IN, G, EXT>(acc, a, st, d, vec, lane_on);
         if (g == 0 && lane_on) {
             finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
+            update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, r0 + rl, a.row_vecs, vec);
             store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
         }
     }
@@ -401,6 +447,7 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gather_segments_kernel(Ga
     const int lane = threadIdx.x & (kWave - 1);
     const int li = lane % G;
     const int64_t s = blockIdx.x;
+    if (a.bounds && (s < a.bounds[2] || s >= a.bounds[3])) return;
     const int64_t owner_start = a.rowptr[a.shadow_owner[s]];
     if (owner_start < a.edge_lo || owner_start >= a.edge_hi) return;
     const int vec = blockIdx.y * G + li;
@@ -429,6 +476,7 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gather_long_rows_kernel(G
         block_range_sum<BF16_IN, G, EXT>(acc, a, b, d, vec, lane_on, sm);
         if (threadIdx.x < G && lane_on) {
             finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, row);
+            update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, row, a.row_vecs, vec);
             store_row_slice<BF16_IN, BF16_OUT>(a.out, row, a.row_vecs, vec, acc);
         }
     }
@@ -442,9 +490,11 @@ template <bool BF16_OUT, bool EXT>
 __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, int32_t dim, int64_t n_hubs,
                                                             const int32_t *hub_ids, const int64_t *hub_shadow_off,
                                                             const int64_t *rowptr, const float *dst_scale, int32_t mode,
-                                                            int64_t edge_lo, int64_t edge_hi, void *out) {
+                                                            int64_t edge_lo, int64_t edge_hi, void *out, const void *addend,
+                                                            const float *bias, int32_t act, const int64_t *bounds) {
     __shared__ float4 sm[1024];
     const int64_t hub = blockIdx.x;
+    if (bounds && (hub < bounds[4] || hub >= bounds[5])) return;
     const int32_t v = hub_ids[hub];
     const int64_t rs = rowptr[v];
     if (rs < edge_lo || rs >= edge_hi) return;
@@ -488,6 +538,23 @@ __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, i
             }
             finish_row<4, EXT>(r, mode, deg, dst_scale, v);
             const int64_t elem0 = (int64_t)v * dim + (int64_t)(q0 + lv) * 4;
+            if (addend) {   // the fused update, as in the row kernels
+                if constexpr (BF16_OUT) {
+                    const uint2 ad = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(addend) + elem0);
+                    r[0] += bf16_lo(ad.x); r[1] += bf16_hi(ad.x); r[2] += bf16_lo(ad.y); r[3] += bf16_hi(ad.y);
+                } else {
+                    const float4 ad = *reinterpret_cast<const float4 *>(static_cast<const float *>(addend) + elem0);
+                    r[0] += ad.x; r[1] += ad.y; r[2] += ad.z; r[3] += ad.w;
+                }
+            }
+            if (bias) {
+                const float4 b = *reinterpret_cast<const float4 *>(bias + (int64_t)(q0 + lv) * 4);
+                r[0] += b.x; r[1] += b.y; r[2] += b.z; r[3] += b.w;
+            }
+            if (act == ITB_ACT_RELU) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) r[i] = fmaxf(r[i], 0.f);
+            }
             if constexpr (BF16_OUT) {
                 uint2 pk;
                 pk.x = pack_bf16x2(r[0], r[1]);
@@ -500,6 +567,60 @@ __global__ __launch_bounds__(1024) void combine_hubs_kernel(const float *part, i
     }
 }
 
+// first index i in [0, n) with key[i] >= x (n if none); key non-decreasing
+template <typename T>
+__device__ __forceinline__ int64_t lower_bound_dev(const T *key, int64_t n, int64_t x) {
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if ((int64_t)key[mid] < x) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+}  // namespace
+
+namespace itb {
+// Range r (r < n_ranges) covers the edge offsets [r * edge_step, (r + 1) * edge_step), the last one to the end; a
+// single range [edge_lo, edge_hi) is given with n_ranges = 1 and edge_step = 0.  Row pointers are non-decreasing, so
+// the rows whose first edge offset lies in a range are a contiguous run of vertex ids: out[6 r ..] =
+// {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi}.
+__global__ void range_bounds_kernel(int64_t n_ranges, int64_t edge_step, int64_t edge_lo, int64_t edge_hi, int64_t n_nodes,
+                                    const int64_t *rowptr, int64_t n_hubs, const int32_t *hub_ids, const int64_t *hub_shadow_off,
+                                    int64_t *out) {
+    const int64_t r = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (r >= n_ranges) return;
+    const int64_t lo = edge_step > 0 ? r * edge_step : edge_lo;
+    const int64_t hi = edge_step > 0 ? (r == n_ranges - 1 ? INT64_MAX : (r + 1) * edge_step) : edge_hi;
+    const int64_t row_lo = lower_bound_dev(rowptr, n_nodes, lo);
+    const int64_t row_hi = lower_bound_dev(rowptr, n_nodes, hi);
+    int64_t hub_lo = 0, hub_hi = 0;
+    if (n_hubs > 0) {
+        hub_lo = lower_bound_dev(hub_ids, n_hubs, row_lo);
+        hub_hi = lower_bound_dev(hub_ids, n_hubs, row_hi);
+    }
+    int64_t *o = out + 6 * r;
+    o[0] = row_lo;
+    o[1] = row_hi;
+    o[2] = n_hubs > 0 ? hub_shadow_off[hub_lo] : 0;
+    o[3] = n_hubs > 0 ? hub_shadow_off[hub_hi] : 0;
+    o[4] = hub_lo;
+    o[5] = hub_hi;
+}
+
+int32_t enqueue_range_bounds(int64_t n_ranges, int64_t edge_step, int64_t edge_lo, int64_t edge_hi, int64_t n_nodes,
+                             const int64_t *rowptr, const itb_split *split, int64_t *out, hipStream_t st) {
+    const bool hubs = split && split->n_hubs > 0;
+    range_bounds_kernel<<<(unsigned)((n_ranges + 63) / 64), 64, 0, st>>>(n_ranges, edge_step, edge_lo, edge_hi, n_nodes, rowptr,
+                                                                          hubs ? split->n_hubs : 0, hubs ? split->hub_ids : nullptr,
+                                                                          hubs ? split->hub_shadow_off : nullptr, out);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
+}  // namespace itb
+
+namespace {
 template <bool BF16_IN, bool BF16_OUT, int G, bool EXT>
 int32_t launch_rows(const GatherArgs &a, hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
@@ -557,17 +678,17 @@ int32_t dispatch_segments(int G, const GatherArgs &a, hipStream_t st) {
 namespace itb {
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
-                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, bool allow_side,
-                        hipStream_t st);
-}
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, const int64_t *bounds,
+                        bool allow_side, hipStream_t st);
 
-namespace {
+// gather_layer with two internal knobs.  `bounds`: device array {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi} of the
+// edge range (see range_bounds_kernel), or nullptr: computed here when the range is not the whole graph.
 // `allow_side`: the hub passes may run on the library's helper stream (false: everything on the caller's stream, no
 // library-owned object is created or touched).
 int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                           const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                           void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
-                          bool allow_side, void *stream) {
+                          const int64_t *bounds, bool allow_side, void *stream) {
     if (!desc || !workspace_bytes) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_MIN) return ITB_ERR_DTYPE;
@@ -580,12 +701,15 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     if (split && (split->threshold <= 0 || split->n_hubs < 0 || split->n_shadows < 0)) return ITB_ERR_SIZE;
     if (desc->agg == ITB_AGG_GAT)
         return gat_gather_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
-                               workspace, workspace_bytes, allow_side, static_cast<hipStream_t>(stream));
+                               workspace, workspace_bytes, bounds, allow_side, static_cast<hipStream_t>(stream));
 
-    if (desc->bias || desc->act != ITB_ACT_NONE) return ITB_ERR_UNSUPPORTED;  // epilogue exists for the GAT reduce only
+    if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
+    // bias and addend are read as 16-byte vectors
+    if ((reinterpret_cast<uintptr_t>(desc->bias) & 15u) || !aligned16(desc->addend)) return ITB_ERR_UNSUPPORTED;
     const bool hubs = split && split->n_hubs > 0;
     Carver cv(workspace);
     uint32_t *long_count = cv.take<uint32_t>(64);
+    int64_t *own_bounds = cv.take<int64_t>(32);
     int32_t *long_list = cv.take<int32_t>((size_t)n_nodes);
     float *part = cv.take<float>(hubs ? (size_t)split->n_shadows * desc->dim : 0);
     if (!workspace) {
@@ -611,9 +735,18 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     a.edge_coef = (desc->agg == ITB_AGG_GCN || desc->agg == ITB_AGG_SUM || desc->agg == ITB_AGG_MEAN) ? desc->edge_coef : nullptr;
     a.dst_scale = (desc->agg == ITB_AGG_GCN) ? dst_scale : nullptr;
     a.out = agg_out;
+    a.addend = desc->addend;
+    a.bias = desc->bias;
+    a.act = desc->act;
     a.threshold = split ? split->threshold : INT64_MAX;
     a.edge_lo = edge_lo;
     a.edge_hi = edge_hi;
+    if (!bounds && (edge_lo > 0 || edge_hi < INT64_MAX)) {   // a partial range: find its rows, segments and hubs once
+        const int32_t brc = enqueue_range_bounds(1, 0, edge_lo, edge_hi, n_nodes, rowptr, split, own_bounds, st);
+        if (brc != ITB_OK) return brc;
+        bounds = own_bounds;
+    }
+    a.bounds = bounds;
     a.row_vecs = desc->dim * elem / 16;
     const bool ext = desc->agg == ITB_AGG_MAX || desc->agg == ITB_AGG_MIN;
     a.mode = desc->agg == ITB_AGG_MEAN ? kModeMean
@@ -654,7 +787,8 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
         auto combine = bout ? (ext ? combine_hubs_kernel<true, true> : combine_hubs_kernel<true, false>)
                             : (ext ? combine_hubs_kernel<false, true> : combine_hubs_kernel<false, false>);
         combine<<<(unsigned)split->n_hubs, 1024, 0, hst>>>(part, desc->dim, split->n_hubs, split->hub_ids, split->hub_shadow_off,
-                                                           rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out);
+                                                           rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out, a.addend, a.bias,
+                                                           a.act, a.bounds);
         ITB_LAUNCH_CHECK();
         rc = fork.mark_done();
         if (rc != ITB_OK) return rc;
@@ -671,7 +805,9 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     if (rc != ITB_OK) return rc;
     return fork.finish();
 }
+}  // namespace itb
 
+namespace {
 // Scratch of gather_layer_noalloc: device memory that belongs to the library image, one copy per GPU, held until the
 // process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels and memory
 // operations get the per-device address looked up below.
@@ -698,23 +834,23 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
                                 const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                                 void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
                                 void *stream) {
-    return gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, workspace,
-                             workspace_bytes, true, stream);
+    return itb::gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
+                                  workspace, workspace_bytes, nullptr, true, stream);
 }
 
 extern "C" int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                                         const itb_split *split, const void *h_src, const float *src_scale,
                                         const float *dst_scale, void *agg_out, int64_t edge_lo, int64_t edge_hi, void *stream) {
     size_t need = 0;
-    int32_t rc = gather_layer_impl(desc, n_nodes, nullptr, nullptr, split, nullptr, nullptr, nullptr, nullptr, edge_lo, edge_hi,
-                                   nullptr, &need, false, nullptr);
+    int32_t rc = itb::gather_layer_impl(desc, n_nodes, nullptr, nullptr, split, nullptr, nullptr, nullptr, nullptr, edge_lo, edge_hi,
+                                        nullptr, &need, nullptr, false, nullptr);
     if (rc != ITB_OK) return rc;
     if (need > kStaticScratchBytes) return ITB_ERR_WORKSPACE;  // sizes beyond the built-in scratch: use gather_layer
     void *ptr = static_scratch_of_current_device();
     if (!ptr) return ITB_ERR_DEVICE;
     size_t have = kStaticScratchBytes;
-    return gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, ptr, &have,
-                             false, stream);
+    return itb::gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, ptr,
+                                  &have, nullptr, false, stream);
 }
 
 extern "C" int32_t itb_shutdown(void) {

@@ -5,6 +5,12 @@
 
 namespace itb {
 bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t heads);
+int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                          const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
+                          void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
+                          const int64_t *bounds, bool allow_side, void *stream);
+int32_t enqueue_range_bounds(int64_t n_ranges, int64_t edge_step, int64_t edge_lo, int64_t edge_hi, int64_t n_nodes,
+                             const int64_t *rowptr, const itb_split *split, int64_t *out, hipStream_t st);
 }
 
 namespace {
@@ -117,7 +123,10 @@ extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const
 
 // Sum, mean and the degree-normalised sum are linear in the source rows, so W_nbr can be applied before the gather
 // (the computation flow may be reorganised around the aggregate, Sec. IV-B "Inference"): when a layer narrows
-// (d_out < d_in) the edges then carry d_out instead of d_in elements.
+// (d_out < d_in) the edges then carry d_out instead of d_in elements.  Such a layer is one matrix launch
+// h . [W_nbr | W_self] (h is read once, two row-major outputs) followed by the gather of the first output, whose row
+// epilogue adds the second output and the bias and applies the activation: no update launch, and the aggregate never
+// makes a round trip through memory.
 // (For a layer of equal width the split into projection + update was measured slower than the fused update, even
 // where it would save the pass that writes the GCN message rows: both launches are bound by their memory traffic,
 // not by the matrix cores.)
@@ -125,6 +134,21 @@ static bool project_before_gather(const itb_layer &L, int32_t dtype) {
     const int elem = dtype == ITB_BF16 ? 2 : 4;
     const bool linear = L.agg == ITB_AGG_SUM || L.agg == ITB_AGG_MEAN || L.agg == ITB_AGG_GCN;
     return linear && L.w_self != nullptr && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
+}
+
+extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_layer *layers, int32_t *plan) {
+    if (!layers || !plan) return ITB_ERR_NULL;
+    if (n_layers <= 0) return ITB_ERR_SIZE;
+    if (dtype != ITB_F32 && dtype != ITB_BF16) return ITB_ERR_DTYPE;
+    for (int l = 0; l < n_layers; ++l) {
+        const itb_layer &L = layers[l];
+        if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_NONE) return ITB_ERR_DTYPE;
+        plan[l] = L.agg == ITB_AGG_NONE  ? ITB_PLAN_UPDATE_ONLY
+                  : L.agg == ITB_AGG_GAT ? ITB_PLAN_ATTENTION
+                  : project_before_gather(L, dtype) ? ITB_PLAN_PROJECT_GATHER
+                                                    : ITB_PLAN_GATHER_UPDATE;
+    }
+    return ITB_OK;
 }
 
 
@@ -164,13 +188,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
                 : (pf ? !apply_shape_supported(dtype, L.d_in, L.d_out, false, 0)
                       : !apply_shape_supported(dtype, L.d_in, L.d_out, L.w_self != nullptr, 0)))
             return ITB_ERR_UNSUPPORTED;
-        itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr, nullptr};
+        itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr, nullptr, nullptr};
         size_t need = 0;
         int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
                                   &need, nullptr);
         if (rc != ITB_OK) return rc;
         if (need > gather_ws) gather_ws = need;
     }
+    const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
+    if (n_chunks > 65536) return ITB_ERR_SIZE;  // (the ranges' row bounds are kept in the workspace)
     Carver cv(workspace);
     const size_t state_bytes = (size_t)n_nodes * max_d * elem;
     char *state0 = cv.take<char>(n_layers > 1 ? state_bytes : 0);
@@ -183,6 +209,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     float *att_s_src = cv.take<float>((size_t)n_nodes * max_heads);
     float *att_s_dst = cv.take<float>((size_t)n_nodes * max_heads);
     char *gws = cv.take<char>(gather_ws);
+    int64_t *range_bounds = cv.take<int64_t>(n_chunks > 1 ? 6 * (size_t)n_chunks : 0);
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -201,6 +228,12 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (rc != ITB_OK) return rc;
     }
     if (events && events->n_events < 0) return ITB_ERR_SIZE;
+    if (n_chunks > 1) {
+        // the rows, shadow segments and hubs of every edge range, once per call (they depend on the graph only)
+        const int32_t rc = enqueue_range_bounds(n_chunks, edge_chunk, 0, 0, n_nodes, rowptr, split, range_bounds,
+                                                static_cast<hipStream_t>(stream));
+        if (rc != ITB_OK) return rc;
+    }
     const Marks mark{events, stream};
     char *state[2] = {state0, state1};
     const void *cur = x;
@@ -213,7 +246,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             // encoder / prediction head (Sec. IV-C): the update alone, on the vertex's own state
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
             int32_t rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, stream);
+                                     nullptr, nullptr, nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;
             cur = dst;
@@ -224,50 +257,48 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         const void *gather_src = cur;
         const float *gs = nullptr, *gd_scale = gcn ? dst_scale : nullptr;
         void *gather_out = aggbuf;
-        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr, gcn ? edge_coef : nullptr};
+        itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr, gcn ? edge_coef : nullptr, nullptr};
         const bool pf = project_before_gather(L, dtype);
         if (gat) {
             // project first (z and the per-head scores), then the attention reduce writes the new state directly
             if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, L.heads};
             int32_t rc = apply_layer(&pd, n_nodes, nullptr, cur, nullptr, L.w_nbr, nullptr, aggbuf, L.att_src, L.att_dst,
-                                     att_s_src, att_s_dst, nullptr, nullptr, nullptr, stream);
+                                     att_s_src, att_s_dst, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             gather_src = aggbuf;
             gs = att_s_src;
             gd_scale = att_s_dst;
             gather_out = dst;
-            gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias, nullptr};
+            gd = itb_gather_desc{L.agg, dtype, dtype, L.d_out, L.heads, L.leaky_slope, L.act, L.bias, nullptr, nullptr};
         }
         if (pf) {
+            // h . [W_nbr | W_self] in one launch; the gather of the first product finishes the layer in its row epilogue
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
             int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, L.w_nbr, nullptr, projbuf, nullptr, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, nullptr, stream);
+                                     nullptr, nullptr, nullptr, nullptr, L.w_self, aggbuf, stream);
             if (rc != ITB_OK) return rc;
             gather_src = projbuf;
+            gather_out = dst;
             gd.dim = L.d_out;
+            gd.addend = aggbuf;
+            gd.bias = L.bias;
+            gd.act = L.act;
         }
         if (mark(l, 1) != ITB_OK) return ITB_ERR_DEVICE;
-        const int64_t n_chunks = (edge_chunk > 0 && n_edges > 0) ? (n_edges + edge_chunk - 1) / edge_chunk : 1;
         for (int64_t c = 0; c < n_chunks; ++c) {
             const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
             const int64_t hi = (c == n_chunks - 1) ? INT64_MAX : (c + 1) * edge_chunk;
             size_t ws = gather_ws;
-            int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws, stream);
+            int32_t rc = gather_layer_impl(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws,
+                                           n_chunks > 1 ? range_bounds + 6 * c : nullptr, true, stream);
             if (rc != ITB_OK) return rc;
         }
         if (mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;
-        if (!gat) {
-            int32_t rc;
-            if (pf) {  // the gathered projection enters the update as an addend to the self product
-                itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-                rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_self, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
-                                 nullptr, nullptr, aggbuf, stream);
-            } else {
-                itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-                rc = apply_layer(&ad, n_nodes, L.w_self ? cur : nullptr, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr,
-                                 nullptr, nullptr, nullptr, nullptr, nullptr, stream);   // no self matrix: no self term
-            }
+        if (!gat && !pf) {
+            itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
+            int32_t rc = apply_layer(&ad, n_nodes, L.w_self ? cur : nullptr, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr,
+                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);   // no self matrix: no self term
             if (rc != ITB_OK) return rc;
         }
         if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;

@@ -44,7 +44,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_struct_layouts_match_header(B):
     assert C.sizeof(B.itb_split) == 8 * 8
-    assert C.sizeof(B.itb_gather_desc) == 8 * 4 + 8 + 8
+    assert C.sizeof(B.itb_gather_desc) == 8 * 4 + 8 + 8 + 8
     assert C.sizeof(B.itb_apply_desc) == 5 * 4
     assert C.sizeof(B.itb_layer) == 6 * 4 + 5 * 8
 
@@ -83,12 +83,17 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert lib.gather_layer(C.byref(d), 10, None, None, C.byref(sp), None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -2
     # apply_layer
     a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
-    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
-    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
     a7 = B.itb_apply_desc(B.ITB_F32, 62, 16, B.ACT_RELU, 0)     # rows of 248 bytes: not whole 16-byte pieces
-    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
+    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
     a9 = B.itb_apply_desc(B.ITB_F32, 64, 16, 5, 0)
-    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
+    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
+    ok = C.c_void_p(1 << 20)   # second product: both or neither; no self term; whole 16-byte vectors per output row
+    assert lib.apply_layer(C.byref(a), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, None, None) == -1
+    assert lib.apply_layer(C.byref(a), 10, ok, ok, ok, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None) == -5
+    a6 = B.itb_apply_desc(B.ITB_F32, 64, 6, B.ACT_NONE, 0)
+    assert lib.apply_layer(C.byref(a6), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None) == -5
     # infer_full_graph
     assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, C.byref(need), None, None) == -1
     lay = (B.itb_layer * 2)()
@@ -112,6 +117,29 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert lib.itb_random_row_read(None, 0, 64, None, 0, None, 0, None) == -2
     assert lib.itb_set_tuning(99, 0) == -5
     assert lib.itb_shutdown() == 0          # nothing to destroy: no call has made the helper stream
+
+
+def test_infer_layer_plan_is_the_librarys_decision(B):
+    """Host-only query: narrowing linear layers with a self matrix and whole 16-byte rows are projected before the gather;
+    everything else keeps gather -> update (or its own form)."""
+    lay = (B.itb_layer * 6)()
+    p = C.c_void_p(256)
+    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 64, B.ACT_RELU, 1, 0.2, p, p, None, None, None)     # narrowing: projected
+    lay[1] = B.itb_layer(B.AGG_GCN, 64, 64, B.ACT_RELU, 1, 0.2, p, p, None, None, None)       # equal width: not
+    lay[2] = B.itb_layer(B.AGG_MAX, 64, 32, B.ACT_RELU, 1, 0.2, p, p, None, None, None)       # not linear: not
+    lay[3] = B.itb_layer(B.AGG_SUM, 32, 16, B.ACT_RELU, 1, 0.2, None, p, None, None, None)    # no self matrix: not
+    lay[4] = B.itb_layer(B.AGG_GAT, 16, 16, B.ACT_RELU, 2, 0.2, None, p, None, p, p)
+    lay[5] = B.itb_layer(B.AGG_NONE, 16, 4, B.ACT_NONE, 1, 0.2, None, p, None, None, None)
+    plan = (C.c_int32 * 6)()
+    assert B.lib.infer_layer_plan(B.ITB_F32, 6, lay, plan) == 0
+    assert list(plan) == [B.PLAN_PROJECT_GATHER, B.PLAN_GATHER_UPDATE, B.PLAN_GATHER_UPDATE, B.PLAN_GATHER_UPDATE,
+                          B.PLAN_ATTENTION, B.PLAN_UPDATE_ONLY]
+    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 6, B.ACT_RELU, 1, 0.2, p, p, None, None, None)      # 24-byte rows (fp32): not
+    assert B.lib.infer_layer_plan(B.ITB_F32, 1, lay, plan) == 0 and plan[0] == B.PLAN_GATHER_UPDATE
+    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 4, B.ACT_RELU, 1, 0.2, p, p, None, None, None)      # 8-byte rows in bf16: not
+    assert B.lib.infer_layer_plan(B.ITB_BF16, 1, lay, plan) == 0 and plan[0] == B.PLAN_GATHER_UPDATE
+    assert B.lib.infer_layer_plan(B.ITB_F32, 0, lay, plan) == -2 and B.lib.infer_layer_plan(5, 1, lay, plan) == -4
+    assert B.lib.infer_layer_plan(B.ITB_F32, 1, None, plan) == -1
 
 
 def test_hub_threshold_heuristic_matches_golden_and_oracle(B):
@@ -228,7 +256,7 @@ def test_misaligned_feature_tensors_are_refused(B):
     assert lib.gather_layer(*args(off, ok)) == -5 and lib.gather_layer(*args(ok, off)) == -5
     a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
     ap = lambda hs, ag, out, add: lib.apply_layer(C.byref(a), 10, hs, ag, ok if hs else None, ok, None, out, None, None, None, None,
-                                                   None, None, add, None)
+                                                   None, None, add, None, None, None)
     assert ap(None, off, ok, None) == -5 and ap(None, ok, off, None) == -5
     assert ap(off, ok, ok, None) == -5 and ap(None, ok, ok, off) == -5
     assert lib.scale_rows(B.ITB_F32, 10, 64, off, ok, ok, None) == -5

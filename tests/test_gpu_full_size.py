@@ -100,10 +100,18 @@ def test_full_size_dense_workloads(B, name):
             ok, worst = tolerance_ok(B.to_numpy(tr.out[vt]), y64, w.dtype)
             assert ok, f"layer {i + 1} apply: {worst}"
         else:
-            # W_nbr was applied before the gather: the gather itself is a plain aggregate of the projected rows
+            # W_nbr and W_self were applied before the gather (one launch, two products); the gather is a plain aggregate
+            # of the projected rows whose row epilogue adds the self product and the bias and applies the activation
+            hv = np.asarray(h_host)[verts]
+            for got, wmat, what in ((tr.gather_src, lay.w_nbr, "neighbour product"), (tr.self_product, lay.w_self, "self product")):
+                ok, worst = tolerance_ok(B.to_numpy(got[vt]), oracle.apply(None, hv, None, wmat, None, oracle.ACT_NONE), w.dtype)
+                assert ok, f"layer {i + 1} {what}: {worst}"
             p64 = oracle.gather(lay.agg, r, c, B.to_numpy(tr.gather_src), deg_out=d, verts=verts)
-            ok, worst = tolerance_ok(B.to_numpy(tr.agg[vt]), p64, w.dtype)
-            assert ok, f"layer {i + 1} gather of projected rows: {worst}"
+            y64 = p64 + W.as_f32(B.to_numpy(tr.self_product[vt])).astype(np.float64) + lay.bias.astype(np.float64)
+            if lay.act == W.ACT_RELU:
+                y64 = np.maximum(y64, 0.0)
+            ok, worst = tolerance_ok(B.to_numpy(tr.out[vt]), y64, w.dtype)
+            assert ok, f"layer {i + 1} gather of projected rows with the fused update: {worst}"
         h_host = B.to_numpy(tr.out)
     h_dev = traces[-1].out
 

@@ -585,6 +585,66 @@ def test_apply_with_addend(B, dtype, d_in, d_out, n):
     check_features(B.to_numpy(msg), want * scale[:, None].astype(np.float64), dtype)
 
 
+@pytest.mark.parametrize("dtype,d_in,d_out", [(W.F32, 128, 64), (W.F32, 64, 16), (W.BF16, 64, 32), (W.BF16, 128, 64),
+                                              (W.BF16, 200, 40), (W.F32, 100, 4), (W.BF16, 256, 128), (W.F32, 64, 200)])
+@pytest.mark.parametrize("n", [3, 1000, 4100])
+def test_apply_second_product(B, dtype, d_in, d_out, n):
+    """Two products of the same rows in one launch: out = act(x W1 + b), out_second = x W2 (plain)."""
+    import torch
+    rng = np.random.default_rng(n + d_in + d_out)
+    x = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    lay = W.dense_layers(rng, W.AGG_MEAN, (d_in, d_out, d_out), dtype, bias_random=True)[0]
+    xd = B.to_device(x)
+    out, second = B.apply_layer(None, xd, None, B.to_device(lay.w_nbr), B.to_device(lay.bias), W.ACT_RELU,
+                                w_second=B.to_device(lay.w_self))
+    check_features(B.to_numpy(out), oracle.apply(None, x, None, lay.w_nbr, lay.bias, oracle.ACT_RELU), dtype, "first")
+    check_features(B.to_numpy(second), oracle.apply(None, x, None, lay.w_self, None, oracle.ACT_NONE), dtype, "second")
+    # each product bitwise equal to the single-product launch
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    alone1 = B.apply_layer(None, xd, None, B.to_device(lay.w_nbr), B.to_device(lay.bias), W.ACT_RELU)
+    alone2 = B.apply_layer(None, xd, None, B.to_device(lay.w_self), None, W.ACT_NONE)
+    assert torch.equal(out.view(view), alone1.view(view)) and torch.equal(second.view(view), alone2.view(view))
+
+
+@pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN])
+@pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.F32, 16), (W.BF16, 32), (W.BF16, 64), (W.BF16, 520)])
+@pytest.mark.parametrize("T", [None, 40])
+def test_gather_with_fused_update(B, kind, dtype, dim, T):
+    """The update in the gather's row epilogue: out = act(agg + addend + bias), through short rows, whole-wavefront
+    rows, long rows (limit lowered), hub partials + combine, and edge-range chunks."""
+    import torch
+    n, e = 3000, 50000
+    src, dst, x = W.random_small_graph(dim + 21, n, e, dim, dtype, 0.3)
+    r, c, d = oracle.build_csr(n, src, dst)
+    rng = np.random.default_rng(dim + 22)
+    add = W.store(rng.standard_normal((n, dim)).astype(np.float32), dtype)
+    bias = rng.uniform(-0.5, 0.5, dim).astype(np.float32)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    split = B.split_hubs(rp, T) if T else None
+    ss = sd = None
+    if kind == W.AGG_GCN:
+        ss, sd = B.gcn_norm_scales(rp, torch.from_numpy(d).cuda())
+    h, addd, biasd = B.to_device(x), B.to_device(add), torch.from_numpy(bias).cuda()
+    a64 = oracle.gather(kind, r, c, x, deg_out=d)
+    want = np.maximum(a64 + W.as_f32(add).astype(np.float64) + bias, 0.0)
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    B.set_tuning(3, 40)
+    try:
+        out = B.gather_layer(kind, rp, cl, h, split, ss, sd, addend=addd, bias=biasd, act=W.ACT_RELU)
+        chunked = torch.full_like(out, float("nan"))
+        for lo in range(0, e, 7001):
+            B.gather_layer(kind, rp, cl, h, split, ss, sd, addend=addd, bias=biasd, act=W.ACT_RELU, edge_lo=lo,
+                           edge_hi=B.INT64_MAX if lo + 7001 >= e else lo + 7001, out=chunked)
+        torch.cuda.synchronize()
+    finally:
+        B.set_tuning(3, 512)
+    check_features(B.to_numpy(out), want, dtype, sum_terms=sum_scale((r, c), x) if kind == W.AGG_SUM else None)
+    assert torch.equal(out.view(view), chunked.view(view))
+    # bias alone, and no activation
+    out2 = B.gather_layer(kind, rp, cl, h, split, ss, sd, bias=biasd)
+    check_features(B.to_numpy(out2), a64 + bias, dtype, sum_terms=sum_scale((r, c), x) if kind == W.AGG_SUM else None)
+
+
 def test_gcn_gather_of_prescaled_rows(B):
     import torch
     n, e, dim = 5000, 80000, 128
