@@ -147,6 +147,25 @@ def gather_weighted(agg, rowptr, col, h, edge_w, verts=None):
     return out
 
 
+def gather_edge_features(agg, rowptr, col, h, edge_feat, w_edge, deg_out=None, verts=None):
+    """fp64 aggregate of messages h[u] + ef[e] . W_e (SUM, MEAN or GCN); ``edge_feat`` is a stored tensor [E x d_e]
+    in CSR order, ``w_edge`` a stored tensor [d_e x D]."""
+    rowptr, col, hf = _i64(rowptr), _i32(col), _f32(h)
+    n, d = hf.shape
+    ef, we = _f32(edge_feat), _f32(w_edge)
+    assert ef.shape[0] == len(col) and we.shape == (ef.shape[1], d)
+    vs = None if verts is None else _i64(verts)
+    out = np.zeros((n if vs is None else len(vs), d), dtype=np.float64)
+    do = None if deg_out is None else _i32(deg_out)
+    rc = lib().oracle_gather_edge_features(C.c_int(agg), C.c_int64(n), _p(rowptr, C.c_int64), _p(col, C.c_int32),
+                                           C.c_int64(d), _p(hf, C.c_float), _p(do, C.c_int32),
+                                           C.c_int64(ef.shape[1]), _p(ef, C.c_float), _p(we, C.c_float),
+                                           _p(vs, C.c_int64), C.c_int64(0 if vs is None else len(vs)), _p(out, C.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle_gather_edge_features failed: {rc}")
+    return out
+
+
 def gather_split(agg, rowptr, col, h, split, deg_out=None):
     """Same aggregate computed through the shadow segments; returns (agg, edge_count)."""
     rowptr, col, hf = _i64(rowptr), _i32(col), _f32(h)
@@ -224,7 +243,7 @@ def round_store(x64, dtype):
 
 
 # ------------------------------------------------------------------ whole layers
-def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=False, return_agg64=False):
+def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=False, return_agg64=False, edge_feat=None):
     """One SAGE/GCN-style layer: gather (sum, mean, degree-normalised sum, max or min), then apply: Eq. (1) in fp64
     with no intermediate rounding, whatever order or storage an implementation uses between the two steps.
     Returns (agg_stored, y64) -- agg_stored is the aggregate rounded to the storage dtype, for stage-wise checks --
@@ -237,7 +256,11 @@ def dense_layer(rowptr, col, deg_out, h, layer, dtype, verts=None, round_agg=Fal
         hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
         y = apply(None, hs, None, layer.w_nbr, layer.bias, layer.act)
         return (None, y, None) if return_agg64 else (None, y)
-    a64 = gather(layer.agg, rowptr, col, h, deg_out=deg_out, verts=verts)
+    if getattr(layer, "w_edge", None) is not None:
+        # messages carry the edge's feature vector: m_e = h[u] + ef[e] . W_e (``edge_feat`` [E x d_e], CSR order)
+        a64 = gather_edge_features(layer.agg, rowptr, col, h, edge_feat, layer.w_edge, deg_out=deg_out, verts=verts)
+    else:
+        a64 = gather(layer.agg, rowptr, col, h, deg_out=deg_out, verts=verts)
     a_st = round_store(a64, dtype)
     hs = h if verts is None else np.asarray(h)[np.asarray(verts)]
     if layer.w_self is None:      # no self matrix: the update sees the aggregate only
@@ -267,16 +290,17 @@ def gat_layer(rowptr, col, h, layer, dtype, verts=None):
     return z_st, s_src, s_dst, y64
 
 
-def infer_full_graph(rowptr, col, deg_out, x, layers, dtype, return_all=False):
+def infer_full_graph(rowptr, col, deg_out, x, layers, dtype, return_all=False, edge_feat=None):
     """L layers over every vertex, h^0 = x; each layer's output is rounded once
-    to the storage dtype before the next layer reads it."""
+    to the storage dtype before the next layer reads it.  ``edge_feat`` ([E x d_e], CSR order) feeds the layers
+    that have an edge matrix ``w_edge``."""
     h = x
     outs = []
     for layer in layers:
         if layer.agg == GAT:
             y64 = gat_layer(rowptr, col, h, layer, dtype)[3]
         else:
-            y64 = dense_layer(rowptr, col, deg_out, h, layer, dtype)[1]
+            y64 = dense_layer(rowptr, col, deg_out, h, layer, dtype, edge_feat=edge_feat)[1]
         h = round_store(y64, dtype)
         outs.append(h)
     return outs if return_all else h

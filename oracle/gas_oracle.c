@@ -205,6 +205,57 @@ int oracle_gather_weighted(int agg, int64_t n_nodes, const int64_t *rowptr, cons
 }
 
 /* ---------------------------------------------------------------------------
+ * Gather of messages built from the source's state AND a feature vector of
+ * the edge (Sec. II-A: edges carry a feature matrix E; Sec. II-B: the message
+ * function M takes the neighbour's state and the edge; Sec. IV-B apply_edge).
+ * Reading taken: the message of edge e = (u -> v) is
+ *     m_e = h[u] + ef[e] . W_e          (ef[e] in R^edge_dim, W_e [edge_dim x dim])
+ * i.e. the edge feature is mapped linearly into the state space and added.
+ * The reduce is the layer's aggregator over the messages, one message at a
+ * time, exactly as for plain states:
+ *   sum : agg[v] = sum_e m_e            mean: divided by the number of messages
+ *   GCN : agg[v] = sum_e m_e / sqrt(max(deg_out(u),1) * max(deg_in(v),1))
+ * Edge features are stored per in-edge in CSR order: ef[(rowptr[v] + j) * edge_dim ..].
+ * ------------------------------------------------------------------------- */
+int oracle_gather_edge_features(int agg, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
+                                int64_t dim, const float *h, const int32_t *deg_out,
+                                int64_t edge_dim, const float *ef, const float *w_e,
+                                const int64_t *verts, int64_t n_verts, double *out)
+{
+    if (agg != ORC_SUM && agg != ORC_MEAN && agg != ORC_GCN) return -1;
+    if (agg == ORC_GCN && !deg_out) return -1;
+    if (!ef || !w_e || edge_dim <= 0) return -1;
+    int64_t n_out = verts ? n_verts : n_nodes;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < n_out; ++i) {
+        int64_t v = verts ? verts[i] : i;
+        double *acc = out + i * dim;
+        double *msg = (double *)malloc(sizeof(double) * (size_t)dim);
+        if (!msg) { failed = 1; continue; }
+        for (int64_t k = 0; k < dim; ++k) acc[k] = 0.0;
+        int64_t b = rowptr[v], e = rowptr[v + 1], d = e - b;
+        for (int64_t j = b; j < e; ++j) {
+            int64_t u = col[j];
+            /* the message of this edge */
+            for (int64_t k = 0; k < dim; ++k) msg[k] = (double)h[u * dim + k];
+            for (int64_t t = 0; t < edge_dim; ++t) {
+                double f = (double)ef[j * edge_dim + t];
+                for (int64_t k = 0; k < dim; ++k) msg[k] += f * (double)w_e[t * dim + k];
+            }
+            /* reduced like any message */
+            double c = 1.0;
+            if (agg == ORC_GCN) c = 1.0 / sqrt((deg_out[u] > 1 ? (double)deg_out[u] : 1.0) * (d > 1 ? (double)d : 1.0));
+            for (int64_t k = 0; k < dim; ++k) acc[k] += c * msg[k];
+        }
+        if (agg == ORC_MEAN && d > 0)
+            for (int64_t k = 0; k < dim; ++k) acc[k] /= (double)d;
+        free(msg);
+    }
+    return failed ? -7 : 0;
+}
+
+/* ---------------------------------------------------------------------------
  * Partial-gather over shadow segments (Sec. IV-D "Partial-Gather": aggregate
  * runs on partially available messages, the receiver aggregates the partials;
  * exact because aggregate is commutative and associative).  Non-hub vertices

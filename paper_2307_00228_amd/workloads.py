@@ -93,6 +93,7 @@ class Layer:
     att_src: Optional[np.ndarray] = None   # [heads, d_out/heads] fp32 (GAT)
     att_dst: Optional[np.ndarray] = None
     leaky_slope: float = 0.2
+    w_edge: Optional[np.ndarray] = None    # [d_e, d_in] storage dtype: messages h[u] + ef[e] . W_e (sum / mean / GCN layers)
 
 
 @dataclass

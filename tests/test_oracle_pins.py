@@ -594,3 +594,81 @@ def test_weighted_gather_is_weighted_spmm_and_reduces_to_the_plain_forms():
     assert np.array_equal(oracle.gather_weighted(oracle.SUM, rowptr, col, x, w_csr, verts=verts), got[verts])
     with pytest.raises(ValueError):
         oracle.gather_weighted(oracle.MAX, rowptr, col, x, w_csr)
+
+
+# ---------------------------------------------------------------- messages with edge feature vectors (Sec. II-A E, Sec. II-B M)
+def edge_feature_case(seed, n, e, d, d_e, hub=0.3):
+    """Graph, states, per-edge features in ORIGINAL edge order and in CSR order, edge matrix."""
+    src, dst, x = small_graph(seed, n, e, d, hub=hub)
+    rng = np.random.default_rng(seed + 500)
+    ef_orig = rng.standard_normal((e, d_e)).astype(np.float32)
+    w_e = rng.uniform(-0.5, 0.5, (d_e, d)).astype(np.float32)
+    rowptr, col, deg_out = oracle.build_csr(n, src, dst)
+    order = np.argsort(dst, kind="stable")                # CSR slot -> original edge (the stable grouping, pinned above)
+    return src, dst, x, ef_orig, ef_orig[order], w_e, rowptr, col, deg_out
+
+
+@pytest.mark.parametrize("seed,n,e", [(0, 1, 0), (1, 1, 4), (2, 9, 0), (3, 12, 50), (4, 40, 400)])
+@pytest.mark.parametrize("kind", [oracle.SUM, oracle.MEAN, oracle.GCN])
+def test_edge_feature_gather_matches_brute_force(seed, n, e, kind):
+    """Definition, edge by edge over the ORIGINAL edge list: m_e = h[src] + ef[e] W_e goes to dst (checks the CSR-slot
+    indexing of the feature array as well as the arithmetic)."""
+    d, d_e = 5, 3
+    src, dst, x, ef_orig, ef_csr, w_e, rowptr, col, deg_out = edge_feature_case(seed, n, e, d, d_e)
+    got = oracle.gather_edge_features(kind, rowptr, col, x, ef_csr, w_e, deg_out=deg_out)
+    want = np.zeros((n, d))
+    din = np.bincount(dst, minlength=n).astype(np.float64)
+    dout = np.bincount(src, minlength=n).astype(np.float64)
+    for k in range(e):
+        u, v = int(src[k]), int(dst[k])
+        m = x[u].astype(np.float64).copy()
+        for t in range(d_e):
+            for j in range(d):
+                m[j] += float(ef_orig[k][t]) * float(w_e[t][j])
+        c = 1.0 / math.sqrt(max(dout[u], 1.0) * max(din[v], 1.0)) if kind == oracle.GCN else 1.0
+        want[v] += c * m
+    if kind == oracle.MEAN:
+        want /= np.maximum(din, 1.0)[:, None]
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("kind", [oracle.SUM, oracle.MEAN, oracle.GCN])
+def test_edge_feature_gather_special_cases_and_factorisation(kind):
+    n, e, d, d_e = 60, 900, 7, 4
+    src, dst, x, ef_orig, ef_csr, w_e, rowptr, col, deg_out = edge_feature_case(77, n, e, d, d_e, hub=0.4)
+    plain = oracle.gather(kind, rowptr, col, x, deg_out=deg_out)
+    full = oracle.gather_edge_features(kind, rowptr, col, x, ef_csr, w_e, deg_out=deg_out)
+    # a zero edge matrix leaves the plain aggregate
+    np.testing.assert_allclose(oracle.gather_edge_features(kind, rowptr, col, x, ef_csr, np.zeros_like(w_e), deg_out=deg_out),
+                               plain, rtol=1e-13, atol=1e-13)
+    # zero states leave the reduced edge features times W_e: a sparse matrix over (destination, edge) by scipy
+    coef = np.ones(e)
+    if kind == oracle.GCN:
+        din, dout = np.bincount(dst, minlength=n), np.bincount(src, minlength=n)
+        coef = 1.0 / np.sqrt(np.maximum(dout[src], 1) * np.maximum(din[dst], 1))
+    if kind == oracle.MEAN:
+        coef = 1.0 / np.maximum(np.bincount(dst, minlength=n), 1)[dst]
+    S = sp.csr_matrix((coef, (dst, np.arange(e))), shape=(n, e)) @ ef_orig.astype(np.float64)
+    only_edges = oracle.gather_edge_features(kind, rowptr, col, np.zeros_like(x), ef_csr, w_e, deg_out=deg_out)
+    np.testing.assert_allclose(only_edges, S @ w_e.astype(np.float64), rtol=1e-12, atol=1e-12)
+    # the reduce is linear in the message, so the whole is the sum of the two parts
+    np.testing.assert_allclose(full, plain + S @ w_e.astype(np.float64), rtol=1e-12, atol=1e-12)
+    # sampled vertices agree with the full evaluation; isolated vertices aggregate to zero
+    verts = np.array([0, 3, 59, 17], dtype=np.int64)
+    np.testing.assert_allclose(oracle.gather_edge_features(kind, rowptr, col, x, ef_csr, w_e, deg_out=deg_out, verts=verts),
+                               full[verts], rtol=0, atol=0)
+    iso = np.nonzero(np.diff(rowptr) == 0)[0]
+    assert not full[iso].any()
+
+
+def test_dense_layer_with_edge_features_is_eq1_with_those_messages():
+    from dataclasses import replace
+    n, e, d, d_e = 30, 300, 8, 4
+    src, dst, x, ef_orig, ef_csr, w_e, rowptr, col, deg_out = edge_feature_case(91, n, e, d, d_e)
+    lay = replace(W.dense_layers(np.random.default_rng(92), W.AGG_MEAN, (d, 6, 6), W.F32, bias_random=True)[0], w_edge=w_e)
+    _, y = oracle.dense_layer(rowptr, col, deg_out, x, lay, W.F32, edge_feat=ef_csr)
+    agg = oracle.gather_edge_features(oracle.MEAN, rowptr, col, x, ef_csr, w_e)
+    want = np.maximum(x.astype(np.float64) @ lay.w_self.astype(np.float64) + agg @ lay.w_nbr.astype(np.float64) + lay.bias, 0.0)
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-12)
+    out = oracle.infer_full_graph(rowptr, col, deg_out, x, [lay], W.F32, edge_feat=ef_csr)
+    np.testing.assert_array_equal(out, want.astype(np.float32))
