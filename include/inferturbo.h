@@ -267,6 +267,34 @@ int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes,
                              void *agg_out, int64_t edge_lo, int64_t edge_hi, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * aggregate_edge_features -- the edge half of apply_edge + aggregate for
+ * messages that carry a feature vector of the edge (Sec. II-A: edge feature
+ * matrix E; Sec. II-B: the message function takes the neighbour's state and
+ * the edge; Sec. IV-B apply_edge).  Reading: the message of e = (u -> v) is
+ * h[u] + ef[e] . W_e with W_e [edge_dim x dim].  Sum, mean and the
+ * degree-normalised sum are linear in the message, so
+ *     aggregate(messages)[v] = aggregate(h)[v] + (reduced edge features)[v] . W_e
+ * and the edge features, which do not change from layer to layer, are reduced
+ * per destination ONCE per graph by this call; a layer then multiplies the
+ * result by its W_e (apply_layer) and hands it to gather_layer as `addend`.
+ *
+ *   out[v] = sum over the in-edges e of v of ef[e]          (ITB_AGG_SUM)
+ *            that sum / in-degree, 0 for an isolated vertex  (ITB_AGG_MEAN)
+ *            dst_scale[v] * sum of edge_coef[e] * ef[e]      (ITB_AGG_GCN; both
+ *            arrays required: gcn_norm_scales, gcn_edge_coefficients)
+ *   edge_feat [n_edges x edge_dim] of `dtype`, in CSR order: the rows
+ *             rowptr[v] .. rowptr[v+1]-1 belong to the in-edges of v, so the
+ *             reduce streams the table once.  out [n_nodes x edge_dim], `dtype`.
+ * Hub rows go through the same partial / combine passes as gather_layer
+ * (`split` may be NULL); workspace protocol as everywhere.  Max / min are not
+ * linear in the message and are refused (ITB_ERR_UNSUPPORTED).
+ * ------------------------------------------------------------------------- */
+int32_t aggregate_edge_features(int32_t agg, int32_t dtype, int64_t n_nodes, const int64_t *rowptr,
+                                const itb_split *split, int32_t edge_dim, const void *edge_feat,
+                                const float *edge_coef, const float *dst_scale, void *out,
+                                void *workspace, size_t *workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * apply_layer -- apply_node (Sec. IV-B), the update U of Eq. (1): combine the
  * vertex's former state with the gathered message, then the activation; the
  * store of h_out is the scatter of the new state for the next layer.
@@ -350,6 +378,12 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  * at most 65536 ranges.
  * An ITB_AGG_NONE layer is h' = act(h . w_nbr + bias) per vertex, no edges
  * touched (w_self must be NULL).
+ *   edge_feat  [n_edges x edge_dim] of `dtype`, the feature vector of every
+ *              in-edge in CSR order (row rowptr[v] + j belongs to the j-th
+ *              in-edge of v), or NULL when no layer has an edge matrix.  A
+ *              layer with w_edge takes the messages h[u] + ef[e] . W_e (see
+ *              aggregate_edge_features); edge_dim * sizeof(element) must be a
+ *              multiple of 16.
  *   events     NULL, or a host struct naming a host array of hipEvent_t
  *              handles, four per layer: the call records events[4l + 0..3] on
  *              `stream` at layer l's begin, before its gather, after its
@@ -366,6 +400,7 @@ typedef struct {
     const void *w_nbr;  /* [d_in x d_out]; GAT: the projection */
     const float *bias;  /* [d_out] or NULL */
     const float *att_src, *att_dst; /* GAT: [heads x d_out/heads] */
+    const void *w_edge; /* sum / mean / GCN, optional: [edge_dim x d_in] edge matrix W_e (messages h[u] + ef[e] . W_e) */
 } itb_layer;
 
 typedef struct {
@@ -377,6 +412,7 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
                          const int32_t *deg_out, const itb_split *split,
                          int32_t dtype, int32_t n_layers, const itb_layer *layers,
                          const void *x, void *out, int64_t edge_chunk,
+                         const void *edge_feat, int32_t edge_dim,
                          void *workspace, size_t *workspace_bytes,
                          const itb_stage_events *events, void *stream);
 

@@ -54,7 +54,7 @@ class itb_layer(C.Structure):
     _fields_ = [("agg", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("act", C.c_int32),
                 ("heads", C.c_int32), ("leaky_slope", C.c_float),
                 ("w_self", C.c_void_p), ("w_nbr", C.c_void_p), ("bias", C.c_void_p),
-                ("att_src", C.c_void_p), ("att_dst", C.c_void_p)]
+                ("att_src", C.c_void_p), ("att_dst", C.c_void_p), ("w_edge", C.c_void_p)]
 
 
 class itb_stage_events(C.Structure):
@@ -79,7 +79,8 @@ def _load():
     lib.gather_layer_noalloc.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                          i64, i64, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
-                                     vp, vp, i64, vp, szp, C.POINTER(itb_stage_events), vp]
+                                     vp, vp, i64, vp, i32, vp, szp, C.POINTER(itb_stage_events), vp]
+    lib.aggregate_edge_features.argtypes = [i32, i32, i64, vp, C.POINTER(itb_split), i32, vp, vp, vp, vp, vp, szp, vp]
     lib.itb_shutdown.argtypes = []
     lib.itb_random_row_read.argtypes = [vp, i64, i32, vp, i64, vp, i64, vp]
     lib.hub_threshold_heuristic.argtypes = [i64, i64, C.c_double, C.POINTER(i64)]
@@ -87,7 +88,8 @@ def _load():
     lib.itb_copy_bytes.argtypes = [vp, vp, i64, vp]
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients",
-              "gather_layer_noalloc", "itb_shutdown", "itb_random_row_read", "infer_layer_plan"):
+              "gather_layer_noalloc", "itb_shutdown", "itb_random_row_read", "infer_layer_plan",
+              "aggregate_edge_features"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -274,6 +276,26 @@ def gather_layer_noalloc(agg: int, rowptr, col, h, out: torch.Tensor, split: Opt
     return out
 
 
+def aggregate_edge_features(agg: int, rowptr, edge_feat: torch.Tensor, split: Optional[Split] = None, edge_coef=None,
+                            dst_scale=None, out: Optional[torch.Tensor] = None):
+    """Per-destination reduce of the per-edge feature table ([E x d_e], CSR order): [N x d_e]."""
+    n = rowptr.numel() - 1
+    d_e = edge_feat.shape[1]
+    if out is None:
+        out = torch.empty((n, d_e), dtype=edge_feat.dtype, device="cuda")
+    sp = split.c_struct() if split is not None else None
+    spp = C.byref(sp) if sp is not None else None
+    need = C.c_size_t(0)
+    _check("aggregate_edge_features(size)", lib.aggregate_edge_features(agg, dtype_code(edge_feat), n, None, spp, d_e, None, None,
+                                                                        None, None, None, C.byref(need), None))
+    ws = _workspace(need.value)
+    size = C.c_size_t(ws.numel())
+    _check("aggregate_edge_features", lib.aggregate_edge_features(agg, dtype_code(edge_feat), n, _ptr(rowptr), spp, d_e,
+                                                                  _ptr(edge_feat), _ptr(edge_coef), _ptr(dst_scale), _ptr(out),
+                                                                  _ptr(ws), C.byref(size), _stream()))
+    return out
+
+
 def scale_rows(x: torch.Tensor, row_scale: torch.Tensor, out: Optional[torch.Tensor] = None):
     n, dim = x.shape
     if out is None:
@@ -319,6 +341,7 @@ class DeviceLayer:
     leaky_slope: float = 0.2
     att_src: Optional[torch.Tensor] = None
     att_dst: Optional[torch.Tensor] = None
+    w_edge: Optional[torch.Tensor] = None
 
 
 def _layer_array(layers: List[DeviceLayer]):
@@ -328,7 +351,8 @@ def _layer_array(layers: List[DeviceLayer]):
                            l.w_self.data_ptr() if l.w_self is not None else None, l.w_nbr.data_ptr(),
                            l.bias.data_ptr() if l.bias is not None else None,
                            l.att_src.data_ptr() if l.att_src is not None else None,
-                           l.att_dst.data_ptr() if l.att_dst is not None else None)
+                           l.att_dst.data_ptr() if l.att_dst is not None else None,
+                           l.w_edge.data_ptr() if l.w_edge is not None else None)
     return arr
 
 
@@ -340,20 +364,22 @@ def infer_layer_plan(layers: List["DeviceLayer"], dtype) -> List[int]:
     return list(plan)
 
 
-def infer_workspace_bytes(n_nodes, n_edges, split: Optional[Split], dtype, layers: List[DeviceLayer], edge_chunk=0) -> int:
+def infer_workspace_bytes(n_nodes, n_edges, split: Optional[Split], dtype, layers: List[DeviceLayer], edge_chunk=0,
+                          edge_dim=0) -> int:
     arr = _layer_array(layers)
     sp = split.c_struct() if split is not None else None
     need = C.c_size_t(0)
     _check("infer_full_graph(size)", lib.infer_full_graph(n_nodes, n_edges, None, None, None,
                                                           C.byref(sp) if sp is not None else None,
                                                           ITB_BF16 if dtype == torch.bfloat16 else ITB_F32, len(layers), arr,
-                                                          None, None, edge_chunk, None, C.byref(need), None, None))
+                                                          None, None, edge_chunk, None, edge_dim, None, C.byref(need), None,
+                                                          None))
     return need.value
 
 
 def infer_full_graph(rowptr, col, deg_out, split: Optional[Split], layers: List[DeviceLayer], x,
                      out: Optional[torch.Tensor] = None, edge_chunk: int = 0, workspace: Optional[torch.Tensor] = None,
-                     events=None):
+                     events=None, edge_feat: Optional[torch.Tensor] = None):
     """``events``: optional list of torch.cuda.Event objects (timing enabled, each recorded once so that its handle
     exists), four per layer, which the call records at layer begin / before gather / after gather / layer end."""
     n = x.shape[0]
@@ -363,8 +389,9 @@ def infer_full_graph(rowptr, col, deg_out, split: Optional[Split], layers: List[
     arr = _layer_array(layers)
     sp = split.c_struct() if split is not None else None
     spp = C.byref(sp) if sp is not None else None
+    edge_dim = edge_feat.shape[1] if edge_feat is not None else 0
     if workspace is None:
-        workspace = _workspace(infer_workspace_bytes(n, e, split, x.dtype, layers, edge_chunk))
+        workspace = _workspace(infer_workspace_bytes(n, e, split, x.dtype, layers, edge_chunk, edge_dim))
     size = C.c_size_t(workspace.numel())
     evp = None
     if events:
@@ -372,8 +399,8 @@ def infer_full_graph(rowptr, col, deg_out, split: Optional[Split], layers: List[
         evs = itb_stage_events(handles, len(events))
         evp = C.byref(evs)
     _check("infer_full_graph", lib.infer_full_graph(n, e, _ptr(rowptr), _ptr(col), _ptr(deg_out), spp, dtype_code(x),
-                                                    len(layers), arr, _ptr(x), _ptr(out), edge_chunk, _ptr(workspace),
-                                                    C.byref(size), evp, _stream()))
+                                                    len(layers), arr, _ptr(x), _ptr(out), edge_chunk, _ptr(edge_feat), edge_dim,
+                                                    _ptr(workspace), C.byref(size), evp, _stream()))
     return out
 
 
@@ -402,5 +429,6 @@ def device_layers(layers) -> List[DeviceLayer]:
     out = []
     for l in layers:
         out.append(DeviceLayer(l.agg, l.d_in, l.d_out, l.act, to_device(l.w_self), to_device(l.w_nbr), to_device(l.bias),
-                               l.heads, l.leaky_slope, to_device(l.att_src), to_device(l.att_dst)))
+                               l.heads, l.leaky_slope, to_device(l.att_src), to_device(l.att_dst),
+                               to_device(getattr(l, "w_edge", None))))
     return out

@@ -23,6 +23,7 @@ class LayerTrace:
     projected: bool                 # W_nbr applied before the gather, update fused into the gather's epilogue
     scores: Optional[tuple] = None  # GAT: (s_src, s_dst)
     self_product: Optional[torch.Tensor] = None   # projected layers: h . W_self, the addend of the gather's epilogue
+    edge_term: Optional[torch.Tensor] = None      # layers with an edge matrix: (reduced edge features) . W_e
 
 
 def plan(layers, dtype) -> List[bool]:
@@ -31,7 +32,8 @@ def plan(layers, dtype) -> List[bool]:
 
 
 def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torch.Tensor,
-               mark: Optional[Callable[[str, int], None]] = None, buffers: Optional[dict] = None) -> List[LayerTrace]:
+               mark: Optional[Callable[[str, int], None]] = None, buffers: Optional[dict] = None,
+               edge_feat: Optional[torch.Tensor] = None) -> List[LayerTrace]:
     """``mark(tag, layer)`` is called right before/after the gather and the update of every layer
     (tags: gather_begin, gather_end, apply_begin, apply_end; for sum/mean/GCN layers also project_begin, project_end around
     the optional projection before the gather).  ``buffers`` caches the intermediates across calls."""
@@ -52,6 +54,12 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         cb = buffers.get("edge_coef")
         coef = B.gcn_edge_coefficients(col, ss, out=cb if cb is not None and cb.numel() == col.numel() else None)
         buffers["edge_coef"] = coef
+    # edge features are reduced per destination once per aggregator that a layer with an edge matrix uses
+    edge_sums = {}
+    for l in layers:
+        if l.w_edge is not None and l.agg not in edge_sums:
+            edge_sums[l.agg] = B.aggregate_edge_features(l.agg, rowptr, edge_feat, split, edge_coef=coef if l.agg == B.AGG_GCN else None,
+                                                         dst_scale=sd if l.agg == B.AGG_GCN else None)
     traces = []
     h = x
     projected = plan(layers, x.dtype)
@@ -95,14 +103,17 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
             h = out
             continue
         mark("project_begin", i)
+        edge_term = None
+        if l.w_edge is not None:
+            edge_term = B.apply_layer(None, edge_sums[l.agg], None, l.w_edge, None, B.ACT_NONE, out=buf(("edge", i), l.d_in))
         mark("project_end", i)
         mark("gather_begin", i)
         agg = B.gather_layer(l.agg, rowptr, col, h, split, None, sd if gcn else None, out=buf(("agg", i), h.shape[1]),
-                             edge_coef=coef if gcn else None)
+                             edge_coef=coef if gcn else None, addend=edge_term)
         mark("gather_end", i)
         mark("apply_begin", i)
         B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
         mark("apply_end", i)
-        traces.append(LayerTrace(h, agg, out, False))
+        traces.append(LayerTrace(h, agg, out, False, None, None, edge_term))
         h = out
     return traces

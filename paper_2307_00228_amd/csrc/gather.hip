@@ -89,7 +89,7 @@ __device__ __forceinline__ float ext_sign(int mode) { return mode == kModeMin ? 
 struct GatherArgs {
     int64_t n_nodes;
     const int64_t *rowptr;
-    const int32_t *col;
+    const int32_t *col;      // nullptr: the source row of in-edge e is row e of `h` (a per-edge table in CSR order)
     const uint4 *h;          // [n_nodes x row_vecs] 16-byte vectors
     const float *src_scale;  // nullable: per-source coefficient, looked up per edge
     const float *edge_coef;  // nullable: per-edge coefficient in CSR order (read beside the column index); wins over src_scale
@@ -272,7 +272,7 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
         int myc = 0;
         float mys = unit;
         if (c + lane < deg) {
-            myc = a.col[start + c + lane];
+            myc = a.col ? a.col[start + c + lane] : (int)(start + c + lane);
             if (has_scale) mys = a.edge_coef ? a.edge_coef[start + c + lane] : a.src_scale[myc];
         }
         const int cnt = (deg - c < kWave) ? (int)(deg - c) : kWave;  // wave-uniform
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
                 int myc = 0;
                 float mys = unit;
                 if (j + li < d) {
-                    myc = a.col[st + j + li];
+                    myc = a.col ? a.col[st + j + li] : (int)(st + j + li);
                     if (has_scale) mys = a.edge_coef ? a.edge_coef[st + j + li] : a.src_scale[myc];
                 }
                 const int cnt = d - j;  // edges left for this group (may be <= 0)
@@ -685,10 +685,12 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
 // edge range (see range_bounds_kernel), or nullptr: computed here when the range is not the whole graph.
 // `allow_side`: the hub passes may run on the library's helper stream (false: everything on the caller's stream, no
 // library-owned object is created or touched).
+// `per_edge_rows`: h_src is a table with one row per in-edge in CSR order (edge feature vectors) and `col` is not used:
+// the reduce runs over the rows rowptr[v] .. rowptr[v+1] of that table.
 int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                           const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                           void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
-                          const int64_t *bounds, bool allow_side, void *stream) {
+                          const int64_t *bounds, bool allow_side, void *stream, bool per_edge_rows) {
     if (!desc || !workspace_bytes) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_MIN) return ITB_ERR_DTYPE;
@@ -728,9 +730,9 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     GatherArgs a{};
     a.n_nodes = n_nodes;
     a.rowptr = rowptr;
-    a.col = col;
+    a.col = per_edge_rows ? nullptr : col;
     a.h = static_cast<const uint4 *>(h_src);
-    a.src_scale = (desc->agg == ITB_AGG_GCN) ? src_scale : nullptr;
+    a.src_scale = (desc->agg == ITB_AGG_GCN && !per_edge_rows) ? src_scale : nullptr;
     // per-edge scalar: the source coefficient of a GCN edge, or the weight of an edge-weighted sum / mean
     a.edge_coef = (desc->agg == ITB_AGG_GCN || desc->agg == ITB_AGG_SUM || desc->agg == ITB_AGG_MEAN) ? desc->edge_coef : nullptr;
     a.dst_scale = (desc->agg == ITB_AGG_GCN) ? dst_scale : nullptr;
@@ -835,7 +837,18 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
                                 void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
                                 void *stream) {
     return itb::gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
-                                  workspace, workspace_bytes, nullptr, true, stream);
+                                  workspace, workspace_bytes, nullptr, true, stream, false);
+}
+
+extern "C" int32_t aggregate_edge_features(int32_t agg, int32_t dtype, int64_t n_nodes, const int64_t *rowptr,
+                                           const itb_split *split, int32_t edge_dim, const void *edge_feat,
+                                           const float *edge_coef, const float *dst_scale, void *out, void *workspace,
+                                           size_t *workspace_bytes, void *stream) {
+    if (agg != ITB_AGG_SUM && agg != ITB_AGG_MEAN && agg != ITB_AGG_GCN) return ITB_ERR_UNSUPPORTED;
+    if (agg == ITB_AGG_GCN && workspace && n_nodes > 0 && (!edge_coef || !dst_scale)) return ITB_ERR_NULL;
+    itb_gather_desc d{agg, dtype, dtype, edge_dim, 1, 0.f, ITB_ACT_NONE, nullptr, agg == ITB_AGG_GCN ? edge_coef : nullptr, nullptr};
+    return itb::gather_layer_impl(&d, n_nodes, rowptr, nullptr, split, edge_feat, nullptr, dst_scale, out, 0, INT64_MAX, workspace,
+                                  workspace_bytes, nullptr, true, stream, true);
 }
 
 extern "C" int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
@@ -843,14 +856,14 @@ extern "C" int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_n
                                         const float *dst_scale, void *agg_out, int64_t edge_lo, int64_t edge_hi, void *stream) {
     size_t need = 0;
     int32_t rc = itb::gather_layer_impl(desc, n_nodes, nullptr, nullptr, split, nullptr, nullptr, nullptr, nullptr, edge_lo, edge_hi,
-                                        nullptr, &need, nullptr, false, nullptr);
+                                        nullptr, &need, nullptr, false, nullptr, false);
     if (rc != ITB_OK) return rc;
     if (need > kStaticScratchBytes) return ITB_ERR_WORKSPACE;  // sizes beyond the built-in scratch: use gather_layer
     void *ptr = static_scratch_of_current_device();
     if (!ptr) return ITB_ERR_DEVICE;
     size_t have = kStaticScratchBytes;
     return itb::gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, ptr,
-                                  &have, nullptr, false, stream);
+                                  &have, nullptr, false, stream, false);
 }
 
 extern "C" int32_t itb_shutdown(void) {

@@ -8,7 +8,7 @@ bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_
 int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                           const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                           void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
-                          const int64_t *bounds, bool allow_side, void *stream);
+                          const int64_t *bounds, bool allow_side, void *stream, bool per_edge_rows);
 int32_t enqueue_range_bounds(int64_t n_ranges, int64_t edge_step, int64_t edge_lo, int64_t edge_hi, int64_t n_nodes,
                              const int64_t *rowptr, const itb_split *split, int64_t *out, hipStream_t st);
 }
@@ -133,7 +133,8 @@ extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const
 static bool project_before_gather(const itb_layer &L, int32_t dtype) {
     const int elem = dtype == ITB_BF16 ? 2 : 4;
     const bool linear = L.agg == ITB_AGG_SUM || L.agg == ITB_AGG_MEAN || L.agg == ITB_AGG_GCN;
-    return linear && L.w_self != nullptr && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
+    // (a layer whose messages carry edge features keeps gather -> update: its edge term is added in the state space)
+    return linear && L.w_self != nullptr && !L.w_edge && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
 }
 
 extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_layer *layers, int32_t *plan) {
@@ -154,8 +155,9 @@ extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_l
 
 extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr, const int32_t *col,
                                     const int32_t *deg_out, const itb_split *split, int32_t dtype, int32_t n_layers,
-                                    const itb_layer *layers, const void *x, void *out, int64_t edge_chunk, void *workspace,
-                                    size_t *workspace_bytes, const itb_stage_events *events, void *stream) {
+                                    const itb_layer *layers, const void *x, void *out, int64_t edge_chunk,
+                                    const void *edge_feat, int32_t edge_dim, void *workspace, size_t *workspace_bytes,
+                                    const itb_stage_events *events, void *stream) {
     if (!workspace_bytes || !layers) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || n_edges < 0 || n_edges >= ((int64_t)1 << 31) || n_layers <= 0 ||
         edge_chunk < 0)
@@ -164,6 +166,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     const size_t elem = dtype == ITB_BF16 ? 2 : 4;
     int32_t max_d = 0;
     bool any_gcn = false, any_project = false;
+    bool edge_kind[3] = {false, false, false};  // layers with an edge matrix, by aggregator (sum, mean, GCN)
     int32_t max_heads = 0;
     size_t gather_ws = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -180,6 +183,14 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         }
         any_gcn = any_gcn || L.agg == ITB_AGG_GCN;
         const bool gat = L.agg == ITB_AGG_GAT;
+        if (L.w_edge) {
+            // messages h[u] + ef[e] . W_e: the reduce is linear, so the edge term is (reduced edge features) . W_e
+            if (L.agg != ITB_AGG_SUM && L.agg != ITB_AGG_MEAN && L.agg != ITB_AGG_GCN) return ITB_ERR_UNSUPPORTED;
+            if (edge_dim <= 0 || (edge_dim * (int)elem) % 16 != 0) return ITB_ERR_UNSUPPORTED;
+            if (!apply_shape_supported(dtype, edge_dim, L.d_in, false, 0)) return ITB_ERR_UNSUPPORTED;
+            edge_kind[L.agg] = true;
+            any_project = true;  // the edge term of the layer lives in the projection buffer
+        }
         if (gat && L.heads > max_heads) max_heads = L.heads;
         const bool pf = project_before_gather(L, dtype);
         any_project = any_project || pf;
@@ -208,6 +219,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     float *dst_scale = cv.take<float>(any_gcn ? (size_t)n_nodes : 0);
     float *att_s_src = cv.take<float>((size_t)n_nodes * max_heads);
     float *att_s_dst = cv.take<float>((size_t)n_nodes * max_heads);
+    char *edge_sum[3];
+    for (int k = 0; k < 3; ++k) edge_sum[k] = cv.take<char>(edge_kind[k] ? (size_t)n_nodes * edge_dim * elem : 0);
+    size_t edge_ws = 0;
+    if (edge_kind[0] || edge_kind[1] || edge_kind[2]) {
+        const int32_t rc = aggregate_edge_features(ITB_AGG_SUM, dtype, n_nodes, nullptr, split, edge_dim, nullptr, nullptr, nullptr,
+                                                   nullptr, nullptr, &edge_ws, nullptr);
+        if (rc != ITB_OK) return rc;
+        if (edge_ws > gather_ws) gather_ws = edge_ws;
+    }
     char *gws = cv.take<char>(gather_ws);
     int64_t *range_bounds = cv.take<int64_t>(n_chunks > 1 ? 6 * (size_t)n_chunks : 0);
     if (!workspace) {
@@ -216,6 +236,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     }
     if (*workspace_bytes < cv.off || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return ITB_ERR_WORKSPACE;
     if (!rowptr || (n_nodes > 0 && (!x || !out)) || (n_edges > 0 && !col) || (any_gcn && n_nodes > 0 && !deg_out)) return ITB_ERR_NULL;
+    if ((edge_kind[0] || edge_kind[1] || edge_kind[2]) && n_edges > 0 && !edge_feat) return ITB_ERR_NULL;
     if (n_nodes == 0) return ITB_OK;
 
     if (any_gcn) {
@@ -235,6 +256,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (rc != ITB_OK) return rc;
     }
     const Marks mark{events, stream};
+    // Edge features are static, so their reduce per destination is taken once per aggregator, before the layer loop
+    // (Sec. IV-B: the computation flow may be reorganised as long as the result is the same function).
+    for (int k = 0; k < 3; ++k) {
+        if (!edge_kind[k]) continue;
+        size_t ws = gather_ws;
+        const int32_t rc = aggregate_edge_features(k, dtype, n_nodes, rowptr, split, edge_dim, edge_feat, edge_coef, dst_scale,
+                                                   edge_sum[k], gws, &ws, stream);
+        if (rc != ITB_OK) return rc;
+    }
     char *state[2] = {state0, state1};
     const void *cur = x;
     for (int l = 0; l < n_layers; ++l) {
@@ -285,13 +315,21 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             gd.bias = L.bias;
             gd.act = L.act;
         }
+        if (L.w_edge) {
+            // the edge term of the aggregate, in the state space: (reduced edge features) . W_e, added in the gather's epilogue
+            itb_apply_desc ed{dtype, edge_dim, L.d_in, ITB_ACT_NONE, 0};
+            int32_t rc = apply_layer(&ed, n_nodes, nullptr, edge_sum[L.agg], nullptr, L.w_edge, nullptr, projbuf, nullptr, nullptr,
+                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
+            if (rc != ITB_OK) return rc;
+            gd.addend = projbuf;
+        }
         if (mark(l, 1) != ITB_OK) return ITB_ERR_DEVICE;
         for (int64_t c = 0; c < n_chunks; ++c) {
             const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
             const int64_t hi = (c == n_chunks - 1) ? INT64_MAX : (c + 1) * edge_chunk;
             size_t ws = gather_ws;
             int32_t rc = gather_layer_impl(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws,
-                                           n_chunks > 1 ? range_bounds + 6 * c : nullptr, true, stream);
+                                           n_chunks > 1 ? range_bounds + 6 * c : nullptr, true, stream, false);
             if (rc != ITB_OK) return rc;
         }
         if (mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;

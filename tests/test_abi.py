@@ -46,7 +46,7 @@ def test_struct_layouts_match_header(B):
     assert C.sizeof(B.itb_split) == 8 * 8
     assert C.sizeof(B.itb_gather_desc) == 8 * 4 + 8 + 8 + 8
     assert C.sizeof(B.itb_apply_desc) == 5 * 4
-    assert C.sizeof(B.itb_layer) == 6 * 4 + 5 * 8
+    assert C.sizeof(B.itb_layer) == 6 * 4 + 6 * 8
 
 
 def test_argument_errors_are_reported_on_the_host(B):
@@ -95,13 +95,13 @@ def test_argument_errors_are_reported_on_the_host(B):
     a6 = B.itb_apply_desc(B.ITB_F32, 64, 6, B.ACT_NONE, 0)
     assert lib.apply_layer(C.byref(a6), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None) == -5
     # infer_full_graph
-    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, C.byref(need), None, None) == -1
+    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, 0, None, C.byref(need), None, None) == -1
     lay = (B.itb_layer * 2)()
     lay[0] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_RELU, 1, 0.2, None, None, None, None, None)
     lay[1] = B.itb_layer(B.AGG_MEAN, 48, 16, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
-    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None, None) == -2
+    assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, 0, None, C.byref(need), None, None) == -2
     lay[1] = B.itb_layer(B.AGG_MEAN, 32, 16, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
-    assert lib.infer_full_graph(1000, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, C.byref(need), None, None) == 0
+    assert lib.infer_full_graph(1000, 10, None, None, None, None, 0, 2, lay, None, None, 0, None, 0, None, C.byref(need), None, None) == 0
     assert need.value >= 2 * 1000 * 64 * 4
     # stage events: a negative count is refused before any launch; the handles are per call (no process-wide setter)
     assert C.sizeof(B.itb_stage_events) == 16
@@ -213,8 +213,8 @@ def test_workspace_errors_are_reported_before_anything_is_touched(B):
     assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, odd, C.byref(big), None) == -6
     lay = (B.itb_layer * 1)()
     lay[0] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)
-    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, fake, C.byref(small), None, None) == -6
-    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, odd, C.byref(big), None, None) == -6
+    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, 0, fake, C.byref(small), None, None) == -6
+    assert lib.infer_full_graph(5000, 9000, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, 0, odd, C.byref(big), None, None) == -6
     # with enough (fake) workspace the next check is the missing inputs
     assert lib.gather_layer(C.byref(d), 5000, None, None, None, None, None, None, None, 0, B.INT64_MAX, fake, C.byref(big), None) == -1
 
@@ -234,7 +234,7 @@ def test_gat_and_layer_descriptor_validation(B):
     def infer(layer):
         lay = (B.itb_layer * 1)()
         lay[0] = layer
-        return lib.infer_full_graph(100, 500, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, C.byref(need), None, None)
+        return lib.infer_full_graph(100, 500, None, None, None, None, B.ITB_F32, 1, lay, None, None, 0, None, 0, None, C.byref(need), None, None)
     assert infer(B.itb_layer(B.AGG_MAX, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == 0
     assert infer(B.itb_layer(B.AGG_NONE, 64, 32, B.ACT_NONE, 1, 0.2, None, None, None, None, None)) == 0
     assert infer(B.itb_layer(B.AGG_NONE, 64, 32, B.ACT_NONE, 1, 0.2, C.c_void_p(256), None, None, None, None)) == -5   # no self matrix there

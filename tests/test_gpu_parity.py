@@ -645,6 +645,95 @@ def test_gather_with_fused_update(B, kind, dtype, dim, T):
     check_features(B.to_numpy(out2), a64 + bias, dtype, sum_terms=sum_scale((r, c), x) if kind == W.AGG_SUM else None)
 
 
+# ------------------------------------------------------------------------------------------ edge feature vectors
+def edge_case(seed, n, e, d, d_e, dtype, hub=0.3):
+    src, dst, x = W.random_small_graph(seed, n, e, d, dtype, hub)
+    rng = np.random.default_rng(seed + 1)
+    ef = W.store(rng.standard_normal((e, d_e)).astype(np.float32), dtype)       # per in-edge, CSR order
+    return src, dst, x, ef, rng
+
+
+@pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN])
+@pytest.mark.parametrize("dtype,d_e", [(W.F32, 4), (W.F32, 16), (W.F32, 36), (W.BF16, 8), (W.BF16, 16), (W.BF16, 72)])
+@pytest.mark.parametrize("T", [None, 40])
+def test_aggregate_edge_features(B, kind, dtype, d_e, T):
+    """Per-destination reduce of the per-edge feature table (streamed in CSR order), through short rows, long rows and
+    hub partials; against the oracle's per-edge message gather with zero states and W_e = identity."""
+    import torch
+    n, e = 3000, 50000
+    src, dst, x, ef, _ = edge_case(d_e + 31, n, e, d_e, d_e, dtype)
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp = torch.from_numpy(r).cuda()
+    split = B.split_hubs(rp, T) if T else None
+    coef = sd = None
+    if kind == W.AGG_GCN:
+        ss, sd = B.gcn_norm_scales(rp, torch.from_numpy(d).cuda())
+        coef = B.gcn_edge_coefficients(torch.from_numpy(c).cuda(), ss)
+    B.set_tuning(3, 40)
+    try:
+        got = B.aggregate_edge_features(kind, rp, B.to_device(ef), split, edge_coef=coef, dst_scale=sd)
+        torch.cuda.synchronize()
+    finally:
+        B.set_tuning(3, 512)
+    want = oracle.gather_edge_features(kind, r, c, np.zeros((n, d_e), np.float32), ef, np.eye(d_e, dtype=np.float32), deg_out=d)
+    check_features(B.to_numpy(got), want, dtype, sum_terms=sum_scale_edges(r, ef) if kind == W.AGG_SUM else None)
+
+
+def sum_scale_edges(r, ef):
+    """Root-sum-square of the terms of every element of a per-destination sum of per-edge rows."""
+    import scipy.sparse as sp
+    n, e = len(r) - 1, len(ef)
+    return np.sqrt(sp.csr_matrix((np.ones(e), np.arange(e), r), shape=(n, e)) @ (W.as_f32(ef).astype(np.float64) ** 2))
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+@pytest.mark.parametrize("kinds", [(W.AGG_MEAN, W.AGG_MEAN), (W.AGG_GCN, W.AGG_SUM), (W.AGG_SUM, W.AGG_MAX)])
+def test_layers_with_edge_features(B, dtype, kinds):
+    """Layers whose messages carry an edge feature vector, m_e = h[u] + ef[e] W_e, through infer_full_graph: equal to the
+    call-by-call loop bitwise, chunked or not, and every layer within its bar of Eq. (1) with those messages."""
+    import torch
+    from dataclasses import replace
+    from paper_2307_00228_amd import compose
+    n, e, d_e = 4000, 60000, 8
+    dims = (32, 64, 32)             # the second layer narrows: with an edge matrix it still runs gather -> update
+    src, dst, x, ef, rng = edge_case(51, n, e, dims[0], d_e, dtype)
+    layers = W.dense_layers(rng, list(kinds), dims, dtype, bias_random=True)
+    # edge matrices on every linear layer (the extremum layer, if any, takes plain states)
+    layers = [replace(l, w_edge=W.store(rng.uniform(-0.4, 0.4, (d_e, l.d_in)).astype(np.float32), dtype))
+              if l.agg in (W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN) else l for l in layers]
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    dl, xd, efd = B.device_layers(layers), B.to_device(x), B.to_device(ef)
+    assert compose.plan(dl, xd.dtype) == [False, False]
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    for T in (None, 50):
+        split = B.split_hubs(rowptr, T) if T else None
+        out = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd, edge_feat=efd)
+        chunked = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd, edge_feat=efd, edge_chunk=e // 4)
+        steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd, edge_feat=efd)
+        assert torch.equal(out.view(view), chunked.view(view)) and torch.equal(out.view(view), steps[-1].out.view(view))
+        h = x
+        for i, (lay, tr) in enumerate(zip(layers, steps)):
+            _, y64, a64 = oracle.dense_layer(r, c, d, h, lay, dtype, return_agg64=True, edge_feat=ef)
+            slack = 0.0 if lay.agg == W.AGG_MAX else agg_rounding_slack(a64, lay.w_nbr, dtype)
+            if dtype == W.BF16 and lay.w_edge is not None:
+                # the edge term (reduced edge features, then their product with W_e) is stored in bf16 twice on its way
+                # into the aggregate: each rounding moves it by at most 2^-9 relative
+                et = np.abs(W.as_f32(B.to_numpy(tr.edge_term)).astype(np.float64))
+                slack = slack + 2.0 ** -8 * (et @ np.abs(W.as_f32(lay.w_nbr).astype(np.float64)))
+            # an un-normalised sum makes states in the hundreds on the hub: fp32 holds 1e-4 relative to the magnitude there
+            unnormalised = W.AGG_SUM in kinds
+            check_features(B.to_numpy(tr.out), y64, dtype, f"T={T} layer {i}", slack=slack,
+                           sum_terms=np.abs(y64) if unnormalised else None)
+            h = B.to_numpy(tr.out)
+    # what the reading does not cover is refused: an edge matrix on a max layer, a feature width that is not whole 16-byte rows
+    bad = [replace(layers[0], agg=W.AGG_MAX)]
+    with pytest.raises(B.InferTurboError, match="UNSUPPORTED"):
+        B.infer_full_graph(rowptr, col, deg_out, None, B.device_layers(bad), xd, edge_feat=efd)
+    with pytest.raises(B.InferTurboError, match="UNSUPPORTED"):
+        B.infer_full_graph(rowptr, col, deg_out, None, dl[:1], xd, edge_feat=efd[:, :3].contiguous())
+
+
 def test_gcn_gather_of_prescaled_rows(B):
     import torch
     n, e, dim = 5000, 80000, 128
