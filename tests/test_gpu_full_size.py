@@ -166,33 +166,32 @@ def test_full_size_attention(B):
     assert torch.equal(whole.view(torch.int16), traces[-1].out.view(torch.int16))
 
 
-def test_huge_share_slice_beyond_4gib(B):
-    """The address arithmetic of the largest configuration inside the default run: 5e7 rows, a 6.4 GB state buffer (row
-    offsets beyond 4 GiB), a hub sixty times the threshold, and gathers issued in four edge-range launch sets.  The CSR
-    and the split are compared in full; features on sampled vertices (all hubs, the largest rows, vertices on both sides
-    of the 4 GiB offset), layer by layer from the state the GPU stored."""
+def check_huge(B, name, chunk, min_hub_ratio):
+    """CSR and split compared in full; features on sampled vertices (all hubs, the largest rows, vertices on both sides
+    of the 4 GiB byte offset), layer by layer from the state the GPU stored; the single call in edge-range launch sets
+    bitwise equal to the call-by-call loop."""
     import torch
+    from paper_2307_00228_amd import compose
     say = lambda msg: print(msg, flush=True)
-    w = W.make("huge_share_slice", 1.0, log=say)
+    w = W.make(name, 1.0, log=say)
     n, e = w.n_nodes, w.n_edges
-    assert n * w.layers[0].d_in * 2 > (1 << 32)
+    assert n * w.layers[0].d_in * 2 > (1 << 32) and e > 3 * chunk
     rowptr, col, _ = B.build_csr_by_dst(n, torch.from_numpy(w.src).cuda(), torch.from_numpy(w.dst).cuda(), want_deg_out=False)
     split = B.split_hubs(rowptr, w.threshold)
-    say(f"GPU: {split.n_hubs} hubs, {split.n_shadows} segments; oracle CSR")
+    say(f"GPU: {split.n_hubs} hubs, {split.n_shadows} segments; oracle: counting sort of {e} edges")
     r, c, d = oracle.build_csr(n, w.src, w.dst)
+    say("oracle CSR done; comparing")
     assert np.array_equal(rowptr.cpu().numpy(), r) and np.array_equal(col.cpu().numpy(), c)
     osplit = oracle.split_hubs(r, w.threshold)
-    assert osplit["n_hubs"] > 0 and np.diff(r).max() > 50 * w.threshold
+    assert osplit["n_hubs"] > 0 and np.diff(r).max() > min_hub_ratio * w.threshold
     for k in ("hub_ids", "hub_shadow_off", "shadow_begin", "shadow_end", "shadow_owner"):
         assert np.array_equal(getattr(split, k).cpu().numpy(), osplit[k]), k
     layers = B.device_layers(w.layers)
     x = B.to_device(w.x)
-    chunk = 1 << 26
-    assert e > 3 * chunk
-    from paper_2307_00228_amd import compose
     traces = compose.run_layers(rowptr, col, None, split, layers, x)
     out = B.infer_full_graph(rowptr, col, None, split, layers, x, edge_chunk=chunk)
     assert torch.equal(out.view(torch.int16), traces[-1].out.view(torch.int16))     # chunked == unchunked, bitwise
+    del out
     first_row_beyond = (1 << 32) // (w.layers[0].d_in * 2)
     verts = sample_vertices(np.random.default_rng(8), n, r, osplit, extra=[first_row_beyond - 1, first_row_beyond, n - 1])
     assert (verts >= first_row_beyond).sum() > 500
@@ -208,48 +207,18 @@ def test_huge_share_slice_beyond_4gib(B):
             slack = agg_rounding_slack(a64, lay.w_nbr, w.dtype)
         ok, worst = tolerance_ok(B.to_numpy(tr.out[vt]), y64, w.dtype, slack)
         assert ok, f"layer {i + 1}: {worst}"
-        h_host = B.to_numpy(tr.out)
+        if i + 1 < len(w.layers):
+            h_host = B.to_numpy(tr.out)
+        say(f"layer {i + 1} ok")
 
 
-@pytest.mark.skipif(os.environ.get("ITB_RUN_HUGE") != "1", reason="2e9-edge run: minutes of host-side generation; set ITB_RUN_HUGE=1")
+def test_huge_share_slice_beyond_4gib(B):
+    """The address arithmetic of the largest configuration at a fraction of its edge count: 5e7 rows, a 6.4 GB state
+    buffer (row offsets beyond 4 GiB), a hub sixty times the threshold, gathers issued in four edge-range launch sets."""
+    check_huge(B, "huge_share_slice", 1 << 26, 50)
+
+
 def test_full_size_huge_share(B):
-    """Single-GPU share of a huge graph: 1e8 vertices, 2e9 edges, 8 edge-range chunks of 2^28."""
-    import torch
-    say = lambda msg: print(msg, flush=True)     # run with -s: every stage reports, none is silent for minutes
-    w = W.make("huge_share", 1.0, log=say)
-    n, e = w.n_nodes, w.n_edges
-    say("GPU: build_csr_by_dst + split_hubs")
-    rowptr, col, deg_out = B.build_csr_by_dst(n, torch.from_numpy(w.src).cuda(), torch.from_numpy(w.dst).cuda(), want_deg_out=False)
-    split = B.split_hubs(rowptr, w.threshold)
-    say(f"GPU: {split.n_hubs} hubs, {split.n_shadows} segments; oracle: counting sort of {e} edges")
-    r, c, d = oracle.build_csr(n, w.src, w.dst)
-    say("oracle CSR done; comparing")
-    assert np.array_equal(rowptr.cpu().numpy(), r) and np.array_equal(col.cpu().numpy(), c)
-    osplit = oracle.split_hubs(r, w.threshold)
-    for k in ("hub_ids", "hub_shadow_off", "shadow_begin", "shadow_end", "shadow_owner"):
-        assert np.array_equal(getattr(split, k).cpu().numpy(), osplit[k]), k
-    layers = B.device_layers(w.layers)
-    x = B.to_device(w.x)
-    say("GPU: infer_full_graph in 2^28-edge chunks")
-    torch.cuda.synchronize()
-    import time
-    t0 = time.perf_counter()
-    out = B.infer_full_graph(rowptr, col, None, split, layers, x, edge_chunk=1 << 28)
-    torch.cuda.synchronize()
-    say(f"GPU: infer_full_graph (first call, 2 layers, 8 chunks) {1e3 * (time.perf_counter() - t0):.1f} ms")
-    verts = sample_vertices(np.random.default_rng(7), n, r, osplit)
-    say(f"oracle: {len(verts)} sampled vertices, layer by layer")
-    vt = torch.from_numpy(verts).cuda()
-    agg1 = B.gather_layer(W.AGG_MEAN, rowptr, col, x, split)
-    h1 = B.apply_layer(x, agg1, layers[0].w_self, layers[0].w_nbr, layers[0].bias, layers[0].act)
-    a64 = oracle.gather(oracle.MEAN, r, c, w.x, verts=verts)
-    ok, worst = tolerance_ok(B.to_numpy(agg1[vt]), a64, w.dtype)
-    assert ok, f"layer 1 gather: {worst}"
-    h1_host = B.to_numpy(h1)
-    a64 = oracle.gather(oracle.MEAN, r, c, h1_host, verts=verts)
-    agg2 = B.gather_layer(W.AGG_MEAN, rowptr, col, h1, split)
-    ok, worst = tolerance_ok(B.to_numpy(agg2[vt]), a64, w.dtype)
-    assert ok, f"layer 2 gather: {worst}"
-    y64 = oracle.apply(h1_host[verts], B.to_numpy(agg2[vt]), w.layers[1].w_self, w.layers[1].w_nbr, w.layers[1].bias, w.layers[1].act)
-    ok, worst = tolerance_ok(B.to_numpy(out[vt]), y64, w.dtype)
-    assert ok, f"layer 2 apply (chunked infer_full_graph): {worst}"
+    """Single-GPU share of a huge graph at its stated size: 1e8 vertices, 2e9 edges, 8 edge-range launch sets of 2^28
+    (about a minute and a half, most of it the host-side generation and the oracle's counting sort)."""
+    check_huge(B, "huge_share", 1 << 28, 500)
