@@ -59,7 +59,7 @@ struct ApplyArgs {
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
 // 4 (fp32) or 8 (bf16) consecutive-k weights W[kc*KC + kh*KC/2 + t][col0 + j].
 // `chunks_per_phase` may exceed d_in / KC (the k range is padded to whole k-groups): weights of k >= d_in are zero.
-template <bool BF16, int NT>
+template <bool BF16, int NT, bool DUAL>
 __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &a, int col0, int chunks_per_phase) {
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
@@ -74,7 +74,7 @@ __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &
         const int phase = kcg / chunks_per_phase;
         const int kc = kcg % chunks_per_phase;
         const int lcol = col0 + j;                       // logical column
-        const bool second = lcol >= a.d_out;             // (only with a second product)
+        const bool second = DUAL && lcol >= a.d_out;     // (only with a second product)
         const void *wbase = second ? a.w2 : ((phases == 2 && phase == 0) ? a.w_self : a.w_nbr);
         const int col = second ? lcol - a.d_out : lcol;
         const int k0 = kc * KC + kh * KH;
@@ -194,7 +194,8 @@ __device__ __forceinline__ int stage_swz(int r) { return (r / (16 / LPR)) % LPR;
 // compiler's wait counts for the prefetched rows conservative).
 // GTS > 0: the number of k-groups per row tile is this compile-time constant (even); the tile body is then one
 // straight line of code and the wait counts for the rows in flight are exact.  GTS == 0: any number of groups.
-template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS>
+// DUAL: a second product of the same rows (logical columns d_out .. 2 d_out - 1 belong to w2 / out2).
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL>
 __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a) {
     constexpr int SPARTS = BF16 ? 2 : 1;
     constexpr int BN = 32 * NT;
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     const int chunks = gpp * PF;                                // padded chunks per phase
     const int phases = a.h_self ? 2 : 1;
     const int total = phases * chunks;
-    load_weight_panel<BF16, NT>(wlds, a, col0, chunks);
+    load_weight_panel<BF16, NT, DUAL>(wlds, a, col0, chunks);
     uint4 *slds = wlds + (int64_t)total * 2 * BN;
     if constexpr (SCORES) load_score_panel<BF16>(slds, a, chunks);
     __syncthreads();
@@ -229,7 +230,8 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     uint32_t *stage32 = reinterpret_cast<uint32_t *>(stage);
     const int GT = GTS > 0 ? GTS : phases * gpp;  // groups per row tile
     const int64_t row_vecs = a.d_in / (KC / 2);    // 16-byte pieces of a stored row (2 * chunks unless the k range is padded)
-    const bool padded_k = (int64_t)2 * chunks != row_vecs;
+    // (the variants with a compile-time group count are dispatched for unpadded k ranges only)
+    const bool padded_k = GTS == 0 && (int64_t)2 * chunks != row_vecs;
     const uint4 *wbase = wlds + kh * BN + i;
     const uint4 *sbase = slds + kh * 32 + i;
     const int lr = lane / LPR, lc = lane % LPR;
@@ -275,13 +277,20 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     int g = 0;   // compute cursor: the group whose rows are written to the staging area and multiplied next
 
     auto stage_write = [&](const uint4(&R)[PF]) __attribute__((always_inline)) {
-        // pieces of group g beyond the row's width (padded k range only) enter as zeros
-        const int gi = (g >= gpp) ? g - gpp : g;
-        const bool pad = padded_k && gi * LPR + lc >= (int)row_vecs;
+        if (padded_k) {  // uniform over the launch: pieces of group g beyond the row's width enter as zeros
+            const int gi = (g >= gpp) ? g - gpp : g;
+            const bool pad = gi * LPR + lc >= (int)row_vecs;
 #pragma unroll
-        for (int q = 0; q < PF; ++q) {
-            const int r = q * RPL + lr;
-            stage[r * LPR + (lc ^ stage_swz<LPR>(r))] = pad ? make_uint4(0, 0, 0, 0) : R[q];
+            for (int q = 0; q < PF; ++q) {
+                const int r = q * RPL + lr;
+                stage[r * LPR + (lc ^ stage_swz<LPR>(r))] = pad ? make_uint4(0, 0, 0, 0) : R[q];
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < PF; ++q) {
+                const int r = q * RPL + lr;
+                stage[r * LPR + (lc ^ stage_swz<LPR>(r))] = R[q];
+            }
         }
     };
 
@@ -375,7 +384,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
                 }
                 const int64_t row = m0 + rho;
                 const int col = col0 + nt0 * 32 + u0 * 4;
-                if (row < a.n && u0 * 4 < npass * 32 && col >= a.d_out && col < a.n_cols) {
+                if (DUAL && row < a.n && u0 * 4 < npass * 32 && col >= a.d_out && col < a.n_cols) {
                     // the second product: plain rows of out2 (d_out is a multiple of the vector width here)
                     const int64_t off = row * a.d_out + (col - a.d_out);
                     if constexpr (BF16)
@@ -505,8 +514,8 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
 // chunks of KC values per phase, rounded up to whole groups of pf chunks
 int padded_chunks(int d_in, int kc, int pf) { return ((d_in + kc - 1) / kc + pf - 1) / pf * pf; }
 
-template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS = 0>
-int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL>
+int32_t launch_staged_one(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     constexpr size_t stage_bytes = (size_t)kApplyWaves * ((32 * 2 * PF > 256) ? 32 * 2 * PF : 256) * 16;
     constexpr int KC = BF16 ? 16 : 8;
@@ -516,7 +525,7 @@ int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     // once per kernel variant (setting it again is harmless, so a race between two first callers is too)
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set.store(true, std::memory_order_release);
     }
@@ -528,9 +537,18 @@ int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
+}
+
+// (the second product exists for whole-vector output rows without score columns only)
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS = 0>
+int32_t launch_staged_cfg(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    if constexpr (!SCORES && !RAGGED) {
+        if (a.w2) return launch_staged_one<BF16, NT, PF, SCORES, RAGGED, GTS, true>(a, n_cus, st);
+    }
+    return launch_staged_one<BF16, NT, PF, SCORES, RAGGED, GTS, false>(a, n_cus, st);
 }
 
 // Widest column tile first (fewer re-reads of A), then the largest k-group whose staging still fits the LDS.
@@ -561,10 +579,12 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
         // First choice: a k-group size (8 or 4 chunks) that cuts the row tile into 2, 4, 8 or 16 groups -- those have
         // variants with a compile-time group count (straight-line tile body, exact wait counts; measured 1.5-2x on
         // shapes whose run-time variant waits for every outstanding request at the loop head).
-        if constexpr (!SCORES) {  // (with the score tile the straight-line body runs out of registers)
-            if (nt >= 2) {
+        if constexpr (!SCORES) {  // (with the score tile the straight-line body runs out of registers; so does the widest
+                                  // bf16 tile with a second product)
+            if (nt >= 2 && !(BF16 && nt == 4 && a.w2)) {
                 for (int pf = 8; pf >= 4; pf /= 2) {
                     if (!fits(pf)) continue;
+                    if (padded_chunks(a.d_in, KC, pf) != real_chunks || a.d_in % KC != 0) continue;  // padded k range: run-time variant
                     const int gt = (padded_chunks(a.d_in, KC, pf) / pf) * phases;
 #define ITB_STATIC_CASE(NT_, PF_, GT_) \
     if (nt == NT_ && pf == PF_ && gt == GT_) return launch_staged_cfg<BF16, NT_, PF_, false, false, GT_>(a, n_cus, st);

@@ -139,7 +139,7 @@ __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPer
                                                      int64_t deg, float sd, int vec, int hk, bool lane_on,
                                                      int first_chunk = 0, int chunk_stride = 1) {
     constexpr int NG = kWave / G;
-    constexpr int U = 4;
+    constexpr int U = 4;   // (8 row loads in flight, which pays for the plain gather, measured no gain here)
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
     const int vec_c = lane_on ? vec : 0;   // lanes beyond the row's width read its first vector (never used)
