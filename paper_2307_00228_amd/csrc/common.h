@@ -91,6 +91,22 @@ class SideFork {
     std::unique_lock<std::mutex> lock_;
 };
 
+// Internal knobs of a gather_layer call.
+struct GatherOptions {
+    // device array {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi} of the edge range, or nullptr: computed by the
+    // call itself when the range is not the whole graph
+    const int64_t *bounds = nullptr;
+    // the hub passes may run on the library's helper stream (false: everything on the caller's stream, no
+    // library-owned object is created or touched)
+    bool allow_side = true;
+    // h_src is a table with one row per in-edge in CSR order and `col` is not used
+    bool per_edge_rows = false;
+    // a fork the CALLER has begun and will finish: the hub passes of this call are enqueued on its stream and the
+    // call does not join.  The layer loop uses one fork for all edge ranges of a layer, so that the hub passes of one
+    // range overlap the row passes of the next instead of every range ending in a join.
+    SideFork *outer_fork = nullptr;
+};
+
 constexpr int kWave = 64;
 
 static inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }

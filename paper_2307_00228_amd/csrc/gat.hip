@@ -574,13 +574,14 @@ __global__ __launch_bounds__(1024) void gat_combine_kernel(GatArgs a, int64_t n_
 
 template <bool BF16, int G>
 int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *hub_ids, const int64_t *hub_shadow_off,
-                   bool allow_side, hipStream_t st) {
+                   const itb::GatherOptions &opt, hipStream_t st) {
     const int64_t waves = (a.n_nodes + kWave - 1) / kWave;
     const unsigned gy = (unsigned)((a.row_vecs + G - 1) / G);
     // hub passes first, on the helper stream when there is one (see gather_layer)
-    itb::SideFork fork;
-    {
-        const int32_t rc = fork.begin((hubs && allow_side && itb::g_tuning.overlap_hubs.load()) ? itb::side_stream() : nullptr, st);
+    itb::SideFork own_fork;
+    itb::SideFork &fork = opt.outer_fork ? *opt.outer_fork : own_fork;
+    if (!opt.outer_fork) {
+        const int32_t rc = own_fork.begin((hubs && opt.allow_side && itb::g_tuning.overlap_hubs.load()) ? itb::side_stream() : nullptr, st);
         if (rc != ITB_OK) return rc;
     }
     if (hubs) {
@@ -589,8 +590,10 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
         ITB_LAUNCH_CHECK();
         gat_combine_kernel<BF16><<<(unsigned)n_hubs, 1024, 0, hst>>>(a, n_hubs, hub_ids, hub_shadow_off);
         ITB_LAUNCH_CHECK();
-        const int32_t rc = fork.mark_done();
-        if (rc != ITB_OK) return rc;
+        if (!opt.outer_fork) {
+            const int32_t rc = own_fork.mark_done();
+            if (rc != ITB_OK) return rc;
+        }
     }
     zero_u32_kernel<<<1, 1, 0, st>>>(a.long_count);
     ITB_LAUNCH_CHECK();
@@ -600,20 +603,20 @@ int32_t launch_all(const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *h
     int64_t lg = waves > 2048 ? 2048 : waves;  // fixed grid over the device-side work list
     gat_long_rows_kernel<BF16, G><<<dim3((unsigned)lg, gy), kRangeWaves * kWave, 0, st>>>(a);
     ITB_LAUNCH_CHECK();
-    return fork.finish();
+    return opt.outer_fork ? ITB_OK : own_fork.finish();
 }
 
 template <bool BF16>
 int32_t dispatch(int G, const GatArgs &a, bool hubs, int64_t n_hubs, const int32_t *hub_ids, const int64_t *hub_shadow_off,
-                 bool allow_side, hipStream_t st) {
+                 const itb::GatherOptions &opt, hipStream_t st) {
     switch (G) {
-        case 1: return launch_all<BF16, 1>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
-        case 2: return launch_all<BF16, 2>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
-        case 4: return launch_all<BF16, 4>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
-        case 8: return launch_all<BF16, 8>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
-        case 16: return launch_all<BF16, 16>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
-        case 32: return launch_all<BF16, 32>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
-        default: return launch_all<BF16, 64>(a, hubs, n_hubs, hub_ids, hub_shadow_off, allow_side, st);
+        case 1: return launch_all<BF16, 1>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
+        case 2: return launch_all<BF16, 2>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
+        case 4: return launch_all<BF16, 4>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
+        case 8: return launch_all<BF16, 8>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
+        case 16: return launch_all<BF16, 16>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
+        case 32: return launch_all<BF16, 32>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
+        default: return launch_all<BF16, 64>(a, hubs, n_hubs, hub_ids, hub_shadow_off, opt, st);
     }
 }
 
@@ -623,8 +626,9 @@ namespace itb {
 
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
-                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, const int64_t *bounds,
-                        bool allow_side, hipStream_t st) {
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, const GatherOptions &opt,
+                        hipStream_t st) {
+    const int64_t *bounds = opt.bounds;
     const bool bf16 = desc->dtype_in == ITB_BF16;
     if (desc->dtype_out != desc->dtype_in) return ITB_ERR_UNSUPPORTED;
     if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
@@ -692,8 +696,8 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
         a.part_l = part_l;
     }
     return bf16 ? dispatch<true>(G, a, hubs, hubs ? split->n_hubs : 0, hubs ? split->hub_ids : nullptr,
-                                 hubs ? split->hub_shadow_off : nullptr, allow_side, st)
+                                 hubs ? split->hub_shadow_off : nullptr, opt, st)
                 : dispatch<false>(G, a, hubs, hubs ? split->n_hubs : 0, hubs ? split->hub_ids : nullptr,
-                                  hubs ? split->hub_shadow_off : nullptr, allow_side, st);
+                                  hubs ? split->hub_shadow_off : nullptr, opt, st);
 }
 }  // namespace itb

@@ -678,19 +678,16 @@ int32_t dispatch_segments(int G, const GatherArgs &a, hipStream_t st) {
 namespace itb {
 int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                         const itb_split *split, const void *z, const float *s_src, const float *s_dst, void *out,
-                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, const int64_t *bounds,
-                        bool allow_side, hipStream_t st);
+                        int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes, const GatherOptions &opt,
+                        hipStream_t st);
 
-// gather_layer with two internal knobs.  `bounds`: device array {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi} of the
-// edge range (see range_bounds_kernel), or nullptr: computed here when the range is not the whole graph.
-// `allow_side`: the hub passes may run on the library's helper stream (false: everything on the caller's stream, no
-// library-owned object is created or touched).
-// `per_edge_rows`: h_src is a table with one row per in-edge in CSR order (edge feature vectors) and `col` is not used:
-// the reduce runs over the rows rowptr[v] .. rowptr[v+1] of that table.
+// gather_layer with its internal knobs (see GatherOptions).
 int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                           const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                           void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
-                          const int64_t *bounds, bool allow_side, void *stream, bool per_edge_rows) {
+                          const GatherOptions &opt, void *stream) {
+    const int64_t *bounds = opt.bounds;
+    const bool per_edge_rows = opt.per_edge_rows;
     if (!desc || !workspace_bytes) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->agg < ITB_AGG_SUM || desc->agg > ITB_AGG_MIN) return ITB_ERR_DTYPE;
@@ -703,7 +700,7 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     if (split && (split->threshold <= 0 || split->n_hubs < 0 || split->n_shadows < 0)) return ITB_ERR_SIZE;
     if (desc->agg == ITB_AGG_GAT)
         return gat_gather_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
-                               workspace, workspace_bytes, bounds, allow_side, static_cast<hipStream_t>(stream));
+                               workspace, workspace_bytes, opt, static_cast<hipStream_t>(stream));
 
     if (desc->act != ITB_ACT_NONE && desc->act != ITB_ACT_RELU) return ITB_ERR_DTYPE;
     // bias and addend are read as 16-byte vectors
@@ -772,9 +769,12 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     int32_t rc;
     // The hub passes touch other rows and other workspace than the row passes: they go first and, when the helper
     // stream exists, run beside the row passes, whose many small blocks fill the gaps the large segment blocks leave.
-    SideFork fork;
-    rc = fork.begin((hubs && allow_side && g_tuning.overlap_hubs.load()) ? side_stream() : nullptr, st);
-    if (rc != ITB_OK) return rc;
+    SideFork own_fork;
+    SideFork &fork = opt.outer_fork ? *opt.outer_fork : own_fork;
+    if (!opt.outer_fork) {
+        rc = own_fork.begin((hubs && opt.allow_side && g_tuning.overlap_hubs.load()) ? side_stream() : nullptr, st);
+        if (rc != ITB_OK) return rc;
+    }
     if (hubs) {
         hipStream_t hst = fork.stream();
         GatherArgs s = a;
@@ -792,8 +792,10 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
                                                            rowptr, a.dst_scale, a.mode, edge_lo, edge_hi, agg_out, a.addend, a.bias,
                                                            a.act, a.bounds);
         ITB_LAUNCH_CHECK();
-        rc = fork.mark_done();
-        if (rc != ITB_OK) return rc;
+        if (!opt.outer_fork) {
+            rc = own_fork.mark_done();
+            if (rc != ITB_OK) return rc;
+        }
     }
     if (ext) {
         if (!bin) rc = dispatch_rows<false, false, true>(G, a, st);
@@ -805,7 +807,7 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
         else rc = dispatch_rows<true, false, false>(G, a, st);
     }
     if (rc != ITB_OK) return rc;
-    return fork.finish();
+    return opt.outer_fork ? ITB_OK : own_fork.finish();
 }
 }  // namespace itb
 
@@ -837,7 +839,7 @@ extern "C" int32_t gather_layer(const itb_gather_desc *desc, int64_t n_nodes, co
                                 void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
                                 void *stream) {
     return itb::gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi,
-                                  workspace, workspace_bytes, nullptr, true, stream, false);
+                                  workspace, workspace_bytes, GatherOptions{}, stream);
 }
 
 extern "C" int32_t aggregate_edge_features(int32_t agg, int32_t dtype, int64_t n_nodes, const int64_t *rowptr,
@@ -847,23 +849,27 @@ extern "C" int32_t aggregate_edge_features(int32_t agg, int32_t dtype, int64_t n
     if (agg != ITB_AGG_SUM && agg != ITB_AGG_MEAN && agg != ITB_AGG_GCN) return ITB_ERR_UNSUPPORTED;
     if (agg == ITB_AGG_GCN && workspace && n_nodes > 0 && (!edge_coef || !dst_scale)) return ITB_ERR_NULL;
     itb_gather_desc d{agg, dtype, dtype, edge_dim, 1, 0.f, ITB_ACT_NONE, nullptr, agg == ITB_AGG_GCN ? edge_coef : nullptr, nullptr};
+    itb::GatherOptions opt;
+    opt.per_edge_rows = true;
     return itb::gather_layer_impl(&d, n_nodes, rowptr, nullptr, split, edge_feat, nullptr, dst_scale, out, 0, INT64_MAX, workspace,
-                                  workspace_bytes, nullptr, true, stream, true);
+                                  workspace_bytes, opt, stream);
 }
 
 extern "C" int32_t gather_layer_noalloc(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                                         const itb_split *split, const void *h_src, const float *src_scale,
                                         const float *dst_scale, void *agg_out, int64_t edge_lo, int64_t edge_hi, void *stream) {
     size_t need = 0;
+    itb::GatherOptions opt;
+    opt.allow_side = false;
     int32_t rc = itb::gather_layer_impl(desc, n_nodes, nullptr, nullptr, split, nullptr, nullptr, nullptr, nullptr, edge_lo, edge_hi,
-                                        nullptr, &need, nullptr, false, nullptr, false);
+                                        nullptr, &need, opt, nullptr);
     if (rc != ITB_OK) return rc;
     if (need > kStaticScratchBytes) return ITB_ERR_WORKSPACE;  // sizes beyond the built-in scratch: use gather_layer
     void *ptr = static_scratch_of_current_device();
     if (!ptr) return ITB_ERR_DEVICE;
     size_t have = kStaticScratchBytes;
     return itb::gather_layer_impl(desc, n_nodes, rowptr, col, split, h_src, src_scale, dst_scale, agg_out, edge_lo, edge_hi, ptr,
-                                  &have, nullptr, false, stream, false);
+                                  &have, opt, stream);
 }
 
 extern "C" int32_t itb_shutdown(void) {

@@ -8,7 +8,8 @@ bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_
 int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                           const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                           void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
-                          const int64_t *bounds, bool allow_side, void *stream, bool per_edge_rows);
+                          const GatherOptions &opt, void *stream);
+SideStream *side_stream();
 int32_t enqueue_range_bounds(int64_t n_ranges, int64_t edge_step, int64_t edge_lo, int64_t edge_hi, int64_t n_nodes,
                              const int64_t *rowptr, const itb_split *split, int64_t *out, hipStream_t st);
 }
@@ -324,12 +325,28 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             gd.addend = projbuf;
         }
         if (mark(l, 1) != ITB_OK) return ITB_ERR_DEVICE;
-        for (int64_t c = 0; c < n_chunks; ++c) {
-            const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
-            const int64_t hi = (c == n_chunks - 1) ? INT64_MAX : (c + 1) * edge_chunk;
-            size_t ws = gather_ws;
-            int32_t rc = gather_layer_impl(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi, gws, &ws,
-                                           n_chunks > 1 ? range_bounds + 6 * c : nullptr, true, stream, false);
+        {
+            // One fork of the helper stream for all edge ranges of the layer: the hub passes of the ranges queue up on the
+            // helper stream, the row passes on the caller's, and the two streams meet once, after the last range
+            // (ranges write disjoint rows; the partials buffer is reused in helper-stream order).
+            SideFork layer_fork;
+            GatherOptions opt;
+            const bool hubs = split && split->n_hubs > 0;
+            if (n_chunks > 1 && hubs && g_tuning.overlap_hubs.load()) {
+                const int32_t rc = layer_fork.begin(side_stream(), static_cast<hipStream_t>(stream));
+                if (rc != ITB_OK) return rc;
+                opt.outer_fork = &layer_fork;
+            }
+            for (int64_t c = 0; c < n_chunks; ++c) {
+                const int64_t lo = (n_chunks == 1) ? 0 : c * edge_chunk;
+                const int64_t hi = (c == n_chunks - 1) ? INT64_MAX : (c + 1) * edge_chunk;
+                size_t ws = gather_ws;
+                opt.bounds = n_chunks > 1 ? range_bounds + 6 * c : nullptr;
+                const int32_t rc = gather_layer_impl(&gd, n_nodes, rowptr, col, split, gather_src, gs, gd_scale, gather_out, lo, hi,
+                                                     gws, &ws, opt, stream);
+                if (rc != ITB_OK) return rc;   // (layer_fork joins in its destructor)
+            }
+            const int32_t rc = layer_fork.finish();
             if (rc != ITB_OK) return rc;
         }
         if (mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;
