@@ -1084,3 +1084,27 @@ def test_readme_example_runs(B):
     assert tuple(out.shape) == (w.n_nodes, w.layers[-1].d_out) and tuple(agg.shape) == (w.n_nodes, w.layers[0].d_in)
     r, c, d = oracle.build_csr(w.n_nodes, w.src, w.dst)
     check_features(B.to_numpy(out), W.as_f32(oracle.infer_full_graph(r, c, d, w.x, w.layers, w.dtype)), w.dtype)
+
+
+def test_shutdown_releases_the_helper_stream_and_later_calls_recreate_it(B):
+    """itb_shutdown destroys the library-owned helper stream and its events; it is not terminal: the next call that wants
+    the helper stream makes a new one, and the results are the same bits as before."""
+    import torch
+    n, e = 4000, 60000
+    src, dst, x = W.random_small_graph(77, n, e, 64, W.F32, 0.3)
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp, cl = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()
+    split = B.split_hubs(rp, 500)
+    assert split.n_hubs >= 1
+    h = B.to_device(x)
+    first = B.gather_layer(W.AGG_MEAN, rp, cl, h, split, None, None)      # hubs: uses the helper stream
+    torch.cuda.synchronize()
+    B.shutdown()
+    B.shutdown()                                                          # idempotent
+    second = B.gather_layer(W.AGG_MEAN, rp, cl, h, split, None, None)
+    src_d, dst_d = dev_i32(src), dev_i32(dst)
+    rp2, cl2, deg2 = B.build_csr_by_dst(n, src_d, dst_d)                  # the out-degree branch forks as well
+    torch.cuda.synchronize()
+    assert torch.equal(first, second)
+    assert torch.equal(rp2, rp) and torch.equal(cl2, cl) and np.array_equal(deg2.cpu().numpy(), d)
+    check_features(B.to_numpy(second), oracle.gather(W.AGG_MEAN, r, c, x, deg_out=d), W.F32)
