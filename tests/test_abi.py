@@ -260,3 +260,50 @@ def test_misaligned_feature_tensors_are_refused(B):
     assert ap(None, off, ok, None) == -5 and ap(None, ok, off, None) == -5
     assert ap(off, ok, ok, None) == -5 and ap(None, ok, ok, off) == -5
     assert lib.scale_rows(B.ITB_F32, 10, 64, off, ok, ok, None) == -5
+
+
+def test_headers_are_plain_c_and_the_binding_mirrors_their_layout(B, tmp_path):
+    """Both headers compile as strict C11 on their own (no C++-only construct, no torch or HIP type), and every struct
+    field offset, struct size and enumerator the ctypes binding retypes equals what the C compiler derives from the header."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    structs = {"itb_split": B.itb_split, "itb_gather_desc": B.itb_gather_desc, "itb_apply_desc": B.itb_apply_desc,
+               "itb_layer": B.itb_layer, "itb_stage_events": B.itb_stage_events}
+    enums = {"ITB_F32": B.ITB_F32, "ITB_BF16": B.ITB_BF16, "ITB_AGG_SUM": B.AGG_SUM, "ITB_AGG_MEAN": B.AGG_MEAN,
+             "ITB_AGG_GCN": B.AGG_GCN, "ITB_AGG_GAT": B.AGG_GAT, "ITB_AGG_MAX": B.AGG_MAX, "ITB_AGG_MIN": B.AGG_MIN,
+             "ITB_AGG_NONE": B.AGG_NONE, "ITB_ACT_NONE": B.ACT_NONE, "ITB_ACT_RELU": B.ACT_RELU,
+             "ITB_PLAN_GATHER_UPDATE": B.PLAN_GATHER_UPDATE, "ITB_PLAN_PROJECT_GATHER": B.PLAN_PROJECT_GATHER,
+             "ITB_PLAN_ATTENTION": B.PLAN_ATTENTION, "ITB_PLAN_UPDATE_ONLY": B.PLAN_UPDATE_ONLY}
+    enums.update({name: code for code, name in B.STATUS.items()})
+    lines = ['#include "inferturbo.h"', '#include "inferturbo_aids.h"', "#include <stddef.h>", "#include <stdio.h>",
+             "int main(void) {"]
+    for name, cls in structs.items():
+        lines.append(f'  printf("{name} %zu\\n", sizeof({name}));')
+        for field, _ in cls._fields_:
+            lines.append(f'  printf("{name}.{field} %zu\\n", offsetof({name}, {field}));')
+    for name in enums:
+        lines.append(f'  printf("{name} %d\\n", (int){name});')
+    lines.append('  printf("ITB_NOALLOC_SCRATCH_BYTES %u\\n", (unsigned)ITB_NOALLOC_SCRATCH_BYTES);')
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                    str(exe)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for name, cls in structs.items():
+        assert int(got[name]) == C.sizeof(cls), name
+        for field, _ in cls._fields_:
+            assert int(got[f"{name}.{field}"]) == getattr(cls, field).offset, (name, field)
+    for name, value in enums.items():
+        assert int(got[name]) == value, name
+    assert int(got["ITB_NOALLOC_SCRATCH_BYTES"]) == 16 << 20
+    # every header also compiles when it is the only one included
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        one = tmp_path / f"only_{header}.c"
+        one.write_text(f'#include "{header}"\nint unused_{header.split(".")[0]};\n')
+        subprocess.run([gcc, "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"),
+                        str(one)], check=True)
