@@ -296,11 +296,21 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *ke
 // slots of the wave + lower lanes of the slot.  The tile is first put in digit order in LDS and then written
 // out by consecutive threads, so that each digit's run leaves the block as contiguous, coalesced stores
 // (scattering straight from registers costs one memory transaction per 4-byte element).
-template <bool HAS_VALS>
+//
+// LAST (the pass over the top digit of the pair sort): the sorted keys themselves are wanted only for the row
+// pointers, so they are not written.  A digit's run of a tile is a contiguous piece of the final order: every key of
+// the run that differs from the key before it in the run starts a row (and the empty rows just before it) at its
+// global position, stored here; what the run cannot see -- whether its FIRST key continues the row that ends the
+// previous non-empty run -- is left to rowptr_run_starts_kernel, for which the first and last key of every run are
+// kept in `run_keys` (two arrays in the histogram's layout).
+// BITS > 0: the digit width as a compile-time constant (the vote loop unrolls into straight-line code, 6 vector
+// instructions per bit); BITS == 0: any width, taken from the `bits` argument.
+template <bool HAS_VALS, bool LAST, int BITS>
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t *keys_in, const int32_t *vals_in,
                                                                  uint32_t *keys_out, int32_t *vals_out, int64_t n,
                                                                  int shift, int bits, const uint32_t *hist_scanned,
-                                                                 int64_t nblocks, int remap) {
+                                                                 int64_t nblocks, int remap, int64_t n_nodes,
+                                                                 int64_t *rowptr, uint32_t *run_keys) {
     __shared__ uint32_t cnt[kWaves][kMaxRadix];   // per wave and digit: count, then start inside the sorted tile
     __shared__ uint32_t gbase[kMaxRadix];         // global position of the tile's first key of the digit
     __shared__ uint32_t lstart[kMaxRadix];        // position of the digit's first key inside the sorted tile
@@ -333,12 +343,23 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t 
         const int64_t idx = wave_base + s * kWave + lane;
         const bool valid = idx < n;
         const uint32_t d = (key[s] >> shift) & mask;
-        uint64_t peers = __ballot(valid);
-        for (int b = 0; b < bits; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const uint64_t vote = __ballot(valid && bit);
-            peers &= bit ? vote : ~vote;
+        // lanes of this slot with the same digit: one vote per bit; a lane keeps the voters when its own bit is set
+        // and the others when it is not (an invalid lane holds key 0, so it never votes and is masked out by `all`)
+        const uint64_t all = __ballot(valid);
+        uint32_t peers_lo = (uint32_t)all, peers_hi = (uint32_t)(all >> 32);
+        auto vote_on = [&](int b) {
+            const uint32_t own = 0u - ((d >> b) & 1u);  // all ones when the lane's bit is set
+            const uint64_t vote = __ballot(own != 0u);
+            peers_lo &= ~((uint32_t)vote ^ own);
+            peers_hi &= ~((uint32_t)(vote >> 32) ^ own);
+        };
+        if constexpr (BITS > 0) {
+#pragma unroll
+            for (int b = 0; b < BITS; ++b) vote_on(b);
+        } else {
+            for (int b = 0; b < bits; ++b) vote_on(b);
         }
+        const uint64_t peers = ((uint64_t)peers_hi << 32) | peers_lo;
         const uint32_t prev = valid ? cnt[w][d] : 0u;
         rank[s] = prev + (uint32_t)__popcll(peers & lower);
         __builtin_amdgcn_wave_barrier();
@@ -371,12 +392,66 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t 
         }
     }
     __syncthreads();
+    if constexpr (LAST) {
+        if (threadIdx.x < radix && total_d > 0) {
+            const int64_t e = (int64_t)threadIdx.x * nblocks + tile;
+            run_keys[e] = skey[ls];
+            run_keys[(int64_t)radix * nblocks + e] = skey[ls + total_d - 1];
+        }
+    }
     for (uint32_t i = threadIdx.x; i < tile_total; i += kThreads) {
         const uint32_t k = skey[i];
         const uint32_t d = (k >> shift) & mask;
         const uint32_t pos = gbase[d] + (i - lstart[d]);
-        keys_out[pos] = k;
+        if constexpr (LAST) {
+            // rows (kp, k] start here when the key before this one in the run, kp, differs; the first key of a run
+            // takes kp = k, which leaves the loop empty (ids are clamped so that invalid input cannot run it long)
+            const uint32_t ls_d = lstart[d];
+            const uint32_t kp = i > ls_d ? skey[i - 1] : k;
+            const uint32_t hi = k < (uint32_t)n_nodes ? k : (uint32_t)n_nodes;
+            for (uint32_t v = (kp < 0x7fffffffu ? kp : 0x7fffffffu) + 1u; v <= hi; ++v) rowptr[v] = (int64_t)pos;
+        } else {
+            keys_out[pos] = k;
+        }
         if constexpr (HAS_VALS) vals_out[pos] = sval[i];
+    }
+}
+
+// Row pointers at the run starts of the last pass.  Entry e = digit * nblocks + tile of the scanned histogram is a
+// run of the final order starting at position gb[e]; entries in ascending e are consecutive pieces of that order.  For
+// a non-empty run the key before its first key is the last key of the closest non-empty run before it (normally
+// e - 1; otherwise found by bisection of the non-decreasing gb, so that long stretches of empty runs cost
+// nothing).  The first run of all also starts the rows from 0, the last one ends the rows up to n_nodes.
+__global__ void rowptr_run_starts_kernel(const uint32_t *gb, const uint32_t *run_keys, int64_t n_entries, int64_t n_edges,
+                                         int64_t n_nodes, int64_t *rowptr) {
+    const uint32_t *first_key = run_keys, *last_key = run_keys + n_entries;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n_entries; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t start = gb[e];
+        const int64_t end = e + 1 < n_entries ? (int64_t)gb[e + 1] : n_edges;
+        if (end == start) continue;
+        int64_t kp = -1;
+        if (start > 0) {
+            int64_t prev = e - 1;
+            if ((int64_t)gb[prev] == start) {
+                // first entry whose start equals this one's, minus one: that run is non-empty and ends at `start`
+                int64_t lo = 0, hi = prev;  // invariant: gb[hi] == start, gb[lo] < start or lo == 0
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if ((int64_t)gb[mid] < start) lo = mid + 1; else hi = mid;
+                }
+                prev = lo - 1;
+            }
+            kp = last_key[prev];
+        }
+        const int64_t k = first_key[e];
+        if (k != kp) {
+            const int64_t hi = k < n_nodes ? k : n_nodes;
+            for (int64_t v = kp + 1; v <= hi; ++v) rowptr[v] = start;
+        }
+        if (end == n_edges) {
+            const int64_t kl = last_key[e];
+            for (int64_t v = kl + 1; v <= n_nodes; ++v) rowptr[v] = n_edges;
+        }
     }
 }
 
@@ -511,6 +586,34 @@ __global__ void adjacent_difference_kernel(const uint32_t *bounds, int64_t n, in
         out[v] = (int32_t)(bounds[v + 1] - bounds[v]);
 }
 
+template <bool HAS_VALS, bool LAST>
+void launch_scatter_bits(int bits, unsigned grid, hipStream_t st, const uint32_t *kin, const int32_t *vin, uint32_t *kout, int32_t *vout,
+                         int64_t n, int shift, const uint32_t *h, int64_t nblocks, int remap, int64_t n_nodes, int64_t *rowptr,
+                         uint32_t *run_keys) {
+#define ITB_SCATTER(B)                                                                                                          \
+    radix_scatter_kernel<HAS_VALS, LAST, B><<<grid, kThreads, 0, st>>>(kin, vin, kout, vout, n, shift, bits, h, nblocks, remap, \
+                                                                       n_nodes, rowptr, run_keys)
+    switch (bits) {  // the widths that graphs beyond a few thousand vertices use get straight-line vote code
+        case 5: ITB_SCATTER(5); break;
+        case 6: ITB_SCATTER(6); break;
+        case 7: ITB_SCATTER(7); break;
+        case 8: ITB_SCATTER(8); break;
+        default: ITB_SCATTER(0); break;
+    }
+#undef ITB_SCATTER
+}
+
+void launch_scatter(bool pairs, bool last, int bits, unsigned grid, hipStream_t st, const uint32_t *kin, const int32_t *vin,
+                    uint32_t *kout, int32_t *vout, int64_t n, int shift, const uint32_t *h, int64_t nblocks, int remap,
+                    int64_t n_nodes, int64_t *rowptr, uint32_t *run_keys) {
+    if (last)
+        launch_scatter_bits<true, true>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys);
+    else if (pairs)
+        launch_scatter_bits<true, false>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys);
+    else
+        launch_scatter_bits<false, false>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys);
+}
+
 int ceil_log2(int64_t n) {
     int b = 0;
     while (((int64_t)1 << b) < n) ++b;
@@ -548,6 +651,7 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
     uint32_t *scan_ws_deg = cv.take<uint32_t>(scan_workspace_elems(part_hist_elems) + 64);
     uint16_t *low_keys = cv.take<uint16_t>((size_t)n_edges);
     uint32_t *bounds = cv.take<uint32_t>((size_t)n_nodes + 1);
+    uint32_t *run_keys = cv.take<uint32_t>(2 * (size_t)hist_elems);  // first and last key of every run of the last pass
     if (!workspace) {
         *workspace_bytes = cv.off;
         return ITB_OK;
@@ -644,12 +748,13 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
             }
             int32_t rc = exclusive_scan_u32(h, hist_n, scan_ws, st);
             if (rc != ITB_OK) return rc;
-            if (pairs)
-                radix_scatter_kernel<true><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, vin, kout, vout, n_edges, shift, bits, h,
-                                                                                   nblocks, xcd_remap);
-            else
-                radix_scatter_kernel<false><<<(unsigned)nblocks, kThreads, 0, st>>>(kin, nullptr, kout, nullptr, n_edges, shift, bits,
-                                                                                    h, nblocks, xcd_remap);
+            const bool last = pairs && p == passes - 1;
+            // last pass of the pair sort: no sorted keys are written, the row pointers come from the runs themselves
+            launch_scatter(pairs, last, bits, (unsigned)nblocks, st, kin, pairs ? vin : nullptr, last ? nullptr : kout,
+                           pairs ? vout : nullptr, n_edges, shift, h, nblocks, xcd_remap, n_nodes, last ? rowptr : nullptr,
+                           last ? run_keys : nullptr);
+            ITB_LAUNCH_CHECK();
+            if (last) rowptr_run_starts_kernel<<<grid_for(hist_n, 256), 256, 0, st>>>(h, run_keys, hist_n, n_edges, n_nodes, rowptr);
             ITB_LAUNCH_CHECK();
             kin = kout;
             vin = vout;
@@ -662,9 +767,6 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
             ITB_LAUNCH_CHECK();
         }
     }
-    rowptr_from_sorted_kernel<int64_t><<<grid_for(n_edges, 256), 256, 0, st>>>(kin, n_edges, n_nodes, rowptr);
-    ITB_LAUNCH_CHECK();
-
     {
         const int32_t rc = fork.finish();
         if (rc != ITB_OK) return rc;
