@@ -83,8 +83,9 @@ __global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v) {
     for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
-// First read of the raw edge table: range check of both endpoints and, in the same pass, the first-digit tile
-// histograms of both sorts (the destinations' for the CSR, the sources' for the out-degrees when WITH_SRC).
+// First read of the raw edge table: range check of the endpoints and, in the same pass, the first-digit tile
+// histograms of both sorts (the destinations' for the CSR, the sources' for the out-degrees when WITH_SRC).  Without
+// out-degrees the source column is not read here: the first scatter pass, which moves it anyway, checks its range.
 // Layout of each histogram as in radix_hist_kernel.
 // SRC_MODE 0: destinations only; 1: source digit = key & (src_radix - 1) (first pass of the keys-only sort);
 // 2: source digit = partition_digit(key, src_shift, src_radix).
@@ -107,20 +108,23 @@ __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, u
     bool bad = false;
     bool fold_d = true, fold_s = true;
     // 16-byte loads where the caller's arrays allow them (counting does not care about the order inside the tile)
-    const bool vec = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0;
-    uint32_t kd[kItems], ks[kItems];
+    const bool vec = (((WITH_SRC ? reinterpret_cast<uintptr_t>(src) : 0) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0;
+    uint32_t kd[kItems], ks[WITH_SRC ? kItems : 1];
 #pragma unroll
     for (int i = 0; i < kItems / 4; ++i) {
         const int64_t idx = base + ((int64_t)i * kThreads + threadIdx.x) * 4;
         if (vec && idx + 3 < n_edges) {
-            const uint4 a = *reinterpret_cast<const uint4 *>(dst + idx), b = *reinterpret_cast<const uint4 *>(src + idx);
+            const uint4 a = *reinterpret_cast<const uint4 *>(dst + idx);
             kd[4 * i] = a.x; kd[4 * i + 1] = a.y; kd[4 * i + 2] = a.z; kd[4 * i + 3] = a.w;
-            ks[4 * i] = b.x; ks[4 * i + 1] = b.y; ks[4 * i + 2] = b.z; ks[4 * i + 3] = b.w;
+            if constexpr (WITH_SRC) {
+                const uint4 b = *reinterpret_cast<const uint4 *>(src + idx);
+                ks[4 * i] = b.x; ks[4 * i + 1] = b.y; ks[4 * i + 2] = b.z; ks[4 * i + 3] = b.w;
+            }
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 kd[4 * i + j] = idx + j < n_edges ? (uint32_t)dst[idx + j] : 0u;
-                ks[4 * i + j] = idx + j < n_edges ? (uint32_t)src[idx + j] : 0u;
+                if constexpr (WITH_SRC) ks[4 * i + j] = idx + j < n_edges ? (uint32_t)src[idx + j] : 0u;
             }
         }
     }
@@ -128,7 +132,9 @@ __global__ __launch_bounds__(kThreads) void first_pass_kernel(int64_t n_edges, u
     for (int i = 0; i < kItems; ++i) {
         const int64_t idx = base + ((int64_t)(i / 4) * kThreads + threadIdx.x) * 4 + (i & 3);
         const bool valid = idx < n_edges;
-        if (valid) bad = bad || kd[i] >= n_nodes || ks[i] >= n_nodes;
+        if (valid) bad = bad || kd[i] >= n_nodes;
+        if constexpr (WITH_SRC)
+            if (valid) bad = bad || ks[i] >= n_nodes;
         wave_count(hd, kd[i] & mask, valid, fold_d);
         if constexpr (SRC_MODE == 1) wave_count(hs, ks[i] & (uint32_t)(src_radix - 1), valid, fold_s);
         if constexpr (SRC_MODE == 2) wave_count(hs, partition_digit(ks[i], src_shift, src_radix), valid, fold_s);
@@ -310,7 +316,8 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t 
                                                                  uint32_t *keys_out, int32_t *vals_out, int64_t n,
                                                                  int shift, int bits, const uint32_t *hist_scanned,
                                                                  int64_t nblocks, int remap, int64_t n_nodes,
-                                                                 int64_t *rowptr, uint32_t *run_keys) {
+                                                                 int64_t *rowptr, uint32_t *run_keys, uint32_t val_limit,
+                                                                 uint32_t *bad_flag) {
     __shared__ uint32_t cnt[kWaves][kMaxRadix];   // per wave and digit: count, then start inside the sorted tile
     __shared__ uint32_t gbase[kMaxRadix];         // global position of the tile's first key of the digit
     __shared__ uint32_t lstart[kMaxRadix];        // position of the digit's first key inside the sorted tile
@@ -337,6 +344,14 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(const uint32_t 
         const int64_t idx = wave_base + s * kWave + lane;
         key[s] = (idx < n) ? keys_in[idx] : 0u;
         if constexpr (HAS_VALS) val[s] = (idx < n) ? vals_in[idx] : 0;
+    }
+    if constexpr (HAS_VALS) {
+        if (val_limit) {  // first pass over a source column that nothing has range-checked yet (padding lanes hold 0)
+            bool bad = false;
+#pragma unroll
+            for (int s = 0; s < kItems; ++s) bad = bad || (uint32_t)val[s] >= val_limit;
+            if (bad) atomicOr(bad_flag, 1u);
+        }
     }
 #pragma unroll
     for (int s = 0; s < kItems; ++s) {
@@ -589,10 +604,10 @@ __global__ void adjacent_difference_kernel(const uint32_t *bounds, int64_t n, in
 template <bool HAS_VALS, bool LAST>
 void launch_scatter_bits(int bits, unsigned grid, hipStream_t st, const uint32_t *kin, const int32_t *vin, uint32_t *kout, int32_t *vout,
                          int64_t n, int shift, const uint32_t *h, int64_t nblocks, int remap, int64_t n_nodes, int64_t *rowptr,
-                         uint32_t *run_keys) {
+                         uint32_t *run_keys, uint32_t val_limit, uint32_t *bad_flag) {
 #define ITB_SCATTER(B)                                                                                                          \
     radix_scatter_kernel<HAS_VALS, LAST, B><<<grid, kThreads, 0, st>>>(kin, vin, kout, vout, n, shift, bits, h, nblocks, remap, \
-                                                                       n_nodes, rowptr, run_keys)
+                                                                       n_nodes, rowptr, run_keys, val_limit, bad_flag)
     switch (bits) {  // the widths that graphs beyond a few thousand vertices use get straight-line vote code
         case 5: ITB_SCATTER(5); break;
         case 6: ITB_SCATTER(6); break;
@@ -605,13 +620,16 @@ void launch_scatter_bits(int bits, unsigned grid, hipStream_t st, const uint32_t
 
 void launch_scatter(bool pairs, bool last, int bits, unsigned grid, hipStream_t st, const uint32_t *kin, const int32_t *vin,
                     uint32_t *kout, int32_t *vout, int64_t n, int shift, const uint32_t *h, int64_t nblocks, int remap,
-                    int64_t n_nodes, int64_t *rowptr, uint32_t *run_keys) {
+                    int64_t n_nodes, int64_t *rowptr, uint32_t *run_keys, uint32_t val_limit, uint32_t *bad_flag) {
     if (last)
-        launch_scatter_bits<true, true>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys);
+        launch_scatter_bits<true, true>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys,
+                                        val_limit, bad_flag);
     else if (pairs)
-        launch_scatter_bits<true, false>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys);
+        launch_scatter_bits<true, false>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys,
+                                         val_limit, bad_flag);
     else
-        launch_scatter_bits<false, false>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys);
+        launch_scatter_bits<false, false>(bits, grid, st, kin, vin, kout, vout, n, shift, h, nblocks, remap, n_nodes, rowptr, run_keys,
+                                          0u, nullptr);
 }
 
 int ceil_log2(int64_t n) {
@@ -752,7 +770,7 @@ extern "C" int32_t build_csr_by_dst(int64_t n_nodes, int64_t n_edges, const int3
             // last pass of the pair sort: no sorted keys are written, the row pointers come from the runs themselves
             launch_scatter(pairs, last, bits, (unsigned)nblocks, st, kin, pairs ? vin : nullptr, last ? nullptr : kout,
                            pairs ? vout : nullptr, n_edges, shift, h, nblocks, xcd_remap, n_nodes, last ? rowptr : nullptr,
-                           last ? run_keys : nullptr);
+                           last ? run_keys : nullptr, (pairs && p == 0 && !deg_out) ? (uint32_t)n_nodes : 0u, flag);
             ITB_LAUNCH_CHECK();
             if (last) rowptr_run_starts_kernel<<<grid_for(hist_n, 256), 256, 0, st>>>(h, run_keys, hist_n, n_edges, n_nodes, rowptr);
             ITB_LAUNCH_CHECK();

@@ -125,9 +125,24 @@ def test_build_csr_range_error(B):
         with pytest.raises(B.InferTurboError) as ei:
             B.build_csr_by_dst(4, dev_i32(src), dev_i32(bad_dst))
         assert ei.value.code == -3
-    with pytest.raises(B.InferTurboError) as ei:
-        B.build_csr_by_dst(4, dev_i32(np.array([7, 1, 2, 3], np.int32)), dev_i32(src))
-    assert ei.value.code == -3
+    # a bad source is found with and without out-degrees (two different kernels look at the source column), also when
+    # it sits in the ragged last tile of a multi-tile table, and a table of valid ids right at the limit passes
+    for want_deg in (True, False):
+        with pytest.raises(B.InferTurboError) as ei:
+            B.build_csr_by_dst(4, dev_i32(np.array([7, 1, 2, 3], np.int32)), dev_i32(src), want_deg_out=want_deg)
+        assert ei.value.code == -3
+        n, e = 1000, 3 * 8192 + 77
+        rng = np.random.default_rng(3)
+        s_ok, d_ok = rng.integers(0, n, e).astype(np.int32), rng.integers(0, n, e).astype(np.int32)
+        s_ok[5], d_ok[9] = n - 1, n - 1
+        B.build_csr_by_dst(n, dev_i32(s_ok), dev_i32(d_ok), want_deg_out=want_deg)
+        for where in (0, 8191, 8192, e - 1):
+            for bad in (n, -1):
+                s_bad = s_ok.copy()
+                s_bad[where] = bad
+                with pytest.raises(B.InferTurboError) as ei:
+                    B.build_csr_by_dst(n, dev_i32(s_bad), dev_i32(d_ok), want_deg_out=want_deg)
+                assert ei.value.code == -3, (want_deg, where, bad)
 
 
 @pytest.mark.parametrize("name,scale", [("tiny_powerlaw", 1.0), ("hub_heavy", 0.01), ("attention", 0.01),
