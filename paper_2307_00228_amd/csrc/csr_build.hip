@@ -263,16 +263,20 @@ __global__ __launch_bounds__(kDegThreads) void bucket_degree_kernel(const uint16
 }
 
 // hist[digit * nblocks + block] = number of keys of this block's tile with that digit.
+// The counters are kept four times over, lane l adding to copy l & 3 (copy c of digit d sits at word 4 d + c, so the
+// copies of a digit lie in different LDS banks): lanes that hold the same digit -- frequent once the lower digits are
+// sorted and the edges of a heavy row sit together -- then spread over four addresses instead of serialising on one.
 __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *keys, int64_t n, int shift, int bits,
                                                               uint32_t *hist, int64_t nblocks, int remap) {
-    __shared__ uint32_t h[kMaxRadix];
+    constexpr int kCopies = 4;
+    __shared__ uint32_t h[kMaxRadix * kCopies];
     const int64_t tile = xcd_contiguous_tile(blockIdx.x, nblocks, remap);
     const int radix = 1 << bits;
     const uint32_t mask = radix - 1;
-    for (int d = threadIdx.x; d < radix; d += kThreads) h[d] = 0;
+    for (int d = threadIdx.x; d < radix * kCopies; d += kThreads) h[d] = 0;
     __syncthreads();
     const int64_t base = tile * kTile;
-    bool fold = true;
+    const uint32_t copy = threadIdx.x & (kCopies - 1);
     // counting does not care about the order inside the tile: 16-byte loads (the key buffers are 16-byte aligned and a
     // tile starts at a multiple of 4096 keys); only the last tile can be ragged
     uint32_t k[kItems];
@@ -288,13 +292,25 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint32_t *ke
         }
         k[4 * i] = v.x; k[4 * i + 1] = v.y; k[4 * i + 2] = v.z; k[4 * i + 3] = v.w;
     }
+    // A thread holds four runs of four consecutive keys; a run that holds one digit four times is counted by one
+    // atomic of 4.
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        const int64_t idx = base + ((int64_t)(i / 4) * kThreads + threadIdx.x) * 4 + (i & 3);
-        wave_count(h, (k[i] >> shift) & mask, idx < n, fold);
+    for (int i = 0; i < kItems; i += 4) {
+        const int64_t idx = base + ((int64_t)(i / 4) * kThreads + threadIdx.x) * 4;
+        const uint32_t d0 = (k[i] >> shift) & mask, d1 = (k[i + 1] >> shift) & mask, d2 = (k[i + 2] >> shift) & mask,
+                       d3 = (k[i + 3] >> shift) & mask;
+        if (idx + 3 < n && d0 == d1 && d0 == d2 && d0 == d3) {
+            atomicAdd(&h[d0 * kCopies + copy], 4u);
+        } else {
+            if (idx < n) atomicAdd(&h[d0 * kCopies + copy], 1u);
+            if (idx + 1 < n) atomicAdd(&h[d1 * kCopies + copy], 1u);
+            if (idx + 2 < n) atomicAdd(&h[d2 * kCopies + copy], 1u);
+            if (idx + 3 < n) atomicAdd(&h[d3 * kCopies + copy], 1u);
+        }
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += kThreads) hist[(int64_t)d * nblocks + tile] = h[d];
+    for (int d = threadIdx.x; d < radix; d += kThreads)
+        hist[(int64_t)d * nblocks + tile] = h[d * kCopies] + h[d * kCopies + 1] + h[d * kCopies + 2] + h[d * kCopies + 3];
 }
 
 // Stable scatter of one digit.  Tile order is (wave, slot, lane) = ascending input index, and the rank of a
