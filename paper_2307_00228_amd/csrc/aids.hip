@@ -20,7 +20,10 @@ __global__ void copy_kernel(const uint4 *src, uint4 *dst, int64_t n_vec) {
 
 // A lane group of G lanes reads the row idx[i] (16 bytes per lane), U independent rows in flight per lane group;
 // the words are folded by xor and one word per thread reaches `sink`, so that no load can be dropped.
-template <int G, int U>
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// NT: non-temporal loads, as the gather uses them for tables far beyond the caches.
+template <int G, int U, bool NT>
 __global__ __launch_bounds__(256) void random_rows_kernel(const uint4 *table, const int32_t *idx, int64_t n_idx, uint32_t *sink) {
     constexpr int NG = kWave / G;
     const int lane = threadIdx.x & (kWave - 1);
@@ -36,7 +39,11 @@ __global__ __launch_bounds__(256) void random_rows_kernel(const uint4 *table, co
 #pragma unroll
             for (int q = 0; q < U; ++q) {
                 const int u = __shfl(myi, (t + q) * NG + g, kWave);
-                raw[q] = u >= 0 ? table[(int64_t)u * G + li] : make_uint4(0, 0, 0, 0);
+                if (u < 0) raw[q] = make_uint4(0, 0, 0, 0);
+                else if constexpr (NT) {
+                    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(table) + ((int64_t)u * G + li));
+                    raw[q] = make_uint4(v.x, v.y, v.z, v.w);
+                } else raw[q] = table[(int64_t)u * G + li];
             }
 #pragma unroll
             for (int q = 0; q < U; ++q) fold ^= raw[q].x ^ raw[q].y ^ raw[q].z ^ raw[q].w;
@@ -46,16 +53,24 @@ __global__ __launch_bounds__(256) void random_rows_kernel(const uint4 *table, co
 }
 
 template <int G>
-int32_t launch_probe(const void *table, const int32_t *idx, int64_t n_idx, void *sink, int blocks, hipStream_t st) {
+int32_t launch_probe(const void *table, int64_t table_bytes, const int32_t *idx, int64_t n_idx, void *sink, int blocks, hipStream_t st) {
     constexpr int U = G < 4 ? G : 4;
     constexpr int U8 = G < 8 ? G : 8;
     const int want = itb::g_tuning.gather_unroll.load();  // A/B switch 7: row loads in flight per lane
-    if (want == 8)
-        random_rows_kernel<G, U8><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
+    // A/B switch 8: 1 = non-temporal loads, 0 = plain, -1 = as the gather would choose for a table of this size
+    const int policy = itb::g_tuning.row_load_policy.load();
+    const bool nt = policy >= 0 ? policy == 1 : table_bytes >= ((int64_t)2 << 30);
+    const uint4 *t = static_cast<const uint4 *>(table);
+    uint32_t *s = static_cast<uint32_t *>(sink);
+    if (nt) {
+        if (want == 8) random_rows_kernel<G, U8, true><<<blocks, 256, 0, st>>>(t, idx, n_idx, s);
+        else random_rows_kernel<G, U, true><<<blocks, 256, 0, st>>>(t, idx, n_idx, s);
+    } else if (want == 8)
+        random_rows_kernel<G, U8, false><<<blocks, 256, 0, st>>>(t, idx, n_idx, s);
     else if (want == 1)
-        random_rows_kernel<G, 1><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
+        random_rows_kernel<G, 1, false><<<blocks, 256, 0, st>>>(t, idx, n_idx, s);
     else
-        random_rows_kernel<G, U><<<blocks, 256, 0, st>>>(static_cast<const uint4 *>(table), idx, n_idx, static_cast<uint32_t *>(sink));
+        random_rows_kernel<G, U, false><<<blocks, 256, 0, st>>>(t, idx, n_idx, s);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -83,13 +98,13 @@ extern "C" int32_t itb_random_row_read(const void *table, int64_t n_rows, int32_
     if (sink_bytes < (int64_t)blocks * 256 * 4) return ITB_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (row_bytes / 16) {
-        case 1: return launch_probe<1>(table, idx, n_idx, sink, blocks, st);
-        case 2: return launch_probe<2>(table, idx, n_idx, sink, blocks, st);
-        case 4: return launch_probe<4>(table, idx, n_idx, sink, blocks, st);
-        case 8: return launch_probe<8>(table, idx, n_idx, sink, blocks, st);
-        case 16: return launch_probe<16>(table, idx, n_idx, sink, blocks, st);
-        case 32: return launch_probe<32>(table, idx, n_idx, sink, blocks, st);
-        default: return launch_probe<64>(table, idx, n_idx, sink, blocks, st);
+        case 1: return launch_probe<1>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
+        case 2: return launch_probe<2>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
+        case 4: return launch_probe<4>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
+        case 8: return launch_probe<8>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
+        case 16: return launch_probe<16>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
+        case 32: return launch_probe<32>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
+        default: return launch_probe<64>(table, n_rows * (int64_t)row_bytes, idx, n_idx, sink, blocks, st);
     }
 }
 
@@ -102,5 +117,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 5) { t.csr_deg_by_sort = value; return ITB_OK; }
     if (key == 6) { t.overlap_hubs = value; return ITB_OK; }
     if (key == 7) { t.gather_unroll = value; return ITB_OK; }
+    if (key == 8 && value >= -1 && value <= 1) { t.row_load_policy = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }

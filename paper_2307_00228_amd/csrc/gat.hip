@@ -34,6 +34,7 @@ struct GatArgs {
     int64_t edge_lo, edge_hi;
     const int64_t *bounds;   // nullable: {row_lo, row_hi, seg_lo, seg_hi, hub_lo, hub_hi} of the edge range (see gather_layer)
     int32_t row_vecs, heads, dh, act;
+    int32_t stream_rows;   // rows of z and scores of the sources are read with non-temporal loads (table far beyond the caches)
     float slope;
     int32_t small_limit;
     int32_t long_limit;    // rows with more in-edges go to the work list and get a whole block
@@ -152,17 +153,21 @@ __device__ __forceinline__ void wave_segment_softmax(SoftState<Elems<BF16>::kPer
             uint4 raw[U];
             float e[U];
             bool on[U];
+            auto issue = [&](auto stream_tag) {
+                constexpr bool S = decltype(stream_tag)::value;
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                // A slot past the end of the chunk re-reads the chunk's last edge and enters with weight zero (its row
-                // is a row this segment sums anyway): the loads need no predicate and no select.
-                const int ei = (t + q) * NG + g;
-                const int eic = ei < cnt ? ei : cnt - 1;
-                const int u = __shfl(myc, eic, kWave);
-                on[q] = lane_on && ei < cnt;
-                raw[q] = a.z[(int64_t)u * a.row_vecs + vec_c];
-                e[q] = a.s_src[(int64_t)u * a.heads + hk];
-            }
+                for (int q = 0; q < U; ++q) {
+                    // A slot past the end of the chunk re-reads the chunk's last edge and enters with weight zero (its
+                    // row is a row this segment sums anyway): the loads need no predicate and no select.
+                    const int ei = (t + q) * NG + g;
+                    const int eic = ei < cnt ? ei : cnt - 1;
+                    const int u = __shfl(myc, eic, kWave);
+                    on[q] = lane_on && ei < cnt;
+                    raw[q] = load_row_piece<S>(a.z + ((int64_t)u * a.row_vecs + vec_c));
+                    e[q] = load_row_scalar<S>(a.s_src + ((int64_t)u * a.heads + hk));
+                }
+            };
+            if (a.stream_rows) issue(std::true_type{}); else issue(std::false_type{});  // kernel argument: wave-uniform
 #pragma unroll
             for (int q = 0; q < U; ++q) e[q] = leaky(e[q] + sd, a.slope);
             absorb_batch<BF16, U>(st, e, raw, on);
@@ -315,13 +320,17 @@ __global__ __launch_bounds__(256) void gat_rows_kernel(GatArgs a) {
                     uint4 raw[R];
                     float e[R];
                     bool on[R];
+                    auto issue = [&](auto stream_tag) {
+                        constexpr bool S = decltype(stream_tag)::value;
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const int u = __shfl(myc[r], g * G + t, kWave);
-                        on[r] = lane_on && (j + t) < d[r];
-                        raw[r] = on[r] ? a.z[(int64_t)u * a.row_vecs + vec] : make_uint4(0, 0, 0, 0);
-                        e[r] = on[r] ? a.s_src[(int64_t)u * a.heads + hk] : 0.f;
-                    }
+                        for (int r = 0; r < R; ++r) {
+                            const int u = __shfl(myc[r], g * G + t, kWave);
+                            on[r] = lane_on && (j + t) < d[r];
+                            raw[r] = on[r] ? load_row_piece<S>(a.z + ((int64_t)u * a.row_vecs + vec)) : make_uint4(0, 0, 0, 0);
+                            e[r] = on[r] ? load_row_scalar<S>(a.s_src + ((int64_t)u * a.heads + hk)) : 0.f;
+                        }
+                    };
+                    if (a.stream_rows) issue(std::true_type{}); else issue(std::false_type{});
 #pragma unroll
                     for (int r = 0; r < R; ++r) absorb<BF16>(st[r], leaky(e[r] + sd[r], a.slope), raw[r], on[r]);
                 }
@@ -661,6 +670,7 @@ int32_t gat_gather_impl(const itb_gather_desc *desc, int64_t n_nodes, const int6
     a.rowptr = rowptr;
     a.col = col;
     a.z = static_cast<const uint4 *>(z);
+    a.stream_rows = stream_rows_for(n_nodes * (int64_t)desc->dim * (bf16 ? 2 : 4));
     a.s_src = s_src;
     a.s_dst = s_dst;
     a.bias = desc->bias;

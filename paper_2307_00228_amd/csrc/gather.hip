@@ -105,6 +105,7 @@ struct GatherArgs {
     // offset can lie in [edge_lo, edge_hi); wavefronts and blocks outside leave after one scalar load
     const int64_t *bounds;
     int32_t row_vecs;        // 16-byte vectors per input row
+    int32_t stream_rows;     // source rows are read with non-temporal loads (tables far beyond the caches)
     int32_t mode;
     int32_t small_limit;
     int32_t long_limit;      // rows with more in-edges than this go to the work list
@@ -170,7 +171,7 @@ __device__ __forceinline__ uint32_t idle_word(float sign) {
 // Store one lane's slice of an output row.  `vec` is the lane's 16-byte vector index in the INPUT row.
 template <bool BF16_IN, bool BF16_OUT>
 __device__ __forceinline__ void store_row_slice(void *out, int64_t row, int32_t row_vecs, int vec,
-                                                const float (&acc)[Elems<BF16_IN>::kPerVec]) {
+                                                const float (&acc)[Elems<BF16_IN>::kPerVec], bool stream = false) {
     constexpr int VE = Elems<BF16_IN>::kPerVec;
     const int64_t elem0 = (row * row_vecs + vec) * VE;
     if constexpr (BF16_OUT) {
@@ -180,11 +181,12 @@ __device__ __forceinline__ void store_row_slice(void *out, int64_t row, int32_t 
         p.y = pack_bf16x2(acc[2], acc[3]);
         p.z = pack_bf16x2(acc[4], acc[5]);
         p.w = pack_bf16x2(acc[6], acc[7]);
-        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + elem0) = p;
+        store_piece(static_cast<uint16_t *>(out) + elem0, p, stream);
     } else {
-        float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(out) + elem0);
-        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        if constexpr (VE == 8) o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        float *o = static_cast<float *>(out) + elem0;
+        store_piece(o, make_uint4(__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])), stream);
+        if constexpr (VE == 8)
+            store_piece(o + 4, make_uint4(__float_as_uint(acc[4]), __float_as_uint(acc[5]), __float_as_uint(acc[6]), __float_as_uint(acc[7])), stream);
     }
 }
 
@@ -253,13 +255,14 @@ __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src) {
 // Whole-wavefront sum of h[col[e]] * scale over the 64-edge chunks first_chunk, first_chunk + chunk_stride, ...
 // of the edge range [start, start+deg).  Group g takes the edges congruent to g modulo 64/G inside every
 // chunk; on return every lane group holds the sum over all the wavefront's chunks.
-template <bool BF16, int G, bool EXT = false>
+template <bool BF16, int G, bool EXT = false, int U = 8>
 __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerVec], const GatherArgs &a, int64_t start,
                                                  int64_t deg, int vec, bool lane_on, int first_chunk = 0,
                                                  int chunk_stride = 1) {
     constexpr int NG = kWave / G;
     constexpr int VE = Elems<BF16>::kPerVec;
-    constexpr int U = 8;   // row loads in flight per lane (8 instead of 4: 3-4 % on 256-byte rows, neutral elsewhere)
+    // U = row loads in flight per lane (8 instead of 4: 3-4 % on 256-byte rows in the segment and long-row kernels; the
+    // row kernel takes 4, whose registers buy it three more resident wavefronts per SIMD)
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / G;
     const bool has_scale = !EXT && (a.src_scale != nullptr || a.edge_coef != nullptr);
@@ -280,15 +283,19 @@ __device__ __forceinline__ void wave_segment_sum(float (&acc)[Elems<BF16>::kPerV
         for (int t = 0; t < steps; t += U) {
             uint4 raw[U];
             float sc[U];
+            auto issue = [&](auto stream_tag) {
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int ei = (t + q) * NG + g;
-                const int u = __shfl(myc, ei & (kWave - 1), kWave);
-                const float s = __shfl(mys, ei & (kWave - 1), kWave);
-                const bool on = lane_on && ei < cnt;
-                raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(idle, idle, idle, idle);
-                sc[q] = on ? s : idle_s;
-            }
+                for (int q = 0; q < U; ++q) {
+                    const int ei = (t + q) * NG + g;
+                    const int u = __shfl(myc, ei & (kWave - 1), kWave);
+                    const float s = __shfl(mys, ei & (kWave - 1), kWave);
+                    const bool on = lane_on && ei < cnt;
+                    raw[q] = on ? load_row_piece<decltype(stream_tag)::value>(a.h + ((int64_t)u * a.row_vecs + vec))
+                                : make_uint4(idle, idle, idle, idle);
+                    sc[q] = on ? s : idle_s;
+                }
+            };
+            if (a.stream_rows) issue(std::true_type{}); else issue(std::false_type{});  // kernel argument: wave-uniform
 #pragma unroll
             for (int q = 0; q < U; ++q) accumulate<BF16, EXT>(acc, raw[q], sc[q]);
         }
@@ -346,48 +353,83 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
         }
     }
 
-    // ---- rows with few in-edges: one lane group per row, 64/G rows at a time ----------------------------
+    // ---- rows with few in-edges: one lane group per row --------------------------------------------------
+    // The 64/G lane groups walk the wavefront's short rows independently: a group that finishes its row takes
+    // the next one not yet started (ascending, decided by wave-uniform bit arithmetic), so a 30-edge row next to
+    // seven 2-edge rows holds up one group, not eight.  A row is still summed by one group, G edges per step in U
+    // at a time, so its result does not depend on which group took it or on what else the wavefront had to do.
     if (small_mask) {
-        for (int sub = 0; sub < kWave; sub += NG) {
-            const uint64_t sel = (NG == kWave) ? small_mask : ((small_mask >> sub) & ((1ull << NG) - 1ull));
-            if (sel == 0) continue;
-            const int rl = sub + g;
-            const bool act = (small_mask >> rl) & 1ull;
-            int d = __shfl(deg, rl, kWave);
-            if (!act) d = 0;
-            const int64_t st = shfl_i64(rs, rl);
-            float acc[VE];
+        uint64_t remaining = small_mask;  // wave-uniform: short rows nobody has started
+        int rl = -1;                      // the group's current row (same in its G lanes), -1 = none
+        int d = 0, j = 0;
+        int64_t st = 0;
+        float acc[VE];
 #pragma unroll
-            for (int i = 0; i < VE; ++i) acc[i] = EXT ? -INFINITY : 0.f;
-            for (int j = 0; __ballot(j < d) != 0ull; j += G) {
-                int myc = 0;
-                float mys = unit;
-                if (j + li < d) {
-                    myc = a.col ? a.col[st + j + li] : (int)(st + j + li);
-                    if (has_scale) mys = a.edge_coef ? a.edge_coef[st + j + li] : a.src_scale[myc];
-                }
-                const int cnt = d - j;  // edges left for this group (may be <= 0)
-                for (int t = 0; t < G; t += U) {
-                    if (__ballot(t < cnt) == 0ull) break;
-                    uint4 raw[U];
-                    float sc[U];
+        for (int i = 0; i < VE; ++i) acc[i] = EXT ? -INFINITY : 0.f;
+        for (;;) {
+            uint64_t idle_groups = __ballot(li == 0 && rl < 0);  // one bit per idle group, at its first lane
+            int take = -1;
+            while (idle_groups && remaining) {                   // wave-uniform, at most 64/G rounds
+                const int first_lane = __ffsll((unsigned long long)idle_groups) - 1;
+                idle_groups &= idle_groups - 1;
+                const int row = __ffsll((unsigned long long)remaining) - 1;
+                remaining &= remaining - 1;
+                if (first_lane == g * G) take = row;
+            }
+            {   // every lane takes part in the shuffles; a group without a new row keeps what it has
+                const int src = take >= 0 ? take : 0;
+                const int nd = __shfl(deg, src, kWave);
+                const int64_t nst = shfl_i64(rs, src);
+                if (take >= 0) {
+                    rl = take;
+                    d = nd;
+                    st = nst;
+                    j = 0;
 #pragma unroll
-                    for (int q = 0; q < U; ++q) {
-                        const int sl = g * G + t + q;
-                        const int u = __shfl(myc, sl, kWave);
-                        const float s = __shfl(mys, sl, kWave);
-                        const bool on = lane_on && (t + q) < cnt;
-                        raw[q] = on ? a.h[(int64_t)u * a.row_vecs + vec] : make_uint4(idle, idle, idle, idle);
-                        sc[q] = on ? s : idle_s;
-                    }
-#pragma unroll
-                    for (int q = 0; q < U; ++q) accumulate<BF16_IN, EXT>(acc, raw[q], sc[q]);
+                    for (int i = 0; i < VE; ++i) acc[i] = EXT ? -INFINITY : 0.f;
                 }
             }
-            if (act && lane_on) {
-                finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
-                update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, r0 + rl, a.row_vecs, vec);
-                store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
+            const bool busy = rl >= 0;
+            if (__ballot(busy) == 0ull) break;
+            int myc = 0;
+            float mys = unit;
+            if (busy && j + li < d) {
+                myc = a.col ? a.col[st + j + li] : (int)(st + j + li);
+                if (has_scale) mys = a.edge_coef ? a.edge_coef[st + j + li] : a.src_scale[myc];
+            }
+            const int cnt = busy ? d - j : 0;  // edges left for this group
+            for (int t = 0; t < G; t += U) {
+                if (__ballot(t < cnt) == 0ull) break;
+                uint4 raw[U];
+                float sc[U];
+                int src_row[U];
+#pragma unroll
+                for (int q = 0; q < U; ++q) {  // all shuffles first: the loads then go out back to back
+                    const int sl = g * G + t + q;
+                    src_row[q] = __shfl(myc, sl, kWave);
+                    const float s = __shfl(mys, sl, kWave);
+                    sc[q] = (lane_on && (t + q) < cnt) ? s : idle_s;
+                }
+                auto issue = [&](auto stream_tag) {
+#pragma unroll
+                    for (int q = 0; q < U; ++q) {
+                        const bool on = lane_on && (t + q) < cnt;
+                        raw[q] = on ? load_row_piece<decltype(stream_tag)::value>(a.h + ((int64_t)src_row[q] * a.row_vecs + vec))
+                                    : make_uint4(idle, idle, idle, idle);
+                    }
+                };
+                if (a.stream_rows) issue(std::true_type{}); else issue(std::false_type{});
+#pragma unroll
+                for (int q = 0; q < U; ++q) accumulate<BF16_IN, EXT>(acc, raw[q], sc[q]);
+            }
+            j += G;
+            if (busy && j >= d) {  // row finished (a row without in-edges finishes at once)
+                if (lane_on) {
+                    finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
+                    update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, r0 + rl, a.row_vecs, vec);
+                    store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc, a.stream_rows);
+                }
+                rl = -1;
             }
         }
     }
@@ -399,11 +441,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
         const int d = __shfl(deg, rl, kWave);
         const int64_t st = shfl_i64(rs, rl);
         float acc[VE];
-        wave_segment_sum<BF16_IN, G, EXT>(acc, a, st, d, vec, lane_on);
+        wave_segment_sum<BF16_IN, G, EXT, 4>(acc, a, st, d, vec, lane_on);
         if (g == 0 && lane_on) {
             finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, r0 + rl);
             update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, r0 + rl, a.row_vecs, vec);
-            store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc);
+            store_row_slice<BF16_IN, BF16_OUT>(a.out, r0 + rl, a.row_vecs, vec, acc, a.stream_rows);
         }
     }
 }
@@ -477,7 +519,7 @@ __global__ __launch_bounds__(kRangeWaves * kWave) void gather_long_rows_kernel(G
         if (threadIdx.x < G && lane_on) {
             finish_row<VE, EXT>(acc, a.mode, d, a.dst_scale, row);
             update_epilogue<BF16_OUT, VE>(acc, a.addend, a.bias, a.act, row, a.row_vecs, vec);
-            store_row_slice<BF16_IN, BF16_OUT>(a.out, row, a.row_vecs, vec, acc);
+            store_row_slice<BF16_IN, BF16_OUT>(a.out, row, a.row_vecs, vec, acc, a.stream_rows);
         }
     }
 }
@@ -729,6 +771,11 @@ int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const in
     a.rowptr = rowptr;
     a.col = per_edge_rows ? nullptr : col;
     a.h = static_cast<const uint4 *>(h_src);
+    {
+        // non-temporal row loads and stores once the table is far beyond what the caches hold
+        const int64_t table_bytes = n_nodes * (int64_t)desc->dim * (desc->dtype_in == ITB_BF16 ? 2 : 4);
+        a.stream_rows = per_edge_rows ? 0 : stream_rows_for(table_bytes);
+    }
     a.src_scale = (desc->agg == ITB_AGG_GCN && !per_edge_rows) ? src_scale : nullptr;
     // per-edge scalar: the source coefficient of a GCN edge, or the weight of an edge-weighted sum / mean
     a.edge_coef = (desc->agg == ITB_AGG_GCN || desc->agg == ITB_AGG_SUM || desc->agg == ITB_AGG_MEAN) ? desc->edge_coef : nullptr;
