@@ -41,7 +41,7 @@ int32_t itb_random_row_read(const void *table, int64_t n_rows, int32_t row_bytes
  * helper-stream overlap (hub passes of a gather, out-degree branch of the CSR
  * build; 1 = on); 7 = row loads in flight per lane of the gather loops (-1 =
  * built-in choice); 8 = loads of the randomly addressed source rows: 0 plain,
- * 1 non-temporal, -1 by table size (non-temporal from 2 GiB on: measured 10 %
+ * 1 non-temporal, -1 by table size (non-temporal from 3 GiB on: measured 10 %
  * faster on a 12.8 GB table, 5-10 % slower on tables of 1 GB and less; the
  * probe itb_random_row_read follows the same switch). */
 int32_t itb_set_tuning(int32_t key, int32_t value);

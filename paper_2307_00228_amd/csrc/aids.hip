@@ -59,7 +59,7 @@ int32_t launch_probe(const void *table, int64_t table_bytes, const int32_t *idx,
     const int want = itb::g_tuning.gather_unroll.load();  // A/B switch 7: row loads in flight per lane
     // A/B switch 8: 1 = non-temporal loads, 0 = plain, -1 = as the gather would choose for a table of this size
     const int policy = itb::g_tuning.row_load_policy.load();
-    const bool nt = policy >= 0 ? policy == 1 : table_bytes >= ((int64_t)2 << 30);
+    const bool nt = policy >= 0 ? policy == 1 : table_bytes >= itb::kStreamRowsFromBytes;
     const uint4 *t = static_cast<const uint4 *>(table);
     uint32_t *s = static_cast<uint32_t *>(sink);
     if (nt) {
