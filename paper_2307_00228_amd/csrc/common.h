@@ -56,7 +56,7 @@ extern Tuning g_tuning;
 // 47 G rows/s (6.2 TB/s) with plain loads, a 3 GB table 4 % faster; tables of 1 GB and less, which partly live in the
 // caches, are 5-10 % faster with plain loads.  The host picks per launch (stream_rows_for).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-constexpr int64_t kStreamRowsFromBytes = (int64_t)3 << 30;  // a 2 GB table still loses 9 % to non-temporal loads
+constexpr int64_t kStreamRowsFromBytes = (int64_t)3 << 30;  // the smallest table size measured to gain
 template <bool STREAM>
 __device__ __forceinline__ uint4 load_row_piece(const uint4 *p) {
     if constexpr (STREAM) {
