@@ -98,6 +98,30 @@ def test_build_csr_bit_exact(B, name, n, e, hub):
     assert np.array_equal(deg_out.cpu().numpy(), d), "deg_out"
 
 
+@pytest.mark.parametrize("bits", [1, 2, 4, 5, 6, 7, 8, 9, 12, 15, 16, 17, 21, 24, 25])
+def test_build_csr_every_digit_width_and_pass_count(B, bits):
+    """The key width decides the number of radix passes (1 to 4) and the digit width of each (1..8 bits; 5..8 have code
+    of their own).  Row pointers come from the runs of the last pass, so the cases also put the edges into a few far-apart
+    vertex ids (long stretches of empty (digit, tile) runs and of empty rows), and use a ragged last tile."""
+    n = (1 << bits) - (3 if bits > 2 else 0)          # not a power of two: the top digit is not full
+    e = 5 * 8192 + 123
+    rng = np.random.default_rng(bits)
+    src = rng.integers(0, n, e).astype(np.int32)
+    for spread in ("uniform", "clustered"):
+        if spread == "uniform":
+            dst = rng.integers(0, n, e).astype(np.int32)
+        else:
+            few = np.unique(np.concatenate([[0, n - 1, n // 2], rng.integers(0, n, 5)])).astype(np.int32)
+            dst = few[rng.integers(0, len(few), e)]
+        r, c, d = oracle.build_csr(n, src, dst)
+        for want_deg in (False, True):
+            rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst), want_deg_out=want_deg)
+            assert np.array_equal(rowptr.cpu().numpy(), r), (spread, want_deg, "rowptr")
+            assert np.array_equal(col.cpu().numpy(), c), (spread, want_deg, "col")
+            if want_deg:
+                assert np.array_equal(deg_out.cpu().numpy(), d), (spread, "deg_out")
+
+
 @pytest.mark.parametrize("n,e,hub", [(5000, 700000, 0.6), (1, 9, 0.0), (17, 100, 0.5), (1 << 17, 200000, 0.1),
                                      (5_000_000, 100000, 0.2), (3000, 0, 0.0)])
 def test_out_degrees_both_strategies(B, n, e, hub):
