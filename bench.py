@@ -58,6 +58,7 @@ def measure(name, scale, steps, warmup, threshold=None, edge_chunk=None, keep=Fa
     is_gat = [l.agg == W.AGG_GAT for l in w.layers]
     needs_deg_out = any(l.agg == W.AGG_GCN for l in w.layers)   # out-degrees enter the GCN coefficients only
     projected = compose.plan(layers, tdt)
+    chained = compose.chained(layers, tdt)   # the update of such a layer also takes the next layer's h . [W_nbr | W_self]
     ev = lambda: torch.cuda.Event(enable_timing=True)
     out = torch.empty((N, w.layers[-1].d_out), dtype=tdt, device="cuda")
     state = {"ws": None}
@@ -136,8 +137,18 @@ def measure(name, scale, steps, warmup, threshold=None, edge_chunk=None, keep=Fa
     a_flops = [(2.0 if g else 4.0) * l.d_in * l.d_out * N for l, g in zip(w.layers, is_gat)]
     a_bytes = [N * ((l.d_in + l.d_out) * esz + 8 * l.heads if g else (l.d_in + 2 * l.d_out) * esz if pf
                     else (2 * l.d_in + l.d_out) * esz) for l, g, pf in zip(w.layers, is_gat, projected)]
+    for i in range(L - 1):
+        if chained[i]:
+            # one launch: reads h and agg, keeps the new state on chip, writes the next layer's two products; the next
+            # layer has no dense launch of its own
+            nxt = w.layers[i + 1]
+            a_flops[i] += a_flops[i + 1]
+            a_bytes[i] = N * (2 * w.layers[i].d_in + 2 * nxt.d_out) * esz
+            a_flops[i + 1] = 0.0
+            a_bytes[i + 1] = 0
     peak_tf = PEAK_TFLOPS[w.dtype]
-    a_attainable = [min(peak_tf, f / b * HBM_PEAK_GBS / 1e3) for f, b in zip(a_flops, a_bytes)]   # TFLOP/s
+    a_attainable = [min(peak_tf, f / b * HBM_PEAK_GBS / 1e3) if b else 0.0 for f, b in zip(a_flops, a_bytes)]   # TFLOP/s
+    rate = lambda num, t, scale: num / (t * 1e-3) / scale if num else 0.0   # (a layer without a dense launch reports 0)
     # the gather the roofline is quoted on: the longest one; among gathers within 3 % of it (two layers of one graph
     # take nearly the same time when their rows fit the same number of memory lines) the one that moves more bytes,
     # so that run-to-run noise cannot flip the choice
@@ -156,11 +167,12 @@ def measure(name, scale, steps, warmup, threshold=None, edge_chunk=None, keep=Fa
         "gather_edges_per_s": [E / (t * 1e-3) for t in g_ms],
         "gather_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(g_bytes, g_ms)],
         "gather_frac_of_hbm_peak": [b / (t * 1e-3) / 1e9 / HBM_PEAK_GBS for b, t in zip(g_bytes, g_ms)],
-        "apply_TFLOPs": [f / (t * 1e-3) / 1e12 for f, t in zip(a_flops, d_ms)],
-        "apply_frac_of_mfma_peak": [f / (t * 1e-3) / 1e12 / peak_tf for f, t in zip(a_flops, d_ms)],
+        "apply_TFLOPs": [rate(f, t, 1e12) for f, t in zip(a_flops, d_ms)],
+        "apply_frac_of_mfma_peak": [rate(f, t, 1e12) / peak_tf for f, t in zip(a_flops, d_ms)],
         "apply_attainable_TFLOPs": a_attainable,
-        "apply_frac_of_attainable_roofline": [f / (t * 1e-3) / 1e12 / at for f, t, at in zip(a_flops, d_ms, a_attainable)],
-        "apply_GBps": [b / (t * 1e-3) / 1e9 for b, t in zip(a_bytes, d_ms)],
+        "apply_frac_of_attainable_roofline": [rate(f, t, 1e12) / at if at else 0.0 for f, t, at in zip(a_flops, d_ms, a_attainable)],
+        "apply_GBps": [rate(b, t, 1e9) for b, t in zip(a_bytes, d_ms)],
+        "update_chained_into_next_projection": chained,
         "nodes_per_s_per_layer": [N / ((g + a) * 1e-3) for g, a in zip(g_ms, d_ms)],
         "n_hubs": graph[3].n_hubs, "n_shadows": graph[3].n_shadows, "dominant_gather": dom,
     }

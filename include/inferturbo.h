@@ -329,6 +329,19 @@ int32_t aggregate_edge_features(int32_t agg, int32_t dtype, int64_t n_nodes, con
  *   only).  A narrowing layer uses it for h . [W_nbr | W_self]: h is read once.
  *   Needs d_out to be a multiple of 4 (fp32) / 8 (bf16), no self term and no
  *   score epilogue; both NULL to skip.
+ *   chain: optional chained projection (Sec. IV-B "Inference": the computation
+ *   flow may be reorganised as long as every vertex gets the same function).
+ *   The finished rows h_out[v], rounded to `dtype` exactly as they would be
+ *   stored, are multiplied on the spot by two more matrices,
+ *     chain->out_first[v]  = h_out[v] . chain->w_first,
+ *     chain->out_second[v] = h_out[v] . chain->w_second   ([d_out x dc] each),
+ *   which is the next layer's h . [W_nbr | W_self] when that layer applies
+ *   W_nbr before its gather: the state between the two layers is then never
+ *   written or read back, and h_out may be NULL.  Built for ITB_BF16,
+ *   d_out == 64, d_in a multiple of 64, dc a multiple of 8 with 2 dc <= 64, no
+ *   score epilogue, no second product, no message output; other shapes return
+ *   ITB_ERR_UNSUPPORTED (infer_layer_plan tells which layers qualify).  NULL to
+ *   skip.
  * ------------------------------------------------------------------------- */
 typedef struct {
     int32_t dtype;
@@ -336,6 +349,14 @@ typedef struct {
     int32_t act;        /* ITB_ACT_* */
     int32_t heads;      /* score epilogue only, else 0 */
 } itb_apply_desc;
+
+typedef struct {
+    const void *w_first;   /* [d_out x dc] of the layer's dtype */
+    const void *w_second;  /* [d_out x dc] */
+    int32_t dc;
+    void *out_first;       /* [n x dc] */
+    void *out_second;      /* [n x dc] */
+} itb_apply_chain;
 
 int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes,
                     const void *h_self, const void *agg,
@@ -345,6 +366,7 @@ int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes,
                     const float *msg_scale, void *msg_out,
                     const void *addend,
                     const void *w_second, void *out_second,
+                    const itb_apply_chain *chain,
                     void *stream);
 
 /* ---------------------------------------------------------------------------
@@ -425,7 +447,10 @@ enum {
     ITB_PLAN_GATHER_UPDATE = 0,   /* gather_layer on the state, then apply_layer */
     ITB_PLAN_PROJECT_GATHER = 1,  /* apply_layer with two products, then gather_layer with the fused update */
     ITB_PLAN_ATTENTION = 2,       /* projection with scores, then the attention reduce */
-    ITB_PLAN_UPDATE_ONLY = 3      /* ITB_AGG_NONE: apply_layer alone */
+    ITB_PLAN_UPDATE_ONLY = 3,     /* ITB_AGG_NONE: apply_layer alone */
+    ITB_PLAN_GATHER_UPDATE_CHAINED = 4 /* gather_layer, then apply_layer whose chained projection is the next layer's
+                                          (ITB_PLAN_PROJECT_GATHER) pair of products: that layer starts at its gather, and
+                                          this layer's state is never stored */
 };
 int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_layer *layers, int32_t *plan);
 

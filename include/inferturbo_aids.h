@@ -43,7 +43,9 @@ int32_t itb_random_row_read(const void *table, int64_t n_rows, int32_t row_bytes
  * built-in choice); 8 = loads of the randomly addressed source rows: 0 plain,
  * 1 non-temporal, -1 by table size (non-temporal from 3 GiB on: measured 10 %
  * faster on a 12.8 GB table, 5-10 % slower on tables of 1 GB and less; the
- * probe itb_random_row_read follows the same switch). */
+ * probe itb_random_row_read follows the same switch); 9 = the update of a
+ * layer feeds the projection of a following narrowing layer in the same
+ * launch (1 = on). */
 int32_t itb_set_tuning(int32_t key, int32_t value);
 
 #ifdef __cplusplus

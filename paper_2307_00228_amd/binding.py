@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libinferturbo_hip.so")
 ITB_F32, ITB_BF16 = 0, 1
 AGG_SUM, AGG_MEAN, AGG_GCN, AGG_GAT, AGG_MAX, AGG_MIN, AGG_NONE = 0, 1, 2, 3, 4, 5, 6
 ACT_NONE, ACT_RELU = 0, 1
-PLAN_GATHER_UPDATE, PLAN_PROJECT_GATHER, PLAN_ATTENTION, PLAN_UPDATE_ONLY = 0, 1, 2, 3
+PLAN_GATHER_UPDATE, PLAN_PROJECT_GATHER, PLAN_ATTENTION, PLAN_UPDATE_ONLY, PLAN_GATHER_UPDATE_CHAINED = 0, 1, 2, 3, 4
 INT64_MAX = (1 << 63) - 1
 
 STATUS = {0: "ITB_OK", -1: "ITB_ERR_NULL", -2: "ITB_ERR_SIZE", -3: "ITB_ERR_RANGE", -4: "ITB_ERR_DTYPE",
@@ -57,6 +57,11 @@ class itb_layer(C.Structure):
                 ("att_src", C.c_void_p), ("att_dst", C.c_void_p), ("w_edge", C.c_void_p)]
 
 
+class itb_apply_chain(C.Structure):
+    _fields_ = [("w_first", C.c_void_p), ("w_second", C.c_void_p), ("dc", C.c_int32), ("out_first", C.c_void_p),
+                ("out_second", C.c_void_p)]
+
+
 class itb_stage_events(C.Structure):
     _fields_ = [("events", C.POINTER(C.c_void_p)), ("n_events", C.c_int32)]
 
@@ -73,7 +78,8 @@ def _load():
     lib.gcn_edge_coefficients.argtypes = [i64, vp, vp, vp, vp]
     lib.gather_layer.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                  i64, i64, vp, szp, vp]
-    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.apply_layer.argtypes = [C.POINTER(itb_apply_desc), i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                C.POINTER(itb_apply_chain), vp]
     lib.infer_layer_plan.argtypes = [i32, i32, C.POINTER(itb_layer), C.POINTER(i32)]
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
     lib.gather_layer_noalloc.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
@@ -306,12 +312,24 @@ def scale_rows(x: torch.Tensor, row_scale: torch.Tensor, out: Optional[torch.Ten
 
 def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.Tensor] = None,
                 heads: int = 0, att_src=None, att_dst=None, msg_scale=None, msg_out=None, addend=None,
-                w_second=None, out_second=None):
-    """Returns out; with heads > 0 (out, s_src, s_dst); with w_second (out, out_second)."""
+                w_second=None, out_second=None, chain=None, store_out: bool = True):
+    """Returns out; with heads > 0 (out, s_src, s_dst); with w_second (out, out_second); with chain = (w_first, w_second[,
+    out_first, out_second]) -- the chained projection of the finished rows -- (out, out_first, out_second), where out is
+    None when store_out is False (the rows themselves are then never written)."""
     n, d_in = agg.shape
     d_out = w_nbr.shape[1]
-    if out is None:
+    if out is None and (store_out or chain is None):
         out = torch.empty((n, d_out), dtype=agg.dtype, device="cuda")
+    ch = None
+    if chain is not None:
+        cw1, cw2 = chain[0], chain[1]
+        dc = cw1.shape[1]
+        co1 = chain[2] if len(chain) > 2 and chain[2] is not None else torch.empty((n, dc), dtype=agg.dtype, device="cuda")
+        co2 = chain[3] if len(chain) > 3 and chain[3] is not None else torch.empty((n, dc), dtype=agg.dtype, device="cuda")
+        assert cw1.shape == cw2.shape == (d_out, dc) and co1.shape == co2.shape == (n, dc)
+        ch = itb_apply_chain(cw1.data_ptr(), cw2.data_ptr(), dc, co1.data_ptr(), co2.data_ptr())
+        if not store_out:
+            out = None
     desc = itb_apply_desc(dtype_code(agg), d_in, d_out, act, heads)
     s_src = s_dst = None
     if heads:
@@ -322,7 +340,9 @@ def apply_layer(h_self, agg, w_self, w_nbr, bias, act: int, out: Optional[torch.
     _check("apply_layer", lib.apply_layer(C.byref(desc), n, _ptr(h_self), _ptr(agg), _ptr(w_self), _ptr(w_nbr), _ptr(bias),
                                           _ptr(out), _ptr(att_src), _ptr(att_dst), _ptr(s_src), _ptr(s_dst),
                                           _ptr(msg_scale), _ptr(msg_out), _ptr(addend), _ptr(w_second), _ptr(out_second),
-                                          _stream()))
+                                          C.byref(ch) if ch is not None else None, _stream()))
+    if ch is not None:
+        return out, co1, co2
     if w_second is not None:
         return out, out_second
     return (out, s_src, s_dst) if heads else out

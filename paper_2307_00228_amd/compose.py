@@ -19,7 +19,7 @@ from . import binding as B
 class LayerTrace:
     gather_src: torch.Tensor        # rows the gather read (state, message rows, or projected rows)
     agg: torch.Tensor               # gather output (GAT and projected layers: the new state)
-    out: torch.Tensor               # new state
+    out: Optional[torch.Tensor]     # new state; None for a layer whose update is chained into the next layer's projection
     projected: bool                 # W_nbr applied before the gather, update fused into the gather's epilogue
     scores: Optional[tuple] = None  # GAT: (s_src, s_dst)
     self_product: Optional[torch.Tensor] = None   # projected layers: h . W_self, the addend of the gather's epilogue
@@ -29,6 +29,11 @@ class LayerTrace:
 def plan(layers, dtype) -> List[bool]:
     """Which layers apply W_nbr before their gather: asked of the library (infer_layer_plan), not decided here."""
     return [p == B.PLAN_PROJECT_GATHER for p in B.infer_layer_plan(layers, dtype)]
+
+
+def chained(layers, dtype) -> List[bool]:
+    """Which layers' updates also produce the next layer's h . [W_nbr | W_self] (and never store their own state)."""
+    return [p == B.PLAN_GATHER_UPDATE_CHAINED for p in B.infer_layer_plan(layers, dtype)]
 
 
 def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torch.Tensor,
@@ -63,9 +68,11 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
     traces = []
     h = x
     projected = plan(layers, x.dtype)
+    chain = chained(layers, x.dtype)
+    handed_over = None   # (h . W_nbr, h . W_self) of this layer, produced by the previous layer's update
     for i, l in enumerate(layers):
         gcn, gat = l.agg == B.AGG_GCN, l.agg == B.AGG_GAT
-        out = buf(("out", i), l.d_out)
+        out = buf(("out", i), l.d_out) if not chain[i] else None
         if l.agg == B.AGG_NONE:       # encoder / prediction head: the update alone
             mark("gather_begin", i)
             mark("gather_end", i)
@@ -90,8 +97,12 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         if projected[i]:
             # h . [W_nbr | W_self] in one launch, then the gather of the first product with the update in its epilogue
             mark("project_begin", i)
-            proj, selfp = B.apply_layer(None, h, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out),
-                                        w_second=l.w_self, out_second=buf(("selfp", i), l.d_out))
+            if handed_over is not None:
+                proj, selfp = handed_over
+                handed_over = None
+            else:
+                proj, selfp = B.apply_layer(None, h, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out),
+                                            w_second=l.w_self, out_second=buf(("selfp", i), l.d_out))
             mark("project_end", i)
             mark("gather_begin", i)
             B.gather_layer(l.agg, rowptr, col, proj, split, None, sd if gcn else None, out=out,
@@ -112,7 +123,15 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
                              edge_coef=coef if gcn else None, addend=edge_term)
         mark("gather_end", i)
         mark("apply_begin", i)
-        B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
+        if chain[i]:
+            nxt = layers[i + 1]
+            _, p1, p2 = B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act,
+                                      chain=(nxt.w_nbr, nxt.w_self, buf(("proj", i + 1), nxt.d_out), buf(("selfp", i + 1), nxt.d_out)),
+                                      store_out=False)
+            handed_over = (p1, p2)
+            out = None
+        else:
+            B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act, out=out)
         mark("apply_end", i)
         traces.append(LayerTrace(h, agg, out, False, None, None, edge_term))
         h = out

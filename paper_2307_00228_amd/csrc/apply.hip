@@ -54,6 +54,13 @@ struct ApplyArgs {
     const void *w2;
     void *out2;
     int32_t n_cols;
+    // optional chained projection (bf16, d_out == 16 * PF so that a finished row tile is exactly one staging area): the
+    // finished rows y = act(...), rounded to the storage type, are multiplied by [wc_first | wc_second] (each
+    // [d_out x dc]) on the spot and stored to outc_first / outc_second ([n x dc]); `out` may then be NULL (y is never
+    // written).  It is the next layer's projection h.[W_nbr | W_self] taken while h is still in the staging area.
+    const void *wc_first, *wc_second;
+    void *outc_first, *outc_second;
+    int32_t dc;
 };
 
 // LDS weight panel: chunk kc (8 fp32 / 16 bf16 values of k), half kh, column j -> one uint4 holding the
@@ -100,6 +107,34 @@ __device__ __forceinline__ void load_weight_panel(uint4 *wlds, const ApplyArgs &
             }
         }
         wlds[idx] = v;
+    }
+}
+
+// LDS panel of the chained projection (bf16): K = d_out of the first product, logical columns [0, dc) from wc_first,
+// [dc, 2 dc) from wc_second, zero beyond; same fragment order as the main panel.
+template <int NT>
+__device__ __forceinline__ void load_chain_panel(uint4 *clds, const ApplyArgs &a) {
+    constexpr int BN = 32 * NT;
+    const int chunks = a.d_out / 16;
+    const int total = chunks * 2 * BN;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int j = idx % BN;
+        const int kh = (idx / BN) & 1;
+        const int kc = idx / (2 * BN);
+        const int k0 = kc * 16 + kh * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (j < 2 * a.dc) {
+            const uint16_t *w = static_cast<const uint16_t *>(j < a.dc ? a.wc_first : a.wc_second);
+            const int col = j < a.dc ? j : j - a.dc;
+            uint32_t e[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) e[t] = w[(int64_t)(k0 + t) * a.dc + col];
+            v.x = e[0] | (e[1] << 16);
+            v.y = e[2] | (e[3] << 16);
+            v.z = e[4] | (e[5] << 16);
+            v.w = e[6] | (e[7] << 16);
+        }
+        clds[idx] = v;
     }
 }
 
@@ -195,8 +230,10 @@ __device__ __forceinline__ int stage_swz(int r) { return (r / (16 / LPR)) % LPR;
 // GTS > 0: the number of k-groups per row tile is this compile-time constant (even); the tile body is then one
 // straight line of code and the wait counts for the rows in flight are exact.  GTS == 0: any number of groups.
 // DUAL: a second product of the same rows (logical columns d_out .. 2 d_out - 1 belong to w2 / out2).
-template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL>
+// CHAIN: the finished row tile is multiplied by a second weight panel before it leaves (ApplyArgs::wc_first).
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL, bool CHAIN = false>
 __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a) {
+    static_assert(!CHAIN || (BF16 && !SCORES && !RAGGED && !DUAL), "the chained projection is built for plain bf16 updates");
     constexpr int SPARTS = BF16 ? 2 : 1;
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
@@ -220,6 +257,8 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     load_weight_panel<BF16, NT, DUAL>(wlds, a, col0, chunks);
     uint4 *slds = wlds + (int64_t)total * 2 * BN;
     if constexpr (SCORES) load_score_panel<BF16>(slds, a, chunks);
+    uint4 *clds = slds + (SCORES ? (int64_t)total * 64 * SPARTS : 0) + (int64_t)kApplyWaves * STG_VECS;  // behind the staging areas
+    if constexpr (CHAIN) load_chain_panel<NT>(clds, a);
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -346,6 +385,10 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     // Accumulator register r of a lane holds row 8*(r/4) + 4*kh + (r%4), column i of its 32-column tile.
     auto epilogue = [&]() __attribute__((always_inline)) {
         const int64_t m0 = tile * kRowsPerBlockTile + (int64_t)w * 32;
+        // CHAIN: the finished rows of this wavefront's tile, as the lanes hold them after the row-wise read-back
+        // (one 16-byte piece = 8 bf16 columns of one row each)
+        constexpr int YK = CHAIN ? ((NT + ENT - 1) / ENT) * (32 / RPI) : 1;
+        uint4 yk[YK];
 #pragma unroll
         for (int nt0 = 0; nt0 < NT; nt0 += ENT) {
             const int npass = (NT - nt0 < ENT) ? NT - nt0 : ENT;
@@ -384,6 +427,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
                 }
                 const int64_t row = m0 + rho;
                 const int col = col0 + nt0 * 32 + u0 * 4;
+                if constexpr (CHAIN) yk[(nt0 / ENT) * (32 / RPI) + t] = make_uint4(0, 0, 0, 0);
                 if (DUAL && row < a.n && u0 * 4 < npass * 32 && col >= a.d_out && col < a.n_cols) {
                     // the second product: plain rows of out2 (d_out is a multiple of the vector width here)
                     const int64_t off = row * a.d_out + (col - a.d_out);
@@ -411,8 +455,14 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
                             for (int e = 0; e < VE; ++e) v[e] = fmaxf(v[e], 0.f);
                         }
                         if constexpr (BF16) {
-                            *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.out) + off) =
+                            const uint4 pk =
                                 make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                            if constexpr (CHAIN) {
+                                yk[(nt0 / ENT) * (32 / RPI) + t] = pk;
+                                if (a.out) *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.out) + off) = pk;
+                            } else {
+                                *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.out) + off) = pk;
+                            }
                             if (a.msg_out)
                                 *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.msg_out) + off) =
                                     make_uint4(pack_bf16x2(v[0] * ms, v[1] * ms), pack_bf16x2(v[2] * ms, v[3] * ms),
@@ -443,6 +493,78 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
                                 }
                             }
                         }
+                    }
+                }
+            }
+        }
+        if constexpr (CHAIN) {
+            // The row tile y [32 x d_out] (d_out == 8 * LPR columns: LPR pieces per row) goes back into the staging area
+            // in the layout the A fragments are read from, is multiplied by the chained panel (PF chunks of 16 k) and
+            // leaves through the staging area once more, as rows of outc_first / outc_second.
+            static_assert(UPL == 2, "a lane holds one 8-column piece per read-back");
+#pragma unroll
+            for (int p = 0; p < (NT + ENT - 1) / ENT; ++p) {
+#pragma unroll
+                for (int t = 0; t < 32 / RPI; ++t) {
+                    const int rho = t * RPI + lane / LPRO;
+                    const int piece = p * ENT * 4 + lane % LPRO;      // 8 columns per piece, 4 pieces per 32-column tile
+                    if (piece < LPR) stage[rho * LPR + (piece ^ stage_swz<LPR>(rho))] = yk[p * (32 / RPI) + t];
+                }
+            }
+            v16f acc2[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc2[nt][r] = 0.f;
+            const uint4 *cbase = clds + kh * BN + i;
+#pragma unroll
+            for (int c2 = 0; c2 < PF; ++c2) {
+                const uint4 av = stage[i * LPR + ((2 * c2 + kh) ^ frag_swz)];
+                uint4 bv[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) bv[nt] = cbase[(int64_t)c2 * 2 * BN + nt * 32];
+                mfma_chunk<true, NT>(acc2, av, bv);
+            }
+#pragma unroll
+            for (int nt0 = 0; nt0 < NT; nt0 += ENT) {
+                const int npass = (NT - nt0 < ENT) ? NT - nt0 : ENT;
+#pragma unroll
+                for (int e = 0; e < ENT; ++e) {
+                    if (e < npass) {
+                        const int nt = nt0 + e;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int rho = 8 * (r / 4) + 4 * kh + (r % 4);
+                            const int col = e * 32 + i;
+                            const int unit = (ENT == 2) ? ((col >> 2) ^ (kh * 8)) : (col >> 2);
+                            const int slot = (ENT == 2) ? rho : (rho ^ kh);
+                            stage32[slot * W + unit * 4 + (col & 3)] = __float_as_uint(acc2[nt][r]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 32 / RPI; ++t) {
+                    const int rho = t * RPI + lane / LPRO;
+                    const int u0 = (lane % LPRO) * UPL;
+                    const int khr = (rho >> 2) & 1;
+                    const int slot = (ENT == 2) ? rho : (rho ^ khr);
+                    const int uswz = (ENT == 2) ? khr * 8 : 0;
+                    float v[8];
+#pragma unroll
+                    for (int j = 0; j < UPL; ++j) {
+                        const uint4 x = stage[(slot * W) / 4 + ((u0 + j) ^ uswz)];
+                        v[4 * j + 0] = __uint_as_float(x.x);
+                        v[4 * j + 1] = __uint_as_float(x.y);
+                        v[4 * j + 2] = __uint_as_float(x.z);
+                        v[4 * j + 3] = __uint_as_float(x.w);
+                    }
+                    const int64_t row = m0 + rho;
+                    const int col = nt0 * 32 + u0 * 4;   // logical column of the chained product (dc is a multiple of 8)
+                    if (row < a.n && u0 * 4 < npass * 32 && col < 2 * a.dc) {
+                        uint16_t *dst = static_cast<uint16_t *>(col < a.dc ? a.outc_first : a.outc_second);
+                        const int64_t off = row * a.dc + (col < a.dc ? col : col - a.dc);
+                        *reinterpret_cast<uint4 *>(dst + off) =
+                            make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
                     }
                 }
             }
@@ -514,18 +636,19 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
 // chunks of KC values per phase, rounded up to whole groups of pf chunks
 int padded_chunks(int d_in, int kc, int pf) { return ((d_in + kc - 1) / kc + pf - 1) / pf * pf; }
 
-template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL>
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL, bool CHAIN = false>
 int32_t launch_staged_one(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     constexpr size_t stage_bytes = (size_t)kApplyWaves * ((32 * 2 * PF > 256) ? 32 * 2 * PF : 256) * 16;
     constexpr int KC = BF16 ? 16 : 8;
     const int k_total = padded_chunks(a.d_in, KC, PF) * KC * (a.h_self ? 2 : 1);
-    const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4) + stage_bytes;
+    const size_t chain_bytes = CHAIN ? (size_t)a.d_out * BN * 2 : 0;   // [d_out x BN] bf16
+    const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4) + stage_bytes + chain_bytes;
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     // once per kernel variant (setting it again is harmless, so a race between two first callers is too)
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL, CHAIN>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set.store(true, std::memory_order_release);
     }
@@ -537,7 +660,7 @@ int32_t launch_staged_one(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL, CHAIN><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -609,9 +732,30 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
     return ITB_ERR_UNSUPPORTED;
 }
 
+// The chained projection: bf16, a finished row tile of exactly one staging area.  Built for 64 output columns (two
+// 32-column tiles, k-groups of 4 chunks); the k range of the first product must be whole groups.
+constexpr int kChainWidth = 64;
+size_t chain_lds_bytes(int d_in, bool has_self) {
+    return (size_t)d_in * (has_self ? 2 : 1) * kChainWidth * 2 + (size_t)kApplyWaves * 256 * 16 + (size_t)kChainWidth * kChainWidth * 2;
+}
+int32_t dispatch_chain(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    if (a.d_out != kChainWidth || a.d_in % 64 != 0 || chain_lds_bytes(a.d_in, a.h_self != nullptr) > kMaxLds) return ITB_ERR_UNSUPPORTED;
+    const int gt = (a.d_in / 64) * (a.h_self ? 2 : 1);
+    if (gt == 2) return launch_staged_one<true, 2, 4, false, false, 2, false, true>(a, n_cus, st);
+    if (gt == 4) return launch_staged_one<true, 2, 4, false, false, 4, false, true>(a, n_cus, st);
+    if (gt == 8) return launch_staged_one<true, 2, 4, false, false, 8, false, true>(a, n_cus, st);
+    return launch_staged_one<true, 2, 4, false, false, 0, false, true>(a, n_cus, st);
+}
+
 }  // namespace
 
 namespace itb {
+// Whether apply_layer takes a chained projection for this shape (the same conditions as its argument checks).
+bool apply_chain_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t dc) {
+    return dtype == ITB_BF16 && d_out == kChainWidth && d_in > 0 && d_in % 64 == 0 && dc > 0 && dc % 8 == 0 && 2 * dc <= kChainWidth &&
+           chain_lds_bytes(d_in, has_self) <= kMaxLds;
+}
+
 // Whether some configuration of the update kernel holds this shape in LDS (the same walk as dispatch_staged): lets
 // the layer loop refuse a model before it has enqueued anything.
 bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t heads) {
@@ -657,7 +801,8 @@ int cached_cu_count() {
 extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, const void *h_self, const void *agg,
                                const void *w_self, const void *w_nbr, const float *bias, void *h_out, const float *att_src,
                                const float *att_dst, float *s_src, float *s_dst, const float *msg_scale, void *msg_out,
-                               const void *addend, const void *w_second, void *out_second, void *stream) {
+                               const void *addend, const void *w_second, void *out_second, const itb_apply_chain *chain,
+                               void *stream) {
     if (!desc) return ITB_ERR_NULL;
     if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31)) return ITB_ERR_SIZE;
     if (desc->dtype != ITB_F32 && desc->dtype != ITB_BF16) return ITB_ERR_DTYPE;
@@ -679,7 +824,14 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     if ((w_second == nullptr) != (out_second == nullptr)) return ITB_ERR_NULL;
     // the second product shares the rows of `agg`: no self term, no score columns, whole 16-byte vectors per row
     if (w_second && (h_self || desc->heads > 0 || desc->d_out % piece != 0)) return ITB_ERR_UNSUPPORTED;
-    if (!w_nbr || !agg || !h_out) return ITB_ERR_NULL;
+    if (chain) {
+        if (!chain->w_first || !chain->w_second || !chain->out_first || !chain->out_second) return ITB_ERR_NULL;
+        if (desc->heads > 0 || w_second || msg_out || desc->d_out % piece != 0 ||
+            !itb::apply_chain_supported(desc->dtype, desc->d_in, desc->d_out, h_self != nullptr, chain->dc))
+            return ITB_ERR_UNSUPPORTED;
+        if (!aligned16(chain->out_first) || !aligned16(chain->out_second)) return ITB_ERR_UNSUPPORTED;
+    }
+    if (!w_nbr || !agg || (!h_out && !chain)) return ITB_ERR_NULL;
     if (!aligned16(h_self) || !aligned16(agg) || !aligned16(h_out) || !aligned16(addend) || !aligned16(msg_out) ||
         !aligned16(out_second))
         return ITB_ERR_UNSUPPORTED;  // rows are moved as 16-byte vectors (a ragged d_out is stored element by element,
@@ -710,6 +862,14 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
     a.n_cols = w_second ? 2 * desc->d_out : desc->d_out;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int cus = cached_cu_count();
+    if (chain) {
+        a.wc_first = chain->w_first;
+        a.wc_second = chain->w_second;
+        a.outc_first = chain->out_first;
+        a.outc_second = chain->out_second;
+        a.dc = chain->dc;
+        return dispatch_chain(a, cus, st);
+    }
     if (desc->dtype == ITB_BF16) return a.heads > 0 ? dispatch_staged<true, true>(a, cus, st) : dispatch_staged<true, false>(a, cus, st);
     return a.heads > 0 ? dispatch_staged<false, true>(a, cus, st) : dispatch_staged<false, false>(a, cus, st);
 }

@@ -5,6 +5,7 @@
 
 namespace itb {
 bool apply_shape_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t heads);
+bool apply_chain_supported(int32_t dtype, int32_t d_in, int32_t d_out, bool has_self, int32_t dc);
 int32_t gather_layer_impl(const itb_gather_desc *desc, int64_t n_nodes, const int64_t *rowptr, const int32_t *col,
                           const itb_split *split, const void *h_src, const float *src_scale, const float *dst_scale,
                           void *agg_out, int64_t edge_lo, int64_t edge_hi, void *workspace, size_t *workspace_bytes,
@@ -138,6 +139,16 @@ static bool project_before_gather(const itb_layer &L, int32_t dtype) {
     return linear && L.w_self != nullptr && !L.w_edge && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
 }
 
+// The update of layer l can hand its rows straight to the projection of a narrowing layer l+1 (one launch, the state
+// between the two layers is never written or read back): layer l is gather -> update, layer l+1 takes W_nbr before its
+// gather and needs nothing of h_l but h_l . [W_nbr | W_self].
+static bool chain_into_next(const itb_layer *layers, int l, int n_layers, int32_t dtype) {
+    if (l + 1 >= n_layers || !g_tuning.chain_updates.load()) return false;
+    const itb_layer &L = layers[l], &N = layers[l + 1];
+    const bool plain = L.agg != ITB_AGG_NONE && L.agg != ITB_AGG_GAT && !project_before_gather(L, dtype);
+    return plain && project_before_gather(N, dtype) && apply_chain_supported(dtype, L.d_in, L.d_out, L.w_self != nullptr, N.d_out);
+}
+
 extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_layer *layers, int32_t *plan) {
     if (!layers || !plan) return ITB_ERR_NULL;
     if (n_layers <= 0) return ITB_ERR_SIZE;
@@ -150,6 +161,9 @@ extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_l
                   : project_before_gather(L, dtype) ? ITB_PLAN_PROJECT_GATHER
                                                     : ITB_PLAN_GATHER_UPDATE;
     }
+    for (int l = 0; l + 1 < n_layers; ++l)
+        if (layers[l + 1].agg >= ITB_AGG_SUM && layers[l + 1].agg <= ITB_AGG_NONE && chain_into_next(layers, l, n_layers, dtype))
+            plan[l] = ITB_PLAN_GATHER_UPDATE_CHAINED;
     return ITB_OK;
 }
 
@@ -268,16 +282,18 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     }
     char *state[2] = {state0, state1};
     const void *cur = x;
+    bool projected_by_previous = false;   // this layer's h . [W_nbr | W_self] came out of the previous layer's update
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         void *dst = (l == n_layers - 1) ? out : static_cast<void *>(state[l & 1]);
+        const bool chain = chain_into_next(layers, l, n_layers, dtype);
         if (mark(l, 0) != ITB_OK) return ITB_ERR_DEVICE;
         if (L.agg == ITB_AGG_NONE) {
             if (mark(l, 1) != ITB_OK || mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;
             // encoder / prediction head (Sec. IV-C): the update alone, on the vertex's own state
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
             int32_t rc = apply_layer(&ad, n_nodes, nullptr, cur, nullptr, L.w_nbr, L.bias, dst, nullptr, nullptr, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, nullptr, nullptr, stream);
+                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;
             cur = dst;
@@ -295,7 +311,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
             itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, L.heads};
             int32_t rc = apply_layer(&pd, n_nodes, nullptr, cur, nullptr, L.w_nbr, nullptr, aggbuf, L.att_src, L.att_dst,
-                                     att_s_src, att_s_dst, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
+                                     att_s_src, att_s_dst, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             gather_src = aggbuf;
             gs = att_s_src;
@@ -305,22 +321,29 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         }
         if (pf) {
             // h . [W_nbr | W_self] in one launch; the gather of the first product finishes the layer in its row epilogue
-            itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
-            int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, L.w_nbr, nullptr, projbuf, nullptr, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, nullptr, L.w_self, aggbuf, stream);
-            if (rc != ITB_OK) return rc;
+            const void *self_product = aggbuf;
+            if (projected_by_previous) {
+                // both products left the previous layer's update: first in projbuf, second in that layer's state buffer
+                self_product = state[(l - 1) & 1];
+            } else {
+                itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
+                int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, L.w_nbr, nullptr, projbuf, nullptr, nullptr,
+                                         nullptr, nullptr, nullptr, nullptr, nullptr, L.w_self, aggbuf, nullptr, stream);
+                if (rc != ITB_OK) return rc;
+            }
             gather_src = projbuf;
             gather_out = dst;
             gd.dim = L.d_out;
-            gd.addend = aggbuf;
+            gd.addend = self_product;
             gd.bias = L.bias;
             gd.act = L.act;
         }
+        projected_by_previous = false;
         if (L.w_edge) {
             // the edge term of the aggregate, in the state space: (reduced edge features) . W_e, added in the gather's epilogue
             itb_apply_desc ed{dtype, edge_dim, L.d_in, ITB_ACT_NONE, 0};
             int32_t rc = apply_layer(&ed, n_nodes, nullptr, edge_sum[L.agg], nullptr, L.w_edge, nullptr, projbuf, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
+                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);
             if (rc != ITB_OK) return rc;
             gd.addend = projbuf;
         }
@@ -352,9 +375,15 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (mark(l, 2) != ITB_OK) return ITB_ERR_DEVICE;
         if (!gat && !pf) {
             itb_apply_desc ad{dtype, L.d_in, L.d_out, L.act, 0};
-            int32_t rc = apply_layer(&ad, n_nodes, L.w_self ? cur : nullptr, aggbuf, L.w_self, L.w_nbr, L.bias, dst, nullptr, nullptr,
-                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, stream);   // no self matrix: no self term
+            // chained: the new state goes straight into the next layer's projection and is never stored; the two products
+            // take the projection buffer and this layer's (otherwise unused) state buffer
+            const itb_layer &N = layers[chain ? l + 1 : l];
+            const itb_apply_chain ch{N.w_nbr, N.w_self, N.d_out, projbuf, dst};
+            int32_t rc = apply_layer(&ad, n_nodes, L.w_self ? cur : nullptr, aggbuf, L.w_self, L.w_nbr, L.bias, chain ? nullptr : dst,
+                                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                     chain ? &ch : nullptr, stream);   // no self matrix: no self term
             if (rc != ITB_OK) return rc;
+            projected_by_previous = chain;
         }
         if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;
         cur = dst;

@@ -83,17 +83,28 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert lib.gather_layer(C.byref(d), 10, None, None, C.byref(sp), None, None, None, None, 0, B.INT64_MAX, None, C.byref(need), None) == -2
     # apply_layer
     a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
-    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
-    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(None, 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.apply_layer(C.byref(a), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -1
     a7 = B.itb_apply_desc(B.ITB_F32, 62, 16, B.ACT_RELU, 0)     # rows of 248 bytes: not whole 16-byte pieces
-    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
+    assert lib.apply_layer(C.byref(a7), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -5
     a9 = B.itb_apply_desc(B.ITB_F32, 64, 16, 5, 0)
-    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
+    assert lib.apply_layer(C.byref(a9), 10, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None, None) == -4
     ok = C.c_void_p(1 << 20)   # second product: both or neither; no self term; whole 16-byte vectors per output row
-    assert lib.apply_layer(C.byref(a), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, None, None) == -1
-    assert lib.apply_layer(C.byref(a), 10, ok, ok, ok, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None) == -5
+    assert lib.apply_layer(C.byref(a), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, None, None, None) == -1
+    assert lib.apply_layer(C.byref(a), 10, ok, ok, ok, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None, None) == -5
     a6 = B.itb_apply_desc(B.ITB_F32, 64, 6, B.ACT_NONE, 0)
-    assert lib.apply_layer(C.byref(a6), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None) == -5
+    assert lib.apply_layer(C.byref(a6), 10, None, ok, None, ok, None, ok, None, None, None, None, None, None, None, ok, ok, None, None) == -5
+    # chained projection: bf16, 64 output columns, k range in whole groups, two products of at most 32 columns each
+    ab = B.itb_apply_desc(B.ITB_BF16, 64, 64, B.ACT_RELU, 0)
+    ch = B.itb_apply_chain(1 << 20, 1 << 20, 32, 1 << 20, 1 << 20)
+    chain_call = lambda desc, c, out=ok: lib.apply_layer(C.byref(desc), 10, None, ok, None, ok, None, out, None, None, None, None,
+                                                         None, None, None, None, None, C.byref(c), None)
+    assert chain_call(a, ch) == -5                                            # fp32
+    assert chain_call(B.itb_apply_desc(B.ITB_BF16, 64, 128, B.ACT_RELU, 0), ch) == -5
+    assert chain_call(B.itb_apply_desc(B.ITB_BF16, 96, 64, B.ACT_RELU, 0), ch) == -5
+    assert chain_call(ab, B.itb_apply_chain(1 << 20, 1 << 20, 40, 1 << 20, 1 << 20)) == -5
+    assert chain_call(ab, B.itb_apply_chain(1 << 20, None, 32, 1 << 20, 1 << 20)) == -1
+    assert chain_call(ab, B.itb_apply_chain(1 << 20, 1 << 20, 32, (1 << 20) + 8, 1 << 20)) == -5
     # infer_full_graph
     assert lib.infer_full_graph(10, 10, None, None, None, None, 0, 0, None, None, None, 0, None, 0, None, C.byref(need), None, None) == -1
     lay = (B.itb_layer * 2)()
@@ -256,7 +267,7 @@ def test_misaligned_feature_tensors_are_refused(B):
     assert lib.gather_layer(*args(off, ok)) == -5 and lib.gather_layer(*args(ok, off)) == -5
     a = B.itb_apply_desc(B.ITB_F32, 64, 16, B.ACT_RELU, 0)
     ap = lambda hs, ag, out, add: lib.apply_layer(C.byref(a), 10, hs, ag, ok if hs else None, ok, None, out, None, None, None, None,
-                                                   None, None, add, None, None, None)
+                                                   None, None, add, None, None, None, None)
     assert ap(None, off, ok, None) == -5 and ap(None, ok, off, None) == -5
     assert ap(off, ok, ok, None) == -5 and ap(None, ok, ok, off) == -5
     assert lib.scale_rows(B.ITB_F32, 10, 64, off, ok, ok, None) == -5
@@ -271,12 +282,13 @@ def test_headers_are_plain_c_and_the_binding_mirrors_their_layout(B, tmp_path):
     if gcc is None:
         pytest.skip("no C compiler")
     structs = {"itb_split": B.itb_split, "itb_gather_desc": B.itb_gather_desc, "itb_apply_desc": B.itb_apply_desc,
-               "itb_layer": B.itb_layer, "itb_stage_events": B.itb_stage_events}
+               "itb_layer": B.itb_layer, "itb_stage_events": B.itb_stage_events, "itb_apply_chain": B.itb_apply_chain}
     enums = {"ITB_F32": B.ITB_F32, "ITB_BF16": B.ITB_BF16, "ITB_AGG_SUM": B.AGG_SUM, "ITB_AGG_MEAN": B.AGG_MEAN,
              "ITB_AGG_GCN": B.AGG_GCN, "ITB_AGG_GAT": B.AGG_GAT, "ITB_AGG_MAX": B.AGG_MAX, "ITB_AGG_MIN": B.AGG_MIN,
              "ITB_AGG_NONE": B.AGG_NONE, "ITB_ACT_NONE": B.ACT_NONE, "ITB_ACT_RELU": B.ACT_RELU,
              "ITB_PLAN_GATHER_UPDATE": B.PLAN_GATHER_UPDATE, "ITB_PLAN_PROJECT_GATHER": B.PLAN_PROJECT_GATHER,
-             "ITB_PLAN_ATTENTION": B.PLAN_ATTENTION, "ITB_PLAN_UPDATE_ONLY": B.PLAN_UPDATE_ONLY}
+             "ITB_PLAN_ATTENTION": B.PLAN_ATTENTION, "ITB_PLAN_UPDATE_ONLY": B.PLAN_UPDATE_ONLY,
+             "ITB_PLAN_GATHER_UPDATE_CHAINED": B.PLAN_GATHER_UPDATE_CHAINED}
     enums.update({name: code for code, name in B.STATUS.items()})
     lines = ['#include "inferturbo.h"', '#include "inferturbo_aids.h"', "#include <stddef.h>", "#include <stdio.h>",
              "int main(void) {"]

@@ -188,9 +188,18 @@ def check_huge(B, name, chunk, min_hub_ratio):
         assert np.array_equal(getattr(split, k).cpu().numpy(), osplit[k]), k
     layers = B.device_layers(w.layers)
     x = B.to_device(w.x)
-    traces = compose.run_layers(rowptr, col, None, split, layers, x)
+    # The single call chains the first layer's update into the second layer's projection (the state between them is
+    # never stored); the layer-by-layer states for the oracle come from the same model with the chaining switched off,
+    # which must end in the same bits.
+    assert B.infer_layer_plan(layers, torch.bfloat16)[0] == B.PLAN_GATHER_UPDATE_CHAINED
+    B.set_tuning(9, 0)
+    try:
+        traces = compose.run_layers(rowptr, col, None, split, layers, x)
+        torch.cuda.synchronize()
+    finally:
+        B.set_tuning(9, 1)
     out = B.infer_full_graph(rowptr, col, None, split, layers, x, edge_chunk=chunk)
-    assert torch.equal(out.view(torch.int16), traces[-1].out.view(torch.int16))     # chunked == unchunked, bitwise
+    assert torch.equal(out.view(torch.int16), traces[-1].out.view(torch.int16))     # chunked + chained == call by call, bitwise
     del out
     first_row_beyond = (1 << 32) // (w.layers[0].d_in * 2)
     verts = sample_vertices(np.random.default_rng(8), n, r, osplit, extra=[first_row_beyond - 1, first_row_beyond, n - 1])

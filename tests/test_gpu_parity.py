@@ -645,6 +645,94 @@ def test_apply_second_product(B, dtype, d_in, d_out, n):
     assert torch.equal(out.view(view), alone1.view(view)) and torch.equal(second.view(view), alone2.view(view))
 
 
+@pytest.mark.parametrize("d_in,with_self", [(64, True), (64, False), (128, True), (256, True), (320, False), (448, True)])
+@pytest.mark.parametrize("dc", [32, 16, 8, 24])
+@pytest.mark.parametrize("n", [1, 37, 1000, 4100])
+def test_apply_chained_projection(B, d_in, with_self, dc, n):
+    """The finished rows of an update (bf16, 64 columns) multiplied by two more matrices in the same launch:
+    y = act(h W_self + agg W_nbr + b), out_first = round(y) W_c1, out_second = round(y) W_c2 -- the oracle applies the
+    two steps one after the other with the stored rounding in between; the chained launch gives the same bits as the
+    two separate launches, with and without storing y."""
+    import torch
+    rng = np.random.default_rng(n + d_in + dc)
+    dtype = W.BF16
+    h = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    agg = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
+    lay = W.dense_layers(rng, W.AGG_MEAN, (d_in, 64, 64), dtype, bias_random=True)[0]
+    nxt = W.dense_layers(rng, W.AGG_MEAN, (64, dc, dc), dtype)[0]
+    hd, ad = B.to_device(h), B.to_device(agg)
+    ws = B.to_device(lay.w_self) if with_self else None
+    wn, bias = B.to_device(lay.w_nbr), B.to_device(lay.bias)
+    c1, c2 = B.to_device(nxt.w_nbr), B.to_device(nxt.w_self)
+    y, p1, p2 = B.apply_layer(hd if with_self else None, ad, ws, wn, bias, W.ACT_RELU, chain=(c1, c2))
+    y64 = oracle.apply(h if with_self else None, agg, lay.w_self if with_self else None, lay.w_nbr, lay.bias, oracle.ACT_RELU)
+    check_features(B.to_numpy(y), y64, dtype, "y")
+    y_st = oracle.round_store(y64, dtype)
+    check_features(B.to_numpy(p1), oracle.apply(None, y_st, None, nxt.w_nbr, None, oracle.ACT_NONE), dtype, "first")
+    check_features(B.to_numpy(p2), oracle.apply(None, y_st, None, nxt.w_self, None, oracle.ACT_NONE), dtype, "second")
+    # the same bits as update and projection issued one after the other
+    y_alone = B.apply_layer(hd if with_self else None, ad, ws, wn, bias, W.ACT_RELU)
+    q1, q2 = B.apply_layer(None, y_alone, None, c1, None, W.ACT_NONE, w_second=c2)
+    view = torch.int16
+    assert torch.equal(y.view(view), y_alone.view(view))
+    assert torch.equal(p1.view(view), q1.view(view)) and torch.equal(p2.view(view), q2.view(view))
+    # and without ever storing y
+    none, r1, r2 = B.apply_layer(hd if with_self else None, ad, ws, wn, bias, W.ACT_RELU, chain=(c1, c2), store_out=False)
+    assert none is None and torch.equal(r1.view(view), p1.view(view)) and torch.equal(r2.view(view), p2.view(view))
+
+
+@pytest.mark.parametrize("dims,kinds", [((64, 64, 32), (W.AGG_MEAN, W.AGG_MEAN)), ((64, 64, 16), (W.AGG_GCN, W.AGG_SUM)),
+                                        ((64, 64, 32, 8), (W.AGG_MEAN, W.AGG_MEAN, W.AGG_MEAN)),
+                                        ((64, 64, 64, 32), (W.AGG_MAX, W.AGG_MEAN, W.AGG_GCN))])
+@pytest.mark.parametrize("chunk", [0, 9000])
+def test_layer_loop_chains_an_update_into_the_next_projection(B, dims, kinds, chunk):
+    """bf16 stacks in which a 64-wide gather -> update layer is followed by a narrowing layer: the plan reports the
+    chaining, the single call matches the oracle and equals, bit for bit, the same model with chaining switched off and
+    the call-by-call composition."""
+    import torch
+    from paper_2307_00228_amd import compose
+    dtype = W.BF16
+    n, e = 5000, 60000
+    src, dst, x = W.random_small_graph(sum(dims), n, e, dims[0], dtype, 0.3)
+    rng = np.random.default_rng(dims[-1])
+    layers = []
+    for i, kind in enumerate(kinds):
+        lay = W.dense_layers(rng, kind, (dims[i], dims[i + 1], dims[i + 1]), dtype, bias_random=True)[0]
+        lay.act = W.ACT_RELU if i + 1 < len(kinds) else W.ACT_NONE
+        layers.append(lay)
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp, cl, dg = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda(), torch.from_numpy(d).cuda()
+    split = B.split_hubs(rp, 1500)
+    dl = B.device_layers(layers)
+    plan = B.infer_layer_plan(dl, torch.bfloat16)
+    assert B.PLAN_GATHER_UPDATE_CHAINED in plan
+    for i, pl in enumerate(plan):
+        if pl == B.PLAN_GATHER_UPDATE_CHAINED:
+            assert plan[i + 1] == B.PLAN_PROJECT_GATHER and dims[i + 1] == 64
+    xd = B.to_device(x)
+    got = B.infer_full_graph(rp, cl, dg, split, dl, xd, edge_chunk=chunk)
+    torch.cuda.synchronize()
+    tr = compose.run_layers(rp, cl, dg, split, dl, xd)
+    assert torch.equal(tr[-1].out.view(torch.int16), got.view(torch.int16))
+    assert any(t.out is None for t in tr)
+    B.set_tuning(9, 0)
+    try:
+        assert B.PLAN_GATHER_UPDATE_CHAINED not in B.infer_layer_plan(dl, torch.bfloat16)
+        plain = B.infer_full_graph(rp, cl, dg, split, dl, xd, edge_chunk=chunk)
+        steps = compose.run_layers(rp, cl, dg, split, dl, xd)
+        torch.cuda.synchronize()
+    finally:
+        B.set_tuning(9, 1)
+    # every layer of the unchained run against Eq. (1) from the state stored for the layer before; the chained run
+    # must then give the same bits
+    h = x
+    for i, (lay, st) in enumerate(zip(layers, steps)):
+        check_layer(B, st, r, c, d, h, lay, dtype, f"layer {i} of {kinds} {dims}")
+        h = B.to_numpy(st.out)
+    assert torch.equal(steps[-1].out.view(torch.int16), got.view(torch.int16))
+    assert torch.equal(plain.view(torch.int16), got.view(torch.int16))
+
+
 @pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN])
 @pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.F32, 16), (W.BF16, 32), (W.BF16, 64), (W.BF16, 520)])
 @pytest.mark.parametrize("T", [None, 40])
@@ -949,6 +1037,16 @@ def test_random_layer_stacks(B, seed):
     assert torch.equal(out.view(view), chunked.view(view))
     steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd)
     assert torch.equal(out.view(view), steps[-1].out.view(view))
+    if any(t.out is None for t in steps):
+        # a chained update never stores its layer's state: take the per-layer states from the same model with chaining
+        # switched off, which must end in the same bits
+        B.set_tuning(9, 0)
+        try:
+            steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd)
+            torch.cuda.synchronize()
+        finally:
+            B.set_tuning(9, 1)
+        assert torch.equal(out.view(view), steps[-1].out.view(view))
     h = x
     for i, (lay, tr) in enumerate(zip(layers, steps)):
         what = f"layer {i} kinds={kinds} widths={widths} T={T}"
