@@ -45,7 +45,9 @@ int32_t itb_random_row_read(const void *table, int64_t n_rows, int32_t row_bytes
  * faster on a 12.8 GB table, 5-10 % slower on tables of 1 GB and less; the
  * probe itb_random_row_read follows the same switch); 9 = the update of a
  * layer feeds the projection of a following narrowing layer in the same
- * launch (1 = on). */
+ * launch (1 = on); 10 = attention scores of a projection taken in its
+ * epilogue instead of by an extra score tile (1 = where the head width allows
+ * it and d_in >= 256, 2 = wherever the head width allows it, 0 = never). */
 int32_t itb_set_tuning(int32_t key, int32_t value);
 
 #ifdef __cplusplus

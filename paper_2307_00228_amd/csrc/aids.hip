@@ -119,5 +119,6 @@ extern "C" int32_t itb_set_tuning(int32_t key, int32_t value) {
     if (key == 7) { t.gather_unroll = value; return ITB_OK; }
     if (key == 8 && value >= -1 && value <= 1) { t.row_load_policy = value; return ITB_OK; }
     if (key == 9) { t.chain_updates = value; return ITB_OK; }
+    if (key == 10) { t.epilogue_scores = value; return ITB_OK; }
     return ITB_ERR_UNSUPPORTED;
 }

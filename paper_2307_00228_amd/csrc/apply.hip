@@ -231,9 +231,15 @@ __device__ __forceinline__ int stage_swz(int r) { return (r / (16 / LPR)) % LPR;
 // straight line of code and the wait counts for the rows in flight are exact.  GTS == 0: any number of groups.
 // DUAL: a second product of the same rows (logical columns d_out .. 2 d_out - 1 belong to w2 / out2).
 // CHAIN: the finished row tile is multiplied by a second weight panel before it leaves (ApplyArgs::wc_first).
-template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL, bool CHAIN = false>
+// ESC: attention scores taken in the epilogue instead of by a score tile: the finished fp32 rows pass through the lanes
+// row by row anyway, so a lane multiplies its piece of the row by the matching piece of att_src / att_dst, the lanes
+// of one head add up by xor-shuffles, and heads wider than one epilogue pass carry their partial sum to the next pass.
+// No score panel in LDS and no extra matrix instructions, which also leaves the registers for the straight-line tile
+// body.  Needs a power-of-two head width that divides the block's column range.
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL, bool CHAIN = false, bool ESC = false>
 __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a) {
     static_assert(!CHAIN || (BF16 && !SCORES && !RAGGED && !DUAL), "the chained projection is built for plain bf16 updates");
+    static_assert(!ESC || (!SCORES && !RAGGED && !DUAL && !CHAIN), "epilogue scores replace the score tile of a plain projection");
     constexpr int SPARTS = BF16 ? 2 : 1;
     constexpr int BN = 32 * NT;
     constexpr int KC = BF16 ? 16 : 8;
@@ -259,6 +265,14 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
     if constexpr (SCORES) load_score_panel<BF16>(slds, a, chunks);
     uint4 *clds = slds + (SCORES ? (int64_t)total * 64 * SPARTS : 0) + (int64_t)kApplyWaves * STG_VECS;  // behind the staging areas
     if constexpr (CHAIN) load_chain_panel<NT>(clds, a);
+    float *attl = reinterpret_cast<float *>(clds);   // ESC: att_src then att_dst of this block's columns
+    if constexpr (ESC) {
+        for (int c = threadIdx.x; c < 2 * BN; c += blockDim.x) {
+            const int col = col0 + (c % BN);
+            const float *att = c < BN ? a.att_src : a.att_dst;
+            attl[c] = col < a.d_out ? att[col] : 0.f;     // att is [heads x dh] = d_out consecutive values
+        }
+    }
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -389,6 +403,12 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
         // (one 16-byte piece = 8 bf16 columns of one row each)
         constexpr int YK = CHAIN ? ((NT + ENT - 1) / ENT) * (32 / RPI) : 1;
         uint4 yk[YK];
+        // ESC: running score sums of the rows this lane reads back (one per read-back step), carried across passes
+        float esc_s[ESC ? 32 / RPI : 1], esc_d[ESC ? 32 / RPI : 1];
+        if constexpr (ESC) {
+#pragma unroll
+            for (int t = 0; t < 32 / RPI; ++t) esc_s[t] = esc_d[t] = 0.f;
+        }
 #pragma unroll
         for (int nt0 = 0; nt0 < NT; nt0 += ENT) {
             const int npass = (NT - nt0 < ENT) ? NT - nt0 : ENT;
@@ -428,6 +448,35 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
                 const int64_t row = m0 + rho;
                 const int col = col0 + nt0 * 32 + u0 * 4;
                 if constexpr (CHAIN) yk[(nt0 / ENT) * (32 / RPI) + t] = make_uint4(0, 0, 0, 0);
+                if constexpr (ESC) {
+                    const int dh = a.d_out / a.heads;
+                    const int cl = nt0 * 32 + u0 * 4;                 // column inside the block
+                    float ps = 0.f, pd = 0.f;
+                    if (u0 * 4 < npass * 32) {                         // (att is zero beyond d_out)
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) {
+                            ps = fmaf(v[e], attl[cl + e], ps);
+                            pd = fmaf(v[e], attl[BN + cl + e], pd);
+                        }
+                    }
+                    const int lanes_per_head = dh / VE < LPRO ? dh / VE : LPRO;   // of this pass; a power of two
+                    for (int off = 1; off < lanes_per_head; off <<= 1) {
+                        ps += __shfl_xor(ps, off, kWave);
+                        pd += __shfl_xor(pd, off, kWave);
+                    }
+                    esc_s[t] += ps;
+                    esc_d[t] += pd;
+                    const int pass_end = col0 + nt0 * 32 + npass * 32;   // first column after this pass
+                    const bool head_done = dh <= npass * 32 || pass_end % dh == 0;
+                    if (head_done) {
+                        if ((lane % LPRO) % lanes_per_head == 0 && row < a.n && col < a.d_out && u0 * 4 < npass * 32) {
+                            const int k = col / dh;
+                            a.s_src[row * a.heads + k] = esc_s[t];
+                            a.s_dst[row * a.heads + k] = esc_d[t];
+                        }
+                        esc_s[t] = esc_d[t] = 0.f;
+                    }
+                }
                 if (DUAL && row < a.n && u0 * 4 < npass * 32 && col >= a.d_out && col < a.n_cols) {
                     // the second product: plain rows of out2 (d_out is a multiple of the vector width here)
                     const int64_t off = row * a.d_out + (col - a.d_out);
@@ -636,19 +685,19 @@ __global__ __launch_bounds__(kApplyThreads) void apply_staged_kernel(ApplyArgs a
 // chunks of KC values per phase, rounded up to whole groups of pf chunks
 int padded_chunks(int d_in, int kc, int pf) { return ((d_in + kc - 1) / kc + pf - 1) / pf * pf; }
 
-template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL, bool CHAIN = false>
+template <bool BF16, int NT, int PF, bool SCORES, bool RAGGED, int GTS, bool DUAL, bool CHAIN = false, bool ESC = false>
 int32_t launch_staged_one(const ApplyArgs &a, int n_cus, hipStream_t st) {
     constexpr int BN = 32 * NT;
     constexpr size_t stage_bytes = (size_t)kApplyWaves * ((32 * 2 * PF > 256) ? 32 * 2 * PF : 256) * 16;
     constexpr int KC = BF16 ? 16 : 8;
     const int k_total = padded_chunks(a.d_in, KC, PF) * KC * (a.h_self ? 2 : 1);
-    const size_t chain_bytes = CHAIN ? (size_t)a.d_out * BN * 2 : 0;   // [d_out x BN] bf16
+    const size_t chain_bytes = CHAIN ? (size_t)a.d_out * BN * 2 : (ESC ? (size_t)2 * BN * 4 : 0);   // [d_out x BN] bf16 / att pieces
     const size_t lds = (size_t)k_total * (BN + (SCORES ? 32 * (BF16 ? 2 : 1) : 0)) * (BF16 ? 2 : 4) + stage_bytes + chain_bytes;
     if (lds > kMaxLds) return ITB_ERR_UNSUPPORTED;
     // once per kernel variant (setting it again is harmless, so a race between two first callers is too)
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL, CHAIN>),
+        ITB_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL, CHAIN, ESC>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds));
         attr_set.store(true, std::memory_order_release);
     }
@@ -660,7 +709,7 @@ int32_t launch_staged_one(const ApplyArgs &a, int n_cus, hipStream_t st) {
     if (gx < 1) gx = 1;
     if (gx > a.n_row_tiles) gx = a.n_row_tiles;
     dim3 grid((unsigned)gx, (unsigned)col_tiles);
-    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL, CHAIN><<<grid, kApplyThreads, lds, st>>>(a);
+    apply_staged_kernel<BF16, NT, PF, SCORES, RAGGED, GTS, DUAL, CHAIN, ESC><<<grid, kApplyThreads, lds, st>>>(a);
     ITB_LAUNCH_CHECK();
     return ITB_OK;
 }
@@ -728,6 +777,52 @@ int32_t dispatch_staged(const ApplyArgs &a, int n_cus, hipStream_t st) {
             ITB_STAGED_CASE(1, 8) ITB_STAGED_CASE(1, 4) ITB_STAGED_CASE(1, 2) ITB_STAGED_CASE(1, 1)
 #undef ITB_STAGED_CASE
         }
+    }
+    return ITB_ERR_UNSUPPORTED;
+}
+
+// Projection with attention scores taken in the epilogue: no score panel, so the shapes that have a straight-line
+// variant keep it.  Column tile of 128 (or the narrowest that covers d_out); returns ITB_ERR_UNSUPPORTED when the
+// caller should fall back to the score-tile variant.
+template <bool BF16>
+int32_t dispatch_epilogue_scores(const ApplyArgs &a, int n_cus, hipStream_t st) {
+    constexpr int KC = BF16 ? 16 : 8;
+    constexpr int VE = BF16 ? 8 : 4;
+    const int want = g_tuning.epilogue_scores.load();   // A/B switch 10: 0 never, 1 by shape, 2 whenever possible
+    if (a.bias || a.h_self || a.heads <= 0 || a.d_out % a.heads != 0 || a.d_out % VE != 0 || want == 0) return ITB_ERR_UNSUPPORTED;
+    // The epilogue work is fixed per row tile, the score tile costs two matrix instructions per 16 values of k: measured
+    // (bf16, 4 heads, 2e6 rows) 256 -> 256: 0.61 ms against 0.77 ms with the score tile; 128 -> 128: 0.33 against 0.30.
+    if (want == 1 && a.d_in < 256) return ITB_ERR_UNSUPPORTED;
+    const int dh = a.d_out / a.heads;
+    if (dh < VE || (dh & (dh - 1)) != 0) return ITB_ERR_UNSUPPORTED;      // power-of-two head width, whole pieces
+    const int nt = a.d_out > 64 ? 4 : (a.d_out > 32 ? 2 : 1);
+    if ((32 * nt) % dh != 0) return ITB_ERR_UNSUPPORTED;                    // a head must not straddle column blocks
+    const int real_chunks = (a.d_in + KC - 1) / KC;
+    const size_t esz = BF16 ? 2 : 4;
+    auto fits = [&](int pf) {
+        const int chunks = padded_chunks(a.d_in, KC, pf);
+        if (pf > 1 && 4 * (chunks - real_chunks) > real_chunks) return false;
+        const size_t panel = (size_t)chunks * KC * 32 * nt * esz;
+        const size_t stage = (size_t)kApplyWaves * ((64 * pf > 256) ? 64 * pf : 256) * 16;
+        return panel + stage + (size_t)2 * 32 * nt * 4 <= kMaxLds;
+    };
+    if (nt == 4) {
+        for (int pf = 8; pf >= 4; pf /= 2) {
+            if (!fits(pf) || padded_chunks(a.d_in, KC, pf) != real_chunks || a.d_in % KC != 0) continue;
+            const int gt = real_chunks / pf;
+#define ITB_ESC_STATIC(PF_, GT_) \
+    if (pf == PF_ && gt == GT_) return launch_staged_one<BF16, 4, PF_, false, false, GT_, false, false, true>(a, n_cus, st);
+            ITB_ESC_STATIC(8, 2) ITB_ESC_STATIC(8, 4) ITB_ESC_STATIC(8, 8) ITB_ESC_STATIC(4, 2) ITB_ESC_STATIC(4, 4) ITB_ESC_STATIC(4, 8)
+#undef ITB_ESC_STATIC
+        }
+    }
+    for (int pf = 8; pf >= 1; pf /= 2) {
+        if (pf == 2 || !fits(pf)) continue;
+#define ITB_ESC_CASE(NT_, PF_) \
+    if (nt == NT_ && pf == PF_) return launch_staged_one<BF16, NT_, PF_, false, false, 0, false, false, true>(a, n_cus, st);
+        ITB_ESC_CASE(4, 8) ITB_ESC_CASE(4, 4) ITB_ESC_CASE(4, 1) ITB_ESC_CASE(2, 8) ITB_ESC_CASE(2, 4) ITB_ESC_CASE(2, 1)
+        ITB_ESC_CASE(1, 8) ITB_ESC_CASE(1, 4) ITB_ESC_CASE(1, 1)
+#undef ITB_ESC_CASE
     }
     return ITB_ERR_UNSUPPORTED;
 }
@@ -869,6 +964,11 @@ extern "C" int32_t apply_layer(const itb_apply_desc *desc, int64_t n_nodes, cons
         a.outc_second = chain->out_second;
         a.dc = chain->dc;
         return dispatch_chain(a, cus, st);
+    }
+    if (a.heads > 0 && aligned16(att_src) && aligned16(att_dst)) {
+        // scores in the epilogue where the head width allows it, else by the score tile
+        const int32_t rc = desc->dtype == ITB_BF16 ? dispatch_epilogue_scores<true>(a, cus, st) : dispatch_epilogue_scores<false>(a, cus, st);
+        if (rc != ITB_ERR_UNSUPPORTED) return rc;
     }
     if (desc->dtype == ITB_BF16) return a.heads > 0 ? dispatch_staged<true, true>(a, cus, st) : dispatch_staged<true, false>(a, cus, st);
     return a.heads > 0 ? dispatch_staged<false, true>(a, cus, st) : dispatch_staged<false, false>(a, cus, st);

@@ -49,6 +49,7 @@ struct Tuning {
     std::atomic<int> gather_unroll{-1};       // [7] row loads in flight per lane of the gather loops (-1 = built-in)
     std::atomic<int> row_load_policy{-1};     // [8] random row loads: 0 = plain, 1 = non-temporal, -1 = by table size
     std::atomic<int> chain_updates{1};        // [9] an update feeds the next (narrowing) layer's projection in the same launch
+    std::atomic<int> epilogue_scores{1};      // [10] attention scores of a projection from its epilogue (0 = always by the score tile)
 };
 extern Tuning g_tuning;
 

@@ -902,19 +902,35 @@ def test_gat_gather(B, dtype, heads, dh, T):
             np.testing.assert_allclose(W.as_f32(B.to_numpy(out))[5], W.as_f32(z)[5], rtol=1e-6)
 
 
-@pytest.mark.parametrize("dtype,d_in,heads,dh", [(W.F32, 64, 4, 32), (W.BF16, 256, 4, 64), (W.BF16, 64, 1, 64), (W.BF16, 32, 3, 64)])
+@pytest.mark.parametrize("dtype,d_in,heads,dh", [(W.F32, 64, 4, 32), (W.BF16, 256, 4, 64), (W.BF16, 64, 1, 64), (W.BF16, 32, 3, 64),
+                                                 (W.BF16, 128, 2, 128), (W.BF16, 64, 1, 256), (W.F32, 96, 8, 4), (W.BF16, 48, 16, 8),
+                                                 (W.F32, 200, 2, 16), (W.BF16, 64, 3, 24), (W.F32, 32, 1, 32), (W.BF16, 512, 2, 64)])
 @pytest.mark.parametrize("n", [1, 33, 3000])
 def test_apply_projection_with_scores(B, dtype, d_in, heads, dh, n):
+    """z = h W and the attention scores of every head from the unrounded z.  The scores come out of the epilogue where
+    the head width is a power of two inside one column block (by default only for d_in >= 256, where it is faster), else out
+    of an extra score tile: both ways are forced in turn and held to the same bar; z is the same bits either way."""
+    import torch
     rng = np.random.default_rng(d_in + heads + n)
     h = W.store(rng.standard_normal((n, d_in)).astype(np.float32), dtype)
     lay = W.gat_layers(rng, (d_in, heads * dh), heads, dtype)[0]
-    out, s_src, s_dst = B.apply_layer(None, B.to_device(h), None, B.to_device(lay.w_nbr), None, W.ACT_NONE, heads=heads,
-                                      att_src=B.to_device(lay.att_src), att_dst=B.to_device(lay.att_dst))
     z64 = oracle.apply(None, h, None, lay.w_nbr, None, oracle.ACT_NONE)
-    check_features(B.to_numpy(out), z64, dtype)
-    for got, att in ((s_src, lay.att_src), (s_dst, lay.att_dst)):
-        want = oracle.gat_scores(z64, att)
-        assert np.abs(got.cpu().numpy() - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+    outs = []
+    try:
+        for epilogue in (2, 0):
+            B.set_tuning(10, epilogue)
+            out, s_src, s_dst = B.apply_layer(None, B.to_device(h), None, B.to_device(lay.w_nbr), None, W.ACT_NONE, heads=heads,
+                                              att_src=B.to_device(lay.att_src), att_dst=B.to_device(lay.att_dst))
+            torch.cuda.synchronize()
+            check_features(B.to_numpy(out), z64, dtype, f"epilogue={epilogue}")
+            for got, att in ((s_src, lay.att_src), (s_dst, lay.att_dst)):
+                want = oracle.gat_scores(z64, att)
+                assert np.abs(got.cpu().numpy() - want).max() <= 1e-4 * max(1.0, np.abs(want).max()), f"epilogue={epilogue}"
+            outs.append(out)
+    finally:
+        B.set_tuning(10, 1)
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    assert torch.equal(outs[0].view(view), outs[1].view(view))
 
 
 @pytest.mark.parametrize("dtype", [W.F32, W.BF16])
