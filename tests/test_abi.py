@@ -151,6 +151,28 @@ def test_infer_layer_plan_is_the_librarys_decision(B):
     assert B.lib.infer_layer_plan(B.ITB_BF16, 1, lay, plan) == 0 and plan[0] == B.PLAN_GATHER_UPDATE
     assert B.lib.infer_layer_plan(B.ITB_F32, 0, lay, plan) == -2 and B.lib.infer_layer_plan(5, 1, lay, plan) == -4
     assert B.lib.infer_layer_plan(B.ITB_F32, 1, None, plan) == -1
+    # a 64-wide bf16 gather -> update layer in front of a narrowing layer hands its rows to that layer's projection
+    ch = (B.itb_layer * 3)()
+    ch[0] = B.itb_layer(B.AGG_MEAN, 64, 64, B.ACT_RELU, 1, 0.2, p, p, None, None, None)
+    ch[1] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_RELU, 1, 0.2, p, p, None, None, None)
+    ch[2] = B.itb_layer(B.AGG_MEAN, 32, 8, B.ACT_NONE, 1, 0.2, p, p, None, None, None)
+    plan3 = (C.c_int32 * 3)()
+    assert B.lib.infer_layer_plan(B.ITB_BF16, 3, ch, plan3) == 0
+    assert list(plan3) == [B.PLAN_GATHER_UPDATE_CHAINED, B.PLAN_PROJECT_GATHER, B.PLAN_PROJECT_GATHER]
+    assert B.lib.infer_layer_plan(B.ITB_F32, 3, ch, plan3) == 0                               # built for bf16 only
+    assert list(plan3) == [B.PLAN_GATHER_UPDATE, B.PLAN_PROJECT_GATHER, B.PLAN_PROJECT_GATHER]
+    ch[0] = B.itb_layer(B.AGG_MEAN, 96, 64, B.ACT_RELU, 1, 0.2, p, p, None, None, None)       # narrowing itself: projected
+    assert B.lib.infer_layer_plan(B.ITB_BF16, 3, ch, plan3) == 0 and plan3[0] == B.PLAN_PROJECT_GATHER
+    ch[0] = B.itb_layer(B.AGG_MAX, 64, 64, B.ACT_RELU, 1, 0.2, p, p, None, None, None)        # any aggregate may feed the chain
+    assert B.lib.infer_layer_plan(B.ITB_BF16, 3, ch, plan3) == 0 and plan3[0] == B.PLAN_GATHER_UPDATE_CHAINED
+    ch[1] = B.itb_layer(B.AGG_MEAN, 64, 48, B.ACT_RELU, 1, 0.2, p, p, None, None, None)       # two products of 48 columns: too wide
+    assert B.lib.infer_layer_plan(B.ITB_BF16, 2, ch, plan3) == 0 and plan3[0] == B.PLAN_GATHER_UPDATE
+    ch[1] = B.itb_layer(B.AGG_MEAN, 64, 32, B.ACT_RELU, 1, 0.2, p, p, None, None, None)
+    assert B.lib.itb_set_tuning(9, 0) == 0
+    try:
+        assert B.lib.infer_layer_plan(B.ITB_BF16, 2, ch, plan3) == 0 and plan3[0] == B.PLAN_GATHER_UPDATE
+    finally:
+        assert B.lib.itb_set_tuning(9, 1) == 0
 
 
 def test_hub_threshold_heuristic_matches_golden_and_oracle(B):
