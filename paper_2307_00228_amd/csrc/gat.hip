@@ -201,9 +201,10 @@ __device__ __forceinline__ void finish_store(const GatArgs &a, int64_t row, int 
         uint4 p;
         p.x = pack_bf16x2(y[0], y[1]); p.y = pack_bf16x2(y[2], y[3]);
         p.z = pack_bf16x2(y[4], y[5]); p.w = pack_bf16x2(y[6], y[7]);
-        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.out) + elem0) = p;
+        store_piece(static_cast<uint16_t *>(a.out) + elem0, p, a.stream_rows);   // non-temporal beside streamed row loads
     } else {
-        *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + elem0) = make_float4(y[0], y[1], y[2], y[3]);
+        store_piece(static_cast<float *>(a.out) + elem0,
+                    make_uint4(__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]), __float_as_uint(y[3])), a.stream_rows);
     }
 }
 
