@@ -394,7 +394,15 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
  * act(gather(h . W_nbr) + h . W_self + bias): one matrix launch with two
  * products, then the gather with the update fused into its row epilogue (see
- * gather_layer); infer_layer_plan reports which layers take that form.  GCN
+ * gather_layer); infer_layer_plan reports which layers take that form.  It
+ * needs whole 16-byte output rows (d_out a multiple of 4 in fp32, of 8 in
+ * bf16): a narrowing layer of another width (47 classes, say) is evaluated as
+ * gather(h) followed by the update, whose gather moves d_in instead of d_out
+ * elements per edge -- padding W_self, W_nbr and the bias with zero columns
+ * up to the next multiple (and ignoring the padding columns of `out`) gets the
+ * cheaper form.  A gather -> update layer of 64 bf16 columns in front of such a
+ * layer hands its rows to that layer's two products inside its own update
+ * launch (apply_layer's `chain`), and its state is never stored.  GCN
  * layers share one array of per-edge source coefficients
  * (gcn_edge_coefficients) built at the start.  With edge_chunk > 0 there may be
  * at most 65536 ranges.
