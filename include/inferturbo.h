@@ -394,13 +394,12 @@ int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, c
  * A sum/mean/GCN layer with d_out < d_in and a self matrix is evaluated as
  * act(gather(h . W_nbr) + h . W_self + bias): one matrix launch with two
  * products, then the gather with the update fused into its row epilogue (see
- * gather_layer); infer_layer_plan reports which layers take that form.  It
- * needs whole 16-byte output rows (d_out a multiple of 4 in fp32, of 8 in
- * bf16): a narrowing layer of another width (47 classes, say) is evaluated as
- * gather(h) followed by the update, whose gather moves d_in instead of d_out
- * elements per edge -- padding W_self, W_nbr and the bias with zero columns
- * up to the next multiple (and ignoring the padding columns of `out`) gets the
- * cheaper form.  A gather -> update layer of 64 bf16 columns in front of such a
+ * gather_layer); infer_layer_plan reports which layers take that form.  The
+ * products have whole 16-byte rows: a last layer of another width (47 classes,
+ * say) runs on zero-padded copies of its matrices and bias made at the start
+ * of the call (copy_columns), and the padding columns are dropped when `out` is
+ * written; the form is taken when the padded width is still below d_in.
+ * A gather -> update layer of 64 bf16 columns in front of such a
  * layer hands its rows to that layer's two products inside its own update
  * launch (apply_layer's `chain`), and its state is never stored.  GCN
  * layers share one array of per-edge source coefficients
@@ -445,6 +444,17 @@ int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int64_t *rowptr
                          const void *edge_feat, int32_t edge_dim,
                          void *workspace, size_t *workspace_bytes,
                          const itb_stage_events *events, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * copy_columns -- out[r][c] = in[r][c] for c < min(cols_in, cols_out) and 0 for
+ * the columns a wider `out` has beyond cols_in: pads a row-major matrix
+ * [rows x cols_in] to [rows x cols_out] with zero columns, or keeps the first
+ * cols_out columns of every row.  infer_full_graph uses it for a projected last
+ * layer whose width is not whole 16-byte pieces (see there).  `in` and `out`
+ * are device buffers of `dtype` elements and must not overlap.
+ * ------------------------------------------------------------------------- */
+int32_t copy_columns(int32_t dtype, int64_t rows, int32_t cols_in, int32_t cols_out, const void *in, void *out,
+                     void *stream);
 
 /* ---------------------------------------------------------------------------
  * infer_layer_plan -- the evaluation order infer_full_graph takes for every

@@ -82,6 +82,7 @@ def _load():
                                 C.POINTER(itb_apply_chain), vp]
     lib.infer_layer_plan.argtypes = [i32, i32, C.POINTER(itb_layer), C.POINTER(i32)]
     lib.scale_rows.argtypes = [i32, i64, i32, vp, vp, vp, vp]
+    lib.copy_columns.argtypes = [i32, i64, i32, i32, vp, vp, vp]
     lib.gather_layer_noalloc.argtypes = [C.POINTER(itb_gather_desc), i64, vp, vp, C.POINTER(itb_split), vp, vp, vp, vp,
                                          i64, i64, vp]
     lib.infer_full_graph.argtypes = [i64, i64, vp, vp, vp, C.POINTER(itb_split), i32, i32, C.POINTER(itb_layer),
@@ -95,7 +96,7 @@ def _load():
     for f in ("itb_copy_bytes", "scale_rows", "build_csr_by_dst", "split_hubs", "gcn_norm_scales", "gather_layer", "apply_layer",
               "infer_full_graph", "itb_set_tuning", "hub_threshold_heuristic", "gcn_edge_coefficients",
               "gather_layer_noalloc", "itb_shutdown", "itb_random_row_read", "infer_layer_plan",
-              "aggregate_edge_features"):
+              "aggregate_edge_features", "copy_columns"):
         getattr(lib, f).restype = i32
     return lib
 
@@ -220,6 +221,15 @@ def split_hubs(rowptr: torch.Tensor, threshold: int) -> Split:
                                               _ptr(sp.hub_shadow_off), _ptr(sp.shadow_begin), _ptr(sp.shadow_end),
                                               _ptr(sp.shadow_owner), _ptr(ws), C.byref(size), _stream()))
     return sp
+
+
+def copy_columns(a: torch.Tensor, cols_out: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """[rows x cols_in] -> [rows x cols_out]: zero columns appended, or the first cols_out columns kept."""
+    rows, cols_in = a.shape
+    if out is None:
+        out = torch.empty((rows, cols_out), dtype=a.dtype, device="cuda")
+    _check("copy_columns", lib.copy_columns(dtype_code(a), rows, cols_in, cols_out, _ptr(a), _ptr(out), _stream()))
+    return out
 
 
 def gcn_norm_scales(rowptr: torch.Tensor, deg_out: torch.Tensor):

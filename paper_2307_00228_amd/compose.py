@@ -70,6 +70,14 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
     projected = plan(layers, x.dtype)
     chain = chained(layers, x.dtype)
     handed_over = None   # (h . W_nbr, h . W_self) of this layer, produced by the previous layer's update
+    # a projected last layer whose width is not whole 16-byte pieces runs on zero-padded copies of its matrices and bias
+    piece = 8 if x.dtype == torch.bfloat16 else 4
+    last = layers[-1]
+    dp_last = (last.d_out + piece - 1) // piece * piece
+    padded = None
+    if projected[-1] and dp_last != last.d_out:
+        padded = (B.copy_columns(last.w_nbr, dp_last), B.copy_columns(last.w_self, dp_last),
+                  B.copy_columns(last.bias.view(1, -1), dp_last).view(-1) if last.bias is not None else None)
     for i, l in enumerate(layers):
         gcn, gat = l.agg == B.AGG_GCN, l.agg == B.AGG_GAT
         out = buf(("out", i), l.d_out) if not chain[i] else None
@@ -97,16 +105,22 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         if projected[i]:
             # h . [W_nbr | W_self] in one launch, then the gather of the first product with the update in its epilogue
             mark("project_begin", i)
+            pad = padded if i == len(layers) - 1 else None
+            width = dp_last if pad else l.d_out
+            w_nbr, w_self, bias = pad if pad else (l.w_nbr, l.w_self, l.bias)
             if handed_over is not None:
                 proj, selfp = handed_over
                 handed_over = None
             else:
-                proj, selfp = B.apply_layer(None, h, None, l.w_nbr, None, B.ACT_NONE, out=buf(("proj", i), l.d_out),
-                                            w_second=l.w_self, out_second=buf(("selfp", i), l.d_out))
+                proj, selfp = B.apply_layer(None, h, None, w_nbr, None, B.ACT_NONE, out=buf(("proj", i), width),
+                                            w_second=w_self, out_second=buf(("selfp", i), width))
             mark("project_end", i)
             mark("gather_begin", i)
-            B.gather_layer(l.agg, rowptr, col, proj, split, None, sd if gcn else None, out=out,
-                           edge_coef=coef if gcn else None, addend=selfp, bias=l.bias, act=l.act)
+            wide = buf(("padded_out", i), width) if pad else out
+            B.gather_layer(l.agg, rowptr, col, proj, split, None, sd if gcn else None, out=wide,
+                           edge_coef=coef if gcn else None, addend=selfp, bias=bias, act=l.act)
+            if pad:
+                B.copy_columns(wide, l.d_out, out=out)       # drop the padding columns
             mark("gather_end", i)
             mark("apply_begin", i)
             mark("apply_end", i)
@@ -125,8 +139,10 @@ def run_layers(rowptr, col, deg_out, split, layers: List[B.DeviceLayer], x: torc
         mark("apply_begin", i)
         if chain[i]:
             nxt = layers[i + 1]
+            nxt_pad = padded if i + 1 == len(layers) - 1 else None
+            nw, ns, nwidth = (nxt_pad[0], nxt_pad[1], dp_last) if nxt_pad else (nxt.w_nbr, nxt.w_self, nxt.d_out)
             _, p1, p2 = B.apply_layer(h if l.w_self is not None else None, agg, l.w_self, l.w_nbr, l.bias, l.act,
-                                      chain=(nxt.w_nbr, nxt.w_self, buf(("proj", i + 1), nxt.d_out), buf(("selfp", i + 1), nxt.d_out)),
+                                      chain=(nw, ns, buf(("proj", i + 1), nwidth), buf(("selfp", i + 1), nwidth)),
                                       store_out=False)
             handed_over = (p1, p2)
             out = None

@@ -76,7 +76,35 @@ __global__ void scale_rows_kernel(const uint4 *x, const float *scale, uint4 *out
     }
 }
 
+// out[r][c] = in[r][c] for c < min(cols_in, cols_out), 0 for the columns a wider `out` has beyond cols_in.
+template <typename T>
+__global__ void copy_columns_kernel(const T *in, T *out, int64_t rows, int32_t cols_in, int32_t cols_out) {
+    const int64_t total = rows * cols_out;
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / cols_out;
+        const int32_t c = (int32_t)(i - r * cols_out);
+        out[i] = c < cols_in ? in[r * cols_in + c] : T(0);
+    }
+}
+
 }  // namespace
+
+extern "C" int32_t copy_columns(int32_t dtype, int64_t rows, int32_t cols_in, int32_t cols_out, const void *in, void *out,
+                                void *stream) {
+    if (dtype != ITB_F32 && dtype != ITB_BF16) return ITB_ERR_DTYPE;
+    if (rows < 0 || cols_in <= 0 || cols_out <= 0 || rows >= ((int64_t)1 << 40)) return ITB_ERR_SIZE;
+    if (rows > 0 && (!in || !out)) return ITB_ERR_NULL;
+    if (rows == 0) return ITB_OK;
+    int64_t g = (rows * cols_out + 255) / 256;
+    if (g > 65536) g = 65536;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == ITB_BF16)
+        copy_columns_kernel<uint16_t><<<(unsigned)g, 256, 0, st>>>(static_cast<const uint16_t *>(in), static_cast<uint16_t *>(out), rows, cols_in, cols_out);
+    else
+        copy_columns_kernel<uint32_t><<<(unsigned)g, 256, 0, st>>>(static_cast<const uint32_t *>(in), static_cast<uint32_t *>(out), rows, cols_in, cols_out);
+    ITB_LAUNCH_CHECK();
+    return ITB_OK;
+}
 
 extern "C" int32_t scale_rows(int32_t dtype, int64_t n_nodes, int32_t dim, const void *x, const float *row_scale, void *out,
                               void *stream) {
@@ -132,11 +160,20 @@ extern "C" int32_t gcn_norm_scales(int64_t n_nodes, const int64_t *rowptr, const
 // (For a layer of equal width the split into projection + update was measured slower than the fused update, even
 // where it would save the pass that writes the GCN message rows: both launches are bound by their memory traffic,
 // not by the matrix cores.)
-static bool project_before_gather(const itb_layer &L, int32_t dtype) {
-    const int elem = dtype == ITB_BF16 ? 2 : 4;
+// Output width of a layer rounded up to whole 16-byte pieces.
+static int32_t padded_width(const itb_layer &L, int32_t dtype) {
+    const int ve = dtype == ITB_BF16 ? 8 : 4;
+    return (L.d_out + ve - 1) / ve * ve;
+}
+// A width that is not whole 16-byte pieces (47 classes, say) is padded: the layer runs on zero-padded copies of its
+// matrices and bias, and the padding columns are dropped when the result is stored.  Only the last layer can have such
+// a width (the next layer could not read rows that are not whole pieces).
+static bool project_before_gather(const itb_layer &L, int32_t dtype, bool is_last) {
     const bool linear = L.agg == ITB_AGG_SUM || L.agg == ITB_AGG_MEAN || L.agg == ITB_AGG_GCN;
+    const int32_t dp = padded_width(L, dtype);
+    if (dp != L.d_out && !is_last) return false;
     // (a layer whose messages carry edge features keeps gather -> update: its edge term is added in the state space)
-    return linear && L.w_self != nullptr && !L.w_edge && L.d_out < L.d_in && (L.d_out * elem) % 16 == 0;
+    return linear && L.w_self != nullptr && !L.w_edge && dp < L.d_in;
 }
 
 // The update of layer l can hand its rows straight to the projection of a narrowing layer l+1 (one launch, the state
@@ -145,8 +182,9 @@ static bool project_before_gather(const itb_layer &L, int32_t dtype) {
 static bool chain_into_next(const itb_layer *layers, int l, int n_layers, int32_t dtype) {
     if (l + 1 >= n_layers || !g_tuning.chain_updates.load()) return false;
     const itb_layer &L = layers[l], &N = layers[l + 1];
-    const bool plain = L.agg != ITB_AGG_NONE && L.agg != ITB_AGG_GAT && !project_before_gather(L, dtype);
-    return plain && project_before_gather(N, dtype) && apply_chain_supported(dtype, L.d_in, L.d_out, L.w_self != nullptr, N.d_out);
+    const bool plain = L.agg != ITB_AGG_NONE && L.agg != ITB_AGG_GAT && !project_before_gather(L, dtype, false);
+    return plain && project_before_gather(N, dtype, l + 2 == n_layers) &&
+           apply_chain_supported(dtype, L.d_in, L.d_out, L.w_self != nullptr, padded_width(N, dtype));
 }
 
 extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_layer *layers, int32_t *plan) {
@@ -158,7 +196,7 @@ extern "C" int32_t infer_layer_plan(int32_t dtype, int32_t n_layers, const itb_l
         if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_NONE) return ITB_ERR_DTYPE;
         plan[l] = L.agg == ITB_AGG_NONE  ? ITB_PLAN_UPDATE_ONLY
                   : L.agg == ITB_AGG_GAT ? ITB_PLAN_ATTENTION
-                  : project_before_gather(L, dtype) ? ITB_PLAN_PROJECT_GATHER
+                  : project_before_gather(L, dtype, l + 1 == n_layers) ? ITB_PLAN_PROJECT_GATHER
                                                     : ITB_PLAN_GATHER_UPDATE;
     }
     for (int l = 0; l + 1 < n_layers; ++l)
@@ -184,6 +222,7 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
     bool edge_kind[3] = {false, false, false};  // layers with an edge matrix, by aggregator (sum, mean, GCN)
     int32_t max_heads = 0;
     size_t gather_ws = 0;
+    int pad_layer = -1;   // the (last) layer that runs on zero-padded matrices, if any
     for (int l = 0; l < n_layers; ++l) {
         const itb_layer &L = layers[l];
         if (L.agg < ITB_AGG_SUM || L.agg > ITB_AGG_NONE) return ITB_ERR_DTYPE;
@@ -207,14 +246,16 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             any_project = true;  // the edge term of the layer lives in the projection buffer
         }
         if (gat && L.heads > max_heads) max_heads = L.heads;
-        const bool pf = project_before_gather(L, dtype);
+        const bool pf = project_before_gather(L, dtype, l + 1 == n_layers);
         any_project = any_project || pf;
+        const int32_t dp = pf ? padded_width(L, dtype) : L.d_out;   // a projected layer runs at whole 16-byte rows
+        if (dp != L.d_out) pad_layer = l;
         // every update launch of the layer must have a kernel configuration: refuse the model before enqueueing anything
         if (gat ? !apply_shape_supported(dtype, L.d_in, L.d_out, false, L.heads)
-                : (pf ? !apply_shape_supported(dtype, L.d_in, L.d_out, false, 0)
+                : (pf ? !apply_shape_supported(dtype, L.d_in, dp, false, 0)
                       : !apply_shape_supported(dtype, L.d_in, L.d_out, L.w_self != nullptr, 0)))
             return ITB_ERR_UNSUPPORTED;
-        itb_gather_desc gd{L.agg, dtype, dtype, (gat || pf) ? L.d_out : L.d_in, gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr, nullptr, nullptr};
+        itb_gather_desc gd{L.agg, dtype, dtype, gat ? L.d_out : (pf ? dp : L.d_in), gat ? L.heads : 1, L.leaky_slope, ITB_ACT_NONE, nullptr, nullptr, nullptr};
         size_t need = 0;
         int32_t rc = gather_layer(&gd, n_nodes, rowptr, col, split, nullptr, nullptr, nullptr, nullptr, 0, INT64_MAX, nullptr,
                                   &need, nullptr);
@@ -243,6 +284,13 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         if (rc != ITB_OK) return rc;
         if (edge_ws > gather_ws) gather_ws = edge_ws;
     }
+    // zero-padded copies of the matrices and the bias of a projected last layer whose width is not whole 16-byte pieces,
+    // and its result at the padded width
+    const int32_t pad_dp = pad_layer >= 0 ? padded_width(layers[pad_layer], dtype) : 0;
+    char *pad_w_nbr = cv.take<char>(pad_layer >= 0 ? (size_t)layers[pad_layer].d_in * pad_dp * elem : 0);
+    char *pad_w_self = cv.take<char>(pad_layer >= 0 ? (size_t)layers[pad_layer].d_in * pad_dp * elem : 0);
+    float *pad_bias = cv.take<float>(pad_layer >= 0 ? (size_t)pad_dp : 0);
+    char *pad_out = cv.take<char>(pad_layer >= 0 ? (size_t)n_nodes * pad_dp * elem : 0);
     char *gws = cv.take<char>(gather_ws);
     int64_t *range_bounds = cv.take<int64_t>(n_chunks > 1 ? 6 * (size_t)n_chunks : 0);
     if (!workspace) {
@@ -268,6 +316,14 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         // the rows, shadow segments and hubs of every edge range, once per call (they depend on the graph only)
         const int32_t rc = enqueue_range_bounds(n_chunks, edge_chunk, 0, 0, n_nodes, rowptr, split, range_bounds,
                                                 static_cast<hipStream_t>(stream));
+        if (rc != ITB_OK) return rc;
+    }
+    if (pad_layer >= 0) {
+        const itb_layer &P = layers[pad_layer];
+        if (!P.w_nbr || !P.w_self) return ITB_ERR_NULL;
+        int32_t rc = copy_columns(dtype, P.d_in, P.d_out, pad_dp, P.w_nbr, pad_w_nbr, stream);
+        if (rc == ITB_OK) rc = copy_columns(dtype, P.d_in, P.d_out, pad_dp, P.w_self, pad_w_self, stream);
+        if (rc == ITB_OK && P.bias) rc = copy_columns(ITB_F32, 1, P.d_out, pad_dp, P.bias, pad_bias, stream);
         if (rc != ITB_OK) return rc;
     }
     const Marks mark{events, stream};
@@ -305,7 +361,11 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
         const float *gs = nullptr, *gd_scale = gcn ? dst_scale : nullptr;
         void *gather_out = aggbuf;
         itb_gather_desc gd{L.agg, dtype, dtype, L.d_in, 1, 0.f, ITB_ACT_NONE, nullptr, gcn ? edge_coef : nullptr, nullptr};
-        const bool pf = project_before_gather(L, dtype);
+        const bool pf = project_before_gather(L, dtype, l + 1 == n_layers);
+        const bool padded = pf && l == pad_layer;
+        const int32_t dp = padded ? pad_dp : L.d_out;
+        const void *w_nbr = padded ? pad_w_nbr : L.w_nbr, *w_self = padded ? pad_w_self : L.w_self;
+        const float *bias = padded ? (L.bias ? pad_bias : nullptr) : L.bias;
         if (gat) {
             // project first (z and the per-head scores), then the attention reduce writes the new state directly
             if (!L.w_nbr || !L.att_src || !L.att_dst) return ITB_ERR_NULL;
@@ -326,16 +386,16 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
                 // both products left the previous layer's update: first in projbuf, second in that layer's state buffer
                 self_product = state[(l - 1) & 1];
             } else {
-                itb_apply_desc pd{dtype, L.d_in, L.d_out, ITB_ACT_NONE, 0};
-                int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, L.w_nbr, nullptr, projbuf, nullptr, nullptr,
-                                         nullptr, nullptr, nullptr, nullptr, nullptr, L.w_self, aggbuf, nullptr, stream);
+                itb_apply_desc pd{dtype, L.d_in, dp, ITB_ACT_NONE, 0};
+                int32_t rc = apply_layer(&pd, n_nodes, nullptr, gather_src, nullptr, w_nbr, nullptr, projbuf, nullptr, nullptr,
+                                         nullptr, nullptr, nullptr, nullptr, nullptr, w_self, aggbuf, nullptr, stream);
                 if (rc != ITB_OK) return rc;
             }
             gather_src = projbuf;
-            gather_out = dst;
-            gd.dim = L.d_out;
+            gather_out = padded ? static_cast<void *>(pad_out) : dst;
+            gd.dim = dp;
             gd.addend = self_product;
-            gd.bias = L.bias;
+            gd.bias = bias;
             gd.act = L.act;
         }
         projected_by_previous = false;
@@ -378,12 +438,18 @@ extern "C" int32_t infer_full_graph(int64_t n_nodes, int64_t n_edges, const int6
             // chained: the new state goes straight into the next layer's projection and is never stored; the two products
             // take the projection buffer and this layer's (otherwise unused) state buffer
             const itb_layer &N = layers[chain ? l + 1 : l];
-            const itb_apply_chain ch{N.w_nbr, N.w_self, N.d_out, projbuf, dst};
+            const bool next_padded = chain && l + 1 == pad_layer;
+            const itb_apply_chain ch{next_padded ? pad_w_nbr : N.w_nbr, next_padded ? pad_w_self : N.w_self,
+                                     next_padded ? pad_dp : N.d_out, projbuf, dst};
             int32_t rc = apply_layer(&ad, n_nodes, L.w_self ? cur : nullptr, aggbuf, L.w_self, L.w_nbr, L.bias, chain ? nullptr : dst,
                                      nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                                      chain ? &ch : nullptr, stream);   // no self matrix: no self term
             if (rc != ITB_OK) return rc;
             projected_by_previous = chain;
+        }
+        if (padded) {   // drop the padding columns
+            const int32_t rc = copy_columns(dtype, n_nodes, dp, L.d_out, pad_out, dst, stream);
+            if (rc != ITB_OK) return rc;
         }
         if (mark(l, 3) != ITB_OK) return ITB_ERR_DEVICE;
         cur = dst;

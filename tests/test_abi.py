@@ -145,9 +145,14 @@ def test_infer_layer_plan_is_the_librarys_decision(B):
     assert B.lib.infer_layer_plan(B.ITB_F32, 6, lay, plan) == 0
     assert list(plan) == [B.PLAN_PROJECT_GATHER, B.PLAN_GATHER_UPDATE, B.PLAN_GATHER_UPDATE, B.PLAN_GATHER_UPDATE,
                           B.PLAN_ATTENTION, B.PLAN_UPDATE_ONLY]
-    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 6, B.ACT_RELU, 1, 0.2, p, p, None, None, None)      # 24-byte rows (fp32): not
-    assert B.lib.infer_layer_plan(B.ITB_F32, 1, lay, plan) == 0 and plan[0] == B.PLAN_GATHER_UPDATE
-    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 4, B.ACT_RELU, 1, 0.2, p, p, None, None, None)      # 8-byte rows in bf16: not
+    # a width that is not whole 16-byte pieces is padded, which only the last layer can be: projected there (while the
+    # padded width is still below d_in), gather -> update anywhere else
+    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 6, B.ACT_RELU, 1, 0.2, p, p, None, None, None)      # 24-byte rows (fp32) -> 8 columns
+    assert B.lib.infer_layer_plan(B.ITB_F32, 1, lay, plan) == 0 and plan[0] == B.PLAN_PROJECT_GATHER
+    assert B.lib.infer_layer_plan(B.ITB_F32, 2, lay, plan) == 0 and plan[0] == B.PLAN_GATHER_UPDATE   # not the last layer
+    lay[0] = B.itb_layer(B.AGG_MEAN, 128, 47, B.ACT_RELU, 1, 0.2, p, p, None, None, None)     # 47 classes in bf16 -> 48 columns
+    assert B.lib.infer_layer_plan(B.ITB_BF16, 1, lay, plan) == 0 and plan[0] == B.PLAN_PROJECT_GATHER
+    lay[0] = B.itb_layer(B.AGG_MEAN, 8, 4, B.ACT_RELU, 1, 0.2, p, p, None, None, None)        # bf16: 4 -> 8 columns = d_in: not
     assert B.lib.infer_layer_plan(B.ITB_BF16, 1, lay, plan) == 0 and plan[0] == B.PLAN_GATHER_UPDATE
     assert B.lib.infer_layer_plan(B.ITB_F32, 0, lay, plan) == -2 and B.lib.infer_layer_plan(5, 1, lay, plan) == -4
     assert B.lib.infer_layer_plan(B.ITB_F32, 1, None, plan) == -1

@@ -733,6 +733,52 @@ def test_layer_loop_chains_an_update_into_the_next_projection(B, dims, kinds, ch
     assert torch.equal(plain.view(torch.int16), got.view(torch.int16))
 
 
+@pytest.mark.parametrize("dtype,dims", [(W.BF16, (64, 64, 47)), (W.BF16, (128, 41)), (W.BF16, (64, 64, 3)), (W.F32, (128, 64, 10)),
+                                        (W.F32, (64, 47)), (W.F32, (32, 16, 5))])
+@pytest.mark.parametrize("kind", [W.AGG_MEAN, W.AGG_GCN])
+def test_last_layer_of_any_width_is_projected_through_padding(B, dtype, dims, kind):
+    """A narrowing last layer whose width is not whole 16-byte pieces (47 classes, say) still takes W_nbr before its
+    gather: on zero-padded copies of its matrices, the padding dropped when the output is stored.  Plan, every layer
+    against Eq. (1), bitwise equality of the single call (chunked or not) with the call-by-call composition, and -- for
+    bf16 stacks with a 64-wide layer in front -- with the chained update switched off."""
+    import torch
+    from dataclasses import replace
+    from paper_2307_00228_amd import compose
+    n, e = 4000, 50000
+    src, dst, x = W.random_small_graph(sum(dims) + kind, n, e, dims[0], dtype, 0.3)
+    rng = np.random.default_rng(dims[-1] + kind)
+    layers = []
+    for i in range(len(dims) - 1):
+        lay = W.dense_layers(rng, kind, (dims[i], dims[i + 1], dims[i + 1]), dtype, bias_random=True)[0]
+        layers.append(replace(lay, act=W.ACT_RELU if i + 2 < len(dims) else W.ACT_NONE))
+    r, c, d = oracle.build_csr(n, src, dst)
+    rp, cl, dg = torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda(), torch.from_numpy(d).cuda()
+    split = B.split_hubs(rp, 900)
+    dl, xd = B.device_layers(layers), B.to_device(x)
+    tdt = torch.bfloat16 if dtype == W.BF16 else torch.float32
+    plan = B.infer_layer_plan(dl, tdt)
+    assert plan[-1] == B.PLAN_PROJECT_GATHER
+    view = torch.int16 if dtype == W.BF16 else torch.int32
+    got = B.infer_full_graph(rp, cl, dg, split, dl, xd)
+    assert tuple(got.shape) == (n, dims[-1])
+    chunked = B.infer_full_graph(rp, cl, dg, split, dl, xd, edge_chunk=e // 3)
+    assert torch.equal(got.view(view), chunked.view(view))
+    B.set_tuning(9, 0)
+    try:
+        steps = compose.run_layers(rp, cl, dg, split, dl, xd)
+        plain = B.infer_full_graph(rp, cl, dg, split, dl, xd)
+        torch.cuda.synchronize()
+    finally:
+        B.set_tuning(9, 1)
+    assert torch.equal(got.view(view), plain.view(view)) and torch.equal(got.view(view), steps[-1].out.view(view))
+    tr = compose.run_layers(rp, cl, dg, split, dl, xd)
+    assert torch.equal(got.view(view), tr[-1].out.view(view))
+    h = x
+    for i, (lay, st) in enumerate(zip(layers, steps)):
+        check_layer(B, st, r, c, d, h, lay, dtype, f"layer {i} of {dims}")
+        h = B.to_numpy(st.out)
+
+
 @pytest.mark.parametrize("kind", [W.AGG_SUM, W.AGG_MEAN, W.AGG_GCN])
 @pytest.mark.parametrize("dtype,dim", [(W.F32, 64), (W.F32, 16), (W.BF16, 32), (W.BF16, 64), (W.BF16, 520)])
 @pytest.mark.parametrize("T", [None, 40])
