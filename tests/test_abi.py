@@ -298,6 +298,10 @@ def test_misaligned_feature_tensors_are_refused(B):
     assert ap(None, off, ok, None) == -5 and ap(None, ok, off, None) == -5
     assert ap(off, ok, ok, None) == -5 and ap(None, ok, ok, off) == -5
     assert lib.scale_rows(B.ITB_F32, 10, 64, off, ok, ok, None) == -5
+    # copy_columns
+    assert lib.copy_columns(7, 10, 4, 8, ok, ok, None) == -4 and lib.copy_columns(B.ITB_F32, -1, 4, 8, ok, ok, None) == -2
+    assert lib.copy_columns(B.ITB_F32, 10, 0, 8, ok, ok, None) == -2 and lib.copy_columns(B.ITB_BF16, 10, 4, 8, None, ok, None) == -1
+    assert lib.copy_columns(B.ITB_BF16, 0, 4, 8, None, None, None) == 0
 
 
 def test_headers_are_plain_c_and_the_binding_mirrors_their_layout(B, tmp_path):
