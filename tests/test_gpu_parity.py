@@ -733,6 +733,19 @@ def test_layer_loop_chains_an_update_into_the_next_projection(B, dims, kinds, ch
     assert torch.equal(plain.view(torch.int16), got.view(torch.int16))
 
 
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+@pytest.mark.parametrize("rows,cin,cout", [(1, 1, 8), (37, 47, 48), (1000, 48, 47), (5, 10, 10), (4099, 3, 16), (64, 130, 7)])
+def test_copy_columns_bit_exact(B, dtype, rows, cin, cout):
+    import torch
+    rng = np.random.default_rng(rows + cin + cout)
+    a = W.store(rng.standard_normal((rows, cin)).astype(np.float32), dtype)
+    got = B.to_numpy(B.copy_columns(B.to_device(a), cout))
+    want = np.zeros((rows, cout), dtype=a.dtype)
+    k = min(cin, cout)
+    want[:, :k] = a[:, :k]
+    assert got.shape == want.shape and np.array_equal(np.asarray(got).view(np.uint8), want.view(np.uint8))
+
+
 @pytest.mark.parametrize("dtype,dims", [(W.BF16, (64, 64, 47)), (W.BF16, (128, 41)), (W.BF16, (64, 64, 3)), (W.F32, (128, 64, 10)),
                                         (W.F32, (64, 47)), (W.F32, (32, 16, 5))])
 @pytest.mark.parametrize("kind", [W.AGG_MEAN, W.AGG_GCN])
