@@ -350,3 +350,24 @@ def test_headers_are_plain_c_and_the_binding_mirrors_their_layout(B, tmp_path):
         one.write_text(f'#include "{header}"\nint unused_{header.split(".")[0]};\n')
         subprocess.run([gcc, "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"),
                         str(one)], check=True)
+
+
+def test_readme_c_sketch_compiles_against_the_header(tmp_path):
+    """The C call sequence shown in README.md, wrapped into a function whose parameters are the buffers it names, compiles
+    as C11 against include/inferturbo.h: argument counts and types of the sketch cannot drift from the header."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    text = open(os.path.join(ROOT, "README.md")).read()
+    block = re.search(r"```c\n(.*?)```", text, flags=re.S).group(1)
+    body = block.replace('#include "inferturbo.h"', "")
+    src = tmp_path / "sketch.c"
+    src.write_text('#include "inferturbo.h"\n'
+                   "void sketch(int64_t n, int64_t e, const int32_t *src, const int32_t *dst, int64_t *rowptr, int32_t *col,\n"
+                   "            int32_t *deg_out, void *ws, void *ws2, void *ws3, size_t need2, size_t need3, void *stream,\n"
+                   "            const void *w_self0, const void *w_nbr0, const float *bias0, const void *w_self1, const void *w_nbr1,\n"
+                   "            const float *bias1, const void *x, void *out, itb_split split) {\n" + body + "}\n")
+    subprocess.run([gcc, "-std=c11", "-Wall", "-Wextra", "-Werror", "-Wno-unused-variable", "-Wno-unused-but-set-variable",
+                    "-fsyntax-only", "-I", os.path.join(ROOT, "include"), str(src)], check=True)
