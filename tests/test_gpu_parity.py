@@ -1214,6 +1214,43 @@ def test_zero_sized_calls_are_accepted(B):
     assert not B.gather_layer(W.AGG_MIN, rowptr, col, x5).any()
 
 
+def test_edge_feature_layer_chained_into_a_narrowing_layer(B):
+    """A 64-wide bf16 layer with an edge matrix (its edge term enters in the gather's epilogue, through the projection
+    buffer) whose update is chained into the next layer's projection (which is written to that same buffer afterwards):
+    same bits as without the chaining, and every layer within its bar of Eq. (1)."""
+    import torch
+    from dataclasses import replace
+    from paper_2307_00228_amd import compose
+    dtype, n, e, d_e = W.BF16, 4000, 60000, 8
+    src, dst, x, ef, rng = edge_case(77, n, e, 64, d_e, dtype)
+    layers = W.dense_layers(rng, [W.AGG_MEAN, W.AGG_MEAN], (64, 64, 32), dtype, bias_random=True)
+    layers[0] = replace(layers[0], w_edge=W.store(rng.uniform(-0.4, 0.4, (d_e, 64)).astype(np.float32), dtype))
+    rowptr, col, deg_out = B.build_csr_by_dst(n, dev_i32(src), dev_i32(dst))
+    r, c, d = oracle.build_csr(n, src, dst)
+    dl, xd, efd = B.device_layers(layers), B.to_device(x), B.to_device(ef)
+    assert B.infer_layer_plan(dl, torch.bfloat16) == [B.PLAN_GATHER_UPDATE_CHAINED, B.PLAN_PROJECT_GATHER]
+    split = B.split_hubs(rowptr, 50)
+    out = B.infer_full_graph(rowptr, col, deg_out, split, dl, xd, edge_feat=efd, edge_chunk=e // 3)
+    tr = compose.run_layers(rowptr, col, deg_out, split, dl, xd, edge_feat=efd)
+    assert tr[0].out is None and torch.equal(out.view(torch.int16), tr[-1].out.view(torch.int16))
+    B.set_tuning(9, 0)
+    try:
+        steps = compose.run_layers(rowptr, col, deg_out, split, dl, xd, edge_feat=efd)
+        torch.cuda.synchronize()
+    finally:
+        B.set_tuning(9, 1)
+    assert torch.equal(out.view(torch.int16), steps[-1].out.view(torch.int16))
+    h = x
+    for i, (lay, st) in enumerate(zip(layers, steps)):
+        _, y64, a64 = oracle.dense_layer(r, c, d, h, lay, dtype, return_agg64=True, edge_feat=ef if lay.w_edge is not None else None)
+        slack = 0.0 if st.projected else agg_rounding_slack(a64, lay.w_nbr, dtype)
+        if lay.w_edge is not None:
+            et = np.abs(W.as_f32(B.to_numpy(st.edge_term)).astype(np.float64))
+            slack = slack + 2.0 ** -8 * (et @ np.abs(W.as_f32(lay.w_nbr).astype(np.float64)))
+        check_features(B.to_numpy(st.out), y64, dtype, f"layer {i}", slack=slack)
+        h = B.to_numpy(st.out)
+
+
 @pytest.mark.parametrize("dtype", [W.F32, W.BF16])
 def test_layers_without_a_self_matrix(B, dtype):
     """h' = act(agg(h) W_nbr + b): dense layers whose self matrix is absent (the vertex's own state does not enter)."""
